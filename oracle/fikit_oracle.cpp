@@ -1,0 +1,272 @@
+// CPU oracle for the FIKIT trace-profiling and gap-filling path.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the definition of "correct" that the GPU library is
+// compared against.  It is plain, single-threaded and slow on purpose, and it shares nothing
+// with the GPU library: no header, no helper, no table.  Only tests, the smoke check and the
+// benchmark's CPU-baseline leg may call it; the product never does.
+//
+// What it computes, and where the paper defines it (arXiv 2311.10359):
+//
+//   oracle_kernel_id  - the Kernel ID of a launch (Section 3.2, "Identifying each kernel": the
+//                       kernel's function name, block dimensions and grid dimensions make up its
+//                       ID).  The ID here is the 64-bit FNV-1a hash of the 32 bytes that hold
+//                       name id, grid[3], block[3] and dynamic shared-memory bytes.
+//   oracle_profile    - the measurement phase's statistical output (Section 3.2, "Data
+//                       acquisition and statistical output during the measurement phase"): the
+//                       set of unique IDs S_UID of each task, and per ID the execution times
+//                       K and the idle times G that follow a kernel of that ID.  The paper
+//                       prints the means SK_j and SG_j; this oracle emits count and sum (so the
+//                       mean is sum/count) and, beyond the paper, min, max and nearest-rank p50
+//                       and p95 of the same samples.
+//   oracle_gapfill    - Algorithm 1 (FIKIT procedure) with Algorithm 2 (BestPrioFit) in the
+//                       case of one high-priority and one low-priority task: the low-priority
+//                       task's waiting queue then holds exactly one request at a time, its next
+//                       kernel, so "best fit" degenerates to first-in-first-out and a gap ends
+//                       as soon as that head request does not fit.
+//
+// All quantities are integers (nanoseconds, counts); nothing is floating point.
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <vector>
+
+namespace {
+
+// Input record, 64 bytes, little endian (own definition; mirrors the documented layout).
+struct Launch {
+  uint32_t name_id;
+  uint32_t grid[3];
+  uint32_t block[3];
+  uint32_t shmem;
+  int64_t start_ns;
+  int64_t end_ns;
+  uint8_t reserved[16];
+};
+static_assert(sizeof(Launch) == 64, "launch record is 64 bytes");
+
+struct Stats {
+  uint64_t count;
+  uint64_t sum;
+  int64_t min, max, p50, p95;
+};
+static_assert(sizeof(Stats) == 48, "stats block is 48 bytes");
+
+struct Row {
+  uint64_t kernel_id;
+  uint32_t task;
+  uint32_t reserved0;
+  Stats exec;
+  Stats gap;
+  uint8_t reserved1[16];
+};
+static_assert(sizeof(Row) == 128, "row is 128 bytes");
+
+enum : int {
+  OK = 0,
+  INVALID_ARG = -1,
+  ROW_CAPACITY = -3,
+  BAD_RECORD = -4,
+  UNKNOWN_ID = -5,
+};
+
+// FNV-1a, 64 bit: start from the offset basis; for every byte, xor it in, then multiply by
+// the FNV prime, modulo 2^64.
+uint64_t fnv1a64(const uint8_t* p, size_t len) {
+  uint64_t h = 0xcbf29ce484222325ull;
+  for (size_t i = 0; i < len; ++i) {
+    h ^= static_cast<uint64_t>(p[i]);
+    h *= 0x100000001b3ull;
+  }
+  return h;
+}
+
+// Nearest-rank percentile of an ascending vector: the value at 1-based rank ceil(K*n/100).
+int64_t nearest_rank(const std::vector<int64_t>& sorted, uint64_t k) {
+  uint64_t n = sorted.size();
+  uint64_t rank = (k * n + 99) / 100;  // ceil(k*n/100)
+  return sorted[rank - 1];
+}
+
+Stats stats_of(std::vector<int64_t> v) {
+  Stats s;
+  std::memset(&s, 0, sizeof(s));
+  if (v.empty()) return s;  // an ID seen only as a task's last launch has no idle-time sample
+  std::sort(v.begin(), v.end());
+  s.count = v.size();
+  uint64_t sum = 0;
+  for (int64_t x : v) sum += static_cast<uint64_t>(x);  // modulo 2^64
+  s.sum = sum;
+  s.min = v.front();
+  s.max = v.back();
+  s.p50 = nearest_rank(v, 50);
+  s.p95 = nearest_rank(v, 95);
+  return s;
+}
+
+struct Samples {
+  std::vector<int64_t> exec;  // K: execution time of every launch with this ID
+  std::vector<int64_t> gap;   // G: idle time after every launch with this ID (not the last of the task)
+};
+
+bool offsets_ok(const uint64_t* off, uint32_t n_tasks, uint64_t n) {
+  if (!off) return false;
+  if (off[0] != 0) return false;
+  for (uint32_t t = 0; t < n_tasks; ++t)
+    if (off[t + 1] < off[t]) return false;
+  return off[n_tasks] == n;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t oracle_kernel_id(const uint8_t* bytes, uint64_t len) { return fnv1a64(bytes, len); }
+
+// Measurement-phase statistics.  rows_out receives one Row per (task, unique ID), tasks
+// ascending, IDs ascending as unsigned numbers; task_row_offsets[t]..[t+1] delimit task t's rows.
+// ids_out (may be null) receives every launch's ID in launch order.
+int oracle_profile(const void* records_v, uint64_t n_records, const uint64_t* task_offsets,
+                   uint32_t n_tasks, uint64_t* ids_out, void* rows_out_v, uint64_t row_capacity,
+                   uint64_t* task_row_offsets, uint64_t* n_rows_out) {
+  const Launch* rec = static_cast<const Launch*>(records_v);
+  Row* rows = static_cast<Row*>(rows_out_v);
+  if (!n_rows_out || !task_row_offsets) return INVALID_ARG;
+  if (n_records && !rec) return INVALID_ARG;
+  if (!offsets_ok(task_offsets, n_tasks, n_records)) return INVALID_ARG;
+
+  uint64_t n_rows = 0;
+  bool overflow = false;
+  for (uint32_t t = 0; t < n_tasks; ++t) {
+    task_row_offsets[t] = n_rows;
+    std::map<uint64_t, Samples> by_id;  // S_UID of this task, ordered by unsigned ID
+    const uint64_t lo = task_offsets[t], hi = task_offsets[t + 1];
+    for (uint64_t i = lo; i < hi; ++i) {
+      const uint64_t id = fnv1a64(reinterpret_cast<const uint8_t*>(&rec[i]), 32);
+      if (ids_out) ids_out[i] = id;
+      if (rec[i].end_ns < rec[i].start_ns) return BAD_RECORD;
+      const int64_t k = rec[i].end_ns - rec[i].start_ns;  // execution time K
+      Samples& s = by_id[id];
+      s.exec.push_back(k);
+      if (i + 1 < hi) {  // idle time G: from this kernel's end to the next kernel's start
+        int64_t g = rec[i + 1].start_ns - rec[i].end_ns;
+        if (g < 0) g = 0;  // overlapping kernels leave no idle time
+        s.gap.push_back(g);
+      }
+    }
+    for (auto& kv : by_id) {
+      if (n_rows < row_capacity && rows) {
+        Row r;
+        std::memset(&r, 0, sizeof(r));
+        r.kernel_id = kv.first;
+        r.task = t;
+        r.exec = stats_of(kv.second.exec);
+        r.gap = stats_of(kv.second.gap);
+        rows[n_rows] = r;
+      } else {
+        overflow = true;
+      }
+      ++n_rows;
+    }
+  }
+  task_row_offsets[n_tasks] = n_rows;
+  *n_rows_out = n_rows;
+  return overflow ? ROW_CAPACITY : OK;
+}
+
+// Gap filling, one (high-priority task, low-priority task) pair per scenario.
+//
+// Predictions come from the profile rows: a launch's predicted execution time is the p50
+// execution time of its ID, the predicted idle time after a high-priority launch is the p50
+// idle time of its ID.  Per high-priority gap the procedure (Algorithm 1) skips gaps below
+// min_gap_ns, reserves margin_ns at the end of the gap, and then keeps issuing the
+// low-priority task's next kernel while its predicted duration does not exceed what is left,
+// subtracting each issued kernel's duration from the remaining idle time.
+//
+// Outputs per gap: number of low-priority kernels issued and nanoseconds filled.  Per scenario:
+// how many low-priority kernels went into gaps, and the time (on the predicted timeline that
+// starts at 0 with the first high-priority kernel) at which the low-priority task finishes;
+// kernels that found no gap run back to back after the last high-priority kernel.
+// assign (optional, indexed through assign_offsets[S+1]) receives for every low-priority launch
+// the gap it was put in, or 0xffffffff if it ran after the high-priority trace.
+int oracle_gapfill(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n_tasks,
+                   const void* rows_v, const uint64_t* task_row_offsets, const uint32_t* hp_task,
+                   const uint32_t* lp_task, uint64_t n_scenarios, int64_t margin_ns,
+                   int64_t min_gap_ns, const uint64_t* gap_offsets, uint32_t* fill_count,
+                   int64_t* filled_ns, int64_t* lp_completion_ns, uint64_t* lp_placed,
+                   const uint64_t* assign_offsets, uint32_t* assign) {
+  const Row* rows = static_cast<const Row*>(rows_v);
+  if (!task_offsets || !task_row_offsets) return INVALID_ARG;
+  if (n_scenarios && (!hp_task || !lp_task || !gap_offsets || !lp_completion_ns || !lp_placed))
+    return INVALID_ARG;
+  if (margin_ns < 0 || min_gap_ns < 0) return INVALID_ARG;
+
+  for (uint64_t s = 0; s < n_scenarios; ++s) {
+    const uint32_t hp = hp_task[s], lp = lp_task[s];
+    if (hp >= n_tasks || lp >= n_tasks) return INVALID_ARG;
+
+    // Load the profiled data of the two tasks, keyed by Kernel ID.
+    std::map<uint64_t, const Row*> hp_rows, lp_rows;
+    for (uint64_t r = task_row_offsets[hp]; r < task_row_offsets[hp + 1]; ++r)
+      hp_rows[rows[r].kernel_id] = &rows[r];
+    for (uint64_t r = task_row_offsets[lp]; r < task_row_offsets[lp + 1]; ++r)
+      lp_rows[rows[r].kernel_id] = &rows[r];
+
+    const uint64_t h0 = task_offsets[hp], H = task_offsets[hp + 1] - h0;
+    const uint64_t l0 = task_offsets[lp], L = task_offsets[lp + 1] - l0;
+
+    std::vector<int64_t> D(L);  // predicted duration of each low-priority kernel
+    for (uint64_t j = 0; j < L; ++j) {
+      auto it = lp_rows.find(ids[l0 + j]);
+      if (it == lp_rows.end()) return UNKNOWN_ID;
+      D[j] = it->second->exec.p50;
+    }
+
+    uint64_t p = 0;        // next low-priority kernel to issue (FIFO)
+    int64_t t = 0;         // predicted time
+    bool done = (L == 0);  // low-priority task finished
+    int64_t completion = 0;
+    const uint64_t g0 = gap_offsets[s];
+    for (uint64_t i = 0; i < H; ++i) {
+      auto it = hp_rows.find(ids[h0 + i]);
+      if (it == hp_rows.end()) return UNKNOWN_ID;
+      const int64_t E = it->second->exec.p50;
+      const int64_t G = it->second->gap.p50;
+      t += E;  // high-priority kernel i runs and ends at t
+      if (i + 1 == H) break;  // no gap after the last launch
+      uint32_t c = 0;
+      int64_t f = 0;
+      if (G >= min_gap_ns && G >= margin_ns) {
+        int64_t r = G - margin_ns;  // remaining idle time
+        while (p < L && D[p] <= r) {
+          r -= D[p];
+          f += D[p];
+          if (assign) assign[assign_offsets[s] + p] = static_cast<uint32_t>(i);
+          ++p;
+          ++c;
+        }
+        if (p == L && c > 0 && !done) {
+          completion = t + f;
+          done = true;
+        }
+      }
+      fill_count[g0 + i] = c;
+      filled_ns[g0 + i] = f;
+      t += G;  // the high-priority timeline is never delayed
+    }
+    lp_placed[s] = p;
+    if (!done) {
+      int64_t rest = 0;
+      for (uint64_t j = p; j < L; ++j) {
+        rest += D[j];
+        if (assign) assign[assign_offsets[s] + j] = 0xffffffffu;
+      }
+      completion = t + rest;
+    }
+    lp_completion_ns[s] = completion;
+  }
+  return OK;
+}
+
+}  // extern "C"

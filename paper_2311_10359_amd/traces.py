@@ -1,0 +1,290 @@
+"""Seeded synthetic kernel-launch traces.
+
+Stands in for the output of the paper's measurement phase (Section 3.2, "Measuring the
+execution and idle time of kernel"): per task, the sequence of intercepted kernel launches,
+each with the ingredients of its Kernel ID (function name, grid and block dimensions; plus
+dynamic shared-memory bytes) and the device start and end time of the kernel.
+
+This module only *draws inputs*.  It contains none of the method's arithmetic (no hashing,
+no statistics, no schedule evaluation) so that the CPU oracle and the HIP library can both be
+fed from it without sharing anything else.
+
+The five workloads mirror the structure the paper describes: a service re-executes the same
+kernel sequence again and again (Section 3.2), few distinct Kernel IDs recur within and
+across runs, the same ID shows somewhat different durations from launch to launch, and idle
+gaps come from launch overhead with occasional long host-side stalls (Section 1).
+
+Every task has its own counter-seeded generator, so any single task can be regenerated alone
+(used by the sampled full-size parity checks).
+"""
+from __future__ import annotations
+
+import math
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, replace
+from typing import Callable, Optional, Sequence, Tuple
+
+import numpy as np
+
+# One launch record: 64 bytes, little endian.
+LAUNCH_DTYPE = np.dtype(
+    [
+        ("name_id", "<u4"),
+        ("grid", "<u4", (3,)),
+        ("block", "<u4", (3,)),
+        ("shmem", "<u4"),
+        ("start_ns", "<i8"),
+        ("end_ns", "<i8"),
+        ("reserved", "u1", (16,)),
+    ]
+)
+assert LAUNCH_DTYPE.itemsize == 64
+
+BASE_SEED = 2311
+
+# Share of the log-scale variance that belongs to the Kernel ID (the kernel's characteristic
+# duration) rather than to the individual launch.  The marginal over launches stays exactly
+# lognormal(mu, sigma) because rho^2 + (1 - rho^2) = 1.
+RHO_EXEC = 0.95
+RHO_GAP = 0.90
+
+
+@dataclass(frozen=True)
+class TraceConfig:
+    index: int
+    name: str
+    n_tasks: int
+    # launches(task) -> number of launches, ids(task) -> number of distinct kernel tuples
+    launches: Callable[[int], int]
+    ids: Callable[[int], int]
+    pattern: str  # "pass50" | "pass200x2" | "zipf" | "uniform" | "pass2k"
+    exec_mu: Callable[[int], float]
+    exec_sigma: Callable[[int], float]
+    gap_mu: Callable[[int], float]
+    gap_sigma: Callable[[int], float]
+    stall_frac: float = 0.0  # share of gaps drawn from the stall distribution
+    stall_mu: float = 0.0
+    stall_sigma: float = 0.0
+    zero_gap_frac: float = 0.0  # share of gaps that are exactly 0 (back-to-back launches)
+    zipf_s: float = 0.0
+    scenario_kind: str = "none"  # "pair01" | "grid" | "adjacent" | "none"
+    margin_ns: int = 500
+    min_gap_ns: int = 0
+
+    @property
+    def n_records(self) -> int:
+        return sum(self.launches(t) for t in range(self.n_tasks))
+
+
+def _const(v):
+    return lambda task: v
+
+
+def config(index: int, *, n_tasks: Optional[int] = None, launches: Optional[int] = None,
+           hp_launches: Optional[int] = None, lp_launches: Optional[int] = None) -> TraceConfig:
+    """The five workloads.  Keyword overrides shrink a workload while keeping its structure
+    (same distributions, same ID pattern) so that it can be checked on a CPU in seconds."""
+    ln = math.log
+    if index == 0:
+        n = launches or 1000
+        cfg = TraceConfig(
+            0, "tiny", 2, _const(n), lambda t: 20 if t == 0 else 15, "pass50",
+            _const(ln(20000)), _const(0.8), _const(ln(8000)), _const(1.0),
+            scenario_kind="pair01")
+    elif index == 1:
+        n = launches or 65536
+        cfg = TraceConfig(
+            1, "medium", n_tasks or 32, _const(n), _const(300), "pass200x2",
+            _const(ln(20000)), _const(0.8), _const(ln(8000)), _const(1.0),
+            stall_frac=0.10, stall_mu=ln(200000), stall_sigma=0.5, scenario_kind="grid")
+    elif index == 2:
+        n = launches or 1048576
+        cfg = TraceConfig(
+            2, "skewed", n_tasks or 64, _const(n), _const(4096), "zipf",
+            _const(ln(5000)), _const(1.5), _const(ln(15000)), _const(1.2),
+            zero_gap_frac=0.30, zipf_s=1.2)
+    elif index == 3:
+        n = launches or 1048576
+        cfg = TraceConfig(
+            3, "large_profile", n_tasks or 256, _const(n), _const(1000), "uniform",
+            _const(ln(20000)), _const(0.8), _const(ln(8000)), _const(1.0))
+    elif index == 4:
+        h = hp_launches or 4096
+        l = lp_launches or 16384
+        nt = n_tasks or 131072
+        assert nt % 2 == 0
+        # even task = high-priority trace, odd task = low-priority queue of the same scenario
+        cfg = TraceConfig(
+            4, "batched_gapfill", nt,
+            lambda t: h if t % 2 == 0 else l,
+            lambda t: 100 if t % 2 == 0 else 80, "pass2k",
+            lambda t: ln(20000) if t % 2 == 0 else ln(6000),
+            lambda t: 0.8 if t % 2 == 0 else 1.0,
+            lambda t: ln(30000) if t % 2 == 0 else ln(8000),
+            lambda t: 1.2 if t % 2 == 0 else 1.0,
+            scenario_kind="adjacent")
+    else:
+        raise ValueError(f"no workload {index}")
+    return cfg
+
+
+def _rng(cfg: TraceConfig, task: int, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64([BASE_SEED + cfg.index, task, stream]))
+
+
+def kernel_tuples(cfg: TraceConfig, task: int) -> np.ndarray:
+    """K distinct (name_id, grid[3], block[3], shmem) tuples of a task as a (K, 8) uint32 array."""
+    k = cfg.ids(task)
+    rng = _rng(cfg, task, 0)
+    out = np.zeros((0, 8), dtype=np.uint32)
+    grid_y_choices = np.array([1, 1, 1, 2, 4, 8, 16, 32, 64], dtype=np.uint32)
+    block_x_choices = np.array([32, 64, 128, 256, 512, 1024], dtype=np.uint32)
+    block_y_choices = np.array([1, 1, 2, 4], dtype=np.uint32)
+    while out.shape[0] < k:
+        m = k - out.shape[0] + 8
+        t = np.zeros((m, 8), dtype=np.uint32)
+        t[:, 0] = rng.integers(0, 1 << 20, m)
+        t[:, 1] = rng.integers(1, 65536, m)
+        t[:, 2] = rng.choice(grid_y_choices, m)
+        t[:, 3] = 1
+        bx = rng.choice(block_x_choices, m)
+        by = rng.choice(block_y_choices, m)
+        by = np.where(bx.astype(np.uint64) * by > 1024, 1, by).astype(np.uint32)
+        t[:, 4] = bx
+        t[:, 5] = by
+        t[:, 6] = 1
+        sh = rng.integers(1, 257, m).astype(np.uint32) * 256
+        t[:, 7] = np.where(rng.random(m) < 0.5, 0, sh)
+        out = np.concatenate([out, t], axis=0)
+        # keep first occurrence of each tuple, in draw order
+        _, first = np.unique(out, axis=0, return_index=True)
+        out = out[np.sort(first)]
+    return out[:k]
+
+
+def _id_sequence(cfg: TraceConfig, task: int, n: int, k: int) -> np.ndarray:
+    """Index (0..k-1) of the kernel tuple used by each of the n launches."""
+    rng = _rng(cfg, task, 1)
+    if cfg.pattern == "pass50":
+        plen = max(50, k)
+        one = np.concatenate([np.arange(k), rng.integers(0, k, plen - k)])
+        rng.shuffle(one)
+        reps = -(-n // plen)
+        return np.tile(one, reps)[:n]
+    if cfg.pattern == "pass200x2":
+        # two variants of the model pass that together touch all k tuples
+        plen = (2 * k) // 3
+        a = rng.permutation(plen)
+        b = rng.permutation(plen) + (k - plen)
+        reps = -(-n // plen)
+        pick = rng.random(reps) < 0.5
+        seq = np.where(pick[:, None], a[None, :], b[None, :]).reshape(-1)
+        return seq[:n]
+    if cfg.pattern == "zipf":
+        w = 1.0 / np.power(np.arange(1, k + 1, dtype=np.float64), cfg.zipf_s)
+        cdf = np.cumsum(w / w.sum())
+        cdf[-1] = 1.0
+        return np.searchsorted(cdf, rng.random(n), side="right").clip(0, k - 1)
+    if cfg.pattern == "uniform":
+        return rng.integers(0, k, n)
+    if cfg.pattern == "pass2k":
+        one = np.concatenate([np.arange(k), np.arange(k)])
+        rng.shuffle(one)
+        reps = -(-n // one.size)
+        return np.tile(one, reps)[:n]
+    raise ValueError(cfg.pattern)
+
+
+def task_records(cfg: TraceConfig, task: int) -> np.ndarray:
+    """All launch records of one task, in launch order."""
+    n = cfg.launches(task)
+    k = cfg.ids(task)
+    rec = np.zeros(n, dtype=LAUNCH_DTYPE)
+    if n == 0:
+        return rec
+    tuples = kernel_tuples(cfg, task)
+    seq = _id_sequence(cfg, task, n, k)
+    chosen = tuples[seq]
+    rec["name_id"] = chosen[:, 0]
+    rec["grid"] = chosen[:, 1:4]
+    rec["block"] = chosen[:, 4:7]
+    rec["shmem"] = chosen[:, 7]
+
+    rng = _rng(cfg, task, 2)
+    # characteristic log-duration and log-gap of each kernel tuple
+    z_exec = rng.standard_normal(k)
+    z_gap = rng.standard_normal(k)
+    e_mu, e_sig = cfg.exec_mu(task), cfg.exec_sigma(task)
+    g_mu, g_sig = cfg.gap_mu(task), cfg.gap_sigma(task)
+    le = e_mu + e_sig * (RHO_EXEC * z_exec[seq] + math.sqrt(1 - RHO_EXEC ** 2) * rng.standard_normal(n))
+    exec_ns = np.maximum(1, np.rint(np.exp(le))).astype(np.int64)
+    lg = g_mu + g_sig * (RHO_GAP * z_gap[seq] + math.sqrt(1 - RHO_GAP ** 2) * rng.standard_normal(n))
+    gap_ns = np.maximum(0, np.rint(np.exp(lg))).astype(np.int64)
+    if cfg.stall_frac > 0:
+        u = rng.random(n)
+        stall = np.rint(np.exp(cfg.stall_mu + cfg.stall_sigma * rng.standard_normal(n))).astype(np.int64)
+        gap_ns = np.where(u < cfg.stall_frac, stall, gap_ns)
+    if cfg.zero_gap_frac > 0:
+        u = rng.random(n)
+        gap_ns = np.where(u < cfg.zero_gap_frac, 0, gap_ns)
+    step = exec_ns + gap_ns
+    start = np.empty(n, dtype=np.int64)
+    start[0] = 0
+    np.cumsum(step[:-1], out=start[1:])
+    rec["start_ns"] = start
+    rec["end_ns"] = start + exec_ns
+    return rec
+
+
+def task_offsets(cfg: TraceConfig, tasks: Optional[Sequence[int]] = None) -> np.ndarray:
+    tasks = range(cfg.n_tasks) if tasks is None else tasks
+    off = np.zeros(len(tasks) + 1, dtype=np.uint64)
+    np.cumsum([cfg.launches(t) for t in tasks], out=off[1:])
+    return off
+
+
+def build(cfg: TraceConfig, tasks: Optional[Sequence[int]] = None, threads: int = 1,
+          out: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Records of the given tasks (default: all) laid out back to back, plus CSR offsets.
+
+    `out`, if given, is a preallocated LAUNCH_DTYPE array of the right length (for example a
+    view of pinned host memory) that receives the records."""
+    tasks = list(range(cfg.n_tasks) if tasks is None else tasks)
+    off = task_offsets(cfg, tasks)
+    total = int(off[-1])
+    rec = np.zeros(total, dtype=LAUNCH_DTYPE) if out is None else out
+    assert rec.shape[0] == total and rec.dtype == LAUNCH_DTYPE
+
+    def fill(i):
+        rec[int(off[i]):int(off[i + 1])] = task_records(cfg, tasks[i])
+
+    if threads <= 1 or len(tasks) <= 1:
+        for i in range(len(tasks)):
+            fill(i)
+    else:
+        with ThreadPoolExecutor(threads) as pool:
+            list(pool.map(fill, range(len(tasks)), chunksize=max(1, len(tasks) // (threads * 8))))
+    return rec, off
+
+
+def scenarios(cfg: TraceConfig) -> Tuple[np.ndarray, np.ndarray]:
+    """(hp_task[S], lp_task[S]) as uint32, task numbers local to the full workload."""
+    if cfg.scenario_kind == "pair01":
+        return np.array([0], dtype=np.uint32), np.array([1], dtype=np.uint32)
+    if cfg.scenario_kind == "grid":
+        half = cfg.n_tasks // 2
+        hp, lp = np.meshgrid(np.arange(half), np.arange(half, 2 * half), indexing="ij")
+        return hp.reshape(-1).astype(np.uint32), lp.reshape(-1).astype(np.uint32)
+    if cfg.scenario_kind == "adjacent":
+        s = np.arange(cfg.n_tasks // 2, dtype=np.uint32)
+        return 2 * s, 2 * s + 1
+    return np.zeros(0, dtype=np.uint32), np.zeros(0, dtype=np.uint32)
+
+
+def gap_offsets(offsets: np.ndarray, hp_task: np.ndarray) -> np.ndarray:
+    """Where each scenario's per-gap outputs start: a scenario whose high-priority trace has H
+    launches owns max(H - 1, 0) consecutive output slots (one per idle gap between launches)."""
+    h = (offsets[1:] - offsets[:-1]).astype(np.int64)[hp_task.astype(np.int64)]
+    out = np.zeros(hp_task.shape[0] + 1, dtype=np.uint64)
+    np.cumsum(np.maximum(h - 1, 0), out=out[1:])
+    return out

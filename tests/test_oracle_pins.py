@@ -1,0 +1,508 @@
+"""Pins of the CPU oracle to things other than itself.
+
+P0  published FNV-1a-64 vectors (kernel ID hash).
+P1  hand-worked 12-launch trace (tests/golden/p1_hand_worked.json).
+P2  the paper's closed forms SK_j, SG_j (Section 3.2) evaluated with the Kronecker delta as printed.
+P3  invariants that hold for any trace.
+P4  brute-force enumeration of every first-in-first-out schedule on tiny traces.
+P5  special cases that reduce to library routines (numpy.sort, numpy.unique) or closed forms.
+"""
+import itertools
+import json
+import os
+import struct
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_10359_amd import traces
+
+U64 = (1 << 64) - 1
+
+
+def make_records(items):
+    """items: list of (name_id, grid3, block3, shmem, start, end)."""
+    rec = np.zeros(len(items), dtype=traces.LAUNCH_DTYPE)
+    for i, (name, grid, block, shmem, start, end) in enumerate(items):
+        rec[i]["name_id"] = name
+        rec[i]["grid"] = grid
+        rec[i]["block"] = block
+        rec[i]["shmem"] = shmem
+        rec[i]["start_ns"] = start
+        rec[i]["end_ns"] = end
+    return rec
+
+
+def stats_tuple(s):
+    return [int(s["count"]), int(s["sum"]), int(s["min"]), int(s["max"]), int(s["p50"]), int(s["p95"])]
+
+
+# ---------------------------------------------------------------- P0
+@pytest.mark.parametrize("data,expected", [
+    (b"", 0xcbf29ce484222325),          # offset basis
+    (b"a", 0xaf63dc4c8601ec8c),         # published FNV-1a 64 test vectors
+    (b"foobar", 0x85944171f73967e8),
+])
+def test_p0_fnv1a64_published_vectors(data, expected):
+    assert oracle.kernel_id(data) == expected
+
+
+def test_p0_id_covers_exactly_the_identity_bytes():
+    base = make_records([(5, (7, 8, 9), (10, 11, 12), 13, 100, 200)])
+    ids0, _, _ = oracle.profile(base, np.array([0, 1], dtype=np.uint64))
+    raw = base.tobytes()
+    assert int(ids0[0]) == oracle.kernel_id(raw[:32])
+    # timestamps and reserved bytes never enter the ID
+    other = base.copy()
+    other["start_ns"] = 1
+    other["end_ns"] = 9
+    other["reserved"] = 0xAB
+    ids1, _, _ = oracle.profile(other, np.array([0, 1], dtype=np.uint64))
+    assert ids1[0] == ids0[0]
+    # every one of the eight identity fields does
+    seen = {int(ids0[0])}
+    for field, idx in [("name_id", None), ("grid", 0), ("grid", 1), ("grid", 2), ("block", 0),
+                       ("block", 1), ("block", 2), ("shmem", None)]:
+        m = base.copy()
+        if idx is None:
+            m[field] += 1
+        else:
+            m[field][0, idx] += 1
+        ids2, _, _ = oracle.profile(m, np.array([0, 1], dtype=np.uint64))
+        seen.add(int(ids2[0]))
+    assert len(seen) == 9
+
+
+# ---------------------------------------------------------------- P1
+@pytest.fixture(scope="module")
+def p1(golden_dir):
+    with open(os.path.join(golden_dir, "p1_hand_worked.json")) as f:
+        g = json.load(f)
+    k = g["kernels"]
+
+    def rec_of(trace):
+        return make_records([(k[n]["name_id"], k[n]["grid"], k[n]["block"], k[n]["shmem"], s, e)
+                             for n, s, e in trace])
+    rec = np.concatenate([rec_of(g["hp_trace"]), rec_of(g["lp_trace"])])
+    off = np.array([0, len(g["hp_trace"]), len(g["hp_trace"]) + len(g["lp_trace"])], dtype=np.uint64)
+    return g, rec, off
+
+
+def test_p1_ids_and_rows(p1):
+    g, rec, off = p1
+    ids, rows, tro = oracle.profile(rec, off)
+    names = [n for n, _, _ in g["hp_trace"]] + [n for n, _, _ in g["lp_trace"]]
+    for i, n in enumerate(names):
+        assert int(ids[i]) == int(g["kernels"][n]["id"], 16)
+    assert list(tro) == [0, 3, 5]
+    assert len(rows) == 5
+    for r, name in zip(rows, g["rows_in_order"]):
+        exp = g["rows"][name]
+        assert int(r["kernel_id"]) == int(g["kernels"][name]["id"], 16)
+        assert int(r["task"]) == exp["task"]
+        assert stats_tuple(r["exec"]) == exp["exec"]
+        assert stats_tuple(r["gap"]) == exp["gap"]
+    # the paper's means: SK_A = 21000, SG_C = 310000 / 3
+    a = rows[1]
+    c = rows[2]
+    assert Fraction(int(a["exec"]["sum"]), int(a["exec"]["count"])) == g["paper_means"]["SK_A"]
+    assert int(c["gap"]["sum"]) == g["paper_means"]["SG_C_times_3"] and int(c["gap"]["count"]) == 3
+    assert sum(int(r["exec"]["count"]) for r in rows[:3]) == 12
+    assert sum(int(r["gap"]["count"]) for r in rows[:3]) == 11
+
+
+@pytest.mark.parametrize("case", [0, 1])
+def test_p1_gapfill(p1, case):
+    g, rec, off = p1
+    exp = g["gapfill"][case]
+    ids, rows, tro = oracle.profile(rec, off)
+    hp = np.array([0], dtype=np.uint32)
+    lp = np.array([1], dtype=np.uint32)
+    go = traces.gap_offsets(off, hp)
+    assert list(go) == [0, 11]
+    fc, fn, comp, placed, assign, aoff = oracle.gapfill(
+        ids, off, rows, tro, hp, lp, exp["margin_ns"], exp["min_gap_ns"], go, want_assign=True)
+    assert list(fc) == exp["fill_count"]
+    assert list(fn) == exp["filled_ns"]
+    assert int(placed[0]) == exp["lp_placed"]
+    assert int(comp[0]) == exp["lp_completion_ns"]
+    assert list(assign) == exp["assign"]
+
+
+# ---------------------------------------------------------------- P2
+def test_p2_paper_closed_forms_sk_sg():
+    cfg = traces.config(0, launches=240)
+    rec, off = traces.build(cfg)
+    ids, rows, tro = oracle.profile(rec, off)
+    for t in range(cfg.n_tasks):
+        lo, hi = int(off[t]), int(off[t + 1])
+        tid = [int(x) for x in ids[lo:hi]]
+        K = [int(rec["end_ns"][i] - rec["start_ns"][i]) for i in range(lo, hi)]
+        G = [max(0, int(rec["start_ns"][i + 1] - rec["end_ns"][i])) for i in range(lo, hi - 1)]
+        s_uid = sorted(set(tid))
+        assert [int(r["kernel_id"]) for r in rows[int(tro[t]):int(tro[t + 1])]] == s_uid
+        for j, r in zip(s_uid, rows[int(tro[t]):int(tro[t + 1])]):
+            num = sum(K[i] * (1 if tid[i] == j else 0) for i in range(len(K)))
+            den = sum(1 * (1 if tid[i] == j else 0) for i in range(len(K)))
+            assert Fraction(int(r["exec"]["sum"]), int(r["exec"]["count"])) == Fraction(num, den)
+            numg = sum(G[i] * (1 if tid[i] == j else 0) for i in range(len(G)))
+            deng = sum(1 * (1 if tid[i] == j else 0) for i in range(len(G)))
+            assert int(r["gap"]["count"]) == deng and int(r["gap"]["sum"]) == numg
+
+
+# ---------------------------------------------------------------- P3
+def small_configs():
+    return [
+        traces.config(0),
+        traces.config(1, n_tasks=4, launches=3000),
+        traces.config(2, n_tasks=2, launches=20000),
+        traces.config(3, n_tasks=3, launches=10000),
+        traces.config(4, n_tasks=6, hp_launches=512, lp_launches=2048),
+    ]
+
+
+@pytest.mark.parametrize("cfg", small_configs(), ids=lambda c: c.name)
+def test_p3_profile_invariants(cfg):
+    rec, off = traces.build(cfg)
+    ids, rows, tro = oracle.profile(rec, off)
+    n = rec.shape[0]
+    nonempty = int(np.count_nonzero(off[1:] > off[:-1]))
+    assert int(rows["exec"]["count"].sum()) == n
+    assert int(rows["gap"]["count"].sum()) == n - nonempty
+    for blk in ("exec", "gap"):
+        s = rows[blk]
+        has = s["count"] > 0
+        assert np.all(s["min"][has] <= s["p50"][has])
+        assert np.all(s["p50"][has] <= s["p95"][has])
+        assert np.all(s["p95"][has] <= s["max"][has])
+        assert np.all(s["min"][has] >= 0)
+        cnt = s["count"][has].astype(object)
+        assert all(c * int(mn) <= int(sm) <= c * int(mx) for c, mn, sm, mx in
+                   zip(cnt, s["min"][has], s["sum"][has], s["max"][has]))
+        z = ~has
+        for f in ("sum", "min", "max", "p50", "p95"):
+            assert np.all(s[f][z] == 0)
+    # rows strictly increasing in (task, id)
+    key = list(zip(rows["task"].tolist(), rows["kernel_id"].tolist()))
+    assert all(a < b for a, b in zip(key, key[1:]))
+    for t in range(cfg.n_tasks):
+        assert np.all(rows["task"][int(tro[t]):int(tro[t + 1])] == t)
+
+
+def test_p3_exec_stats_do_not_depend_on_launch_order():
+    # Section 3.2: the Kernel ID is independent of the kernel's position within the task.
+    cfg = traces.config(1, n_tasks=2, launches=2000)
+    rec, off = traces.build(cfg)
+    _, rows, _ = oracle.profile(rec, off)
+    rng = np.random.default_rng(7)
+    perm = rec.copy()
+    for t in range(cfg.n_tasks):
+        lo, hi = int(off[t]), int(off[t + 1])
+        perm[lo:hi] = rec[lo:hi][rng.permutation(hi - lo)]
+    _, rows2, _ = oracle.profile(perm, off)
+    assert np.array_equal(rows["kernel_id"], rows2["kernel_id"])
+    assert np.array_equal(rows["exec"], rows2["exec"])
+
+
+def test_p3_negative_idle_time_clamps_to_zero():
+    rec = make_records([(1, (1, 1, 1), (1, 1, 1), 0, 0, 100),     # overlaps with the next
+                        (1, (1, 1, 1), (1, 1, 1), 0, 50, 150),
+                        (1, (1, 1, 1), (1, 1, 1), 0, 170, 180)])
+    _, rows, _ = oracle.profile(rec, np.array([0, 3], dtype=np.uint64))
+    assert stats_tuple(rows[0]["gap"]) == [2, 20, 0, 20, 0, 20]
+    assert stats_tuple(rows[0]["exec"]) == [3, 210, 10, 100, 100, 100]
+
+
+@pytest.mark.parametrize("cfg", [small_configs()[0], small_configs()[1], small_configs()[4]],
+                         ids=lambda c: c.name)
+@pytest.mark.parametrize("min_gap", [0, 100000])
+def test_p3_gapfill_invariants(cfg, min_gap):
+    rec, off = traces.build(cfg)
+    ids, rows, tro = oracle.profile(rec, off)
+    hp, lp = traces.scenarios(cfg)
+    go = traces.gap_offsets(off, hp)
+    margin = cfg.margin_ns
+    fc, fn, comp, placed, assign, aoff = oracle.gapfill(ids, off, rows, tro, hp, lp, margin, min_gap, go,
+                                                        want_assign=True)
+    for s in range(hp.shape[0]):
+        h0, h1 = int(off[hp[s]]), int(off[hp[s] + 1])
+        l0, l1 = int(off[lp[s]]), int(off[lp[s] + 1])
+        hr = rows[int(tro[hp[s]]):int(tro[hp[s] + 1])]
+        lr = rows[int(tro[lp[s]]):int(tro[lp[s] + 1])]
+        gp50 = dict(zip(hr["kernel_id"].tolist(), hr["gap"]["p50"].tolist()))
+        ep50 = dict(zip(hr["kernel_id"].tolist(), hr["exec"]["p50"].tolist()))
+        dp50 = dict(zip(lr["kernel_id"].tolist(), lr["exec"]["p50"].tolist()))
+        G = np.array([gp50[i] for i in ids[h0:h1 - 1].tolist()], dtype=np.int64)
+        D = np.array([dp50[i] for i in ids[l0:l1].tolist()], dtype=np.int64)
+        f = fn[int(go[s]):int(go[s + 1])]
+        c = fc[int(go[s]):int(go[s + 1])]
+        a = assign[int(aoff[s]):int(aoff[s + 1])]
+        assert np.all(f >= 0)
+        assert np.all(f <= np.maximum(0, G - margin)) and np.all(f <= G)
+        assert np.all(f[G < min_gap] == 0) and np.all(c[G < min_gap] == 0)
+        assert int(c.sum()) == int(placed[s]) <= l1 - l0
+        # first-in-first-out: the gap index is non-decreasing along the low-priority queue
+        assert np.all(np.diff(a.astype(np.int64)) >= 0)
+        p = int(placed[s])
+        assert np.all(a[:p] != 0xffffffff) and np.all(a[p:] == 0xffffffff)
+        assert np.array_equal(np.bincount(a[:p], minlength=c.shape[0])[:c.shape[0]], c)
+        assert np.array_equal(np.bincount(a[:p], weights=D[:p], minlength=f.shape[0]).astype(np.int64), f)
+        # completion can never precede doing all the low-priority work back to back
+        assert int(comp[s]) >= int(D.sum())
+        t_end = sum(ep50[i] for i in ids[h0:h1].tolist()) + int(G.sum())
+        if p < l1 - l0:
+            assert int(comp[s]) == t_end + int(D[p:].sum())
+        else:
+            assert int(comp[s]) <= t_end
+
+
+# ---------------------------------------------------------------- P4
+def tiny_scenario(rng, H, L, durations, gaps):
+    """One HP task and one LP task whose every kernel ID occurs once, so p50 == the sample."""
+    items = []
+    t = 0
+    for i in range(H):
+        e = int(rng.choice([1000, 3000]))
+        g = int(rng.choice(gaps))
+        items.append((100 + i, (1, 1, 1), (64, 1, 1), 0, t, t + e))
+        t += e + g
+    hp_n = len(items)
+    t = 0
+    for j in range(L):
+        d = int(rng.choice(durations))
+        items.append((200 + j, (2, 1, 1), (64, 1, 1), 0, t, t + d))
+        t += d + 10
+    rec = make_records(items)
+    off = np.array([0, hp_n, hp_n + L], dtype=np.uint64)
+    return rec, off
+
+
+def brute_force_schedule(E, G, D, margin, min_gap):
+    """Component-wise earliest feasible first-in-first-out assignment, by full enumeration."""
+    H, L = len(E), len(D)
+    n_gaps = max(H - 1, 0)
+    TAIL = n_gaps  # "after the high-priority trace"
+    budget = [(G[i] - margin) if (G[i] >= min_gap and G[i] >= margin) else None for i in range(n_gaps)]
+    feasible = []
+    for a in itertools.combinations_with_replacement(range(n_gaps + 1), L):  # non-decreasing tuples
+        load = [0] * n_gaps
+        cnt = [0] * n_gaps
+        ok = True
+        for j, g in enumerate(a):
+            if g == TAIL:
+                continue
+            if budget[g] is None:
+                ok = False
+                break
+            load[g] += D[j]
+            cnt[g] += 1
+        if ok and all(budget[g] is None or load[g] <= budget[g] for g in range(n_gaps)):
+            feasible.append(a)
+    assert feasible  # everything in the tail is always feasible
+    best = tuple(min(a[j] for a in feasible) for j in range(L))
+    assert best in feasible
+    # the earliest schedule also places the most kernels within every prefix of gaps
+    for g in range(n_gaps + 1):
+        most = max(sum(1 for x in a if x < g) for a in feasible)
+        assert sum(1 for x in best if x < g) == most
+    fill = [sum(1 for x in best if x == g) for g in range(n_gaps)]
+    filled = [sum(D[j] for j, x in enumerate(best) if x == g) for g in range(n_gaps)]
+    placed = sum(fill)
+    # timeline: HP kernel i ends (gap i opens) at sum(E[:i+1]) + sum(G[:i])
+    opens = [sum(E[:i + 1]) + sum(G[:i]) for i in range(H)]
+    if L == 0:
+        completion = 0
+    elif placed == L:
+        last = best[-1]
+        completion = opens[last] + filled[last]
+    else:
+        t_end = opens[-1] if H else 0
+        completion = t_end + sum(D[placed:])
+    return best, fill, filled, placed, completion
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_p4_bruteforce_tiny(seed):
+    rng = np.random.default_rng(1000 + seed)
+    H = int(rng.integers(1, 7))
+    L = int(rng.integers(0, 7))
+    margin = int(rng.choice([0, 500]))
+    min_gap = int(rng.choice([0, 2500]))
+    durations = [0, 500, 1000, 1500, 2000, 4000]
+    gaps = [0, 400, 500, 1500, 2500, 3000, 5000, 9000]
+    rec, off = tiny_scenario(rng, H, L, durations, gaps)
+    ids, rows, tro = oracle.profile(rec, off)
+    E = [int(rec["end_ns"][i] - rec["start_ns"][i]) for i in range(H)]
+    G = [int(rec["start_ns"][i + 1] - rec["end_ns"][i]) for i in range(H - 1)]
+    D = [int(rec["end_ns"][H + j] - rec["start_ns"][H + j]) for j in range(L)]
+    hp = np.array([0], dtype=np.uint32)
+    lp = np.array([1], dtype=np.uint32)
+    go = traces.gap_offsets(off, hp)
+    fc, fn, comp, placed, assign, _ = oracle.gapfill(ids, off, rows, tro, hp, lp, margin, min_gap, go,
+                                                     want_assign=True)
+    best, fill, filled, n_placed, completion = brute_force_schedule(E, G, D, margin, min_gap)
+    tail = max(H - 1, 0)
+    got = tuple(tail if x == 0xffffffff else int(x) for x in assign)
+    assert got == best
+    assert list(fc) == fill
+    assert list(fn) == filled
+    assert int(placed[0]) == n_placed
+    assert int(comp[0]) == completion
+
+
+# ---------------------------------------------------------------- P5
+def numpy_stats(v):
+    v = np.sort(np.asarray(v, dtype=np.int64))
+    n = v.shape[0]
+    if n == 0:
+        return [0, 0, 0, 0, 0, 0]
+    r50 = -(-50 * n // 100)
+    r95 = -(-95 * n // 100)
+    return [n, int(v.astype(object).sum()) & U64, int(v[0]), int(v[-1]), int(v[r50 - 1]), int(v[r95 - 1])]
+
+
+def test_p5_nearest_rank_textbook_examples():
+    # worked examples of the nearest-rank definition: ordered list 15 20 35 40 50 -> the 50th
+    # percentile is the 3rd value; 3 6 7 8 8 10 13 15 16 20 -> the 50th percentile is the 5th value
+    for values, p50, p95 in [([15, 20, 35, 40, 50], 35, 50),
+                             ([3, 6, 7, 8, 8, 10, 13, 15, 16, 20], 8, 20),
+                             ([7], 7, 7), ([9, 1], 1, 9),
+                             (list(range(1, 101)), 50, 95), (list(range(1, 102)), 51, 96)]:
+        rng = np.random.default_rng(len(values))
+        order = rng.permutation(len(values))
+        t = 0
+        items = []
+        for k in order:
+            items.append((3, (1, 1, 1), (1, 1, 1), 0, t, t + values[k]))
+            t += values[k] + 5
+        _, rows, _ = oracle.profile(make_records(items), np.array([0, len(items)], dtype=np.uint64))
+        assert len(rows) == 1
+        assert int(rows[0]["exec"]["p50"]) == p50 and int(rows[0]["exec"]["p95"]) == p95
+        assert int(rows[0]["exec"]["min"]) == min(values) and int(rows[0]["exec"]["max"]) == max(values)
+
+
+def test_p5_all_identical_and_all_distinct():
+    n = 257
+    same = make_records([(4, (2, 2, 2), (8, 8, 1), 64, 1000 * i, 1000 * i + 300) for i in range(n)])
+    _, rows, tro = oracle.profile(same, np.array([0, n], dtype=np.uint64))
+    assert len(rows) == 1 and list(tro) == [0, 1]
+    assert stats_tuple(rows[0]["exec"]) == [n, 300 * n, 300, 300, 300, 300]
+    assert stats_tuple(rows[0]["gap"]) == [n - 1, 700 * (n - 1), 700, 700, 700, 700]
+    distinct = make_records([(i, (1, 1, 1), (1, 1, 1), 0, 10 * i, 10 * i + 1 + i % 7) for i in range(n)])
+    ids, rows, _ = oracle.profile(distinct, np.array([0, n], dtype=np.uint64))
+    assert len(rows) == n and np.all(rows["exec"]["count"] == 1)
+    assert np.array_equal(rows["kernel_id"], np.sort(ids))
+    assert int(rows["gap"]["count"].sum()) == n - 1
+
+
+@pytest.mark.parametrize("cfg", small_configs(), ids=lambda c: c.name)
+def test_p5_groupby_and_order_statistics_match_numpy(cfg):
+    rec, off = traces.build(cfg)
+    ids, rows, tro = oracle.profile(rec, off)
+    ex = rec["end_ns"] - rec["start_ns"]
+    for t in range(cfg.n_tasks):
+        lo, hi = int(off[t]), int(off[t + 1])
+        uid, inv, cnt = np.unique(ids[lo:hi], return_inverse=True, return_counts=True)
+        r = rows[int(tro[t]):int(tro[t + 1])]
+        assert np.array_equal(r["kernel_id"], uid)
+        assert np.array_equal(r["exec"]["count"], cnt.astype(np.uint64))
+        gap = np.maximum(0, rec["start_ns"][lo + 1:hi] - rec["end_ns"][lo:hi - 1])
+        pick = np.random.default_rng(t).choice(len(uid), size=min(len(uid), 12), replace=False)
+        for k in pick:
+            assert stats_tuple(r[k]["exec"]) == numpy_stats(ex[lo:hi][inv == k])
+            assert stats_tuple(r[k]["gap"]) == numpy_stats(gap[inv[:-1] == k])
+
+
+def test_p5_sum_wraps_modulo_2_64():
+    big = (1 << 62) + 12345
+    items = []
+    t = -(1 << 62)
+    for i in range(5):
+        items.append((1, (1, 1, 1), (1, 1, 1), 0, t, t + big))
+        t = t + big  # back to back; start of next equals end
+        t -= big     # rewind so that timestamps stay inside int64 (overlap -> gap clamps to 0)
+    _, rows, _ = oracle.profile(make_records(items), np.array([0, 5], dtype=np.uint64))
+    assert int(rows[0]["exec"]["sum"]) == (5 * big) & U64
+    assert int(rows[0]["exec"]["p50"]) == big
+
+
+def test_p5_gapfill_equal_durations_closed_form():
+    d = 700
+    rng = np.random.default_rng(5)
+    H, L = 40, 90
+    items = []
+    t = 0
+    gaps = rng.integers(0, 6000, H)
+    for i in range(H):
+        items.append((100 + i, (1, 1, 1), (64, 1, 1), 0, t, t + 1000))
+        t += 1000 + int(gaps[i])
+    t = 0
+    for j in range(L):
+        items.append((7, (1, 1, 1), (32, 1, 1), 0, t, t + d))
+        t += d
+    rec = make_records(items)
+    off = np.array([0, H, H + L], dtype=np.uint64)
+    ids, rows, tro = oracle.profile(rec, off)
+    hp = np.array([0], dtype=np.uint32)
+    lp = np.array([1], dtype=np.uint32)
+    margin, min_gap = 500, 1000
+    fc, fn, comp, placed = oracle.gapfill(ids, off, rows, tro, hp, lp, margin, min_gap,
+                                          traces.gap_offsets(off, hp))
+    remaining = L
+    for i in range(H - 1):
+        g = int(gaps[i])
+        exp = 0 if (g < min_gap or g < margin) else min((g - margin) // d, remaining)
+        remaining -= exp
+        assert int(fc[i]) == exp and int(fn[i]) == exp * d
+    assert int(placed[0]) == L - remaining
+
+
+# ---------------------------------------------------------------- error statuses
+def test_oracle_error_statuses():
+    rec = make_records([(1, (1, 1, 1), (1, 1, 1), 0, 10, 5)])
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.profile(rec, np.array([0, 1], dtype=np.uint64))
+    assert e.value.status == oracle.BAD_RECORD
+    ok = make_records([(1, (1, 1, 1), (1, 1, 1), 0, 0, 5), (2, (1, 1, 1), (1, 1, 1), 0, 6, 9)])
+    for bad in ([0, 3], [1, 2], [0, 2, 1, 2]):
+        with pytest.raises(oracle.OracleError) as e:
+            oracle.profile(ok, np.array(bad, dtype=np.uint64))
+        assert e.value.status == oracle.INVALID_ARG
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.profile(ok, np.array([0, 2], dtype=np.uint64), row_capacity=1)
+    assert e.value.status == oracle.ROW_CAPACITY and e.value.n_rows == 2
+    ids, rows, tro = oracle.profile(ok, np.array([0, 1, 2], dtype=np.uint64))
+    hp = np.array([0], dtype=np.uint32)
+    lp = np.array([1], dtype=np.uint32)
+    off = np.array([0, 1, 2], dtype=np.uint64)
+    wrong = ids.copy()
+    wrong[1] ^= np.uint64(1)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.gapfill(wrong, off, rows, tro, hp, lp, 0, 0, traces.gap_offsets(off, hp))
+    assert e.value.status == oracle.UNKNOWN_ID
+
+
+def test_empty_inputs():
+    rec = np.zeros(0, dtype=traces.LAUNCH_DTYPE)
+    ids, rows, tro = oracle.profile(rec, np.array([0, 0, 0], dtype=np.uint64))
+    assert len(ids) == 0 and len(rows) == 0 and list(tro) == [0, 0, 0]
+    # empty tasks between non-empty ones; scenarios with H <= 1 and L == 0
+    one = make_records([(1, (1, 1, 1), (1, 1, 1), 0, 0, 700), (2, (1, 1, 1), (1, 1, 1), 0, 0, 300),
+                        (2, (1, 1, 1), (1, 1, 1), 0, 400, 800)])
+    off = np.array([0, 0, 1, 1, 3, 3], dtype=np.uint64)
+    ids, rows, tro = oracle.profile(one, off)
+    assert list(tro) == [0, 0, 1, 1, 2, 2]
+    assert stats_tuple(rows[0]["gap"]) == [0, 0, 0, 0, 0, 0]
+    hp = np.array([1, 0, 1, 3], dtype=np.uint32)
+    lp = np.array([3, 3, 0, 0], dtype=np.uint32)
+    go = traces.gap_offsets(off, hp)
+    assert list(go) == [0, 0, 0, 0, 1]
+    fc, fn, comp, placed = oracle.gapfill(ids, off, rows, tro, hp, lp, 0, 0, go)
+    d = int(rows[1]["exec"]["p50"])
+    assert d == 300
+    assert int(comp[0]) == 700 + 2 * d and int(placed[0]) == 0   # H == 1: no gap, LP runs afterwards
+    assert int(comp[1]) == 2 * d                                   # H == 0
+    assert int(comp[2]) == 0 and int(placed[2]) == 0               # L == 0
+    assert int(comp[3]) == 0 and list(fc) == [0]                   # L == 0 with one (unused) gap
