@@ -1,0 +1,165 @@
+/*
+ * fikit.h - C ABI of the FIKIT trace-profiling and gap-fill evaluation library (gfx950).
+ *
+ * The library evaluates, offline and in bulk, two steps of FIKIT (arXiv 2311.10359):
+ *
+ *   fikit_profile  - the statistical output of the measurement phase (Section 3.2, "Data
+ *                    acquisition and statistical output during the measurement phase"): every
+ *                    intercepted launch is given its Kernel ID (Section 3.2, "Identifying each
+ *                    kernel"), its execution time K and the idle time G up to the next launch
+ *                    of the same task are measured from the recorded start/end times, and per
+ *                    task and unique ID (the set S_UID) the samples are reduced.  The paper
+ *                    keeps the means SK_j and SG_j; a row here carries count and sum (mean =
+ *                    sum / count) and also min, max and the nearest-rank 50th and 95th
+ *                    percentile of the same samples.
+ *
+ *   fikit_gapfill  - Algorithm 1 (FIKIT procedure) driven by that table, for one
+ *                    high-priority and one low-priority task per scenario: after each
+ *                    high-priority kernel the predicted idle time of its ID is looked up, small
+ *                    gaps are skipped, and the low-priority task's next kernel is issued for as
+ *                    long as its predicted duration does not exceed what is left of the gap
+ *                    (Algorithm 2 with a single waiting request is first-in-first-out).
+ *
+ * Conventions
+ *   - d_* arguments are device pointers, h_* are host pointers.  The caller owns every buffer,
+ *     including the workspace; the library allocates no device memory and keeps no state
+ *     between calls.  Inputs are left untouched.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  Both calls synchronise that stream before they return, so outputs and the
+ *     returned status are final on return.
+ *   - Return value: FIKIT_OK or a negative fikit_status.  Nothing aborts or throws.  After an
+ *     error the contents of the output buffers are unspecified.
+ *   - Everything is integer arithmetic (nanoseconds, counts); results are exact.
+ *   - Limits: n_records, n_ids < 2^32 - 2^24.  Timestamps must be such that end - start and
+ *     next start - end fit in int64, and a task's predicted timeline (sum of p50 values over
+ *     its launches) fits in int64.
+ */
+#ifndef FIKIT_H
+#define FIKIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* One intercepted kernel launch.  64 bytes, little endian, 16-byte aligned.
+ * Bytes 0..31 are the identity of the kernel (what the Kernel ID is made of); bytes 48..63
+ * are ignored. */
+typedef struct fikit_launch {
+  uint32_t name_id;      /*  0  interned kernel function name          */
+  uint32_t grid[3];      /*  4  grid dimensions x, y, z                */
+  uint32_t block[3];     /* 16  block dimensions x, y, z               */
+  uint32_t shmem;        /* 28  dynamic shared-memory bytes            */
+  int64_t start_ns;      /* 32  device time at which the kernel began  */
+  int64_t end_ns;        /* 40  device time at which the kernel ended  */
+  uint8_t reserved[16];  /* 48  ignored                                */
+} fikit_launch;
+
+/* Statistics of one sample set.  count == 0 implies every other field is 0. */
+typedef struct fikit_stats {
+  uint64_t count; /* number of samples                                            */
+  uint64_t sum;   /* sum of samples modulo 2^64                                   */
+  int64_t min;
+  int64_t max;
+  int64_t p50;    /* nearest rank: the ceil(50*count/100)-th smallest sample     */
+  int64_t p95;    /* nearest rank: the ceil(95*count/100)-th smallest sample     */
+} fikit_stats;
+
+/* One row of a task's profile: a unique Kernel ID with the statistics of its execution
+ * times (exec) and of the idle times that followed its launches (gap).  128 bytes. */
+typedef struct fikit_row {
+  uint64_t kernel_id;
+  uint32_t task;
+  uint32_t reserved0;
+  fikit_stats exec; /* offset 16 */
+  fikit_stats gap;  /* offset 64 */
+  uint8_t reserved1[16];
+} fikit_row;
+
+typedef enum fikit_status {
+  FIKIT_OK = 0,
+  FIKIT_INVALID_ARG = -1,         /* NULL or misaligned pointer, offsets not monotone or not ending
+                                     at the element count, task index out of range, size limit  */
+  FIKIT_WORKSPACE_TOO_SMALL = -2,
+  FIKIT_ROW_CAPACITY = -3,        /* more rows than row_capacity; *h_n_rows holds the need       */
+  FIKIT_BAD_RECORD = -4,          /* some record has end_ns < start_ns                          */
+  FIKIT_UNKNOWN_ID = -5,          /* a scenario launch whose ID is absent from its task's rows  */
+  FIKIT_HIP_ERROR = -6            /* the HIP runtime reported an error                          */
+} fikit_status;
+
+/* Bytes of device workspace fikit_profile needs for these sizes (0 on size overflow). */
+size_t fikit_profile_workspace_bytes(uint64_t n_records, uint32_t n_tasks);
+
+/*
+ * Measurement-phase statistics (Section 3.2).
+ *
+ *   d_records          [n_records] launches; task t owns records
+ *                      d_task_offsets[t] .. d_task_offsets[t+1]-1, in launch order.
+ *   d_task_offsets     [n_tasks+1] uint64, non-decreasing, first 0, last n_records.
+ *   d_ids_out          [n_records] receives every launch's Kernel ID in launch order: the
+ *                      64-bit FNV-1a hash of record bytes 0..31.  May be NULL.
+ *   d_rows_out         [row_capacity] receives the rows, ordered by task, then by kernel_id as
+ *                      an unsigned number.  Execution time of a launch = end_ns - start_ns; the
+ *                      idle time after a launch = max(0, next start_ns - end_ns), where "next"
+ *                      is the following launch of the same task; a task's last launch has none.
+ *   d_task_row_offsets [n_tasks+1] receives, per task, where its rows start (last = row count).
+ *   h_n_rows           host; receives the number of rows (also on FIKIT_ROW_CAPACITY).
+ *   d_workspace        256-byte aligned, at least fikit_profile_workspace_bytes(...) bytes.
+ *
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, ROW_CAPACITY, BAD_RECORD, HIP_ERROR.
+ * n_records == 0 yields zero rows and FIKIT_OK.
+ */
+int fikit_profile(const fikit_launch* d_records, uint64_t n_records,
+                  const uint64_t* d_task_offsets, uint32_t n_tasks, uint64_t* d_ids_out,
+                  fikit_row* d_rows_out, uint64_t row_capacity, uint64_t* d_task_row_offsets,
+                  uint64_t* h_n_rows, void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+typedef struct fikit_gapfill_params {
+  int64_t margin_ns;  /* reserved at the end of every gap; a gap shorter than this is skipped */
+  int64_t min_gap_ns; /* gaps predicted shorter than this are skipped (Algorithm 1)           */
+} fikit_gapfill_params;
+
+/* Bytes of device workspace fikit_gapfill needs for these sizes (0 on size overflow). */
+size_t fikit_gapfill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios);
+
+/*
+ * Gap filling (Algorithm 1, with Algorithm 2 reduced to one waiting request).
+ *
+ *   d_ids, d_task_offsets, n_tasks   Kernel IDs of every launch of every task, laid out as in
+ *                      fikit_profile (its d_ids_out and d_task_offsets).
+ *   d_rows, d_task_row_offsets       the profile of those tasks (fikit_profile's outputs).
+ *   d_hp_task, d_lp_task [n_scenarios] the high- and the low-priority task of each scenario.
+ *   h_params           host pointer.  margin_ns, min_gap_ns >= 0.
+ *   d_gap_offsets      [n_scenarios+1] where each scenario's per-gap outputs start; scenario s
+ *                      with H launches in its high-priority trace owns max(H-1, 0) slots.
+ *   d_fill_count, d_filled_ns  per gap: low-priority kernels issued into it, and the sum of
+ *                      their predicted durations.
+ *   d_lp_completion_ns [n_scenarios] predicted time at which the low-priority task ends, on a
+ *                      timeline that starts at 0 with the first high-priority kernel and on
+ *                      which high-priority kernels are never delayed; low-priority kernels
+ *                      that found no gap run back to back after the last high-priority kernel.
+ *   d_lp_placed        [n_scenarios] number of low-priority kernels issued into gaps.
+ *
+ * Predicted execution time of a launch = exec.p50 of its ID's row; predicted idle time after a
+ * high-priority launch = gap.p50 of its ID's row.  A gap is skipped if its prediction is below
+ * min_gap_ns or below margin_ns; otherwise gap - margin_ns nanoseconds may be filled.
+ *
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNKNOWN_ID, HIP_ERROR.
+ */
+int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks,
+                  const fikit_row* d_rows, const uint64_t* d_task_row_offsets,
+                  const uint32_t* d_hp_task, const uint32_t* d_lp_task, uint64_t n_scenarios,
+                  const fikit_gapfill_params* h_params, const uint64_t* d_gap_offsets,
+                  uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_lp_completion_ns,
+                  uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes,
+                  void* hip_stream);
+
+const char* fikit_status_string(int status);
+int fikit_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FIKIT_H */

@@ -1,0 +1,218 @@
+"""ctypes binding of the C-ABI library (`include/fikit.h`).
+
+Argument marshalling only: tensors in, tensors out; every step of the path runs in the library's
+HIP kernels.  PyTorch provides device memory and the stream.  There is no fallback: if the
+library is missing or cannot be loaded, importing the functions fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+FIKIT_OK = 0
+FIKIT_INVALID_ARG = -1
+FIKIT_WORKSPACE_TOO_SMALL = -2
+FIKIT_ROW_CAPACITY = -3
+FIKIT_BAD_RECORD = -4
+FIKIT_UNKNOWN_ID = -5
+FIKIT_HIP_ERROR = -6
+
+EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
+           "fikit_gapfill", "fikit_status_string", "fikit_version")
+
+# Layout of a profile row as seen from numpy (128 bytes; see fikit_row in fikit.h).
+STATS_DTYPE = np.dtype([("count", "<u8"), ("sum", "<u8"), ("min", "<i8"), ("max", "<i8"),
+                        ("p50", "<i8"), ("p95", "<i8")])
+ROW_DTYPE = np.dtype([("kernel_id", "<u8"), ("task", "<u4"), ("reserved0", "<u4"),
+                      ("exec", STATS_DTYPE), ("gap", STATS_DTYPE), ("reserved1", "u1", (16,))])
+ROW_BYTES = 128
+LAUNCH_BYTES = 64
+
+
+class FikitError(RuntimeError):
+    def __init__(self, status: int, what: str, n_rows: Optional[int] = None):
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+        self.status = status
+        self.n_rows = n_rows
+
+
+class _GapfillParams(ctypes.Structure):
+    _fields_ = [("margin_ns", ctypes.c_int64), ("min_gap_ns", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load() -> ctypes.CDLL:
+    """Loads the built library (building it first only if no library file exists)."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            _build.build_library()
+        lib = ctypes.CDLL(path)
+        vp, u64, u32, sz = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_size_t
+        lib.fikit_profile_workspace_bytes.restype = sz
+        lib.fikit_profile_workspace_bytes.argtypes = [u64, u32]
+        lib.fikit_profile.restype = ctypes.c_int
+        lib.fikit_profile.argtypes = [vp, u64, vp, u32, vp, vp, u64, vp, ctypes.POINTER(u64), vp, sz, vp]
+        lib.fikit_gapfill_workspace_bytes.restype = sz
+        lib.fikit_gapfill_workspace_bytes.argtypes = [u64, u32, u64]
+        lib.fikit_gapfill.restype = ctypes.c_int
+        lib.fikit_gapfill.argtypes = [vp, vp, u32, vp, vp, vp, vp, u64, ctypes.POINTER(_GapfillParams), vp,
+                                      vp, vp, vp, vp, vp, sz, vp]
+        lib.fikit_status_string.restype = ctypes.c_char_p
+        lib.fikit_status_string.argtypes = [ctypes.c_int]
+        lib.fikit_version.restype = ctypes.c_int
+        lib.fikit_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().fikit_status_string(status).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def fikit_profile_workspace_bytes(n_records: int, n_tasks: int) -> int:
+    return int(load().fikit_profile_workspace_bytes(n_records, n_tasks))
+
+
+def fikit_gapfill_workspace_bytes(n_ids: int, n_tasks: int, n_scenarios: int) -> int:
+    return int(load().fikit_gapfill_workspace_bytes(n_ids, n_tasks, n_scenarios))
+
+
+def workspace(nbytes: int, device) -> torch.Tensor:
+    """A device buffer of at least nbytes (torch allocations are 256-byte aligned or better)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+class Profile(NamedTuple):
+    ids: torch.Tensor               # int64 view of the uint64 Kernel IDs, launch order
+    rows: torch.Tensor              # uint8 [n_rows, 128]
+    task_row_offsets: torch.Tensor  # int64 [n_tasks + 1]
+    n_rows: int
+
+
+def fikit_profile(records: torch.Tensor, task_offsets: torch.Tensor, *, row_capacity: Optional[int] = None,
+                  ids_out: Optional[torch.Tensor] = None, rows_out: Optional[torch.Tensor] = None,
+                  task_row_offsets_out: Optional[torch.Tensor] = None, workspace_buf: Optional[torch.Tensor] = None,
+                  want_ids: bool = True, stream: Optional[torch.cuda.Stream] = None) -> Profile:
+    """records: uint8 [n, 64] device tensor of launch records; task_offsets: int64 [T+1] device
+    tensor holding the uint64 CSR offsets.  Output tensors are allocated unless given."""
+    lib = load()
+    dev = records.device
+    assert records.dtype == torch.uint8 and records.is_contiguous()
+    n = records.numel() // LAUNCH_BYTES
+    assert records.numel() == n * LAUNCH_BYTES
+    assert task_offsets.dtype == torch.int64 and task_offsets.is_contiguous() and task_offsets.device == dev
+    n_tasks = task_offsets.numel() - 1
+    if row_capacity is None:
+        row_capacity = rows_out.shape[0] if rows_out is not None else n
+    if ids_out is None and want_ids:
+        ids_out = torch.empty(n, dtype=torch.int64, device=dev)
+    if rows_out is None:
+        rows_out = torch.empty((row_capacity, ROW_BYTES), dtype=torch.uint8, device=dev)
+    if task_row_offsets_out is None:
+        task_row_offsets_out = torch.empty(n_tasks + 1, dtype=torch.int64, device=dev)
+    need = fikit_profile_workspace_bytes(n, n_tasks)
+    if workspace_buf is None:
+        workspace_buf = workspace(need, dev)
+    n_rows = ctypes.c_uint64(0)
+    with torch.cuda.device(dev):
+        st = lib.fikit_profile(_ptr(records), n, _ptr(task_offsets), n_tasks, _ptr(ids_out), _ptr(rows_out),
+                               row_capacity, _ptr(task_row_offsets_out), ctypes.byref(n_rows),
+                               _ptr(workspace_buf), workspace_buf.numel(), _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_profile", int(n_rows.value))
+    return Profile(ids_out, rows_out[: int(n_rows.value)], task_row_offsets_out, int(n_rows.value))
+
+
+class GapFill(NamedTuple):
+    fill_count: torch.Tensor        # int32 view of uint32 [n_gaps]
+    filled_ns: torch.Tensor         # int64 [n_gaps]
+    lp_completion_ns: torch.Tensor  # int64 [S]
+    lp_placed: torch.Tensor         # int64 view of uint64 [S]
+
+
+def fikit_gapfill(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Tensor, task_row_offsets: torch.Tensor,
+                  hp_task: torch.Tensor, lp_task: torch.Tensor, gap_offsets: torch.Tensor, *, margin_ns: int,
+                  min_gap_ns: int, n_gaps: Optional[int] = None, n_ids: Optional[int] = None,
+                  out: Optional[GapFill] = None, workspace_buf: Optional[torch.Tensor] = None,
+                  stream: Optional[torch.cuda.Stream] = None) -> GapFill:
+    """hp_task / lp_task: int32 views of the uint32 task numbers; gap_offsets: int64 [S+1]."""
+    lib = load()
+    dev = task_offsets.device
+    n_tasks = task_offsets.numel() - 1
+    s = hp_task.numel()
+    assert hp_task.dtype == torch.int32 and lp_task.dtype == torch.int32 and lp_task.numel() == s
+    assert gap_offsets.dtype == torch.int64 and gap_offsets.numel() == s + 1
+    for t in (ids, task_offsets, rows, task_row_offsets, hp_task, lp_task, gap_offsets):
+        assert t.is_contiguous() and t.device == dev
+    if n_gaps is None:
+        n_gaps = int(gap_offsets[-1].item()) if s else 0
+    if n_ids is None:
+        n_ids = ids.numel()
+    if out is None:
+        out = GapFill(torch.empty(n_gaps, dtype=torch.int32, device=dev),
+                      torch.empty(n_gaps, dtype=torch.int64, device=dev),
+                      torch.empty(s, dtype=torch.int64, device=dev),
+                      torch.empty(s, dtype=torch.int64, device=dev))
+    need = fikit_gapfill_workspace_bytes(n_ids, n_tasks, s)
+    if workspace_buf is None:
+        workspace_buf = workspace(need, dev)
+    params = _GapfillParams(margin_ns, min_gap_ns)
+    with torch.cuda.device(dev):
+        st = lib.fikit_gapfill(_ptr(ids), _ptr(task_offsets), n_tasks, _ptr(rows), _ptr(task_row_offsets),
+                               _ptr(hp_task), _ptr(lp_task), s, ctypes.byref(params), _ptr(gap_offsets),
+                               _ptr(out.fill_count), _ptr(out.filled_ns), _ptr(out.lp_completion_ns),
+                               _ptr(out.lp_placed), _ptr(workspace_buf), workspace_buf.numel(),
+                               _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_gapfill")
+    return out
+
+
+# ---- helpers to move host arrays in and out (marshalling only) ---------------------------------
+def to_device_records(records: np.ndarray, device) -> torch.Tensor:
+    assert records.dtype.itemsize == LAUNCH_BYTES
+    flat = np.ascontiguousarray(records).view(np.uint8).reshape(-1, LAUNCH_BYTES)
+    return torch.from_numpy(flat).to(device)
+
+
+def to_device_u64(a: np.ndarray, device) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64)).to(device)
+
+
+def to_device_u32(a: np.ndarray, device) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).to(device)
+
+
+def rows_to_numpy(rows: torch.Tensor) -> np.ndarray:
+    return rows.cpu().numpy().reshape(-1).view(ROW_DTYPE).copy()
+
+
+def u64_to_numpy(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint64)
+
+
+def u32_to_numpy(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)

@@ -1,0 +1,131 @@
+// Shared device helpers for the FIKIT kernels (gfx950, 64-wide wavefronts).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fikit.h"
+
+namespace fikit {
+
+constexpr int WAVE = 64;
+
+// Sentinel for "this launch is the last of its task and has no idle time after it".
+// Real idle times are clamped to >= 0, so a negative value cannot be a sample.
+constexpr int64_t GAP_NONE = -1;
+
+// Sticky error bits collected on the device during a call.
+enum : uint32_t {
+  ERR_OFFSETS = 1u << 0,     // task offsets not monotone / wrong end
+  ERR_BAD_RECORD = 1u << 1,  // end_ns < start_ns
+  ERR_UNKNOWN_ID = 1u << 2,  // launch ID without a row in its task's profile
+  ERR_TASK_INDEX = 1u << 3,  // scenario names a task >= n_tasks
+  ERR_GAP_OFFSETS = 1u << 4, // scenario gap offsets do not match the trace lengths
+};
+
+// Control block at the start of the workspace; cleared by k_clear_ctrl at the start of a call.
+struct Ctrl {
+  uint32_t status;        // ERR_* bits
+  uint32_t pad0;
+  uint64_t n_big_tiles;   // tiles of the tasks sorted by the multi-pass path
+  uint64_t n_rows;        // number of (task, ID) rows
+  uint64_t pad1[5];
+};
+static_assert(sizeof(Ctrl) == 64, "control block is 64 bytes");
+
+__device__ __forceinline__ uint32_t lane_id() { return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
+
+// Number of set bits of a 64-bit wave mask in lanes below the calling lane.
+__device__ __forceinline__ uint32_t popc_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+}
+
+__device__ __forceinline__ uint64_t ballot(bool p) { return __ballot(p); }
+
+template <typename T>
+__device__ __forceinline__ T shfl(T v, int src) { return __shfl(v, src, WAVE); }
+
+__device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src) {
+  uint32_t lo = __shfl(static_cast<uint32_t>(v), src, WAVE);
+  uint32_t hi = __shfl(static_cast<uint32_t>(v >> 32), src, WAVE);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int m) {
+  uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), m, WAVE);
+  uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), m, WAVE);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int d) {
+  uint32_t lo = __shfl_up(static_cast<uint32_t>(v), d, WAVE);
+  uint32_t hi = __shfl_up(static_cast<uint32_t>(v >> 32), d, WAVE);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+// Wave-wide reductions over all 64 lanes (result in every lane).
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += shfl_xor_u64(v, m);
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, WAVE);
+  return v;
+}
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) { uint64_t o = shfl_xor_u64(v, m); v = o < v ? o : v; }
+  return v;
+}
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) { uint64_t o = shfl_xor_u64(v, m); v = o > v ? o : v; }
+  return v;
+}
+
+// Inclusive prefix sum across the 64 lanes.
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+  const uint32_t l = lane_id();
+#pragma unroll
+  for (int d = 1; d < WAVE; d <<= 1) { uint32_t o = __shfl_up(v, d, WAVE); if (l >= (uint32_t)d) v += o; }
+  return v;
+}
+__device__ __forceinline__ uint64_t wave_incl_scan_u64(uint64_t v) {
+  const uint32_t l = lane_id();
+#pragma unroll
+  for (int d = 1; d < WAVE; d <<= 1) { uint64_t o = shfl_up_u64(v, d); if (l >= (uint32_t)d) v += o; }
+  return v;
+}
+
+// Exclusive prefix sum across a 256-thread block; returns this thread's exclusive prefix and
+// the block total (in every thread).  `lds` needs 8 words.
+__device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t* lds, uint32_t& total) {
+  const uint32_t lane = lane_id(), w = threadIdx.x >> 6;
+  const uint32_t incl = wave_incl_scan_u32(v);
+  __syncthreads();  // protect lds reuse
+  if (lane == 63) lds[w] = incl;
+  __syncthreads();
+  uint32_t base = 0;
+  const uint32_t t0 = lds[0], t1 = lds[1], t2 = lds[2], t3 = lds[3];
+  if (w > 0) base += t0;
+  if (w > 1) base += t1;
+  if (w > 2) base += t2;
+  total = t0 + t1 + t2 + t3;
+  return base + incl - v;
+}
+
+// Largest t in [0, n_tasks) with off[t] <= pos, skipping empty tasks to the one that owns pos
+// (requires pos < off[n_tasks]).
+__device__ __forceinline__ uint32_t task_of(const uint64_t* __restrict__ off, uint32_t n_tasks, uint64_t pos) {
+  uint32_t lo = 0, hi = n_tasks;  // invariant: off[lo] <= pos < off[hi]
+  while (hi - lo > 1) {
+    uint32_t mid = lo + ((hi - lo) >> 1);
+    if (off[mid] <= pos) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+}  // namespace fikit

@@ -1,0 +1,293 @@
+// C ABI of the FIKIT trace-profiling and gap-fill library: argument checks, workspace
+// carving and kernel sequencing.  All arithmetic of the method runs in the HIP kernels.
+#include "fikit.h"
+
+#include <hip/hip_runtime.h>
+
+#include "common.hip.h"
+#include "gapfill_kernels.hip.h"
+#include "profile_kernels.hip.h"
+#include "sort_kernels.hip.h"
+#include "stats_kernels.hip.h"
+
+namespace {
+
+using namespace fikit;
+
+constexpr uint64_t MAX_ELEMS = (1ull << 32) - (1ull << 24);
+
+#define FIKIT_HIP(expr)                           \
+  do {                                            \
+    if ((expr) != hipSuccess) {                   \
+      (void)hipGetLastError();                    \
+      return FIKIT_HIP_ERROR;                     \
+    }                                             \
+  } while (0)
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+inline uint32_t blocks_for(uint64_t items, uint32_t per_block) {
+  uint64_t b = (items + per_block - 1) / per_block;
+  return static_cast<uint32_t>(b == 0 ? 1 : b);
+}
+
+// Carves consecutive 256-byte aligned regions out of the workspace.
+struct Carver {
+  uint64_t at = 0;
+  uint64_t take(uint64_t bytes) {
+    const uint64_t here = at;
+    at = align_up(at + bytes, 256);
+    return here;
+  }
+};
+
+struct ProfileLayout {
+  uint64_t ctrl, k0, k1, k2, e0, e1, g0, g1, tiles, hist, sums, bits, word_prefix, total;
+  uint64_t max_tiles, n_words;
+};
+
+ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
+  ProfileLayout L;
+  Carver c;
+  L.n_words = (n + 63) / 64;
+  uint64_t big_tasks = n / (static_cast<uint64_t>(LEAF) + 1);
+  if (big_tasks > n_tasks) big_tasks = n_tasks;
+  L.max_tiles = n / TILE + big_tasks;
+  L.ctrl = c.take(256);
+  L.k0 = c.take(n * 8);
+  L.k1 = c.take(n * 8);
+  L.k2 = c.take(n * 8);
+  L.e0 = c.take(n * 8);
+  L.e1 = c.take(n * 8 + 8);  // after the sort: segment starts
+  L.g0 = c.take(n * 8);
+  L.g1 = c.take(n * 8);
+  L.tiles = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
+  L.hist = c.take(L.max_tiles * 256 * 4);
+  uint64_t longest = L.max_tiles * 256;
+  if (longest < static_cast<uint64_t>(n_tasks) + 1) longest = static_cast<uint64_t>(n_tasks) + 1;
+  if (longest < L.n_words) longest = L.n_words;
+  L.sums = c.take((longest / SCAN_TILE + 2) * 4);
+  L.bits = c.take(L.n_words * 8);
+  L.word_prefix = c.take(L.n_words * 4);
+  L.total = c.at;
+  return L;
+}
+
+// In-place exclusive prefix sum of `count` 32-bit words; the grand total goes to *d_total (may be null).
+int scan_u32(uint32_t* d_data, uint64_t count, uint32_t* d_sums, uint64_t* d_total, hipStream_t st) {
+  const uint32_t nb = blocks_for(count, SCAN_TILE);
+  hipLaunchKernelGGL(k_scan_reduce, dim3(nb), dim3(SCAN_BLOCK), 0, st, d_data, count, d_sums);
+  hipLaunchKernelGGL(k_scan_spine, dim3(1), dim3(SCAN_BLOCK), 0, st, d_sums, static_cast<uint64_t>(nb), d_total);
+  hipLaunchKernelGGL(k_scan_apply, dim3(nb), dim3(SCAN_BLOCK), 0, st, d_data, count, d_sums);
+  FIKIT_HIP(hipGetLastError());
+  return FIKIT_OK;
+}
+
+int status_from_bits(uint32_t bits) {
+  if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return FIKIT_INVALID_ARG;
+  if (bits & ERR_BAD_RECORD) return FIKIT_BAD_RECORD;
+  if (bits & ERR_UNKNOWN_ID) return FIKIT_UNKNOWN_ID;
+  return FIKIT_OK;
+}
+
+int read_ctrl(const Ctrl* d_ctrl, Ctrl* h, hipStream_t st) {
+  FIKIT_HIP(hipMemcpyAsync(h, d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipStreamSynchronize(st));
+  return FIKIT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fikit_version(void) { return 1; }
+
+const char* fikit_status_string(int status) {
+  switch (status) {
+    case FIKIT_OK: return "ok";
+    case FIKIT_INVALID_ARG: return "invalid argument";
+    case FIKIT_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case FIKIT_ROW_CAPACITY: return "row capacity exceeded";
+    case FIKIT_BAD_RECORD: return "record with end_ns < start_ns";
+    case FIKIT_UNKNOWN_ID: return "launch ID missing from its task's profile";
+    case FIKIT_HIP_ERROR: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+size_t fikit_profile_workspace_bytes(uint64_t n_records, uint32_t n_tasks) {
+  if (n_records >= MAX_ELEMS) return 0;
+  return static_cast<size_t>(profile_layout(n_records, n_tasks).total);
+}
+
+int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint64_t* d_task_offsets,
+                  uint32_t n_tasks, uint64_t* d_ids_out, fikit_row* d_rows_out, uint64_t row_capacity,
+                  uint64_t* d_task_row_offsets, uint64_t* h_n_rows, void* d_workspace, size_t workspace_bytes,
+                  void* hip_stream) {
+  if (!h_n_rows) return FIKIT_INVALID_ARG;
+  *h_n_rows = 0;
+  if (!d_task_offsets || !d_task_row_offsets || !d_workspace) return FIKIT_INVALID_ARG;
+  if (n_records >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_records > 0 && (!d_records || n_tasks == 0)) return FIKIT_INVALID_ARG;
+  if (row_capacity > 0 && !d_rows_out) return FIKIT_INVALID_ARG;
+  if (!aligned(d_records, 16) || !aligned(d_task_offsets, 8) || !aligned(d_ids_out, 8) || !aligned(d_rows_out, 16) ||
+      !aligned(d_task_row_offsets, 8) || !aligned(d_workspace, 256))
+    return FIKIT_INVALID_ARG;
+  const ProfileLayout L = profile_layout(n_records, n_tasks);
+  if (workspace_bytes < L.total) return FIKIT_WORKSPACE_TOO_SMALL;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = static_cast<unsigned char*>(d_workspace);
+  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + L.ctrl);
+  const uint64_t n = n_records;
+  uint64_t* ids = d_ids_out ? d_ids_out : reinterpret_cast<uint64_t*>(ws + L.k0);
+  uint64_t* k1 = reinterpret_cast<uint64_t*>(ws + L.k1);
+  uint64_t* k2 = reinterpret_cast<uint64_t*>(ws + L.k2);
+  int64_t* e0 = reinterpret_cast<int64_t*>(ws + L.e0);
+  int64_t* e1 = reinterpret_cast<int64_t*>(ws + L.e1);
+  int64_t* g0 = reinterpret_cast<int64_t*>(ws + L.g0);
+  int64_t* g1 = reinterpret_cast<int64_t*>(ws + L.g1);
+  uint32_t* tiles = reinterpret_cast<uint32_t*>(ws + L.tiles);
+  uint32_t* hist = reinterpret_cast<uint32_t*>(ws + L.hist);
+  uint32_t* sums = reinterpret_cast<uint32_t*>(ws + L.sums);
+
+  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n, ctrl);
+  Ctrl h{};
+  if (n == 0) {
+    hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(2 * (static_cast<uint64_t>(n_tasks) + 1), 256)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t*>(d_task_row_offsets), 2 * (static_cast<uint64_t>(n_tasks) + 1), 0u);
+    FIKIT_HIP(hipGetLastError());
+    if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+    return status_from_bits(h.status);
+  }
+
+  // Kernel ID, execution time and idle time of every launch.
+  hipLaunchKernelGGL(k_hash_measure, dim3(blocks_for(n, HASH_BLOCK)), dim3(HASH_BLOCK), 0, st, d_records, n, ids, e0, g0, ctrl);
+  hipLaunchKernelGGL(k_mark_task_ends, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, g0, ctrl);
+
+  // Which tasks are sorted in LDS, which go through the multi-pass path.
+  hipLaunchKernelGGL(k_plan_tiles, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st,
+                     d_task_offsets, n_tasks, tiles, ctrl);
+  if (int rc = scan_u32(tiles, static_cast<uint64_t>(n_tasks) + 1, sums, &ctrl->n_big_tiles, st)) return rc;
+  if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+  if (int rc = status_from_bits(h.status)) return rc;
+  const uint64_t n_big_tiles = h.n_big_tiles;
+  if (n_big_tiles > L.max_tiles) return FIKIT_HIP_ERROR;  // cannot happen for valid offsets
+
+  // Sort every task by ID: sorted keys end in k2, payload in e0 / g0.
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_leaf_sort), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                static_cast<int>(sizeof(LeafSmem))));
+  hipLaunchKernelGGL(k_leaf_sort, dim3(n_tasks), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, ids, k2,
+                     e0, g0, ctrl);
+  FIKIT_HIP(hipGetLastError());
+  if (n_big_tiles > 0) {
+    const uint64_t* kin = ids;
+    uint64_t* kout = k1;
+    int64_t *ein = e0, *eout = e1, *gin = g0, *gout = g1;
+    for (int pass = 0; pass < 8; ++pass) {
+      const int shift = 8 * pass;
+      hipLaunchKernelGGL(k_tile_hist, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(256), 0, st, d_task_offsets, n_tasks,
+                         tiles, kin, shift, hist);
+      if (int rc = scan_u32(hist, n_big_tiles * 256, sums, nullptr, st)) return rc;
+      hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets,
+                         n_tasks, tiles, hist, shift, kin, kout, ein, eout, gin, gout);
+      FIKIT_HIP(hipGetLastError());
+      kin = kout;
+      kout = (kout == k1) ? k2 : k1;
+      int64_t* t = ein; ein = eout; eout = t;
+      t = gin; gin = gout; gout = t;
+    }
+  }
+
+  // Segment heads -> number of rows and where each row's launches start.
+  uint64_t* bits = reinterpret_cast<uint64_t*>(ws + L.bits);
+  uint32_t* word_prefix = reinterpret_cast<uint32_t*>(ws + L.word_prefix);
+  uint32_t* seg_start = reinterpret_cast<uint32_t*>(e1);
+  hipLaunchKernelGGL(k_head_bits, dim3(blocks_for(n, 256)), dim3(256), 0, st, k2, n, bits);
+  hipLaunchKernelGGL(k_task_head_bits, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, bits, ctrl);
+  hipLaunchKernelGGL(k_popcount_words, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, L.n_words, word_prefix);
+  if (int rc = scan_u32(word_prefix, L.n_words, sums, &ctrl->n_rows, st)) return rc;
+  if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+  const uint64_t n_rows = h.n_rows;
+  *h_n_rows = n_rows;
+  if (n_rows > row_capacity) return FIKIT_ROW_CAPACITY;
+
+  hipLaunchKernelGGL(k_seg_starts, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, word_prefix, L.n_words, n, n_rows,
+                     seg_start);
+  hipLaunchKernelGGL(k_task_row_offsets, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st,
+                     d_task_offsets, n_tasks, bits, word_prefix, n, n_rows, d_task_row_offsets);
+  hipLaunchKernelGGL(k_stats_small, dim3(blocks_for(n_rows, 4)), dim3(256), 0, st, seg_start, n_rows, d_task_offsets, n_tasks,
+                     k2, e0, g0, d_rows_out);
+  hipLaunchKernelGGL(k_stats_big, dim3(static_cast<uint32_t>(n_rows)), dim3(BIG_THREADS), 0, st, seg_start, n_rows,
+                     d_task_offsets, n_tasks, k2, e0, g0, d_rows_out);
+  FIKIT_HIP(hipGetLastError());
+  FIKIT_HIP(hipStreamSynchronize(st));
+  return FIKIT_OK;
+}
+
+size_t fikit_gapfill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios) {
+  (void)n_scenarios;
+  if (n_ids >= MAX_ELEMS) return 0;
+  Carver c;
+  c.take(256);
+  c.take(static_cast<uint64_t>(n_tasks) * 4);
+  c.take(n_ids * 8);
+  c.take(n_ids * 8);
+  c.take(n_ids * 8);
+  return static_cast<size_t>(c.at);
+}
+
+int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks, const fikit_row* d_rows,
+                  const uint64_t* d_task_row_offsets, const uint32_t* d_hp_task, const uint32_t* d_lp_task,
+                  uint64_t n_scenarios, const fikit_gapfill_params* h_params, const uint64_t* d_gap_offsets,
+                  uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_lp_completion_ns, uint64_t* d_lp_placed,
+                  void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!h_params || h_params->margin_ns < 0 || h_params->min_gap_ns < 0) return FIKIT_INVALID_ARG;
+  if (!d_task_offsets || !d_task_row_offsets || !d_workspace) return FIKIT_INVALID_ARG;
+  if (n_scenarios >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_scenarios > 0 && (!d_hp_task || !d_lp_task || !d_gap_offsets || !d_lp_completion_ns || !d_lp_placed || n_tasks == 0))
+    return FIKIT_INVALID_ARG;
+  if (!aligned(d_ids, 8) || !aligned(d_task_offsets, 8) || !aligned(d_rows, 16) || !aligned(d_task_row_offsets, 8) ||
+      !aligned(d_hp_task, 4) || !aligned(d_lp_task, 4) || !aligned(d_gap_offsets, 8) || !aligned(d_fill_count, 4) ||
+      !aligned(d_filled_ns, 8) || !aligned(d_lp_completion_ns, 8) || !aligned(d_lp_placed, 8) || !aligned(d_workspace, 256))
+    return FIKIT_INVALID_ARG;
+  if (n_scenarios == 0) return FIKIT_OK;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // The element counts live on the device: total launches and total gaps.
+  uint64_t n_ids = 0, n_gaps = 0;
+  FIKIT_HIP(hipMemcpyAsync(&n_ids, d_task_offsets + n_tasks, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipMemcpyAsync(&n_gaps, d_gap_offsets + n_scenarios, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipStreamSynchronize(st));
+  if (n_ids >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_ids > 0 && (!d_ids || !d_rows)) return FIKIT_INVALID_ARG;
+  if (n_gaps > 0 && (!d_fill_count || !d_filled_ns)) return FIKIT_INVALID_ARG;
+  if (workspace_bytes < fikit_gapfill_workspace_bytes(n_ids, n_tasks, n_scenarios)) return FIKIT_WORKSPACE_TOO_SMALL;
+
+  unsigned char* ws = static_cast<unsigned char*>(d_workspace);
+  Carver c;
+  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
+  uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
+  int64_t* pe = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
+  int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
+  int64_t* open = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
+
+  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+  hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, role, static_cast<uint64_t>(n_tasks), 0u);
+  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_ids, ctrl);
+  hipLaunchKernelGGL(k_gf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
+                     d_lp_task, n_scenarios, d_gap_offsets, role, ctrl);
+  hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                     d_task_row_offsets, role, pe, pg, open, ctrl);
+  constexpr int GW = 16;
+  hipLaunchKernelGGL(k_gf_walk<GW>, dim3(blocks_for(n_scenarios, 256 / GW)), dim3(256), 0, st, d_task_offsets, d_hp_task,
+                     d_lp_task, n_scenarios, d_gap_offsets, pe, pg, open, h_params->margin_ns, h_params->min_gap_ns,
+                     d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed, ctrl);
+  FIKIT_HIP(hipGetLastError());
+  Ctrl h{};
+  if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+  return status_from_bits(h.status);
+}
+
+}  // extern "C"

@@ -21,7 +21,7 @@ from __future__ import annotations
 
 import math
 from concurrent.futures import ThreadPoolExecutor
-from dataclasses import dataclass, replace
+from dataclasses import dataclass
 from typing import Callable, Optional, Sequence, Tuple
 
 import numpy as np
@@ -156,8 +156,9 @@ def kernel_tuples(cfg: TraceConfig, task: int) -> np.ndarray:
         sh = rng.integers(1, 257, m).astype(np.uint32) * 256
         t[:, 7] = np.where(rng.random(m) < 0.5, 0, sh)
         out = np.concatenate([out, t], axis=0)
-        # keep first occurrence of each tuple, in draw order
-        _, first = np.unique(out, axis=0, return_index=True)
+        # keep the first occurrence of each (name_id, grid.x) pair, in draw order
+        key = (out[:, 0].astype(np.uint64) << np.uint64(16)) | out[:, 1].astype(np.uint64)
+        _, first = np.unique(key, return_index=True)
         out = out[np.sort(first)]
     return out[:k]
 
@@ -204,11 +205,9 @@ def task_records(cfg: TraceConfig, task: int) -> np.ndarray:
         return rec
     tuples = kernel_tuples(cfg, task)
     seq = _id_sequence(cfg, task, n, k)
-    chosen = tuples[seq]
-    rec["name_id"] = chosen[:, 0]
-    rec["grid"] = chosen[:, 1:4]
-    rec["block"] = chosen[:, 4:7]
-    rec["shmem"] = chosen[:, 7]
+    # identity fields are the first eight 32-bit words of the record
+    words = rec.view("<u4").reshape(n, 16)
+    words[:, :8] = tuples[seq]
 
     rng = _rng(cfg, task, 2)
     # characteristic log-duration and log-gap of each kernel tuple
@@ -231,8 +230,9 @@ def task_records(cfg: TraceConfig, task: int) -> np.ndarray:
     start = np.empty(n, dtype=np.int64)
     start[0] = 0
     np.cumsum(step[:-1], out=start[1:])
-    rec["start_ns"] = start
-    rec["end_ns"] = start + exec_ns
+    quads = rec.view("<i8").reshape(n, 8)
+    quads[:, 4] = start
+    np.add(start, exec_ns, out=quads[:, 5])
     return rec
 
 

@@ -1,0 +1,190 @@
+"""HIP library vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_10359_amd import binding, traces
+from parity_util import DEV, assert_profile_equal, check_gapfill, check_profile, run_profile_gpu
+from test_oracle_pins import make_records
+
+pytestmark = pytest.mark.gpu
+
+
+def small_cases():
+    return {
+        "cfg0_tiny": traces.config(0),
+        "cfg1_medium_3x20000": traces.config(1, n_tasks=4, launches=20000),     # multi-pass path, ragged tail
+        "cfg1_medium_2x8192": traces.config(1, n_tasks=2, launches=8192),       # exactly one LDS leaf
+        "cfg1_medium_2x8193": traces.config(1, n_tasks=2, launches=8193),       # just over the leaf
+        "cfg2_skewed_2x100000": traces.config(2, n_tasks=2, launches=100000),   # long segments
+        "cfg3_large_3x30000": traces.config(3, n_tasks=3, launches=30000),
+        "cfg4_batched_64": traces.config(4, n_tasks=64),                         # full-size scenarios
+        "cfg4_batched_small": traces.config(4, n_tasks=40, hp_launches=500, lp_launches=1500),
+    }
+
+
+@pytest.mark.parametrize("name", list(small_cases()))
+def test_profile_and_gapfill_match_oracle(name):
+    cfg = small_cases()[name]
+    print(f"case {name}: {cfg.n_records} records, {cfg.n_tasks} tasks", flush=True)
+    rec, off = traces.build(cfg, threads=4)
+    prof, d_off, o_prof = check_profile(rec, off)
+    hp, lp = traces.scenarios(cfg)
+    if hp.size:
+        for min_gap in (cfg.min_gap_ns, 100000):
+            check_gapfill(prof, d_off, off, o_prof, hp, lp, cfg.margin_ns, min_gap)
+
+
+def test_hand_worked_trace(golden_dir):
+    with open(os.path.join(golden_dir, "p1_hand_worked.json")) as f:
+        g = json.load(f)
+    k = g["kernels"]
+
+    def rec_of(trace):
+        return make_records([(k[n]["name_id"], k[n]["grid"], k[n]["block"], k[n]["shmem"], s, e) for n, s, e in trace])
+    rec = np.concatenate([rec_of(g["hp_trace"]), rec_of(g["lp_trace"])])
+    off = np.array([0, 12, 20], dtype=np.uint64)
+    prof, d_off, o_prof = check_profile(rec, off)
+    rows = binding.rows_to_numpy(prof.rows)
+    for r, name in zip(rows, g["rows_in_order"]):
+        assert int(r["kernel_id"]) == int(k[name]["id"], 16)
+        assert [int(r["exec"][f]) for f in g["_stats_order"]] == g["rows"][name]["exec"]
+        assert [int(r["gap"][f]) for f in g["_stats_order"]] == g["rows"][name]["gap"]
+    hp = np.array([0], dtype=np.uint32)
+    lp = np.array([1], dtype=np.uint32)
+    for exp in g["gapfill"]:
+        got = check_gapfill(prof, d_off, off, o_prof, hp, lp, exp["margin_ns"], exp["min_gap_ns"])
+        assert binding.u32_to_numpy(got.fill_count).tolist() == exp["fill_count"]
+        assert got.filled_ns.cpu().tolist() == exp["filled_ns"]
+        assert int(got.lp_completion_ns[0]) == exp["lp_completion_ns"]
+        assert int(got.lp_placed[0]) == exp["lp_placed"]
+
+
+def ragged_trace(seed, lens, n_kernels):
+    """Tasks of the given lengths (zeros allowed) over a small shared set of kernel tuples, so
+    that neighbouring tasks end and begin with the same ID."""
+    rng = np.random.default_rng(seed)
+    total = int(sum(lens))
+    rec = np.zeros(total, dtype=traces.LAUNCH_DTYPE)
+    kid = rng.integers(0, n_kernels, total)
+    rec["name_id"] = kid
+    rec["grid"][:, 0] = 1 + kid % 3
+    rec["grid"][:, 1:] = 1
+    rec["block"][:, 0] = 64
+    rec["block"][:, 1:] = 1
+    ex = rng.integers(0, 50000, total)          # zero-length kernels allowed
+    gp = rng.integers(-2000, 30000, total)      # overlaps allowed: they clamp to 0
+    start = np.cumsum(ex + gp) - (ex + gp)
+    rec["start_ns"] = start
+    rec["end_ns"] = start + ex
+    off = np.zeros(len(lens) + 1, dtype=np.uint64)
+    np.cumsum(lens, out=off[1:])
+    return rec, off
+
+
+@pytest.mark.parametrize("lens,n_kernels", [
+    ([0, 1, 0, 0, 2, 63, 64, 65, 0, 1000, 1, 0], 5),
+    ([8192, 8193, 4096, 4097, 12288, 1], 40),
+    ([5000] * 7 + [0] + [9000] * 3, 3),
+    ([70000], 1),                 # one segment much longer than a workgroup
+    ([3, 0, 0, 0, 0, 20000, 0], 2000),
+])
+def test_ragged_and_degenerate_tasks(lens, n_kernels):
+    print(f"lens {lens[:12]} kernels {n_kernels}", flush=True)
+    rec, off = ragged_trace(len(lens) * 131 + n_kernels, lens, n_kernels)
+    prof, d_off, o_prof = check_profile(rec, off)
+    nonempty = [t for t, l in enumerate(lens) if l > 0]
+    hp = np.array([nonempty[i % len(nonempty)] for i in range(6)] + [0], dtype=np.uint32)
+    lp = np.array([nonempty[(i + 1) % len(nonempty)] for i in range(6)] + [nonempty[0]], dtype=np.uint32)
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 300, 0)
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 0, 5000)
+
+
+def test_all_distinct_ids_one_row_per_launch():
+    n = 20000
+    rec = np.zeros(n, dtype=traces.LAUNCH_DTYPE)
+    rec["name_id"] = np.arange(n)
+    rec["grid"] = 1
+    rec["block"] = 1
+    rec["start_ns"] = np.arange(n) * 100
+    rec["end_ns"] = rec["start_ns"] + 1 + np.arange(n) % 37
+    off = np.array([0, 9000, n], dtype=np.uint64)
+    prof, _, _ = check_profile(rec, off)
+    assert prof.n_rows == n
+
+
+def test_empty_inputs():
+    rec = np.zeros(0, dtype=traces.LAUNCH_DTYPE)
+    for off in ([0], [0, 0, 0]):
+        off = np.array(off, dtype=np.uint64)
+        prof, _ = run_profile_gpu(rec, off)
+        assert prof.n_rows == 0
+        assert binding.u64_to_numpy(prof.task_row_offsets).tolist() == [0] * len(off)
+
+
+def test_ids_optional_and_buffers_reusable():
+    cfg = traces.config(1, n_tasks=2, launches=12000)
+    rec, off = traces.build(cfg)
+    o = oracle.profile(rec, off)
+    d_rec = binding.to_device_records(rec, DEV)
+    d_off = binding.to_device_u64(off, DEV)
+    ws = binding.workspace(binding.fikit_profile_workspace_bytes(rec.shape[0], 2), DEV)
+    a = binding.fikit_profile(d_rec, d_off, workspace_buf=ws)
+    b = binding.fikit_profile(d_rec, d_off, workspace_buf=ws, want_ids=False)   # same workspace, no ID output
+    assert b.ids is None
+    assert_profile_equal(a, *o)
+    assert torch.equal(a.rows, b.rows) and torch.equal(a.task_row_offsets, b.task_row_offsets)
+    assert np.array_equal(d_rec.cpu().numpy().reshape(-1).view(traces.LAUNCH_DTYPE), rec)  # inputs untouched
+
+
+def test_error_statuses():
+    cfg = traces.config(0)
+    rec, off = traces.build(cfg)
+    bad = rec.copy()
+    bad["end_ns"][777] = bad["start_ns"][777] - 1
+    with pytest.raises(binding.FikitError) as e:
+        run_profile_gpu(bad, off)
+    assert e.value.status == binding.FIKIT_BAD_RECORD
+    for wrong in ([0, 1000, 1999], [0, 1200, 1100, 2000], [1, 1000, 2000]):
+        w = np.array(wrong, dtype=np.uint64)
+        with pytest.raises(binding.FikitError) as e:
+            run_profile_gpu(rec, w)
+        assert e.value.status == binding.FIKIT_INVALID_ARG
+    with pytest.raises(binding.FikitError) as e:
+        run_profile_gpu(rec, off, row_capacity=10)
+    assert e.value.status == binding.FIKIT_ROW_CAPACITY and e.value.n_rows == 35
+    with pytest.raises(binding.FikitError) as e:
+        run_profile_gpu(rec, off, workspace_buf=torch.empty(4096, dtype=torch.uint8, device=DEV))
+    assert e.value.status == binding.FIKIT_WORKSPACE_TOO_SMALL
+    d_rec = binding.to_device_records(rec, DEV)
+    d_off = binding.to_device_u64(off, DEV)
+    shifted = torch.empty(d_rec.numel() + 16, dtype=torch.uint8, device=DEV)[8:8 + d_rec.numel()].reshape(-1, 64)
+    with pytest.raises(binding.FikitError) as e:   # record pointer not 16-byte aligned
+        binding.fikit_profile(shifted, d_off)
+    assert e.value.status == binding.FIKIT_INVALID_ARG
+
+    prof, d_off, o_prof = check_profile(rec, off)
+    hp = np.array([0], dtype=np.uint32)
+    lp = np.array([1], dtype=np.uint32)
+    go = binding.to_device_u64(traces.gap_offsets(off, hp), DEV)
+    args = (binding.to_device_u32(hp, DEV), binding.to_device_u32(lp, DEV), go)
+    ids2 = prof.ids.clone()
+    ids2[1500] ^= 1
+    with pytest.raises(binding.FikitError) as e:
+        binding.fikit_gapfill(ids2, d_off, prof.rows, prof.task_row_offsets, *args, margin_ns=0, min_gap_ns=0)
+    assert e.value.status == binding.FIKIT_UNKNOWN_ID
+    with pytest.raises(binding.FikitError) as e:
+        binding.fikit_gapfill(prof.ids, d_off, prof.rows, prof.task_row_offsets, binding.to_device_u32(hp + 2, DEV),
+                              args[1], go, margin_ns=0, min_gap_ns=0)
+    assert e.value.status == binding.FIKIT_INVALID_ARG
+    with pytest.raises(binding.FikitError) as e:
+        binding.fikit_gapfill(prof.ids, d_off, prof.rows, prof.task_row_offsets, args[0], args[1], go + 1,
+                              margin_ns=0, min_gap_ns=0, n_gaps=1000)
+    assert e.value.status == binding.FIKIT_INVALID_ARG
+    with pytest.raises(binding.FikitError) as e:
+        binding.fikit_gapfill(prof.ids, d_off, prof.rows, prof.task_row_offsets, *args, margin_ns=-1, min_gap_ns=0)
+    assert e.value.status == binding.FIKIT_INVALID_ARG
