@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path (fikit_profile + fikit_gapfill) on one MI355X.
+
+One "step" = one fikit_profile call over every launch record of the workload followed by one
+fikit_gapfill call over every scenario, inputs resident in HBM.  Default workload: the batched
+gap-fill configuration (65,536 scenarios; 4,096 + 16,384 launches each; 1.34 G records).
+
+Prints ONE JSON line.  `value` is launch records per second through the whole step.
+`roofline` describes the kernel with the largest share of device time, timed with HIP events
+on the stream it runs on (the library's fikit_trace_* facility).  `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# Algorithmic bytes each kernel must move per record it processes (natural widths):
+#   hash + measure: read the 64-byte record, write 8-byte ID, execution time and idle time
+#   LDS sort of a short task: read ID, write ID, read and write both payload values
+#   one scatter pass of the multi-pass sort: read and write ID and both payload values
+#   statistics: read the sorted ID and both payload values once
+ALGO_BYTES_PER_RECORD = {
+    "k_hash_measure": 64 + 24,
+    "k_leaf_sort": 8 + 8 + 16 + 16,
+    "k_tile_scatter": 24 + 24,
+    "k_tile_hist": 8,
+    "k_stats_small": 24,
+    "k_stats_big": 24,
+}
+# gap fill, per launch of the scenarios' traces
+ALGO_BYTES_PER_LAUNCH = {
+    "k_gf_predict": 8 + 8,   # read the ID, write one predicted prefix value
+    "k_gf_walk": 8,          # read the predicted value once (+ 12 bytes per gap written, added below)
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg3", "cfg4"])
+    ap.add_argument("--scenarios", type=int, default=None, help="cfg4 only: fewer scenarios (smoke runs)")
+    ap.add_argument("--tasks", type=int, default=None, help="cfg1/cfg3 only: fewer tasks (smoke runs)")
+    ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--cpu-sample-tasks", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU; --gpus {args.gpus} is not supported: tasks and scenarios are independent, "
+              "so more GPUs would each run this same program on their own shard (no exchange).", file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2311_10359_amd import traces
+
+    if args.workload == "cfg4":
+        cfg = traces.config(4, n_tasks=2 * args.scenarios if args.scenarios else None)
+        sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 4096)
+        name = "config 4: batched gap-fill"
+    elif args.workload == "cfg3":
+        cfg = traces.config(3, n_tasks=args.tasks)
+        sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 48)
+        name = "config 3: large profile (profile only)"
+    else:
+        cfg = traces.config(1, n_tasks=args.tasks)
+        sample_tasks = args.cpu_sample_tasks or cfg.n_tasks
+        name = "config 1: medium"
+    off = traces.task_offsets(cfg)
+    n = int(off[-1])
+    hp, lp = traces.scenarios(cfg)
+    n_scen = int(hp.size)
+    go = traces.gap_offsets(off, hp)
+    n_gaps = int(go[-1]) if n_scen else 0
+    row_cap = sum(cfg.ids(t) for t in range(cfg.n_tasks))
+    log(f"[bench] workload {name}: {n} records, {cfg.n_tasks} tasks, {n_scen} scenarios, {n_gaps} gaps")
+
+    # ---- generate on the host (worker processes) and stream into HBM --------------------------
+    t0 = time.time()
+    gen = traces.stream(cfg, workers=args.workers)
+    first_piece = next(gen)   # starts the worker pool before this process touches the GPU
+    import torch
+    from paper_2311_10359_amd import binding
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    d_rec = torch.empty((n, 64), dtype=torch.uint8, device=dev)
+    sample_n = int(off[sample_tasks])
+    sample = np.zeros(sample_n, dtype=traces.LAUNCH_DTYPE)
+    pieces = 0
+    last_print = time.time()
+
+    def take(first, view):
+        u8 = view.view(np.uint8).reshape(-1, 64)
+        d_rec[first:first + u8.shape[0]].copy_(torch.from_numpy(u8))
+        if first < sample_n:
+            k = min(sample_n - first, u8.shape[0])
+            sample.view(np.uint8).reshape(-1, 64)[first:first + k] = u8[:k]
+
+    take(*first_piece)
+    del first_piece
+    for first, view in gen:
+        take(first, view)
+        pieces += 1
+        if time.time() - last_print > 20:
+            last_print = time.time()
+            log(f"[bench] generated and uploaded piece {pieces} ({time.time() - t0:.0f}s)")
+    torch.cuda.synchronize()
+    log(f"[bench] inputs resident after {time.time() - t0:.1f}s")
+
+    d_off = binding.to_device_u64(off, dev)
+    d_hp, d_lp, d_go = binding.to_device_u32(hp, dev), binding.to_device_u32(lp, dev), binding.to_device_u64(go, dev)
+    ids = torch.empty(n, dtype=torch.int64, device=dev)
+    rows = torch.empty((row_cap, 128), dtype=torch.uint8, device=dev)
+    tro = torch.empty(cfg.n_tasks + 1, dtype=torch.int64, device=dev)
+    ws_bytes = max(binding.fikit_profile_workspace_bytes(n, cfg.n_tasks),
+                   binding.fikit_gapfill_workspace_bytes(n, cfg.n_tasks, n_scen))
+    ws = binding.workspace(ws_bytes, dev)
+    gf_out = binding.GapFill(torch.empty(n_gaps, dtype=torch.int32, device=dev),
+                             torch.empty(n_gaps, dtype=torch.int64, device=dev),
+                             torch.empty(n_scen, dtype=torch.int64, device=dev),
+                             torch.empty(n_scen, dtype=torch.int64, device=dev))
+    log(f"[bench] device memory in use: {torch.cuda.memory_allocated() / 2**30:.1f} GiB "
+        f"(workspace {ws_bytes / 2**30:.1f} GiB)")
+
+    def step(timers=None):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if timers is not None else None
+        if e:
+            e[0].record()
+        prof = binding.fikit_profile(d_rec, d_off, ids_out=ids, rows_out=rows, task_row_offsets_out=tro,
+                                     workspace_buf=ws, row_capacity=row_cap)
+        if e:
+            e[1].record()
+        if n_scen:
+            binding.fikit_gapfill(ids, d_off, prof.rows, tro, d_hp, d_lp, d_go, margin_ns=cfg.margin_ns,
+                                  min_gap_ns=cfg.min_gap_ns, n_gaps=n_gaps, n_ids=n, out=gf_out, workspace_buf=ws)
+        if e:
+            e[2].record()
+            timers.append(e)
+        return prof
+
+    for i in range(args.warmup):
+        prof = step()
+        log(f"[bench] warmup {i + 1}/{args.warmup} done")
+    binding.fikit_trace_enable(True)
+    timers = []
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        prof = step(timers)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    trace = binding.fikit_trace_read()
+    binding.fikit_trace_enable(False)
+    ms_per_step = elapsed / args.steps * 1e3
+    prof_ms = float(np.median([a[0].elapsed_time(a[1]) for a in timers]))
+    gf_ms = float(np.median([a[1].elapsed_time(a[2]) for a in timers]))
+    log(f"[bench] {ms_per_step:.2f} ms/step (profile {prof_ms:.2f} ms, gap fill {gf_ms:.2f} ms), {prof.n_rows} rows")
+    for k, (ms, cnt) in sorted(trace.items(), key=lambda kv: -kv[1][0]):
+        log(f"[bench]   {k:18s} {ms / args.steps:9.3f} ms/step  {cnt // args.steps:3d} launches/step")
+
+    # ---- roofline of the dominant kernel ------------------------------------------------------
+    big_tasks = [t for t in range(cfg.n_tasks) if cfg.launches(t) > 8192]
+    n_big = sum(cfg.launches(t) for t in big_tasks)
+    n_leaf = n - n_big
+    n_hp = int(sum(cfg.launches(int(t)) for t in np.unique(hp))) if n_scen else 0
+    n_lp = int(sum(cfg.launches(int(t)) for t in np.unique(lp))) if n_scen else 0
+    units = {"k_hash_measure": n, "k_leaf_sort": n_leaf, "k_tile_scatter": n_big, "k_tile_hist": n_big,
+             "k_stats_small": n, "k_stats_big": n}
+    kernels = {k: v for k, v in trace.items() if k in ALGO_BYTES_PER_RECORD or k in ALGO_BYTES_PER_LAUNCH}
+    dom = max(kernels, key=lambda k: kernels[k][0])
+    dom_ms, dom_cnt = kernels[dom]
+    avg_ms = dom_ms / dom_cnt
+    if dom in ALGO_BYTES_PER_RECORD:
+        algo_bytes = ALGO_BYTES_PER_RECORD[dom] * units[dom]
+    elif dom == "k_gf_predict":
+        algo_bytes = 8 * (n_hp + n_lp) + 8 * n_lp + 16 * n_hp
+    else:
+        algo_bytes = 8 * n_hp * (n_scen // max(1, len(np.unique(hp)))) + 8 * n_lp * (n_scen // max(1, len(np.unique(lp)))) \
+            + 12 * n_gaps
+    achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_ms": round(avg_ms, 4), "algorithmic_bytes_per_launch": int(algo_bytes),
+                "share_of_step": round(dom_ms / args.steps / ms_per_step, 3)}
+
+    # ---- CPU oracle on a bounded sample -------------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        s_off = off[: sample_tasks + 1].copy()
+        t1 = time.perf_counter()
+        o_ids, o_rows, o_tro = oracle.profile(sample, s_off)
+        t2 = time.perf_counter()
+        pick = np.nonzero((hp < sample_tasks) & (lp < sample_tasks))[0] if n_scen else np.zeros(0, dtype=np.int64)
+        s_hp, s_lp = hp[pick], lp[pick]
+        if pick.size:
+            oracle.gapfill(o_ids, s_off, o_rows, o_tro, s_hp, s_lp, cfg.margin_ns, cfg.min_gap_ns,
+                           traces.gap_offsets(s_off, s_hp))
+        t3 = time.perf_counter()
+        cpu = {"value": round(sample_n / (t3 - t1), 1), "unit": "records/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {sample_tasks} tasks ({sample_n} records, {pick.size} scenarios) of the same workload: "
+                         f"profile {t2 - t1:.2f}s + gap fill {t3 - t2:.2f}s, single thread",
+               "profile_records_per_s": round(sample_n / (t2 - t1), 1),
+               "gapfill_scenarios_per_s": round(pick.size / (t3 - t2), 1) if pick.size else None,
+               "host_cpus": os.cpu_count()}
+        # the sample doubles as a spot check of the timed run's output
+        got_rows = binding.rows_to_numpy(prof.rows[: len(o_rows)])
+        assert got_rows.tobytes() == o_rows.tobytes(), "benchmark output differs from the oracle on the sample"
+        log(f"[bench] oracle sample: {cpu['value'] / 1e6:.2f} M records/s on one core; sample rows match")
+
+    out = {
+        "metric": "launch records/s profiled + gap-fill scenarios/s; % of peak HBM GB/s",
+        "value": round(n / (ms_per_step * 1e-3), 1),
+        "unit": "records/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+        "config": {"workload": name, "records": n, "tasks": cfg.n_tasks, "scenarios": n_scen, "gaps": n_gaps,
+                   "rows": prof.n_rows, "margin_ns": cfg.margin_ns, "min_gap_ns": cfg.min_gap_ns},
+        "profile_records_per_s": round(n / (prof_ms * 1e-3), 1),
+        "gapfill_scenarios_per_s": round(n_scen / (gf_ms * 1e-3), 1) if n_scen else None,
+        "profile_ms": round(prof_ms, 3), "gapfill_ms": round(gf_ms, 3),
+        "kernel_ms_per_step": {k: round(ms / args.steps, 3) for k, (ms, _) in trace.items()},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

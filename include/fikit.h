@@ -159,6 +159,19 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
 const char* fikit_status_string(int status);
 int fikit_version(void);
 
+/*
+ * Per-kernel timing, a measurement aid (off by default; process-wide, not thread safe).
+ * fikit_trace_enable(1) clears the table and makes every later fikit_profile / fikit_gapfill
+ * call record a HIP event on its stream before each kernel launch; when the call ends, the time
+ * between consecutive events is added to the entry named after the launch that opened the
+ * interval ("host_sync" entries hold the time the host spent reading a count back).
+ * fikit_trace_read returns the number of entries and, for 0 <= index < that number, stores the
+ * entry's name (a static string), its accumulated milliseconds and its number of intervals;
+ * any of the three output pointers may be NULL.
+ */
+void fikit_trace_enable(int on);
+int fikit_trace_read(int index, const char** name, double* total_ms, int* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ FIKIT_UNKNOWN_ID = -5
 FIKIT_HIP_ERROR = -6
 
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
-           "fikit_gapfill", "fikit_status_string", "fikit_version")
+           "fikit_gapfill", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
 
 # Layout of a profile row as seen from numpy (128 bytes; see fikit_row in fikit.h).
 STATS_DTYPE = np.dtype([("count", "<u8"), ("sum", "<u8"), ("min", "<i8"), ("max", "<i8"),
@@ -75,12 +75,33 @@ def load() -> ctypes.CDLL:
         lib.fikit_status_string.argtypes = [ctypes.c_int]
         lib.fikit_version.restype = ctypes.c_int
         lib.fikit_version.argtypes = []
+        lib.fikit_trace_enable.restype = None
+        lib.fikit_trace_enable.argtypes = [ctypes.c_int]
+        lib.fikit_trace_read.restype = ctypes.c_int
+        lib.fikit_trace_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
+                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
         _lib = lib
     return _lib
 
 
 def status_string(status: int) -> str:
     return load().fikit_status_string(status).decode()
+
+
+def fikit_trace_enable(on: bool) -> None:
+    load().fikit_trace_enable(1 if on else 0)
+
+
+def fikit_trace_read() -> dict:
+    """{name: (total_ms, intervals)} accumulated since fikit_trace_enable(True)."""
+    lib = load()
+    out = {}
+    n = lib.fikit_trace_read(-1, None, None, None)
+    for i in range(n):
+        name, ms, k = ctypes.c_char_p(), ctypes.c_double(), ctypes.c_int()
+        lib.fikit_trace_read(i, ctypes.byref(name), ctypes.byref(ms), ctypes.byref(k))
+        out[name.value.decode()] = (ms.value, k.value)
+    return out
 
 
 def _ptr(t: Optional[torch.Tensor]):

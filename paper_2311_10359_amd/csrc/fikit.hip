@@ -83,6 +83,51 @@ int scan_u32(uint32_t* d_data, uint64_t count, uint32_t* d_sums, uint64_t* d_tot
   return FIKIT_OK;
 }
 
+// ---- optional per-kernel timing (fikit_trace_*) ---------------------------------------------
+// When enabled, every launch site records a HIP event on the caller's stream; at the end of
+// the call the time between consecutive events is added to the entry of the launch that
+// opened the interval.  Process-wide and not thread safe: a measurement aid, off by default.
+constexpr int TRACE_MAX_MARKS = 192;
+constexpr int TRACE_MAX_NAMES = 48;
+struct TraceEntry { const char* name; double ms; int launches; };
+bool g_trace_on = false;
+TraceEntry g_trace[TRACE_MAX_NAMES];
+int g_trace_n = 0;
+
+struct Tracer {
+  hipStream_t st;
+  hipEvent_t ev[TRACE_MAX_MARKS];
+  const char* name[TRACE_MAX_MARKS];
+  int n = 0;
+  bool on;
+  explicit Tracer(hipStream_t s) : st(s), on(g_trace_on) {}
+  void mark(const char* what) {
+    if (!on || n >= TRACE_MAX_MARKS) return;
+    if (hipEventCreate(&ev[n]) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(ev[n], st);
+    name[n++] = what;
+  }
+  // Called once the stream has been synchronised (or on any early return).
+  ~Tracer() {
+    if (n == 0) return;
+    if (n < TRACE_MAX_MARKS) mark("end");
+    (void)hipStreamSynchronize(st);
+    for (int i = 0; i + 1 < n; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) { (void)hipGetLastError(); continue; }
+      int k = 0;
+      while (k < g_trace_n && g_trace[k].name != name[i]) ++k;
+      if (k == g_trace_n) {
+        if (g_trace_n == TRACE_MAX_NAMES) continue;
+        g_trace[g_trace_n++] = TraceEntry{name[i], 0.0, 0};
+      }
+      g_trace[k].ms += ms;
+      g_trace[k].launches += 1;
+    }
+    for (int i = 0; i < n; ++i) (void)hipEventDestroy(ev[i]);
+  }
+};
+
 int status_from_bits(uint32_t bits) {
   if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return FIKIT_INVALID_ARG;
   if (bits & ERR_BAD_RECORD) return FIKIT_BAD_RECORD;
@@ -101,6 +146,20 @@ int read_ctrl(const Ctrl* d_ctrl, Ctrl* h, hipStream_t st) {
 extern "C" {
 
 int fikit_version(void) { return 1; }
+
+void fikit_trace_enable(int on) {
+  g_trace_on = on != 0;
+  g_trace_n = 0;
+}
+
+int fikit_trace_read(int index, const char** name, double* total_ms, int* launches) {
+  if (index >= 0 && index < g_trace_n) {
+    if (name) *name = g_trace[index].name;
+    if (total_ms) *total_ms = g_trace[index].ms;
+    if (launches) *launches = g_trace[index].launches;
+  }
+  return g_trace_n;
+}
 
 const char* fikit_status_string(int status) {
   switch (status) {
@@ -151,6 +210,8 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   uint32_t* hist = reinterpret_cast<uint32_t*>(ws + L.hist);
   uint32_t* sums = reinterpret_cast<uint32_t*>(ws + L.sums);
 
+  Tracer tr(st);
+  tr.mark("setup");
   hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
   hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n, ctrl);
   Ctrl h{};
@@ -163,13 +224,16 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   }
 
   // Kernel ID, execution time and idle time of every launch.
+  tr.mark("k_hash_measure");
   hipLaunchKernelGGL(k_hash_measure, dim3(blocks_for(n, HASH_BLOCK)), dim3(HASH_BLOCK), 0, st, d_records, n, ids, e0, g0, ctrl);
+  tr.mark("plan");
   hipLaunchKernelGGL(k_mark_task_ends, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, g0, ctrl);
 
   // Which tasks are sorted in LDS, which go through the multi-pass path.
   hipLaunchKernelGGL(k_plan_tiles, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st,
                      d_task_offsets, n_tasks, tiles, ctrl);
   if (int rc = scan_u32(tiles, static_cast<uint64_t>(n_tasks) + 1, sums, &ctrl->n_big_tiles, st)) return rc;
+  tr.mark("host_sync");
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   if (int rc = status_from_bits(h.status)) return rc;
   const uint64_t n_big_tiles = h.n_big_tiles;
@@ -178,6 +242,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   // Sort every task by ID: sorted keys end in k2, payload in e0 / g0.
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_leaf_sort), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 static_cast<int>(sizeof(LeafSmem))));
+  tr.mark("k_leaf_sort");
   hipLaunchKernelGGL(k_leaf_sort, dim3(n_tasks), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, ids, k2,
                      e0, g0, ctrl);
   FIKIT_HIP(hipGetLastError());
@@ -187,9 +252,12 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     int64_t *ein = e0, *eout = e1, *gin = g0, *gout = g1;
     for (int pass = 0; pass < 8; ++pass) {
       const int shift = 8 * pass;
+      tr.mark("k_tile_hist");
       hipLaunchKernelGGL(k_tile_hist, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(256), 0, st, d_task_offsets, n_tasks,
                          tiles, kin, shift, hist);
+      tr.mark("scan_tile_hist");
       if (int rc = scan_u32(hist, n_big_tiles * 256, sums, nullptr, st)) return rc;
+      tr.mark("k_tile_scatter");
       hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets,
                          n_tasks, tiles, hist, shift, kin, kout, ein, eout, gin, gout);
       FIKIT_HIP(hipGetLastError());
@@ -204,21 +272,26 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   uint64_t* bits = reinterpret_cast<uint64_t*>(ws + L.bits);
   uint32_t* word_prefix = reinterpret_cast<uint32_t*>(ws + L.word_prefix);
   uint32_t* seg_start = reinterpret_cast<uint32_t*>(e1);
+  tr.mark("heads");
   hipLaunchKernelGGL(k_head_bits, dim3(blocks_for(n, 256)), dim3(256), 0, st, k2, n, bits);
   hipLaunchKernelGGL(k_task_head_bits, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, bits, ctrl);
   hipLaunchKernelGGL(k_popcount_words, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, L.n_words, word_prefix);
   if (int rc = scan_u32(word_prefix, L.n_words, sums, &ctrl->n_rows, st)) return rc;
+  tr.mark("host_sync");
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   const uint64_t n_rows = h.n_rows;
   *h_n_rows = n_rows;
   if (n_rows > row_capacity) return FIKIT_ROW_CAPACITY;
 
+  tr.mark("seg_starts");
   hipLaunchKernelGGL(k_seg_starts, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, word_prefix, L.n_words, n, n_rows,
                      seg_start);
   hipLaunchKernelGGL(k_task_row_offsets, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st,
                      d_task_offsets, n_tasks, bits, word_prefix, n, n_rows, d_task_row_offsets);
+  tr.mark("k_stats_small");
   hipLaunchKernelGGL(k_stats_small, dim3(blocks_for(n_rows, 4)), dim3(256), 0, st, seg_start, n_rows, d_task_offsets, n_tasks,
                      k2, e0, g0, d_rows_out);
+  tr.mark("k_stats_big");
   hipLaunchKernelGGL(k_stats_big, dim3(static_cast<uint32_t>(n_rows)), dim3(BIG_THREADS), 0, st, seg_start, n_rows,
                      d_task_offsets, n_tasks, k2, e0, g0, d_rows_out);
   FIKIT_HIP(hipGetLastError());
@@ -273,18 +346,23 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
   int64_t* open = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
 
+  Tracer tr(st);
+  tr.mark("gf_setup");
   hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
   hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, role, static_cast<uint64_t>(n_tasks), 0u);
   hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_ids, ctrl);
   hipLaunchKernelGGL(k_gf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
                      d_lp_task, n_scenarios, d_gap_offsets, role, ctrl);
+  tr.mark("k_gf_predict");
   hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
                      d_task_row_offsets, role, pe, pg, open, ctrl);
   constexpr int GW = 16;
+  tr.mark("k_gf_walk");
   hipLaunchKernelGGL(k_gf_walk<GW>, dim3(blocks_for(n_scenarios, 256 / GW)), dim3(256), 0, st, d_task_offsets, d_hp_task,
                      d_lp_task, n_scenarios, d_gap_offsets, pe, pg, open, h_params->margin_ns, h_params->min_gap_ns,
                      d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed, ctrl);
   FIKIT_HIP(hipGetLastError());
+  tr.mark("host_sync");
   Ctrl h{};
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   return status_from_bits(h.status);

@@ -21,7 +21,7 @@ from __future__ import annotations
 
 import math
 from concurrent.futures import ThreadPoolExecutor
-from dataclasses import dataclass
+from dataclasses import dataclass, replace
 from typing import Callable, Optional, Sequence, Tuple
 
 import numpy as np
@@ -70,6 +70,7 @@ class TraceConfig:
     scenario_kind: str = "none"  # "pair01" | "grid" | "adjacent" | "none"
     margin_ns: int = 500
     min_gap_ns: int = 0
+    overrides: tuple = ()  # the keyword overrides config() was called with (to rebuild it elsewhere)
 
     @property
     def n_records(self) -> int:
@@ -125,7 +126,9 @@ def config(index: int, *, n_tasks: Optional[int] = None, launches: Optional[int]
             scenario_kind="adjacent")
     else:
         raise ValueError(f"no workload {index}")
-    return cfg
+    ov = tuple((k, v) for k, v in (("n_tasks", n_tasks), ("launches", launches), ("hp_launches", hp_launches),
+                                   ("lp_launches", lp_launches)) if v is not None)
+    return replace(cfg, overrides=ov)
 
 
 def _rng(cfg: TraceConfig, task: int, stream: int) -> np.random.Generator:
@@ -196,11 +199,13 @@ def _id_sequence(cfg: TraceConfig, task: int, n: int, k: int) -> np.ndarray:
     raise ValueError(cfg.pattern)
 
 
-def task_records(cfg: TraceConfig, task: int) -> np.ndarray:
-    """All launch records of one task, in launch order."""
+def task_records(cfg: TraceConfig, task: int, out: Optional[np.ndarray] = None) -> np.ndarray:
+    """All launch records of one task, in launch order.  `out`, if given, is a zero-filled
+    LAUNCH_DTYPE array of the task's length that receives them."""
     n = cfg.launches(task)
     k = cfg.ids(task)
-    rec = np.zeros(n, dtype=LAUNCH_DTYPE)
+    rec = np.zeros(n, dtype=LAUNCH_DTYPE) if out is None else out
+    assert rec.shape == (n,) and rec.dtype == LAUNCH_DTYPE and rec.flags["C_CONTIGUOUS"]
     if n == 0:
         return rec
     tuples = kernel_tuples(cfg, task)
@@ -256,7 +261,7 @@ def build(cfg: TraceConfig, tasks: Optional[Sequence[int]] = None, threads: int 
     assert rec.shape[0] == total and rec.dtype == LAUNCH_DTYPE
 
     def fill(i):
-        rec[int(off[i]):int(off[i + 1])] = task_records(cfg, tasks[i])
+        task_records(cfg, tasks[i], out=rec[int(off[i]):int(off[i + 1])])
 
     if threads <= 1 or len(tasks) <= 1:
         for i in range(len(tasks)):
@@ -265,6 +270,75 @@ def build(cfg: TraceConfig, tasks: Optional[Sequence[int]] = None, threads: int 
         with ThreadPoolExecutor(threads) as pool:
             list(pool.map(fill, range(len(tasks)), chunksize=max(1, len(tasks) // (threads * 8))))
     return rec, off
+
+
+def _fill_slot(args):
+    """Worker of stream(): regenerates a range of tasks into one slot of the shared staging block."""
+    from multiprocessing import shared_memory
+    name, index, overrides, lo, hi, slot, slot_records = args
+    cfg = config(index, **dict(overrides))
+    shm = shared_memory.SharedMemory(name=name)
+    try:
+        rec = np.ndarray((slot_records,), dtype=LAUNCH_DTYPE, buffer=shm.buf, offset=slot * slot_records * 64)
+        at = 0
+        for t in range(lo, hi):
+            n_t = cfg.launches(t)
+            view = rec[at:at + n_t]
+            view.view(np.uint8)[:] = 0   # slots are reused
+            task_records(cfg, t, out=view)
+            at += n_t
+        del rec, view
+    finally:
+        shm.close()
+    return slot, lo, hi, at
+
+
+def stream(cfg: TraceConfig, workers: int = 8, slot_records: int = 1 << 20, slots: Optional[int] = None):
+    """Generates a whole workload with worker processes and yields it piecewise:
+    (first_record_index, records) for consecutive ranges of whole tasks, in completion order.
+    `records` is a view of a reused staging slot: copy it away before asking for the next piece.
+
+    Workers are started with the fork-free "forkserver" method, so the caller may already hold
+    a GPU context.  A worker that dies raises here instead of being respawned."""
+    import multiprocessing as mp
+    from concurrent.futures import FIRST_COMPLETED, ProcessPoolExecutor, wait
+    from multiprocessing import shared_memory
+    off = task_offsets(cfg)
+    lens = (off[1:] - off[:-1]).astype(np.int64)
+    if lens.size:
+        slot_records = max(slot_records, int(lens.max()))
+    slots = slots or 2 * workers
+    jobs = []
+    lo = 0
+    while lo < cfg.n_tasks:
+        hi = lo + 1
+        while hi < cfg.n_tasks and int(off[hi + 1] - off[lo]) <= slot_records:
+            hi += 1
+        jobs.append((lo, hi))
+        lo = hi
+    shm = shared_memory.SharedMemory(create=True, size=max(1, slots * slot_records * 64))
+    try:
+        ctx = mp.get_context("forkserver")
+        with ProcessPoolExecutor(max_workers=workers, mp_context=ctx) as pool:
+            free = list(range(slots))
+            pending = set()
+            nxt = 0
+            while nxt < len(jobs) or pending:
+                while free and nxt < len(jobs):
+                    lo, hi = jobs[nxt]
+                    nxt += 1
+                    pending.add(pool.submit(_fill_slot, (shm.name, cfg.index, cfg.overrides, lo, hi, free.pop(),
+                                                         slot_records)))
+                finished, pending = wait(pending, return_when=FIRST_COMPLETED)
+                for f in finished:
+                    slot, lo, hi, count = f.result()
+                    view = np.ndarray((count,), dtype=LAUNCH_DTYPE, buffer=shm.buf, offset=slot * slot_records * 64)
+                    yield int(off[lo]), view
+                    del view
+                    free.append(slot)
+    finally:
+        shm.close()
+        shm.unlink()
 
 
 def scenarios(cfg: TraceConfig) -> Tuple[np.ndarray, np.ndarray]:
