@@ -56,7 +56,8 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg3", "cfg4"])
     ap.add_argument("--scenarios", type=int, default=None, help="cfg4 only: fewer scenarios (smoke runs)")
     ap.add_argument("--tasks", type=int, default=None, help="cfg1/cfg3 only: fewer tasks (smoke runs)")
-    ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 1),
+                    help="processes that generate the input; 0 = generate in this process")
     ap.add_argument("--cpu-sample-tasks", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -90,7 +91,20 @@ def main():
 
     # ---- generate on the host (worker processes) and stream into HBM --------------------------
     t0 = time.time()
-    gen = traces.stream(cfg, workers=args.workers)
+    if args.workers > 0:
+        gen = traces.stream(cfg, workers=args.workers)
+    else:
+        # in-process generation: no child processes (use this under a profiler)
+        def in_process(chunk=1 << 20):
+            lo = 0
+            while lo < cfg.n_tasks:
+                hi = lo + 1
+                while hi < cfg.n_tasks and int(off[hi + 1] - off[lo]) <= chunk:
+                    hi += 1
+                rec, _ = traces.build(cfg, tasks=range(lo, hi), threads=1 if cfg.launches(lo) < 100000 else 4)
+                yield int(off[lo]), rec
+                lo = hi
+        gen = in_process()
     first_piece = next(gen)   # starts the worker pool before this process touches the GPU
     import torch
     from paper_2311_10359_amd import binding
