@@ -10,6 +10,14 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # The full-size GPU tests generate their inputs with worker processes.  Start the process
+    # server now, before any test initialises the GPU, so that no program is started from a
+    # process that holds a GPU context.
+    if "gpu" in (config.getoption("-m") or "") and "not gpu" not in (config.getoption("-m") or ""):
+        import multiprocessing as mp
+        from multiprocessing import forkserver
+        mp.set_forkserver_preload(["numpy"])
+        forkserver.ensure_running()
 
 
 @pytest.fixture(scope="session")

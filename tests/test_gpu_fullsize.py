@@ -1,0 +1,156 @@
+"""The five workloads at their full sizes, in the launch configuration bench.py times.
+
+The oracle cannot redo a billion records in seconds, so it recomputes a sample of tasks and
+scenarios one by one (every task's records can be regenerated alone from its seed); the rest
+is covered by properties that hold at any size."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_10359_amd import binding, traces
+from parity_util import DEV
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def upload(cfg, workers=16):
+    off = traces.task_offsets(cfg)
+    n = int(off[-1])
+    d_rec = torch.empty((n, 64), dtype=torch.uint8, device=DEV)
+    t0 = time.time()
+    last = t0
+    for first, view in traces.stream(cfg, workers=workers):
+        u8 = view.view(np.uint8).reshape(-1, 64)
+        d_rec[first:first + u8.shape[0]].copy_(torch.from_numpy(u8))
+        if time.time() - last > 15:
+            last = time.time()
+            say(f"  uploading ... {time.time() - t0:.0f}s")
+    torch.cuda.synchronize()
+    say(f"  {n} records resident after {time.time() - t0:.1f}s")
+    return d_rec, off
+
+
+def check_global_properties(prof, off, n_tasks):
+    rows = prof.rows.view(torch.int64).reshape(-1, 16)      # 16 eight-byte fields per row
+    n = int(off[-1])
+    nonempty = int(np.count_nonzero(off[1:] > off[:-1]))
+    assert int(rows[:, 2].sum()) == n                      # exec.count
+    assert int(rows[:, 8].sum()) == n - nonempty           # gap.count
+    for base in (2, 8):
+        cnt, mn, mx, p50, p95 = rows[:, base], rows[:, base + 2], rows[:, base + 3], rows[:, base + 4], rows[:, base + 5]
+        has = cnt > 0
+        assert bool(((mn <= p50) & (p50 <= p95) & (p95 <= mx) & (mn >= 0))[has].all())
+        assert bool((rows[:, base + 1:base + 6][~has] == 0).all())
+    task = rows[:, 1] & 0xffffffff
+    tro = prof.task_row_offsets
+    assert int(tro[0]) == 0 and int(tro[-1]) == prof.n_rows
+    assert bool((tro[1:] >= tro[:-1]).all())
+    # rows are grouped by task in order, IDs strictly ascending (unsigned) inside a task
+    assert bool((task[1:] >= task[:-1]).all())
+    same = task[1:] == task[:-1]
+    kid = rows[:, 0]
+    flip = torch.tensor(-2 ** 63, dtype=torch.int64, device=kid.device)
+    ukey = kid ^ flip                                       # unsigned order as signed order
+    assert bool((ukey[1:] > ukey[:-1])[same].all())
+    expect_task = torch.repeat_interleave(torch.arange(n_tasks, device=kid.device), tro[1:] - tro[:-1])
+    assert torch.equal(task, expect_task)
+
+
+def check_sampled_tasks(cfg, prof, off, tasks):
+    tro = binding.u64_to_numpy(prof.task_row_offsets)
+    for t in tasks:
+        rec = traces.task_records(cfg, t)
+        o_ids, o_rows, _ = oracle.profile(rec, np.array([0, rec.shape[0]], dtype=np.uint64))
+        lo, hi = int(off[t]), int(off[t + 1])
+        assert np.array_equal(binding.u64_to_numpy(prof.ids[lo:hi]), o_ids), f"task {t}: IDs differ"
+        got = binding.rows_to_numpy(prof.rows[int(tro[t]):int(tro[t + 1])])
+        o_rows = o_rows.copy()
+        o_rows["task"] = t
+        assert got.shape == o_rows.shape, f"task {t}: {got.shape[0]} rows, oracle {o_rows.shape[0]}"
+        assert got.tobytes() == o_rows.tobytes(), f"task {t}: rows differ"
+    say(f"  sampled tasks {list(tasks)} match the oracle")
+
+
+def profile_full(cfg):
+    d_rec, off = upload(cfg)
+    d_off = binding.to_device_u64(off, DEV)
+    row_cap = sum(cfg.ids(t) for t in range(cfg.n_tasks))
+    t0 = time.time()
+    prof = binding.fikit_profile(d_rec, d_off, row_capacity=row_cap)
+    say(f"  fikit_profile: {prof.n_rows} rows in {time.time() - t0:.2f}s")
+    return prof, off, d_off, d_rec
+
+
+def test_config1_medium_full_oracle():
+    cfg = traces.config(1)
+    say("config 1 (medium), whole workload against the oracle")
+    rec, off = traces.build(cfg, threads=8)
+    o_ids, o_rows, o_tro = oracle.profile(rec, off)
+    d_off = binding.to_device_u64(off, DEV)
+    prof = binding.fikit_profile(binding.to_device_records(rec, DEV), d_off)
+    assert np.array_equal(binding.u64_to_numpy(prof.ids), o_ids)
+    assert binding.rows_to_numpy(prof.rows).tobytes() == o_rows.tobytes()
+    assert np.array_equal(binding.u64_to_numpy(prof.task_row_offsets), o_tro)
+    check_global_properties(prof, off, cfg.n_tasks)
+    hp, lp = traces.scenarios(cfg)
+    go = traces.gap_offsets(off, hp)
+    exp = oracle.gapfill(o_ids, off, o_rows, o_tro, hp, lp, cfg.margin_ns, cfg.min_gap_ns, go)
+    got = binding.fikit_gapfill(prof.ids, d_off, prof.rows, prof.task_row_offsets, binding.to_device_u32(hp, DEV),
+                                binding.to_device_u32(lp, DEV), binding.to_device_u64(go, DEV),
+                                margin_ns=cfg.margin_ns, min_gap_ns=cfg.min_gap_ns)
+    assert np.array_equal(binding.u32_to_numpy(got.fill_count), exp[0])
+    assert np.array_equal(got.filled_ns.cpu().numpy(), exp[1])
+    assert np.array_equal(got.lp_completion_ns.cpu().numpy(), exp[2])
+    assert np.array_equal(binding.u64_to_numpy(got.lp_placed), exp[3])
+
+
+@pytest.mark.parametrize("index,sample", [(2, (0, 37, 63)), (3, (0, 101, 255))])
+def test_profile_only_workloads_full_size(index, sample):
+    cfg = traces.config(index)
+    say(f"config {index} ({cfg.name}), {cfg.n_records} records")
+    prof, off, d_off, d_rec = profile_full(cfg)
+    check_global_properties(prof, off, cfg.n_tasks)
+    check_sampled_tasks(cfg, prof, off, sample)
+
+
+def test_config4_batched_gapfill_full_size():
+    cfg = traces.config(4)
+    say(f"config 4 ({cfg.name}), {cfg.n_records} records")
+    prof, off, d_off, d_rec = profile_full(cfg)
+    check_global_properties(prof, off, cfg.n_tasks)
+    scen = [0, 1, 777, 32768, 65534, 65535]
+    check_sampled_tasks(cfg, prof, off, [t for s in scen for t in (2 * s, 2 * s + 1)])
+    del d_rec
+    hp, lp = traces.scenarios(cfg)
+    go = traces.gap_offsets(off, hp)
+    t0 = time.time()
+    got = binding.fikit_gapfill(prof.ids, d_off, prof.rows, prof.task_row_offsets, binding.to_device_u32(hp, DEV),
+                                binding.to_device_u32(lp, DEV), binding.to_device_u64(go, DEV),
+                                margin_ns=cfg.margin_ns, min_gap_ns=cfg.min_gap_ns)
+    say(f"  fikit_gapfill: {hp.size} scenarios in {time.time() - t0:.2f}s")
+    # properties at full size: per scenario, the per-gap counts add up to the number placed
+    fc = got.fill_count.view(-1, 4095).to(torch.int64)
+    placed = got.lp_placed
+    assert torch.equal(fc.sum(dim=1), placed)
+    assert bool((placed <= 16384).all()) and bool((got.filled_ns >= 0).all())
+    assert bool((got.lp_completion_ns > 0).all())
+    # sampled scenarios one by one
+    for s in scen:
+        recs = [traces.task_records(cfg, 2 * s), traces.task_records(cfg, 2 * s + 1)]
+        loc_off = np.array([0, recs[0].shape[0], recs[0].shape[0] + recs[1].shape[0]], dtype=np.uint64)
+        o_ids, o_rows, o_tro = oracle.profile(np.concatenate(recs), loc_off)
+        one = np.array([0], dtype=np.uint32)
+        exp = oracle.gapfill(o_ids, loc_off, o_rows, o_tro, one, one + 1, cfg.margin_ns, cfg.min_gap_ns,
+                             traces.gap_offsets(loc_off, one))
+        g0, g1 = int(go[s]), int(go[s + 1])
+        assert np.array_equal(binding.u32_to_numpy(got.fill_count[g0:g1]), exp[0]), f"scenario {s}"
+        assert np.array_equal(got.filled_ns[g0:g1].cpu().numpy(), exp[1]), f"scenario {s}"
+        assert int(got.lp_completion_ns[s]) == int(exp[2][0]) and int(got.lp_placed[s]) == int(exp[3][0])
+    say(f"  sampled scenarios {scen} match the oracle")
