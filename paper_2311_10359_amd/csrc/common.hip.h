@@ -29,7 +29,10 @@ struct Ctrl {
   uint32_t pad0;
   uint64_t n_big_tiles;   // tiles of the tasks sorted by the multi-pass path
   uint64_t n_rows;        // number of (task, ID) rows
-  uint64_t pad1[5];
+  uint64_t n_general;     // tasks that take the general sort-based path
+  uint64_t n_long;        // tasks too long for the one-workgroup path
+  uint64_t n_heads;       // rows found by the general path
+  uint64_t pad1[2];
 };
 static_assert(sizeof(Ctrl) == 64, "control block is 64 bytes");
 
@@ -115,6 +118,18 @@ __device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t* ld
   if (w > 2) base += t2;
   total = t0 + t1 + t2 + t3;
   return base + incl - v;
+}
+
+// Nearest rank: the ceil(K * count / 100)-th smallest, as a 0-based index (count >= 1).
+__device__ __forceinline__ uint64_t rank_index(uint64_t k, uint64_t count) { return (k * count + 99) / 100 - 1; }
+__device__ __forceinline__ uint32_t rank_index_u32(uint32_t k, uint32_t count) { return (k * count + 99) / 100 - 1; }
+
+// Number of segment heads before sorted position pos (head bit mask + per-word prefix counts).
+__device__ __forceinline__ uint32_t heads_before(const uint64_t* __restrict__ bits, const uint32_t* __restrict__ word_prefix,
+                                                 uint64_t n, uint32_t n_heads, uint64_t pos) {
+  if (pos >= n) return n_heads;
+  const uint64_t w = pos >> 6;
+  return word_prefix[w] + static_cast<uint32_t>(__popcll(bits[w] & ((1ull << (pos & 63)) - 1ull)));
 }
 
 // Largest t in [0, n_tasks) with off[t] <= pos, skipping empty tasks to the one that owns pos

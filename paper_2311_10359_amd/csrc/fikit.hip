@@ -9,6 +9,7 @@
 #include "profile_kernels.hip.h"
 #include "sort_kernels.hip.h"
 #include "stats_kernels.hip.h"
+#include "task_kernels.hip.h"
 
 namespace {
 
@@ -42,7 +43,7 @@ struct Carver {
 };
 
 struct ProfileLayout {
-  uint64_t ctrl, k0, k1, k2, e0, e1, g0, g1, tiles, hist, sums, bits, word_prefix, total;
+  uint64_t ctrl, k0, k1, k2, e0, e1, g0, g1, tiles, hist, sums, bits, word_prefix, gflag, dcount, total;
   uint64_t max_tiles, n_words;
 };
 
@@ -55,12 +56,12 @@ ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
   L.max_tiles = n / TILE + big_tasks;
   L.ctrl = c.take(256);
   L.k0 = c.take(n * 8);
-  L.k1 = c.take(n * 8);
+  L.k1 = c.take(n * 8 + 8);  // after the sort: segment starts
   L.k2 = c.take(n * 8);
   L.e0 = c.take(n * 8);
-  L.e1 = c.take(n * 8 + 8);  // after the sort: segment starts
+  L.e1 = c.take(n * 8);      // also: first half of the staged rows of one-workgroup tasks
   L.g0 = c.take(n * 8);
-  L.g1 = c.take(n * 8);
+  L.g1 = c.take(n * 8);      // also: second half of the staged rows
   L.tiles = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
   L.hist = c.take(L.max_tiles * 256 * 4);
   uint64_t longest = L.max_tiles * 256;
@@ -69,6 +70,8 @@ ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
   L.sums = c.take((longest / SCAN_TILE + 2) * 4);
   L.bits = c.take(L.n_words * 8);
   L.word_prefix = c.take(L.n_words * 4);
+  L.gflag = c.take(static_cast<uint64_t>(n_tasks) * 4);
+  L.dcount = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
   L.total = c.at;
   return L;
 }
@@ -223,77 +226,119 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     return status_from_bits(h.status);
   }
 
-  // Kernel ID, execution time and idle time of every launch.
-  tr.mark("k_hash_measure");
-  hipLaunchKernelGGL(k_hash_measure, dim3(blocks_for(n, HASH_BLOCK)), dim3(HASH_BLOCK), 0, st, d_records, n, ids, e0, g0, ctrl);
-  tr.mark("plan");
-  hipLaunchKernelGGL(k_mark_task_ends, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, g0, ctrl);
+  uint32_t* gflag = reinterpret_cast<uint32_t*>(ws + L.gflag);
+  uint32_t* dcount = reinterpret_cast<uint32_t*>(ws + L.dcount);
+  uint64_t* bits = reinterpret_cast<uint64_t*>(ws + L.bits);
+  uint32_t* word_prefix = reinterpret_cast<uint32_t*>(ws + L.word_prefix);
+  uint32_t* seg_start = reinterpret_cast<uint32_t*>(k1);
 
-  // Which tasks are sorted in LDS, which go through the multi-pass path.
-  hipLaunchKernelGGL(k_plan_tiles, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st,
-                     d_task_offsets, n_tasks, tiles, ctrl);
-  if (int rc = scan_u32(tiles, static_cast<uint64_t>(n_tasks) + 1, sums, &ctrl->n_big_tiles, st)) return rc;
+  // Short tasks with few distinct IDs: one workgroup each, records read once, rows staged.
+  tr.mark("plan");
+  hipLaunchKernelGGL(k_classify, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st, d_task_offsets,
+                     n_tasks, FUSE_MAX, gflag, dcount, ctrl);
+  {
+    auto small = k_task_fused<256, 16, 256, 7168>;
+    auto medium = k_task_fused<1024, 16, 512, 16384>;
+    constexpr size_t small_lds = sizeof(FusedSmem<256, 256, 7168>), medium_lds = sizeof(FusedSmem<1024, 512, 16384>);
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  static_cast<int>(small_lds)));
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(medium), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  static_cast<int>(medium_lds)));
+    tr.mark("k_task_fused_small");
+    hipLaunchKernelGGL(small, dim3(n_tasks), dim3(256), small_lds, st, d_records, d_task_offsets, 1u, FUSE_SMALL_MAX, ids, e0,
+                       g0, e1, g1, dcount, gflag, ctrl);
+    tr.mark("k_task_fused_medium");
+    hipLaunchKernelGGL(medium, dim3(n_tasks), dim3(1024), medium_lds, st, d_records, d_task_offsets, FUSE_SMALL_MAX + 1,
+                       FUSE_MAX, ids, e0, g0, e1, g1, dcount, gflag, ctrl);
+    FIKIT_HIP(hipGetLastError());
+  }
   tr.mark("host_sync");
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   if (int rc = status_from_bits(h.status)) return rc;
-  const uint64_t n_big_tiles = h.n_big_tiles;
-  if (n_big_tiles > L.max_tiles) return FIKIT_HIP_ERROR;  // cannot happen for valid offsets
+  const bool any_general = h.n_general > 0;
+  uint64_t n_heads = 0;
 
-  // Sort every task by ID: sorted keys end in k2, payload in e0 / g0.
-  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_leaf_sort), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(sizeof(LeafSmem))));
-  tr.mark("k_leaf_sort");
-  hipLaunchKernelGGL(k_leaf_sort, dim3(n_tasks), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, ids, k2,
-                     e0, g0, ctrl);
-  FIKIT_HIP(hipGetLastError());
-  if (n_big_tiles > 0) {
-    const uint64_t* kin = ids;
-    uint64_t* kout = k1;
-    int64_t *ein = e0, *eout = e1, *gin = g0, *gout = g1;
-    for (int pass = 0; pass < 8; ++pass) {
-      const int shift = 8 * pass;
-      tr.mark("k_tile_hist");
-      hipLaunchKernelGGL(k_tile_hist, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(256), 0, st, d_task_offsets, n_tasks,
-                         tiles, kin, shift, hist);
-      tr.mark("scan_tile_hist");
-      if (int rc = scan_u32(hist, n_big_tiles * 256, sums, nullptr, st)) return rc;
-      tr.mark("k_tile_scatter");
-      hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets,
-                         n_tasks, tiles, hist, shift, kin, kout, ein, eout, gin, gout);
-      FIKIT_HIP(hipGetLastError());
-      kin = kout;
-      kout = (kout == k1) ? k2 : k1;
-      int64_t* t = ein; ein = eout; eout = t;
-      t = gin; gin = gout; gout = t;
+  if (any_general) {
+    // General path: per-launch values in memory, sort by ID, find the segment heads.
+    if (h.n_long > 0) {
+      tr.mark("k_hash_measure");
+      hipLaunchKernelGGL(k_hash_measure, dim3(blocks_for(n, HASH_BLOCK)), dim3(HASH_BLOCK), 0, st, d_records, n, ids, e0, g0, ctrl);
+      hipLaunchKernelGGL(k_mark_task_ends, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, g0, ctrl);
     }
+    tr.mark("plan");
+    hipLaunchKernelGGL(k_plan_tiles, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st,
+                       d_task_offsets, n_tasks, gflag, tiles, ctrl);
+    if (int rc = scan_u32(tiles, static_cast<uint64_t>(n_tasks) + 1, sums, &ctrl->n_big_tiles, st)) return rc;
+    tr.mark("host_sync");
+    if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+    if (int rc = status_from_bits(h.status)) return rc;
+    const uint64_t n_big_tiles = h.n_big_tiles;
+    if (n_big_tiles > L.max_tiles) return FIKIT_HIP_ERROR;  // cannot happen for valid offsets
+
+    // sorted keys end in k2, payload in e0 / g0
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_leaf_sort), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  static_cast<int>(sizeof(LeafSmem))));
+    tr.mark("k_leaf_sort");
+    hipLaunchKernelGGL(k_leaf_sort, dim3(n_tasks), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, gflag, ids,
+                       k2, e0, g0, ctrl);
+    FIKIT_HIP(hipGetLastError());
+    if (n_big_tiles > 0) {
+      const uint64_t* kin = ids;
+      uint64_t* kout = k1;
+      int64_t *ein = e0, *eout = e1, *gin = g0, *gout = g1;
+      for (int pass = 0; pass < 8; ++pass) {
+        const int shift = 8 * pass;
+        tr.mark("k_tile_hist");
+        hipLaunchKernelGGL(k_tile_hist, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(256), 0, st, d_task_offsets, n_tasks,
+                           tiles, kin, shift, hist);
+        tr.mark("scan_tile_hist");
+        if (int rc = scan_u32(hist, n_big_tiles * 256, sums, nullptr, st)) return rc;
+        tr.mark("k_tile_scatter");
+        hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets,
+                           n_tasks, tiles, hist, shift, kin, kout, ein, eout, gin, gout);
+        FIKIT_HIP(hipGetLastError());
+        kin = kout;
+        kout = (kout == k1) ? k2 : k1;
+        int64_t* t = ein; ein = eout; eout = t;
+        t = gin; gin = gout; gout = t;
+      }
+    }
+    tr.mark("heads");
+    hipLaunchKernelGGL(k_head_bits, dim3(blocks_for(n, 256)), dim3(256), 0, st, k2, n, d_task_offsets, n_tasks, gflag, bits);
+    hipLaunchKernelGGL(k_popcount_words, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, L.n_words, word_prefix);
+    if (int rc = scan_u32(word_prefix, L.n_words, sums, &ctrl->n_heads, st)) return rc;
+    tr.mark("host_sync");
+    if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+    n_heads = h.n_heads;
+    tr.mark("heads");
+    hipLaunchKernelGGL(k_general_row_counts, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, gflag,
+                       bits, word_prefix, n, static_cast<uint32_t>(n_heads), dcount);
   }
 
-  // Segment heads -> number of rows and where each row's launches start.
-  uint64_t* bits = reinterpret_cast<uint64_t*>(ws + L.bits);
-  uint32_t* word_prefix = reinterpret_cast<uint32_t*>(ws + L.word_prefix);
-  uint32_t* seg_start = reinterpret_cast<uint32_t*>(e1);
-  tr.mark("heads");
-  hipLaunchKernelGGL(k_head_bits, dim3(blocks_for(n, 256)), dim3(256), 0, st, k2, n, bits);
-  hipLaunchKernelGGL(k_task_head_bits, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, bits, ctrl);
-  hipLaunchKernelGGL(k_popcount_words, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, L.n_words, word_prefix);
-  if (int rc = scan_u32(word_prefix, L.n_words, sums, &ctrl->n_rows, st)) return rc;
+  // Row offsets of every task, and the total.
+  tr.mark("row_offsets");
+  if (int rc = scan_u32(dcount, static_cast<uint64_t>(n_tasks) + 1, sums, &ctrl->n_rows, st)) return rc;
+  hipLaunchKernelGGL(k_widen_offsets, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st, dcount,
+                     static_cast<uint64_t>(n_tasks) + 1, d_task_row_offsets);
   tr.mark("host_sync");
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   const uint64_t n_rows = h.n_rows;
   *h_n_rows = n_rows;
   if (n_rows > row_capacity) return FIKIT_ROW_CAPACITY;
 
-  tr.mark("seg_starts");
-  hipLaunchKernelGGL(k_seg_starts, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, word_prefix, L.n_words, n, n_rows,
-                     seg_start);
-  hipLaunchKernelGGL(k_task_row_offsets, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st,
-                     d_task_offsets, n_tasks, bits, word_prefix, n, n_rows, d_task_row_offsets);
-  tr.mark("k_stats_small");
-  hipLaunchKernelGGL(k_stats_small, dim3(blocks_for(n_rows, 4)), dim3(256), 0, st, seg_start, n_rows, d_task_offsets, n_tasks,
-                     k2, e0, g0, d_rows_out);
-  tr.mark("k_stats_big");
-  hipLaunchKernelGGL(k_stats_big, dim3(static_cast<uint32_t>(n_rows)), dim3(BIG_THREADS), 0, st, seg_start, n_rows,
-                     d_task_offsets, n_tasks, k2, e0, g0, d_rows_out);
+  tr.mark("k_gather_rows");
+  hipLaunchKernelGGL(k_gather_rows, dim3(n_tasks), dim3(256), 0, st, d_task_offsets, dcount, gflag, e1, g1, d_rows_out);
+  if (any_general && n_heads > 0) {
+    tr.mark("seg_starts");
+    hipLaunchKernelGGL(k_seg_starts, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, word_prefix, L.n_words, n, n_heads,
+                       seg_start);
+    tr.mark("k_stats_small");
+    hipLaunchKernelGGL(k_stats_small, dim3(blocks_for(n_heads, 4)), dim3(256), 0, st, seg_start, n_heads, d_task_offsets,
+                       n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out);
+    tr.mark("k_stats_big");
+    hipLaunchKernelGGL(k_stats_big, dim3(static_cast<uint32_t>(n_heads)), dim3(BIG_THREADS), 0, st, seg_start, n_heads,
+                       d_task_offsets, n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out);
+  }
   FIKIT_HIP(hipGetLastError());
   FIKIT_HIP(hipStreamSynchronize(st));
   return FIKIT_OK;

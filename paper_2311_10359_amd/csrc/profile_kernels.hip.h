@@ -33,6 +33,22 @@ __global__ void k_validate_offsets(const uint64_t* __restrict__ off, uint32_t n_
   if (bad) atomicOr(&ctrl->status, ERR_OFFSETS);
 }
 
+// Tasks longer than max_fused launches take the general sort-based path from the start.
+__global__ void k_classify(const uint64_t* __restrict__ off, uint32_t n_tasks, uint32_t max_fused, uint32_t* __restrict__ gflag,
+                           uint32_t* __restrict__ dcount, Ctrl* ctrl) {
+  if (ctrl->status & ERR_OFFSETS) return;
+  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (t > n_tasks) return;
+  dcount[t] = 0;
+  if (t == n_tasks) return;
+  const bool is_long = (off[t + 1] - off[t]) > max_fused;
+  gflag[t] = is_long ? 1u : 0u;
+  if (is_long) {
+    atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), 1ull);
+    atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_long), 1ull);
+  }
+}
+
 // FNV-1a, 64 bit, over the eight little-endian 32-bit words that hold a launch's identity
 // (name id, grid x y z, block x y z, dynamic shared-memory bytes): for each byte in memory
 // order, xor it into the hash, then multiply by the FNV prime 2^40 + 0x1b3 modulo 2^64.

@@ -73,16 +73,17 @@ constexpr int TILE_THREADS = 512;
 constexpr int TILE_WAVES = TILE_THREADS / WAVE;
 constexpr int TILE_KPT = TILE / TILE_THREADS;
 
-// tiles[t] = number of tiles task t contributes to the multi-pass path (0 for LDS-sorted tasks).
+// tiles[t] = number of tiles task t contributes to the multi-pass path (0 for LDS-sorted tasks and
+// for tasks that do not take the general path at all).
 // tiles has n_tasks + 1 entries; the last is 0 so that an exclusive scan leaves the total there.
-__global__ void k_plan_tiles(const uint64_t* __restrict__ off, uint32_t n_tasks, uint32_t* __restrict__ tiles,
-                             const Ctrl* ctrl) {
+__global__ void k_plan_tiles(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ gflag,
+                             uint32_t* __restrict__ tiles, const Ctrl* ctrl) {
   const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (t > n_tasks) return;
   uint32_t v = 0;
   if (t < n_tasks && !(ctrl->status & ERR_OFFSETS)) {
     const uint64_t len = off[t + 1] - off[t];
-    if (len > LEAF) v = static_cast<uint32_t>((len + TILE - 1) / TILE);
+    if (gflag[t] && len > LEAF) v = static_cast<uint32_t>((len + TILE - 1) / TILE);
   }
   tiles[t] = v;
 }
@@ -159,13 +160,14 @@ struct LeafSmem {
 };
 
 __global__ void __launch_bounds__(LEAF_THREADS)
-k_leaf_sort(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint64_t* __restrict__ ids,
+k_leaf_sort(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ gflag, const uint64_t* __restrict__ ids,
             uint64_t* __restrict__ key_out, int64_t* __restrict__ exec_io, int64_t* __restrict__ gap_io,
             const Ctrl* ctrl) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   LeafSmem& sm = *reinterpret_cast<LeafSmem*>(smem_raw);
   if (ctrl->status & ERR_OFFSETS) return;
   const uint32_t t = blockIdx.x;
+  if (!gflag[t]) return;
   const uint64_t base = off[t];
   const uint64_t len64 = off[t + 1] - base;
   if (len64 == 0 || len64 > LEAF) return;

@@ -9,25 +9,24 @@
 namespace fikit {
 
 // ------------------------------------------------------------------ segment heads
-// One bit per sorted position: set where a new (task, ID) group begins.  A wave produces one
-// 64-bit word with a ballot of "my key differs from my left neighbour's".
+// One bit per sorted position: set where a new (task, ID) group of a general-path task begins
+// (positions of other tasks give 0).  A wave produces one 64-bit word with a ballot of "I start a
+// task, or my key differs from my left neighbour's".
 __global__ void __launch_bounds__(256)
-k_head_bits(const uint64_t* __restrict__ key, uint64_t n, uint64_t* __restrict__ bits) {
+k_head_bits(const uint64_t* __restrict__ key, uint64_t n, const uint64_t* __restrict__ off, uint32_t n_tasks,
+            const uint32_t* __restrict__ gflag, uint64_t* __restrict__ bits) {
   const uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const uint64_t first = i - lane_id();  // the wave's first position (same in every lane)
   bool head = false;
-  if (i < n) head = (i == 0) || (key[i] != key[i - 1]);
+  if (first < n) {
+    uint32_t t = task_of(off, n_tasks, first);
+    if (i < n) {
+      while (off[t + 1] <= i) ++t;      // step over task boundaries inside the wave's window
+      if (gflag[t]) head = (i == off[t]) || (key[i] != key[i - 1]);
+    }
+  }
   const uint64_t word = ballot(head);
   if (lane_id() == 0 && (i < n)) bits[i >> 6] = word;
-}
-
-// Task starts are heads too (two neighbouring tasks may end and begin with the same ID).
-__global__ void k_task_head_bits(const uint64_t* __restrict__ off, uint32_t n_tasks, uint64_t* __restrict__ bits,
-                                 const Ctrl* ctrl) {
-  if (ctrl->status & ERR_OFFSETS) return;
-  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (t >= n_tasks) return;
-  const uint64_t a = off[t], b = off[t + 1];
-  if (b > a) atomicOr(reinterpret_cast<unsigned long long*>(&bits[a >> 6]), 1ull << (a & 63));
 }
 
 __global__ void k_popcount_words(const uint64_t* __restrict__ bits, uint64_t n_words, uint32_t* __restrict__ out) {
@@ -50,25 +49,21 @@ __global__ void k_seg_starts(const uint64_t* __restrict__ bits, const uint32_t* 
   }
 }
 
-// task_row_offsets[t] = number of heads before position off[t].
-__global__ void k_task_row_offsets(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint64_t* __restrict__ bits,
-                                   const uint32_t* __restrict__ word_prefix, uint64_t n, uint64_t n_rows,
-                                   uint64_t* __restrict__ task_row_offsets) {
+// Row count of every general-path task: heads inside its range of sorted positions.
+__global__ void k_general_row_counts(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ gflag,
+                                     const uint64_t* __restrict__ bits, const uint32_t* __restrict__ word_prefix, uint64_t n,
+                                     uint32_t n_heads, uint32_t* __restrict__ dcount) {
   const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (t > n_tasks) return;
-  const uint64_t pos = off[t];
-  uint64_t r = n_rows;
-  if (pos < n) {
-    const uint64_t w = pos >> 6;
-    const uint64_t below = bits[w] & ((1ull << (pos & 63)) - 1ull);
-    r = word_prefix[w] + static_cast<uint32_t>(__popcll(below));
-  }
-  task_row_offsets[t] = r;
+  if (t >= n_tasks || !gflag[t]) return;
+  dcount[t] = heads_before(bits, word_prefix, n, n_heads, off[t + 1]) - heads_before(bits, word_prefix, n, n_heads, off[t]);
+}
+
+__global__ void k_widen_offsets(const uint32_t* __restrict__ in, uint64_t count, uint64_t* __restrict__ out) {
+  const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < count) out[i] = in[i];
 }
 
 // ------------------------------------------------------------------ rows
-// Nearest rank: the ceil(K * count / 100)-th smallest, as a 0-based index.
-__device__ __forceinline__ uint64_t rank_index(uint64_t k, uint64_t count) { return (k * count + 99) / 100 - 1; }
 
 struct StatsAcc {
   uint64_t count, sum, mn, mx, p50, p95;
@@ -128,10 +123,15 @@ __device__ __forceinline__ StatsAcc wave_stats_le64(uint64_t v, bool valid, uint
 __global__ void __launch_bounds__(256)
 k_stats_small(const uint32_t* __restrict__ seg_start, uint64_t n_rows, const uint64_t* __restrict__ off, uint32_t n_tasks,
               const uint64_t* __restrict__ key, const int64_t* __restrict__ exec, const int64_t* __restrict__ gap,
-              fikit_row* __restrict__ rows) {
+              const uint64_t* __restrict__ bits, const uint32_t* __restrict__ word_prefix, uint64_t n,
+              const uint32_t* __restrict__ row_off32, fikit_row* __restrict__ rows) {
   const uint64_t r = static_cast<uint64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   if (r >= n_rows) return;
-  const uint32_t s = seg_start[r], e = seg_start[r + 1];
+  const uint32_t s = seg_start[r];
+  const uint32_t task = task_of(off, n_tasks, s);
+  // the next head may lie beyond tasks that do not take this path: a segment ends with its task
+  const uint64_t task_end = off[task + 1];
+  const uint32_t e = seg_start[r + 1] < task_end ? seg_start[r + 1] : static_cast<uint32_t>(task_end);
   const uint32_t m = e - s;
   if (m > 64) return;
   const uint32_t lane = lane_id();
@@ -141,8 +141,9 @@ k_stats_small(const uint32_t* __restrict__ seg_start, uint64_t n_rows, const uin
   const StatsAcc es = wave_stats_le64(ev, in, m);
   const StatsAcc gs = wave_stats_le64(static_cast<uint64_t>(gv), in && gv != GAP_NONE, m);
   const uint64_t id = key[s];
-  const uint32_t task = task_of(off, n_tasks, s);
-  write_row(rows + r, id, task, es, gs);
+  // r counts general-path rows only; the row's final place is relative to its task's first row
+  const uint64_t dst = row_off32[task] + (r - heads_before(bits, word_prefix, n, static_cast<uint32_t>(n_rows), off[task]));
+  write_row(rows + dst, id, task, es, gs);
 }
 
 // ------------------------------------------------------------------ long segments
@@ -217,19 +218,23 @@ __device__ __forceinline__ StatsAcc block_stats(const int64_t* __restrict__ vals
 __global__ void __launch_bounds__(BIG_THREADS)
 k_stats_big(const uint32_t* __restrict__ seg_start, uint64_t n_rows, const uint64_t* __restrict__ off, uint32_t n_tasks,
             const uint64_t* __restrict__ key, const int64_t* __restrict__ exec, const int64_t* __restrict__ gap,
-            fikit_row* __restrict__ rows) {
+            const uint64_t* __restrict__ bits, const uint32_t* __restrict__ word_prefix, uint64_t n,
+            const uint32_t* __restrict__ row_off32, fikit_row* __restrict__ rows) {
   __shared__ BigSmem sm;
   const uint64_t r = blockIdx.x;
   if (r >= n_rows) return;
-  const uint32_t s = seg_start[r], e = seg_start[r + 1];
+  const uint32_t s = seg_start[r];
+  const uint32_t task = task_of(off, n_tasks, s);
+  const uint64_t task_end = off[task + 1];
+  const uint32_t e = seg_start[r + 1] < task_end ? seg_start[r + 1] : static_cast<uint32_t>(task_end);
   const uint32_t m = e - s;
   if (m <= 64) return;
   const StatsAcc es = block_stats(exec + s, m, false, sm);
   const StatsAcc gs = block_stats(gap + s, m, true, sm);
   if (threadIdx.x < 64) {
     const uint64_t id = key[s];
-    const uint32_t task = task_of(off, n_tasks, s);
-    write_row(rows + r, id, task, es, gs);
+    const uint64_t dst = row_off32[task] + (r - heads_before(bits, word_prefix, n, static_cast<uint32_t>(n_rows), off[task]));
+    write_row(rows + dst, id, task, es, gs);
   }
 }
 
