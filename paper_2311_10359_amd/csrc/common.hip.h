@@ -78,6 +78,11 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
   for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, WAVE);
   return v;
 }
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) { uint32_t o = __shfl_xor(v, m, WAVE); v = o > v ? o : v; }
+  return v;
+}
 __device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) { uint64_t o = shfl_xor_u64(v, m); v = o < v ? o : v; }

@@ -237,9 +237,10 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   hipLaunchKernelGGL(k_classify, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st, d_task_offsets,
                      n_tasks, FUSE_MAX, gflag, dcount, ctrl);
   {
-    auto small = k_task_fused<256, 16, 256, 7168>;
-    auto medium = k_task_fused<1024, 16, 512, 16384>;
-    constexpr size_t small_lds = sizeof(FusedSmem<256, 256, 7168>), medium_lds = sizeof(FusedSmem<1024, 512, 16384>);
+    auto small = k_task_fused<256, 16, 256, 7168, 4>;
+    auto medium = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2>;
+    constexpr size_t small_lds = sizeof(FusedSmem<256, 256, 7168>),
+                     medium_lds = sizeof(FusedSmem<FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST>);
     FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   static_cast<int>(small_lds)));
     FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(medium), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -248,7 +249,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     hipLaunchKernelGGL(small, dim3(n_tasks), dim3(256), small_lds, st, d_records, d_task_offsets, 1u, FUSE_SMALL_MAX, ids, e0,
                        g0, e1, g1, dcount, gflag, ctrl);
     tr.mark("k_task_fused_medium");
-    hipLaunchKernelGGL(medium, dim3(n_tasks), dim3(1024), medium_lds, st, d_records, d_task_offsets, FUSE_SMALL_MAX + 1,
+    hipLaunchKernelGGL(medium, dim3(n_tasks), dim3(FUSE_M_THREADS), medium_lds, st, d_records, d_task_offsets, FUSE_SMALL_MAX + 1,
                        FUSE_MAX, ids, e0, g0, e1, g1, dcount, gflag, ctrl);
     FIKIT_HIP(hipGetLastError());
   }

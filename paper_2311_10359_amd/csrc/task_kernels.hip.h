@@ -4,7 +4,10 @@
 // One workgroup reads a task's launch records once, and produces its rows without ever writing
 // per-launch intermediates to memory:
 //   1. Kernel ID (Section 3.2 "Identifying each kernel"), execution time K and idle time G of
-//      every launch stay in registers; the IDs are also written out in launch order.
+//      every launch stay in registers; the IDs are also written out in launch order.  Because
+//      a task keeps launching the same few kernels, the hash of an identity (32 bytes) is
+//      computed once and remembered in LDS under a cheap tag; later launches with the same 32
+//      bytes (compared in full) reuse it.
 //   2. The task's set of unique IDs (S_UID, Section 3.2) is built in an LDS hash table, then
 //      ranked so that rows come out in ascending ID order.
 //   3. count / sum / min / max per ID (sum / count = SK_j, SG_j of Section 3.2) by LDS atomics.
@@ -26,7 +29,16 @@ namespace fikit {
 
 constexpr uint64_t HT_EMPTY = ~0ull;
 constexpr uint32_t FUSE_SMALL_MAX = 4096;    // tasks up to this many launches: 256-thread workgroup
-constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: 1024-thread workgroup
+constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: one larger workgroup
+#ifndef FUSE_M_THREADS_V
+#define FUSE_M_THREADS_V 1024
+#define FUSE_M_DMAX_V 512
+#define FUSE_M_HIST_V 16384
+#endif
+#ifndef FUSE_ATTR
+#define FUSE_ATTR
+#endif
+constexpr int FUSE_M_THREADS = FUSE_M_THREADS_V, FUSE_M_DMAX = FUSE_M_DMAX_V, FUSE_M_HIST = FUSE_M_HIST_V;
 
 template <int NT>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* aux, uint32_t& total) {
@@ -47,27 +59,42 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* aux, u
   return base + incl - v;
 }
 
+// One remembered kernel identity: the 32 identity bytes, the Kernel ID they hash to and the
+// slot that ID occupies in the ID table.  `ready` holds the entry's tag once the rest is valid.
+struct MemoEntry {
+  uint32_t w[8];
+  uint64_t id;
+  uint32_t slot;
+  uint32_t ready;
+};
+static_assert(sizeof(MemoEntry) == 48, "memo entry is 48 bytes");
+
 template <int NT, int DMAX, int HIST_WORDS>
 struct FusedSmem {
   static constexpr int HT = 2 * DMAX;
-  uint64_t ht_key[HT];
-  uint32_t ht_cnt[HT];
-  uint16_t slot_rank[HT];
-  uint64_t rkey[DMAX];
-  uint32_t rcnt[DMAX];
-  uint32_t gcnt[DMAX];
-  uint64_t pref[4][DMAX];
-  uint16_t kth[4][DMAX];
+  uint64_t ht_key[HT];       // ID table (open addressing): the task's unique IDs
+  uint32_t ht_cnt[HT];       // launches per ID
+  uint16_t slot_rank[HT];    // slot -> rank of its ID among the task's IDs
+  uint64_t rkey[DMAX];       // by rank: the ID
+  uint32_t rcnt[DMAX];       //          number of execution-time samples
+  uint32_t gcnt[DMAX];       //          number of idle-time samples
+  uint4 pref[DMAX];          // radix selection: digits fixed so far (x exec p50, y exec p95, z gap p50, w gap p95)
+  uint16_t kth[4][DMAX];     //                  rank still to find inside the current candidates
+  uint8_t npass[2][DMAX];    //                  passes this ID's execution / idle times need (from their max)
+  uint32_t memo_claim[HT];   // 0 = free, else the tag of the claiming identity
   union {
-    struct { uint64_t ckey[DMAX]; uint32_t cslot[DMAX]; } tmp;
-    struct { uint64_t esum[DMAX], emin[DMAX], emax[DMAX], gsum[DMAX], gmin[DMAX], gmax[DMAX]; } acc;
-    uint32_t hist[HIST_WORDS];
+    MemoEntry memo[HT];      // phase 1
+    struct { uint64_t ckey[DMAX]; uint32_t cslot[DMAX]; } tmp;   // phase 2
+    struct { uint64_t esum[DMAX], gsum[DMAX]; uint32_t emin[DMAX], emax[DMAX], gmin[DMAX], gmax[DMAX]; } acc;  // phase 3
+    uint32_t hist[HIST_WORDS];  // phase 4
   } u;
-  uint64_t maxv;
   uint32_t aux[NT / WAVE];
+  uint32_t maxe, maxg;
   uint32_t ndist;
   uint32_t fallback;
 };
+
+constexpr uint32_t NONE32 = 0xffffffffu;   // "no idle time after this launch" in the 32-bit value registers
 
 // Where row j of a task is staged: the task's slice of stage_a, then its slice of stage_b.
 __device__ __forceinline__ uint64_t* staged_row(int64_t* stage_a, int64_t* stage_b, uint64_t base, uint32_t m, uint32_t j) {
@@ -76,8 +103,22 @@ __device__ __forceinline__ uint64_t* staged_row(int64_t* stage_a, int64_t* stage
                   : reinterpret_cast<uint64_t*>(stage_b + base) + static_cast<uint64_t>(j - cap1) * 16;
 }
 
-template <int NT, int KPT, int DMAX, int HIST_WORDS>
-__global__ void __launch_bounds__(NT)
+__device__ __forceinline__ uint32_t rotl32(uint32_t x, int k) { return (x << k) | (x >> (32 - k)); }
+
+// Cheap, non-zero tag of the identity words; only used to find the remembered entry quickly.
+__device__ __forceinline__ uint32_t identity_tag(const uint32_t (&w)[8]) {
+  uint32_t t = w[0] ^ rotl32(w[1], 5) ^ rotl32(w[2], 11) ^ rotl32(w[3], 17) ^ rotl32(w[4], 23) ^ rotl32(w[5], 29) ^
+               rotl32(w[6], 3) ^ rotl32(w[7], 13);
+  t ^= t >> 15;
+  t = t * 0x2c1b3c6du;
+  t ^= t >> 13;
+  return t | 1u;
+}
+
+// Values are kept as 32-bit numbers in registers (a task with an execution or idle time of
+// 2^32 - 1 ns or more takes the general path), KPT launches per thread.
+template <int NT, int KPT, int DMAX, int HIST_WORDS, int LB>
+__global__ void __launch_bounds__(NT) FUSE_ATTR
 k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ off, uint32_t min_len, uint32_t max_len,
              uint64_t* __restrict__ ids, int64_t* __restrict__ e0, int64_t* __restrict__ g0,
              int64_t* __restrict__ stage_a, int64_t* __restrict__ stage_b, uint32_t* __restrict__ dcount,
@@ -94,78 +135,175 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
   const uint32_t m = static_cast<uint32_t>(len64);
   const uint32_t tid = threadIdx.x;
 
-  for (uint32_t i = tid; i < HT; i += NT) { sm.ht_key[i] = HT_EMPTY; sm.ht_cnt[i] = 0; }
-  if (tid == 0) { sm.ndist = 0; sm.fallback = 0; sm.maxv = 0; }
+  for (uint32_t i = tid; i < HT; i += NT) {
+    sm.ht_key[i] = HT_EMPTY; sm.ht_cnt[i] = 0; sm.memo_claim[i] = 0; sm.u.memo[i].ready = 0;
+  }
+  if (tid == 0) { sm.ndist = 0; sm.fallback = 0; sm.maxe = 0; sm.maxg = 0; }
   __syncthreads();
 
-  // ---- 1. read, hash, measure; 2a. insert IDs ---------------------------------------------
-  uint64_t ev[KPT], gv[KPT];   // execution time, idle time (GAP_NONE for the task's last launch)
-  uint32_t sl[KPT];            // hash slot, later the rank of the launch's ID
-  uint64_t my_max = 0;
-  bool bad = false;
+  // ---- 1. read, identify, measure ------------------------------------------------------------
+  uint32_t ev[KPT], gv[KPT];   // execution time, idle time (NONE32 for the task's last launch)
+  uint32_t sl[KPT];            // ID-table slot, later the rank of the launch's ID
+  uint32_t my_maxe = 0, my_maxg = 0;
+  bool bad = false, wide = false;
 #pragma unroll
-  for (int r = 0; r < KPT; ++r) {
-    ev[r] = 0; gv[r] = static_cast<uint64_t>(GAP_NONE); sl[r] = 0;
-    if (static_cast<uint32_t>(r) * NT < m) {
-      const uint32_t i = r * NT + tid;
-      if (i < m) {
-        const uint4* p = reinterpret_cast<const uint4*>(rec + base + i);
-        const uint4 a = p[0], b = p[1], c = p[2];
-        int64_t next_start = 0;
-        const bool has_next = (i + 1 < m);
-        if (has_next) next_start = rec[base + i + 1].start_ns;
-        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        const uint64_t id = kernel_id_of(w);
-        const int64_t start = static_cast<int64_t>((static_cast<uint64_t>(c.y) << 32) | c.x);
-        const int64_t end = static_cast<int64_t>((static_cast<uint64_t>(c.w) << 32) | c.z);
-        bad |= (end < start);
-        ev[r] = static_cast<uint64_t>(end - start);
-        if (has_next) { const int64_t g = next_start - end; gv[r] = static_cast<uint64_t>(g < 0 ? 0 : g); }
-        ids[base + i] = id;
-        my_max = ev[r] > my_max ? ev[r] : my_max;
-        if (has_next) my_max = gv[r] > my_max ? gv[r] : my_max;
-        // open addressing, linear probing; the ID is already a hash
-        uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (HT - 1);
-        bool placed = false;
-        if (id != HT_EMPTY) {
-          for (int probe = 0; probe < HT; ++probe) {
-            const uint64_t k = __hip_atomic_load(&sm.ht_key[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (k == id) { placed = true; break; }
-            if (k == HT_EMPTY) {
-              const uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(&sm.ht_key[h]), HT_EMPTY, id);
-              if (old == HT_EMPTY) { atomicAdd(&sm.ndist, 1u); placed = true; break; }
-              if (old == id) { placed = true; break; }
-            }
-            h = (h + 1) & (HT - 1);
-          }
+  for (int r = 0; r < KPT; ++r) { ev[r] = 0; gv[r] = NONE32; sl[r] = 0; }
+  // LB rounds of loads are issued before the first of them is used, to keep more bytes in flight
+#pragma unroll
+  for (int r0 = 0; r0 < KPT; r0 += LB) {
+    if (static_cast<uint32_t>(r0) * NT < m) {
+      uint4 qa[LB], qb[LB], qc[LB];
+      int64_t qn[LB];
+#pragma unroll
+      for (int u = 0; u < LB; ++u) {
+        const uint32_t i = (r0 + u) * NT + tid;
+        qa[u] = qb[u] = qc[u] = make_uint4(0, 0, 0, 0);
+        qn[u] = 0;
+        if (i < m) {
+          const uint4* p = reinterpret_cast<const uint4*>(rec + base + i);
+          qa[u] = p[0]; qb[u] = p[1]; qc[u] = p[2];
+          if (i + 1 < m) qn[u] = rec[base + i + 1].start_ns;
         }
-        if (placed) atomicAdd(&sm.ht_cnt[h], 1u); else atomicOr(&sm.fallback, 1u);
-        sl[r] = h;
+      }
+#pragma unroll
+      for (int u = 0; u < LB; ++u) {
+        const int r = r0 + u;
+        const uint32_t i = r * NT + tid;
+        if (i < m) {
+          const uint4 a = qa[u], b = qb[u], c = qc[u];
+          const int64_t next_start = qn[u];
+          const bool has_next = (i + 1 < m);
+          const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+          const int64_t start = static_cast<int64_t>((static_cast<uint64_t>(c.y) << 32) | c.x);
+          const int64_t end = static_cast<int64_t>((static_cast<uint64_t>(c.w) << 32) | c.z);
+          bad |= (end < start);
+          const uint64_t e64 = static_cast<uint64_t>(end - start);
+          wide |= (e64 >= NONE32);
+          ev[r] = static_cast<uint32_t>(e64);
+          my_maxe = ev[r] > my_maxe ? ev[r] : my_maxe;
+          if (has_next) {
+            const int64_t g = next_start - end;
+            const uint64_t g64 = static_cast<uint64_t>(g < 0 ? 0 : g);
+            wide |= (g64 >= NONE32);
+            gv[r] = static_cast<uint32_t>(g64);
+            my_maxg = gv[r] > my_maxg ? gv[r] : my_maxg;
+          }
+          // Has this identity been seen before?  Then its Kernel ID and slot are remembered.
+          const uint32_t tag = identity_tag(w);
+          uint32_t mh = tag & (HT - 1);
+          uint64_t id = 0;
+          uint32_t slot = 0;
+          bool hit = false;
+#pragma unroll 1
+          for (int probe = 0; probe < 4; ++probe) {
+            const uint32_t rd = __hip_atomic_load(&sm.u.memo[mh].ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (rd == tag) {
+              const uint4 ma = *reinterpret_cast<const uint4*>(&sm.u.memo[mh].w[0]);
+              const uint4 mb = *reinterpret_cast<const uint4*>(&sm.u.memo[mh].w[4]);
+              if (ma.x == a.x && ma.y == a.y && ma.z == a.z && ma.w == a.w && mb.x == b.x && mb.y == b.y && mb.z == b.z &&
+                  mb.w == b.w) {
+                id = sm.u.memo[mh].id;
+                slot = sm.u.memo[mh].slot;
+                hit = true;
+                break;
+              }
+            } else if (rd == 0 && __hip_atomic_load(&sm.memo_claim[mh], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) {
+              break;  // free entry: this identity has not been remembered
+            }
+            mh = (mh + 1) & (HT - 1);
+          }
+          if (!hit) {
+            id = kernel_id_of(w);
+            // ID table: open addressing, linear probing; the ID is already a hash
+            uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (HT - 1);
+            bool placed = false;
+            if (id != HT_EMPTY) {
+              for (int probe = 0; probe < HT; ++probe) {
+                const uint64_t k = __hip_atomic_load(&sm.ht_key[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (k == id) { placed = true; break; }
+                if (k == HT_EMPTY) {
+                  const uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(&sm.ht_key[h]), HT_EMPTY, id);
+                  if (old == HT_EMPTY) { atomicAdd(&sm.ndist, 1u); placed = true; break; }
+                  if (old == id) { placed = true; break; }
+                }
+                h = (h + 1) & (HT - 1);
+              }
+            }
+            if (!placed) atomicOr(&sm.fallback, 1u);
+            slot = h;
+            // remember it: claim a free entry near the tag's home, fill it, then publish the tag
+            if (placed) {
+              uint32_t ch = tag & (HT - 1);
+#pragma unroll 1
+              for (int probe = 0; probe < 4; ++probe) {
+                const uint32_t old = atomicCAS(&sm.memo_claim[ch], 0u, tag);
+                if (old == 0) {
+                  MemoEntry& me = sm.u.memo[ch];
+                  *reinterpret_cast<uint4*>(&me.w[0]) = a;
+                  *reinterpret_cast<uint4*>(&me.w[4]) = b;
+                  me.id = id;
+                  me.slot = slot;
+                  __hip_atomic_store(&me.ready, tag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                  break;
+                }
+                if (old == tag) {
+                  // same tag: the same identity is being (or has been) remembered by someone else, or a
+                  // different identity shares the tag; either way leave this one out if it is the former
+                  const uint32_t rd = __hip_atomic_load(&sm.u.memo[ch].ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                  if (rd == 0) break;  // being written right now: do not wait for it
+                  const uint4 ma = *reinterpret_cast<const uint4*>(&sm.u.memo[ch].w[0]);
+                  const uint4 mb = *reinterpret_cast<const uint4*>(&sm.u.memo[ch].w[4]);
+                  if (ma.x == a.x && ma.y == a.y && ma.z == a.z && ma.w == a.w && mb.x == b.x && mb.y == b.y &&
+                      mb.z == b.z && mb.w == b.w)
+                    break;
+                }
+                ch = (ch + 1) & (HT - 1);
+              }
+            }
+          }
+          ids[base + i] = id;
+          atomicAdd(&sm.ht_cnt[slot], 1u);
+          sl[r] = slot;
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
   if (bad) atomicOr(&ctrl->status, ERR_BAD_RECORD);
-  my_max = wave_max_u64(my_max);
-  if (lane_id() == 0) atomicMax(reinterpret_cast<unsigned long long*>(&sm.maxv), my_max);
+  if (wide) atomicOr(&sm.fallback, 1u);
+  my_maxe = wave_max_u32(my_maxe);
+  my_maxg = wave_max_u32(my_maxg);
+  if (lane_id() == 0) { atomicMax(&sm.maxe, my_maxe); atomicMax(&sm.maxg, my_maxg); }
   __syncthreads();
   const uint32_t D = sm.ndist;
   if (sm.fallback || D > DMAX || D > 2 * (m >> 4)) {
-    // general path: hand over the per-launch values
-#pragma unroll
-    for (int r = 0; r < KPT; ++r) {
-      const uint32_t i = r * NT + tid;
-      if (i < m) { e0[base + i] = static_cast<int64_t>(ev[r]); g0[base + i] = static_cast<int64_t>(gv[r]); }
+    // general path: hand over the per-launch values (recomputed at full width)
+    for (uint32_t i = tid; i < m; i += NT) {
+      const fikit_launch* q = rec + base + i;
+      const int64_t end = q->end_ns;
+      e0[base + i] = end - q->start_ns;
+      int64_t g = GAP_NONE;
+      if (i + 1 < m) { g = q[1].start_ns - end; g = g < 0 ? 0 : g; }
+      g0[base + i] = g;
     }
     if (tid == 0) { gflag[t] = 1; atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), 1ull); }
     return;
   }
 
-  // ---- 2b. rank the distinct IDs -----------------------------------------------------------
+  // digit width of the radix selection: 16-bit counters, two per word, shared by 4 * D (ID, percentile) pairs
+  int B = 31 - __builtin_clz(static_cast<uint32_t>(HIST_WORDS * 2) / (4 * D));
+  B = B > 8 ? 8 : B;
+  // the fast percentile path keeps one histogram per (ID, array) instead of four: its bins can be twice as fine
+  // (bin numbers must stay below 0xff, which marks "no samples")
+  int B1 = (static_cast<uint32_t>(HIST_WORDS * 2) >> (B + 1)) >= 2 * D ? B + 1 : B;
+  B1 = B1 > 7 ? 7 : B1;
+
+  // ---- 2. rank the distinct IDs --------------------------------------------------------------
   {
     uint32_t mine = 0;
     for (uint32_t s = tid; s < HT; s += NT) mine += (sm.ht_key[s] != HT_EMPTY);
     uint32_t total;
-    uint32_t at = block_excl_scan<NT>(mine, sm.aux, total);
+    uint32_t at = block_excl_scan<NT>(mine, sm.aux, total);   // (memo is dead after the barriers inside)
     for (uint32_t s = tid; s < HT; s += NT)
       if (sm.ht_key[s] != HT_EMPTY) { sm.u.tmp.ckey[at] = sm.ht_key[s]; sm.u.tmp.cslot[at] = s; ++at; }
     __syncthreads();
@@ -182,12 +320,12 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
   }
 #pragma unroll
   for (int r = 0; r < KPT; ++r) sl[r] = sm.slot_rank[sl[r]];
-  __syncthreads();  // tmp (ckey/cslot) is dead from here on; acc reuses the space
+  __syncthreads();  // tmp is dead from here on; acc reuses the space
 
-  // ---- 3. count / sum / min / max per ID ----------------------------------------------------
+  // ---- 3. count / sum / min / max per ID ------------------------------------------------------
   for (uint32_t j = tid; j < D; j += NT) {
-    sm.u.acc.esum[j] = 0; sm.u.acc.emin[j] = ~0ull; sm.u.acc.emax[j] = 0;
-    sm.u.acc.gsum[j] = 0; sm.u.acc.gmin[j] = ~0ull; sm.u.acc.gmax[j] = 0;
+    sm.u.acc.esum[j] = 0; sm.u.acc.emin[j] = ~0u; sm.u.acc.emax[j] = 0;
+    sm.u.acc.gsum[j] = 0; sm.u.acc.gmin[j] = ~0u; sm.u.acc.gmax[j] = 0;
     sm.gcnt[j] = 0;
   }
   __syncthreads();
@@ -196,14 +334,14 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
     const uint32_t i = r * NT + tid;
     if (i < m) {
       const uint32_t j = sl[r];
-      atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.esum[j]), ev[r]);
-      atomicMin(reinterpret_cast<unsigned long long*>(&sm.u.acc.emin[j]), ev[r]);
-      atomicMax(reinterpret_cast<unsigned long long*>(&sm.u.acc.emax[j]), ev[r]);
-      if (gv[r] != static_cast<uint64_t>(GAP_NONE)) {
+      atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.esum[j]), static_cast<unsigned long long>(ev[r]));
+      atomicMin(&sm.u.acc.emin[j], ev[r]);
+      atomicMax(&sm.u.acc.emax[j], ev[r]);
+      if (gv[r] != NONE32) {
         atomicAdd(&sm.gcnt[j], 1u);
-        atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.gsum[j]), gv[r]);
-        atomicMin(reinterpret_cast<unsigned long long*>(&sm.u.acc.gmin[j]), gv[r]);
-        atomicMax(reinterpret_cast<unsigned long long*>(&sm.u.acc.gmax[j]), gv[r]);
+        atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.gsum[j]), static_cast<unsigned long long>(gv[r]));
+        atomicMin(&sm.u.acc.gmin[j], gv[r]);
+        atomicMax(&sm.u.acc.gmax[j], gv[r]);
       }
     }
   }
@@ -221,19 +359,211 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
     sm.kth[1][j] = static_cast<uint16_t>(rank_index_u32(95, ec));
     sm.kth[2][j] = static_cast<uint16_t>(gc ? rank_index_u32(50, gc) : 0);
     sm.kth[3][j] = static_cast<uint16_t>(gc ? rank_index_u32(95, gc) : 0);
-    sm.pref[0][j] = 0; sm.pref[1][j] = 0; sm.pref[2][j] = 0; sm.pref[3][j] = 0;
+    sm.pref[j] = make_uint4(0, 0, 0, 0);
+    const uint32_t mxe = sm.u.acc.emax[j], mxg = gc ? sm.u.acc.gmax[j] : 0;
+    {
+      // window of the fast percentile path: the ID's own value range, cut into 2^B1 bins
+      uint2* sel0 = reinterpret_cast<uint2*>(sm.ht_key);   // the ID table is dead by now
+      const uint32_t lo_e = sm.u.acc.emin[j], lo_g = gc ? sm.u.acc.gmin[j] : 0;
+      const uint32_t re = mxe - lo_e, rg = mxg - lo_g;
+      const uint32_t we = re ? 32 - __builtin_clz(re) : 0, wg = rg ? 32 - __builtin_clz(rg) : 0;
+      sel0[j] = make_uint2(lo_e, we > static_cast<uint32_t>(B1) ? we - B1 : 0);
+      sel0[D + j] = make_uint2(lo_g, wg > static_cast<uint32_t>(B1) ? wg - B1 : 0);
+    }
+    sm.npass[0][j] = static_cast<uint8_t>(((mxe ? 32 - __builtin_clz(mxe) : 1) + B - 1) / B);
+    sm.npass[1][j] = static_cast<uint8_t>(((mxg ? 32 - __builtin_clz(mxg) : 1) + B - 1) / B);
   }
   __syncthreads();  // acc is dead from here on; hist reuses the space
 
-  // ---- 4. nearest-rank percentiles by radix selection ---------------------------------------
-  for (uint32_t i = tid; i < HIST_WORDS; i += NT) sm.u.hist[i] = 0;
-  const uint64_t maxv = sm.maxv;
-  const int nbits = maxv ? 64 - __builtin_clzll(maxv) : 1;
-  // 16-bit counters, two per word: bins available per (ID, percentile) pair
-  int B = 31 - __builtin_clz(static_cast<uint32_t>(HIST_WORDS * 2) / (4 * D));
-  B = B > 8 ? 8 : B;
+  // ---- 4. nearest-rank percentiles ---------------------------------------------------------------
+  // Fast way: one histogram pass over each ID's own value range [min, max] (2^B bins), which
+  // tells in which bin the wanted rank lies; the few samples of that bin are then collected in
+  // a short list and ranked directly.  If some bin is too crowded for that (many equal or
+  // clustered samples), the general multi-pass radix selection below does the whole job instead.
+  // Tables of earlier phases are dead by now and are reused:
+  uint2* sel = reinterpret_cast<uint2*>(sm.ht_key);            // [2][DMAX]: x = window low end, y = shift | bin50 << 8 | bin95 << 16
+  uint16_t* lcnt = reinterpret_cast<uint16_t*>(sm.ht_cnt);     // [2][2][DMAX]: list lengths (array, list A / B, ID)
+  uint16_t* loff = reinterpret_cast<uint16_t*>(sm.memo_claim); // [2][2][DMAX]: list starts
+  constexpr uint32_t LIST_MAX = 64;
   const uint32_t bins = 1u << B;
-  const int passes = (nbits + B - 1) / B;
+  const uint32_t P2 = 2 * D;   // (ID, array) pairs
+  const uint32_t bins1 = 1u << B1;
+  for (uint32_t i = tid; i < HIST_WORDS; i += NT) sm.u.hist[i] = 0;
+  if (tid == 0) sm.fallback = 0;
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const uint32_t i = r * NT + tid;
+    if (i < m) {
+      uint32_t j = sl[r];
+      asm volatile("" : "+v"(j));
+      const uint2 se = sel[j];
+      const uint32_t de = (ev[r] - se.x) >> se.y;
+      atomicAdd(&sm.u.hist[__umul24(de >> 1, P2) + j], (de & 1u) ? 0x10000u : 1u);
+      if (gv[r] != NONE32) {
+        const uint2 sg = sel[D + j];
+        const uint32_t dg = (gv[r] - sg.x) >> sg.y;
+        atomicAdd(&sm.u.hist[__umul24(dg >> 1, P2) + D + j], (dg & 1u) ? 0x10000u : 1u);
+      }
+    }
+  }
+  __syncthreads();
+  for (uint32_t q = tid; q < P2; q += NT) {
+    const uint32_t arr = q >= D ? 1u : 0u, j = q - arr * D;
+    const uint32_t k50 = sm.kth[2 * arr][j], k95 = sm.kth[2 * arr + 1][j];
+    const uint32_t cnt_all = arr ? sm.gcnt[j] : sm.rcnt[j];
+    uint32_t cum = 0, d50 = 0, d95 = 0, n50 = 0, n95 = 0, c50 = 0, c95 = 0;
+    bool f50 = false, f95 = false;
+    for (uint32_t wd = 0; wd < (bins1 >> 1); ++wd) {
+      const uint32_t pair = sm.u.hist[wd * P2 + q];
+      sm.u.hist[wd * P2 + q] = 0;
+      const uint32_t c0 = pair & 0xffffu, c1 = pair >> 16;
+      if (!f50 && k50 < cum + c0) { f50 = true; d50 = 2 * wd; n50 = k50 - cum; c50 = c0; }
+      if (!f95 && k95 < cum + c0) { f95 = true; d95 = 2 * wd; n95 = k95 - cum; c95 = c0; }
+      cum += c0;
+      if (!f50 && k50 < cum + c1) { f50 = true; d50 = 2 * wd + 1; n50 = k50 - cum; c50 = c1; }
+      if (!f95 && k95 < cum + c1) { f95 = true; d95 = 2 * wd + 1; n95 = k95 - cum; c95 = c1; }
+      cum += c1;
+    }
+    const uint2 se = sel[q];
+    uint32_t la = 0, lb = 0;
+    if (cnt_all == 0) {
+      // no samples: both percentiles are 0, nothing to collect (bins 0xff never match a digit)
+      sel[q] = make_uint2(se.x, se.y | (0xffu << 8) | (0xffu << 16));
+    } else {
+      sel[q] = make_uint2(se.x, se.y | (d50 << 8) | (d95 << 16));
+      if (se.y != 0) {   // (bins one value wide: the bin is the answer, nothing to collect)
+        la = c50;
+        lb = (d95 != d50) ? c95 : 0;
+        if (la > LIST_MAX || lb > LIST_MAX) atomicOr(&sm.fallback, 1u);
+        sm.kth[2 * arr][j] = static_cast<uint16_t>(n50);
+        sm.kth[2 * arr + 1][j] = static_cast<uint16_t>(n95);
+      }
+    }
+    lcnt[(2 * arr) * DMAX + j] = static_cast<uint16_t>(la);
+    lcnt[(2 * arr + 1) * DMAX + j] = static_cast<uint16_t>(lb);
+  }
+  __syncthreads();
+  const bool use_lists = (sm.fallback == 0);
+  if (use_lists) {
+    // list starts: exclusive scan of the 4 * D list lengths (order: array, list, ID)
+    uint32_t carry = 0;
+    for (uint32_t q0 = 0; q0 < 4 * D; q0 += NT) {
+      const uint32_t q = q0 + tid;
+      uint32_t c = 0, at = 0;
+      if (q < 4 * D) { at = (q / D) * DMAX + (q % D); c = lcnt[at]; }
+      uint32_t total;
+      const uint32_t ex = block_excl_scan<NT>(c, sm.aux, total);
+      if (q < 4 * D) loff[at] = static_cast<uint16_t>(carry + ex);
+      carry += total;
+    }
+    // (4 * D lists of at most 64 samples: carry <= 4 * DMAX * 64 may exceed the space)
+    const bool fits = carry <= static_cast<uint32_t>(HIST_WORDS);
+    for (uint32_t j = tid; j < D; j += NT) {
+      // pref's four words serve as the four list cursors of an ID; results go elsewhere until the end
+      sm.pref[j] = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+    if (fits) {
+      uint32_t* lists = sm.u.hist;
+      uint32_t* cursor = reinterpret_cast<uint32_t*>(sm.pref);   // [ID][4]: exec A, exec B, gap A, gap B
+#pragma unroll
+      for (int r = 0; r < KPT; ++r) {
+        const uint32_t i = r * NT + tid;
+        if (i < m) {
+          uint32_t j = sl[r];
+          asm volatile("" : "+v"(j));
+          const uint2 se = sel[j];
+          const uint32_t sh = se.y & 0xffu;
+          if (sh) {
+            const uint32_t de = (ev[r] - se.x) >> sh, b50 = (se.y >> 8) & 0xffu, b95 = (se.y >> 16) & 0xffu;
+            if (de == b50) lists[loff[j] + atomicAdd(&cursor[4 * j], 1u)] = ev[r];
+            else if (de == b95) lists[loff[DMAX + j] + atomicAdd(&cursor[4 * j + 1], 1u)] = ev[r];
+          }
+          if (gv[r] != NONE32) {
+            const uint2 sg = sel[D + j];
+            const uint32_t shg = sg.y & 0xffu;
+            if (shg) {
+              const uint32_t dg = (gv[r] - sg.x) >> shg, b50 = (sg.y >> 8) & 0xffu, b95 = (sg.y >> 16) & 0xffu;
+              if (dg == b50) lists[loff[2 * DMAX + j] + atomicAdd(&cursor[4 * j + 2], 1u)] = gv[r];
+              else if (dg == b95) lists[loff[3 * DMAX + j] + atomicAdd(&cursor[4 * j + 3], 1u)] = gv[r];
+            }
+          }
+        }
+      }
+      __syncthreads();
+      // eight lanes per (ID, array): every lane ranks some of the collected samples by counting how
+      // many samples of the list precede them; the lane that finds the wanted rank writes the result
+      constexpr uint32_t GS = 8;
+      const uint32_t gl = tid % GS;
+      for (uint32_t q = tid / GS; q < P2; q += NT / GS) {
+        const uint32_t arr = q >= D ? 1u : 0u, j = q - arr * D;
+        const uint2 se = sel[q];
+        const uint32_t sh = se.y & 0xffu, b50 = (se.y >> 8) & 0xffu, b95 = (se.y >> 16) & 0xffu;
+        uint64_t* row = staged_row(stage_a, stage_b, base, m, j);
+        if (b50 == 0xffu || sh == 0) {
+          if (gl == 0) {
+            row[arr ? 12 : 6] = b50 == 0xffu ? 0 : se.x + b50;
+            row[arr ? 13 : 7] = b50 == 0xffu ? 0 : se.x + b95;
+          }
+          continue;
+        }
+        const uint32_t ca = lcnt[(2 * arr) * DMAX + j], cb = lcnt[(2 * arr + 1) * DMAX + j];
+        const uint32_t k50 = sm.kth[2 * arr][j], k95 = sm.kth[2 * arr + 1][j];
+        const uint32_t* la = lists + loff[(2 * arr) * DMAX + j];
+        for (uint32_t x = gl; x < ca; x += GS) {
+          const uint32_t v = la[x];
+          uint32_t rank = 0;
+          for (uint32_t y = 0; y < ca; ++y) { const uint32_t o = la[y]; rank += (o < v || (o == v && y < x)) ? 1u : 0u; }
+          if (rank == k50) row[arr ? 12 : 6] = v;
+          if (cb == 0 && rank == k95) row[arr ? 13 : 7] = v;
+        }
+        if (cb) {
+          const uint32_t* lb = lists + loff[(2 * arr + 1) * DMAX + j];
+          for (uint32_t x = gl; x < cb; x += GS) {
+            const uint32_t v = lb[x];
+            uint32_t rank = 0;
+            for (uint32_t y = 0; y < cb; ++y) { const uint32_t o = lb[y]; rank += (o < v || (o == v && y < x)) ? 1u : 0u; }
+            if (rank == k95) row[arr ? 13 : 7] = v;
+          }
+        }
+      }
+      if (tid == 0) dcount[t] = D;
+      return;
+    }
+  }
+
+  // ---- 4b. general way: multi-pass radix selection ------------------------------------------------
+  __syncthreads();
+  for (uint32_t j = tid; j < D; j += NT) {
+    sm.pref[j] = make_uint4(0, 0, 0, 0);
+    const uint32_t ec = sm.rcnt[j], gc = sm.gcnt[j];
+    sm.kth[0][j] = static_cast<uint16_t>(rank_index_u32(50, ec));
+    sm.kth[1][j] = static_cast<uint16_t>(rank_index_u32(95, ec));
+    sm.kth[2][j] = static_cast<uint16_t>(gc ? rank_index_u32(50, gc) : 0);
+    sm.kth[3][j] = static_cast<uint16_t>(gc ? rank_index_u32(95, gc) : 0);
+  }
+  __syncthreads();
+  for (uint32_t i = tid; i < HIST_WORDS; i += NT) sm.u.hist[i] = 0;
+  const uint32_t maxe = sm.maxe, maxg = sm.maxg;
+  const int nbits_e = maxe ? 32 - __builtin_clz(maxe) : 1, nbits_g = maxg ? 32 - __builtin_clz(maxg) : 1;
+  const uint32_t P = 4 * D;  // (ID, percentile) pairs
+  const int passes_e = (nbits_e + B - 1) / B, passes_g = (nbits_g + B - 1) / B;
+  const int passes = passes_e > passes_g ? passes_e : passes_g;
+  // per launch: passes its ID needs (4 bits for execution time, 4 for idle time), packed 4 launches per register
+  uint32_t np[KPT / 4];
+#pragma unroll
+  for (int r4 = 0; r4 < KPT / 4; ++r4) np[r4] = 0;
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const uint32_t j = sl[r];
+    const uint32_t v = static_cast<uint32_t>(sm.npass[0][j]) | (static_cast<uint32_t>(sm.npass[1][j]) << 4);
+    np[r / 4] |= v << (8 * (r % 4));
+  }
+  // one bit per (launch, percentile): still a candidate?
+  uint64_t alive[(KPT + 15) / 16];
+#pragma unroll
+  for (int a16 = 0; a16 < (KPT + 15) / 16; ++a16) alive[a16] = ~0ull;
   __syncthreads();
   for (int p = passes - 1; p >= 0; --p) {
     const int shift = p * B;
@@ -241,48 +571,85 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
       const uint32_t i = r * NT + tid;
-      if (i < m) {
-        const uint32_t j = sl[r];
-#pragma unroll
-        for (int tg = 0; tg < 4; ++tg) {
-          const uint64_t v = tg < 2 ? ev[r] : gv[r];
-          if (tg >= 2 && v == static_cast<uint64_t>(GAP_NONE)) continue;
-          const uint64_t pf = sm.pref[tg][j];
-          const bool match = hi >= 64 ? true : (((v ^ pf) >> hi) == 0);
-          if (match) {
-            const uint32_t idx = ((tg * D + j) << B) + (static_cast<uint32_t>(v >> shift) & (bins - 1));
-            atomicAdd(&sm.u.hist[idx >> 1], (idx & 1u) ? 0x10000u : 1u);
-          }
+      const uint32_t npr = (np[r / 4] >> (8 * (r % 4))) & 0xffu;
+      const bool on_e = static_cast<uint32_t>(p) < (npr & 15u), on_g = static_cast<uint32_t>(p) < (npr >> 4) && gv[r] != NONE32;
+      const uint32_t live = static_cast<uint32_t>(alive[r / 16] >> (4 * (r % 16))) & ((on_e ? 3u : 0u) | (on_g ? 12u : 0u));
+      if (i < m && live) {
+        uint32_t j = sl[r];
+        asm volatile("" : "+v"(j));  // keep address arithmetic inside the pass (hoisting it costs 16 launches' worth of registers)
+        const uint4 pf = sm.pref[j];
+        uint32_t dead = 0;
+        // execution time: p50 (pair j) and p95 (pair D + j); one count serves both while their digits agree
+        if (live & 3u) {
+          const uint32_t v = ev[r];
+          const bool m50 = (live & 1u) && (hi >= 32 || ((v ^ pf.x) >> hi) == 0);
+          const bool m95 = (live & 2u) && (hi >= 32 || ((v ^ pf.y) >> hi) == 0);
+          dead |= ((live & 1u) && !m50 ? 1u : 0u) | ((live & 2u) && !m95 ? 2u : 0u);
+          const uint32_t digit = (v >> shift) & (bins - 1);
+          const uint32_t at = __umul24(digit >> 1, P) + j, inc = (digit & 1u) ? 0x10000u : 1u;
+          if (m50) atomicAdd(&sm.u.hist[at], inc);
+          if (m95 && pf.x != pf.y) atomicAdd(&sm.u.hist[at + D], inc);
         }
+        if (live & 12u) {
+          const uint32_t v = gv[r];
+          const bool m50 = (live & 4u) && (hi >= 32 || ((v ^ pf.z) >> hi) == 0);
+          const bool m95 = (live & 8u) && (hi >= 32 || ((v ^ pf.w) >> hi) == 0);
+          dead |= ((live & 4u) && !m50 ? 4u : 0u) | ((live & 8u) && !m95 ? 8u : 0u);
+          const uint32_t digit = (v >> shift) & (bins - 1);
+          const uint32_t at = __umul24(digit >> 1, P) + 2 * D + j, inc = (digit & 1u) ? 0x10000u : 1u;
+          if (m50) atomicAdd(&sm.u.hist[at], inc);
+          if (m95 && pf.z != pf.w) atomicAdd(&sm.u.hist[at + D], inc);
+        }
+        alive[r / 16] &= ~(static_cast<uint64_t>(dead) << (4 * (r % 16)));
       }
+      __builtin_amdgcn_sched_barrier(0);  // keep the unrolled iterations apart: they would only cost registers
     }
     __syncthreads();
-    for (uint32_t q = tid; q < 4 * D; q += NT) {
-      const uint32_t tg = q / D, j = q - tg * D;
-      uint32_t k = sm.kth[tg][j];
-      uint32_t cum = 0, digit = 0, knew = 0;
-      bool found = false;
-      const uint32_t w0 = (q << B) >> 1;
-      for (uint32_t wd = 0; wd < (bins >> 1); ++wd) {
-        const uint32_t pair = sm.u.hist[w0 + wd];
-        sm.u.hist[w0 + wd] = 0;
-        const uint32_t c0 = pair & 0xffffu, c1 = pair >> 16;
-        if (!found && k < cum + c0) { found = true; digit = 2 * wd; knew = k - cum; }
-        cum += c0;
-        if (!found && k < cum + c1) { found = true; digit = 2 * wd + 1; knew = k - cum; }
-        cum += c1;
-      }
-      if (found) {
-        sm.kth[tg][j] = static_cast<uint16_t>(knew);
-        sm.pref[tg][j] |= static_cast<uint64_t>(digit) << shift;
+    // one thread per (ID, array) walks the digit counts to the bins that hold the wanted ranks
+    for (uint32_t q = tid; q < 2 * D; q += NT) {
+      const uint32_t arr = q >= D ? 1u : 0u, j = q - arr * D;
+      if (static_cast<uint32_t>(p) < sm.npass[arr][j]) {
+        const uint4 pf = sm.pref[j];
+        const uint32_t p50 = arr ? pf.z : pf.x, p95 = arr ? pf.w : pf.y;
+        const bool share = (p50 == p95);
+        const uint32_t q50 = 2 * arr * D + j, q95 = q50 + D;
+        const uint32_t k50 = sm.kth[2 * arr][j], k95 = sm.kth[2 * arr + 1][j];
+        uint32_t cum = 0, d50 = 0, d95 = 0, n50 = 0, n95 = 0;
+        bool f50 = false, f95 = false;
+        for (uint32_t wd = 0; wd < (bins >> 1); ++wd) {
+          const uint32_t pair = sm.u.hist[wd * P + q50];
+          sm.u.hist[wd * P + q50] = 0;
+          const uint32_t c0 = pair & 0xffffu, c1 = pair >> 16;
+          if (!f50 && k50 < cum + c0) { f50 = true; d50 = 2 * wd; n50 = k50 - cum; }
+          if (share && !f95 && k95 < cum + c0) { f95 = true; d95 = 2 * wd; n95 = k95 - cum; }
+          cum += c0;
+          if (!f50 && k50 < cum + c1) { f50 = true; d50 = 2 * wd + 1; n50 = k50 - cum; }
+          if (share && !f95 && k95 < cum + c1) { f95 = true; d95 = 2 * wd + 1; n95 = k95 - cum; }
+          cum += c1;
+        }
+        if (!share) {
+          cum = 0;
+          for (uint32_t wd = 0; wd < (bins >> 1); ++wd) {
+            const uint32_t pair = sm.u.hist[wd * P + q95];
+            sm.u.hist[wd * P + q95] = 0;
+            const uint32_t c0 = pair & 0xffffu, c1 = pair >> 16;
+            if (!f95 && k95 < cum + c0) { f95 = true; d95 = 2 * wd; n95 = k95 - cum; }
+            cum += c0;
+            if (!f95 && k95 < cum + c1) { f95 = true; d95 = 2 * wd + 1; n95 = k95 - cum; }
+            cum += c1;
+          }
+        }
+        if (f50) { sm.kth[2 * arr][j] = static_cast<uint16_t>(n50); if (arr) sm.pref[j].z = p50 | (d50 << shift); else sm.pref[j].x = p50 | (d50 << shift); }
+        if (f95) { sm.kth[2 * arr + 1][j] = static_cast<uint16_t>(n95); if (arr) sm.pref[j].w = p95 | (d95 << shift); else sm.pref[j].y = p95 | (d95 << shift); }
       }
     }
     __syncthreads();
   }
   for (uint32_t j = tid; j < D; j += NT) {
     uint64_t* row = staged_row(stage_a, stage_b, base, m, j);
-    row[6] = sm.pref[0][j]; row[7] = sm.pref[1][j];
-    row[12] = sm.pref[2][j]; row[13] = sm.pref[3][j];
+    const uint4 pf = sm.pref[j];
+    row[6] = pf.x; row[7] = pf.y;
+    row[12] = pf.z; row[13] = pf.w;
   }
   if (tid == 0) dcount[t] = D;
 }
