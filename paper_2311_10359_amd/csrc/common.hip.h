@@ -94,17 +94,36 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
   return v;
 }
 
-// Inclusive prefix sum across the 64 lanes.
+// Inclusive prefix sum across the 64 lanes, with data-parallel-primitive moves (no LDS traffic):
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0 / 2 is broadcast
+// into the next row (rows 1 and 3), then the last lane of row 1 into rows 2 and 3.  Lanes without a
+// source receive 0.  Must be called by all 64 lanes of the wave.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint64_t dpp_or_zero_u64(uint64_t v) {
+  const uint32_t lo = dpp_or_zero<CTRL, ROW_MASK>(static_cast<uint32_t>(v));
+  const uint32_t hi = dpp_or_zero<CTRL, ROW_MASK>(static_cast<uint32_t>(v >> 32));
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
-  const uint32_t l = lane_id();
-#pragma unroll
-  for (int d = 1; d < WAVE; d <<= 1) { uint32_t o = __shfl_up(v, d, WAVE); if (l >= (uint32_t)d) v += o; }
+  v += dpp_or_zero<0x111, 0xf>(v);   // row_shr:1
+  v += dpp_or_zero<0x112, 0xf>(v);   // row_shr:2
+  v += dpp_or_zero<0x114, 0xf>(v);   // row_shr:4
+  v += dpp_or_zero<0x118, 0xf>(v);   // row_shr:8
+  v += dpp_or_zero<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_or_zero<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
   return v;
 }
 __device__ __forceinline__ uint64_t wave_incl_scan_u64(uint64_t v) {
-  const uint32_t l = lane_id();
-#pragma unroll
-  for (int d = 1; d < WAVE; d <<= 1) { uint64_t o = shfl_up_u64(v, d); if (l >= (uint32_t)d) v += o; }
+  v += dpp_or_zero_u64<0x111, 0xf>(v);
+  v += dpp_or_zero_u64<0x112, 0xf>(v);
+  v += dpp_or_zero_u64<0x114, 0xf>(v);
+  v += dpp_or_zero_u64<0x118, 0xf>(v);
+  v += dpp_or_zero_u64<0x142, 0xa>(v);
+  v += dpp_or_zero_u64<0x143, 0xc>(v);
   return v;
 }
 

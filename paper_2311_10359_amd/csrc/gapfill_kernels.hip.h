@@ -31,25 +31,50 @@ __global__ void k_gf_scenarios(const uint64_t* __restrict__ off, uint32_t n_task
   atomicOr(&role[lp], ROLE_LP);
 }
 
-// Predicted values of one launch, looked up by Kernel ID in the task's rows (sorted by ID).
-struct Pred { int64_t e, g; bool found; };
-
 constexpr int PRED_THREADS = 256;
-constexpr int PRED_TABLE = 2048;  // rows of a task kept in LDS for the lookup
+constexpr int PRED_KPT = 8;                       // consecutive launches per thread and chunk
+constexpr int PRED_CHUNK = PRED_THREADS * PRED_KPT;
+constexpr int PRED_ROWS = 512;                    // rows of a task kept in an LDS hash table for the lookup
+constexpr int PRED_HT = 2 * PRED_ROWS;
+
+// Predicted execution time and idle time of a launch: p50 values of its ID's row.  Rows of a
+// task with few IDs sit in an LDS hash table keyed by the ID; otherwise the task's sorted rows
+// are searched in memory.
+struct PredTable {
+  uint64_t key[PRED_HT];
+  int64_t e[PRED_HT];
+  int64_t g[PRED_HT];
+};
+
+__device__ __forceinline__ bool predict_one(uint64_t id, bool in_lds, const PredTable& tb, const fikit_row* __restrict__ rows,
+                                            uint64_t r0, uint64_t nr, int64_t& e, int64_t& g) {
+  if (in_lds) {
+    uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (PRED_HT - 1);
+    for (int probe = 0; probe < PRED_HT; ++probe) {
+      const uint64_t k = tb.key[h];
+      if (k == id) { e = tb.e[h]; g = tb.g[h]; return true; }
+      if (k == ~0ull) return false;
+      h = (h + 1) & (PRED_HT - 1);
+    }
+    return false;
+  }
+  uint64_t lo = 0, hi = nr;
+  while (lo < hi) { const uint64_t mid = (lo + hi) >> 1; if (rows[r0 + mid].kernel_id < id) lo = mid + 1; else hi = mid; }
+  if (lo < nr && rows[r0 + lo].kernel_id == id) { e = rows[r0 + lo].exec.p50; g = rows[r0 + lo].gap.p50; return true; }
+  return false;
+}
 
 // One workgroup per task that takes part in a scenario.  For every launch i of the task:
 //   as low-priority queue:   pe[i]   = sum of predicted execution times of launches 0..i
 //   as high-priority trace:  pg[i]   = predicted idle time after launch i
 //                            open[i] = predicted time at which launch i ends (its gap opens):
 //                                      sum_{k<=i} E_k + sum_{k<i} G_k
-__global__ void __launch_bounds__(PRED_THREADS)
+// Prefix sums run thread -> wave -> workgroup, with a running carry from chunk to chunk.
+__global__ void __launch_bounds__(PRED_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8)))
 k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
              const fikit_row* __restrict__ rows, const uint64_t* __restrict__ row_off, const uint32_t* __restrict__ role,
              int64_t* __restrict__ pe, int64_t* __restrict__ pg, int64_t* __restrict__ open, Ctrl* ctrl) {
-  __shared__ uint64_t t_key[PRED_TABLE];
-  __shared__ int64_t t_e[PRED_TABLE];
-  __shared__ int64_t t_g[PRED_TABLE];
-  __shared__ uint64_t wsum[2][4];
+  __shared__ PredTable tb;
   // only bits that earlier kernels set: the decision must be the same for the whole workgroup
   if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
   const uint32_t t = blockIdx.x;
@@ -58,50 +83,94 @@ k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off,
   const uint64_t base = off[t], len = off[t + 1] - base;
   const uint64_t r0 = row_off[t], nr = row_off[t + 1] - r0;
   const uint32_t tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const bool in_lds = nr <= PRED_TABLE;
+  // (an ID equal to the table's "empty" mark can only be the largest one)
+  const bool in_lds = nr <= PRED_ROWS && (nr == 0 || rows[r0 + nr - 1].kernel_id != ~0ull);
   if (in_lds) {
+    for (uint32_t h = tid; h < PRED_HT; h += PRED_THREADS) tb.key[h] = ~0ull;
+    __syncthreads();
     for (uint32_t r = tid; r < nr; r += PRED_THREADS) {
       const fikit_row* row = rows + r0 + r;
-      t_key[r] = row->kernel_id;
-      t_e[r] = row->exec.p50;
-      t_g[r] = row->gap.p50;
+      const uint64_t id = row->kernel_id;
+      uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (PRED_HT - 1);
+      for (;;) {   // IDs of a task are distinct and fill at most half the table: a free slot exists
+        const uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(&tb.key[h]), ~0ull, id);
+        if (old == ~0ull) break;
+        h = (h + 1) & (PRED_HT - 1);
+      }
+      tb.e[h] = row->exec.p50;
+      tb.g[h] = row->gap.p50;
     }
   }
   __syncthreads();
   uint64_t carry_e = 0, carry_o = 0;  // sums over all earlier launches: E, and E + G
-  for (uint64_t c0 = 0; c0 < len; c0 += PRED_THREADS) {
-    const uint64_t i = c0 + tid;
-    int64_t e = 0, g = 0;
-    if (i < len) {
-      const uint64_t id = ids[base + i];
-      // lower bound in the task's sorted IDs
-      uint64_t lo = 0, hi = nr;
-      if (in_lds) {
-        while (lo < hi) { const uint64_t mid = (lo + hi) >> 1; if (t_key[mid] < id) lo = mid + 1; else hi = mid; }
-        if (lo < nr && t_key[lo] == id) { e = t_e[lo]; g = t_g[lo]; } else atomicOr(&ctrl->status, ERR_UNKNOWN_ID);
+  bool unknown = false;
+  // A chunk is PRED_SUB sub-chunks of 2 * PRED_THREADS launches; in a sub-chunk every thread owns
+  // two neighbouring launches, so that a wave reads and writes 1 KiB of consecutive memory per access.
+  constexpr int PRED_SUB = PRED_KPT / 2;
+  __shared__ uint64_t sub_sum[2][PRED_SUB * 4];
+  const bool even = ((base & 1) == 0);   // 16-byte accesses need an even first index
+  for (uint64_t c0 = 0; c0 < len; c0 += PRED_CHUNK) {
+    int64_t e[PRED_KPT], g[PRED_KPT];
+    uint64_t ie[PRED_SUB], io[PRED_SUB];
+#pragma unroll
+    for (int k = 0; k < PRED_SUB; ++k) {
+      const uint64_t i0 = c0 + static_cast<uint64_t>(k) * (2 * PRED_THREADS) + 2 * tid;
+      uint64_t id0 = 0, id1 = 0;
+      if (even && i0 + 1 < len) {
+        const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(ids + base + i0);
+        id0 = v.x; id1 = v.y;
       } else {
-        while (lo < hi) { const uint64_t mid = (lo + hi) >> 1; if (rows[r0 + mid].kernel_id < id) lo = mid + 1; else hi = mid; }
-        if (lo < nr && rows[r0 + lo].kernel_id == id) { e = rows[r0 + lo].exec.p50; g = rows[r0 + lo].gap.p50; }
-        else atomicOr(&ctrl->status, ERR_UNKNOWN_ID);
+        if (i0 < len) id0 = ids[base + i0];
+        if (i0 + 1 < len) id1 = ids[base + i0 + 1];
+      }
+      e[2 * k] = e[2 * k + 1] = g[2 * k] = g[2 * k + 1] = 0;
+      if (i0 < len) unknown |= !predict_one(id0, in_lds, tb, rows, r0, nr, e[2 * k], g[2 * k]);
+      if (i0 + 1 < len) unknown |= !predict_one(id1, in_lds, tb, rows, r0, nr, e[2 * k + 1], g[2 * k + 1]);
+      const uint64_t se = static_cast<uint64_t>(e[2 * k]) + static_cast<uint64_t>(e[2 * k + 1]);
+      const uint64_t so = se + static_cast<uint64_t>(g[2 * k]) + static_cast<uint64_t>(g[2 * k + 1]);
+      // a task needs the sums of the role it plays only (the branch is the same for the whole workgroup)
+      ie[k] = io[k] = 0;
+      if (rl & ROLE_LP) { ie[k] = wave_incl_scan_u64(se); if (lane == 63) sub_sum[0][k * 4 + w] = ie[k]; ie[k] -= se; }
+      if (rl & ROLE_HP) { io[k] = wave_incl_scan_u64(so); if (lane == 63) sub_sum[1][k * 4 + w] = io[k]; io[k] -= so; }
+    }
+    __syncthreads();
+    uint64_t run_e = carry_e, run_o = carry_o;
+#pragma unroll
+    for (int k = 0; k < PRED_SUB; ++k) {
+      uint64_t be = run_e, bo = run_o;
+#pragma unroll
+      for (int ww = 0; ww < 4; ++ww) {
+        const uint64_t te = (rl & ROLE_LP) ? sub_sum[0][k * 4 + ww] : 0, to = (rl & ROLE_HP) ? sub_sum[1][k * 4 + ww] : 0;
+        if (static_cast<uint32_t>(ww) < w) { be += te; bo += to; }
+        run_e += te; run_o += to;
+      }
+      be += ie[k]; bo += io[k];
+      const uint64_t i0 = c0 + static_cast<uint64_t>(k) * (2 * PRED_THREADS) + 2 * tid;
+      const uint64_t pe0 = be + static_cast<uint64_t>(e[2 * k]), pe1 = pe0 + static_cast<uint64_t>(e[2 * k + 1]);
+      const uint64_t op0 = bo + static_cast<uint64_t>(e[2 * k]);   // E and G of earlier launches + own E
+      const uint64_t op1 = op0 + static_cast<uint64_t>(g[2 * k]) + static_cast<uint64_t>(e[2 * k + 1]);
+      if (even && i0 + 1 < len) {
+        if (rl & ROLE_LP) *reinterpret_cast<ulonglong2*>(pe + base + i0) = make_ulonglong2(pe0, pe1);
+        if (rl & ROLE_HP) {
+          *reinterpret_cast<ulonglong2*>(pg + base + i0) = make_ulonglong2(static_cast<uint64_t>(g[2 * k]), static_cast<uint64_t>(g[2 * k + 1]));
+          *reinterpret_cast<ulonglong2*>(open + base + i0) = make_ulonglong2(op0, op1);
+        }
+      } else {
+        if (i0 < len) {
+          if (rl & ROLE_LP) pe[base + i0] = static_cast<int64_t>(pe0);
+          if (rl & ROLE_HP) { pg[base + i0] = g[2 * k]; open[base + i0] = static_cast<int64_t>(op0); }
+        }
+        if (i0 + 1 < len) {
+          if (rl & ROLE_LP) pe[base + i0 + 1] = static_cast<int64_t>(pe1);
+          if (rl & ROLE_HP) { pg[base + i0 + 1] = g[2 * k + 1]; open[base + i0 + 1] = static_cast<int64_t>(op1); }
+        }
       }
     }
-    const uint64_t ue = static_cast<uint64_t>(e), uo = static_cast<uint64_t>(e) + static_cast<uint64_t>(g);
-    const uint64_t ie = wave_incl_scan_u64(ue), io = wave_incl_scan_u64(uo);
-    __syncthreads();
-    if (lane == 63) { wsum[0][w] = ie; wsum[1][w] = io; }
-    __syncthreads();
-    uint64_t be = carry_e, bo = carry_o;
-    for (uint32_t k = 0; k < w; ++k) { be += wsum[0][k]; bo += wsum[1][k]; }
-    if (i < len) {
-      if (rl & ROLE_LP) pe[base + i] = static_cast<int64_t>(be + ie);
-      if (rl & ROLE_HP) {
-        pg[base + i] = g;
-        open[base + i] = static_cast<int64_t>(bo + io - static_cast<uint64_t>(g));
-      }
-    }
-    carry_e += wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
-    carry_o += wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
+    carry_e = run_e;
+    carry_o = run_o;
+    __syncthreads();   // sub_sum is rewritten by the next chunk
   }
+  if (unknown) atomicOr(&ctrl->status, ERR_UNKNOWN_ID);
 }
 
 // The walk.  GW lanes cooperate on one scenario (GW divides 64): they read GW predicted gaps
