@@ -402,9 +402,13 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   tr.mark("k_gf_predict");
   hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
                      d_task_row_offsets, role, pe, pg, open, ctrl);
-  constexpr int GW = 16;
+#ifndef FIKIT_WALK_GW
+#define FIKIT_WALK_GW 16
+#define FIKIT_WALK_WINDOW false
+#endif
+  constexpr int GW = FIKIT_WALK_GW;
   tr.mark("k_gf_walk");
-  hipLaunchKernelGGL(k_gf_walk<GW>, dim3(blocks_for(n_scenarios, 256 / GW)), dim3(256), 0, st, d_task_offsets, d_hp_task,
+  hipLaunchKernelGGL((k_gf_walk<GW, FIKIT_WALK_WINDOW>), dim3(blocks_for(n_scenarios, 256 / GW)), dim3(256), 0, st, d_task_offsets, d_hp_task,
                      d_lp_task, n_scenarios, d_gap_offsets, pe, pg, open, h_params->margin_ns, h_params->min_gap_ns,
                      d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed, ctrl);
   FIKIT_HIP(hipGetLastError());

@@ -175,7 +175,7 @@ k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off,
 
 // The walk.  GW lanes cooperate on one scenario (GW divides 64): they read GW predicted gaps
 // at a time, and search the low-priority prefix sums GW candidates at a time with a ballot.
-template <int GW>
+template <int GW, bool WINDOW>
 __global__ void __launch_bounds__(256)
 k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task, const uint32_t* __restrict__ lp_task,
           uint64_t n_scen, const uint64_t* __restrict__ gap_off, const int64_t* __restrict__ pe,
@@ -201,6 +201,15 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
   int64_t consumed = 0;   // their total predicted duration = pe[l0 + p - 1]
   bool done = (L == 0);
   int64_t completion = 0;
+  // The group keeps 2 * GW consecutive prefix sums of the low-priority queue in registers (win0: entries
+  // wb .. wb+GW-1, win1: the next GW), with wb <= p < wb + GW, so that most gaps are searched without
+  // touching memory.
+  uint64_t wb = 0;
+  int64_t win0 = INT64_MAX, win1 = INT64_MAX;
+  if (WINDOW) {
+    win0 = gl < L ? pe[l0 + gl] : INT64_MAX;
+    win1 = GW + gl < L ? pe[l0 + GW + gl] : INT64_MAX;
+  }
 
   for (uint64_t i0 = 0; i0 < n_gaps; i0 += GW) {
     const uint64_t mine = i0 + gl;
@@ -216,13 +225,28 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
         const int64_t limit = consumed + (G - margin);
         int64_t last_fit = consumed;
         for (;;) {
-          const uint64_t j = p + c + gl;
-          const int64_t val = j < L ? pe[l0 + j] : INT64_MAX;
-          const bool fits = (j < L) && (val <= limit);
+          // candidate of this lane: queue entry p + c + gl, which lives in the window at idx
+          int64_t val;
+          if (WINDOW) {
+            const uint32_t idx = static_cast<uint32_t>(p + c - wb) + gl;          // 0 .. 2 * GW - 2
+            const int64_t a0 = static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(win0), gbase + (idx & (GW - 1))));
+            const int64_t a1 = static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(win1), gbase + (idx & (GW - 1))));
+            val = idx < GW ? a0 : a1;    // INT64_MAX beyond the end of the queue
+          } else {
+            const uint64_t j = p + c + gl;
+            val = j < L ? pe[l0 + j] : INT64_MAX;
+          }
+          const bool fits = val <= limit;
           const uint64_t b = (ballot(fits) >> gbase) & gmask;
           const uint32_t cnt = (b == gmask) ? GW : static_cast<uint32_t>(__builtin_ctzll(~b));
           if (cnt > 0) last_fit = static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(val), gbase + cnt - 1));
           c += cnt;
+          // keep the window under the search position
+          if (WINDOW && p + c >= wb + GW) {
+            wb += GW;
+            win0 = win1;
+            win1 = wb + GW + gl < L ? pe[l0 + wb + GW + gl] : INT64_MAX;
+          }
           if (cnt < GW) break;
         }
         f = last_fit - consumed;
