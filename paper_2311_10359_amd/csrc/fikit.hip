@@ -10,6 +10,7 @@
 #include "sort_kernels.hip.h"
 #include "stats_kernels.hip.h"
 #include "task_kernels.hip.h"
+#include "msd_kernels.hip.h"
 
 namespace {
 
@@ -44,7 +45,8 @@ struct Carver {
 
 struct ProfileLayout {
   uint64_t ctrl, k0, k1, k2, e0, e1, g0, g1, tiles, hist, sums, bits, word_prefix, gflag, dcount, total;
-  uint64_t max_tiles, n_words;
+  uint64_t is_long, mtiles, mflag, units;   // long-task partition path
+  uint64_t max_tiles, n_words, max_units;
 };
 
 ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
@@ -72,6 +74,13 @@ ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
   L.word_prefix = c.take(L.n_words * 4);
   L.gflag = c.take(static_cast<uint64_t>(n_tasks) * 4);
   L.dcount = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
+  L.is_long = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
+  L.mtiles = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
+  L.mflag = c.take(static_cast<uint64_t>(n_tasks) * 4);
+  uint64_t long_tasks = n / (static_cast<uint64_t>(FUSE_MAX) + 1);
+  if (long_tasks > n_tasks) long_tasks = n_tasks;
+  L.max_units = long_tasks * MSD_SLOTS;
+  L.units = c.take(L.max_units * 4 * 5);   // start, length, task, row count, first row
   L.total = c.at;
   return L;
 }
@@ -236,36 +245,97 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   tr.mark("plan");
   hipLaunchKernelGGL(k_classify, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st, d_task_offsets,
                      n_tasks, FUSE_MAX, gflag, dcount, ctrl);
+  uint32_t* is_long = reinterpret_cast<uint32_t*>(ws + L.is_long);
+  uint32_t* mtiles = reinterpret_cast<uint32_t*>(ws + L.mtiles);
+  uint32_t* mflag = reinterpret_cast<uint32_t*>(ws + L.mflag);
+  uint32_t* ustart = reinterpret_cast<uint32_t*>(ws + L.units);
+  uint32_t* ulen = ustart + L.max_units;
+  uint32_t* utask = ulen + L.max_units;
+  uint32_t* udcount = utask + L.max_units;
+  uint32_t* urow = udcount + L.max_units;
+  auto small = k_task_fused<256, 16, 256, 7168, 4, false, 3>;
+  auto medium = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, false, 4>;
+  auto mid = k_task_fused<512, 16, 256, 7168, 2, false, 4>;
+  auto small_u = k_task_fused<256, 16, 256, 7168, 4, true, 3>;
+  auto mid_u = k_task_fused<512, 16, 256, 7168, 4, true, 4>;
+  auto medium_u = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, true, 4>;
+  constexpr size_t mid_lds = sizeof(FusedSmem<512, 256, 7168>);
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
+  constexpr size_t small_lds = sizeof(FusedSmem<256, 256, 7168>),
+                   medium_lds = sizeof(FusedSmem<FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST>);
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(small_lds)));
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(medium), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(medium_lds)));
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(small_lds)));
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(medium_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(medium_lds)));
+  FusedArgs fa{};
+  fa.rec = d_records; fa.off = d_task_offsets; fa.ids = ids; fa.e0 = e0; fa.g0 = g0;
+  fa.stage_a = e1; fa.stage_b = g1; fa.dcount = dcount; fa.gflag = gflag; fa.ctrl = ctrl;
   {
-    auto small = k_task_fused<256, 16, 256, 7168, 4>;
-    auto medium = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2>;
-    constexpr size_t small_lds = sizeof(FusedSmem<256, 256, 7168>),
-                     medium_lds = sizeof(FusedSmem<FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST>);
-    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  static_cast<int>(small_lds)));
-    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(medium), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  static_cast<int>(medium_lds)));
     tr.mark("k_task_fused_small");
-    hipLaunchKernelGGL(small, dim3(n_tasks), dim3(256), small_lds, st, d_records, d_task_offsets, 1u, FUSE_SMALL_MAX, ids, e0,
-                       g0, e1, g1, dcount, gflag, ctrl);
+    fa.min_len = 1; fa.max_len = FUSE_SMALL_MAX;
+    hipLaunchKernelGGL(small, dim3(n_tasks), dim3(256), small_lds, st, fa);
+    tr.mark("k_task_fused_mid");
+    fa.min_len = FUSE_SMALL_MAX + 1; fa.max_len = FUSE_MID_MAX;
+    hipLaunchKernelGGL(mid, dim3(n_tasks), dim3(512), mid_lds, st, fa);
     tr.mark("k_task_fused_medium");
-    hipLaunchKernelGGL(medium, dim3(n_tasks), dim3(FUSE_M_THREADS), medium_lds, st, d_records, d_task_offsets, FUSE_SMALL_MAX + 1,
-                       FUSE_MAX, ids, e0, g0, e1, g1, dcount, gflag, ctrl);
+    fa.min_len = FUSE_MID_MAX + 1; fa.max_len = FUSE_MAX;
+    hipLaunchKernelGGL(medium, dim3(n_tasks), dim3(FUSE_M_THREADS), medium_lds, st, fa);
     FIKIT_HIP(hipGetLastError());
   }
   tr.mark("host_sync");
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   if (int rc = status_from_bits(h.status)) return rc;
+  uint64_t n_units = 0;
+  if (h.n_long > 0) {
+    // Long tasks: Kernel ID and per-launch values into memory, one partition pass by the top ID bits,
+    // then the one-workgroup kernel on units of buckets.
+    n_units = h.n_long * MSD_SLOTS;
+    if (n_units > L.max_units) return FIKIT_HIP_ERROR;   // cannot happen: a long task has more than FUSE_MAX launches
+    tr.mark("plan");
+    hipLaunchKernelGGL(k_plan_msd, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st, d_task_offsets,
+                       n_tasks, gflag, is_long, mtiles);
+    if (int rc = scan_u32(is_long, static_cast<uint64_t>(n_tasks) + 1, sums, nullptr, st)) return rc;
+    if (int rc = scan_u32(mtiles, static_cast<uint64_t>(n_tasks) + 1, sums, &ctrl->n_big_tiles, st)) return rc;
+    tr.mark("host_sync");
+    if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+    const uint64_t n_msd_tiles = h.n_big_tiles;
+    if (n_msd_tiles == 0 || n_msd_tiles > L.max_tiles) return FIKIT_HIP_ERROR;
+    tr.mark("k_hash_tiles");
+    hipLaunchKernelGGL(k_hash_tiles, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(256), 0, st, d_records, d_task_offsets, n_tasks,
+                       mtiles, ids, e0, g0, hist, ctrl);
+    tr.mark("scan_tile_hist");
+    if (int rc = scan_u32(hist, n_msd_tiles * 256, sums, nullptr, st)) return rc;
+    tr.mark("plan");
+    hipLaunchKernelGGL(k_msd_units, dim3(blocks_for(n_tasks, 64)), dim3(64), 0, st, d_task_offsets, n_tasks, is_long, mtiles, hist,
+                       ustart, ulen, utask, udcount, mflag, gflag, ctrl);
+    tr.mark("k_tile_scatter");
+    hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets, n_tasks,
+                       mtiles, hist, 0, mflag, FUSE_SMALL_MAX, ids, k1, e0, e1, g0, g1);
+    FusedArgs ua = fa;
+    ua.ustart = ustart; ua.ulen = ulen; ua.utask = utask; ua.skey = k1; ua.mflag = mflag; ua.dcount = udcount;
+    tr.mark("k_unit_fused_small");
+    ua.min_len = 1; ua.max_len = FUSE_SMALL_MAX;
+    hipLaunchKernelGGL(small_u, dim3(static_cast<uint32_t>(n_units)), dim3(256), small_lds, st, ua);
+    tr.mark("k_unit_fused_mid");
+    ua.min_len = FUSE_SMALL_MAX + 1; ua.max_len = FUSE_MID_MAX;
+    hipLaunchKernelGGL(mid_u, dim3(static_cast<uint32_t>(n_units)), dim3(512), mid_lds, st, ua);
+    tr.mark("k_unit_fused_medium");
+    ua.min_len = FUSE_MID_MAX + 1; ua.max_len = FUSE_MAX;
+    hipLaunchKernelGGL(medium_u, dim3(static_cast<uint32_t>(n_units)), dim3(FUSE_M_THREADS), medium_lds, st, ua);
+    tr.mark("plan");
+    hipLaunchKernelGGL(k_msd_task_rows, dim3(blocks_for(n_tasks, 64)), dim3(64), 0, st, n_tasks, is_long, mflag, udcount, urow, dcount);
+    FIKIT_HIP(hipGetLastError());
+    tr.mark("host_sync");
+    if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+    if (int rc = status_from_bits(h.status)) return rc;
+  }
   const bool any_general = h.n_general > 0;
   uint64_t n_heads = 0;
 
   if (any_general) {
-    // General path: per-launch values in memory, sort by ID, find the segment heads.
-    if (h.n_long > 0) {
-      tr.mark("k_hash_measure");
-      hipLaunchKernelGGL(k_hash_measure, dim3(blocks_for(n, HASH_BLOCK)), dim3(HASH_BLOCK), 0, st, d_records, n, ids, e0, g0, ctrl);
-      hipLaunchKernelGGL(k_mark_task_ends, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, g0, ctrl);
-    }
+    // General path: per-launch values are in memory (written by whichever kernel gave the task up);
+    // sort by ID, find the segment heads.
     tr.mark("plan");
     hipLaunchKernelGGL(k_plan_tiles, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st,
                        d_task_offsets, n_tasks, gflag, tiles, ctrl);
@@ -296,7 +366,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
         if (int rc = scan_u32(hist, n_big_tiles * 256, sums, nullptr, st)) return rc;
         tr.mark("k_tile_scatter");
         hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets,
-                           n_tasks, tiles, hist, shift, kin, kout, ein, eout, gin, gout);
+                           n_tasks, tiles, hist, shift, static_cast<const uint32_t*>(nullptr), 0u, kin, kout, ein, eout, gin, gout);
         FIKIT_HIP(hipGetLastError());
         kin = kout;
         kout = (kout == k1) ? k2 : k1;
@@ -328,7 +398,11 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   if (n_rows > row_capacity) return FIKIT_ROW_CAPACITY;
 
   tr.mark("k_gather_rows");
-  hipLaunchKernelGGL(k_gather_rows, dim3(n_tasks), dim3(256), 0, st, d_task_offsets, dcount, gflag, e1, g1, d_rows_out);
+  hipLaunchKernelGGL(k_gather_rows, dim3(n_tasks), dim3(256), 0, st, d_task_offsets, dcount, gflag, is_long, n_units > 0 ? 1 : 0, e1,
+                     g1, d_rows_out);
+  if (n_units > 0)
+    hipLaunchKernelGGL(k_gather_units, dim3(static_cast<uint32_t>(n_units)), dim3(256), 0, st, ustart, ulen, utask, udcount, urow,
+                       mflag, dcount, e1, g1, d_rows_out);
   if (any_general && n_heads > 0) {
     tr.mark("seg_starts");
     hipLaunchKernelGGL(k_seg_starts, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, word_prefix, L.n_words, n, n_heads,

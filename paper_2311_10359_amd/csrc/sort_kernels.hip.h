@@ -269,7 +269,7 @@ struct TileSmem {
 // Stable scatter of one tile by the current digit.  Hs is H after the exclusive scan.
 __global__ void __launch_bounds__(TILE_THREADS)
 k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix,
-               const uint32_t* __restrict__ Hs, int shift,
+               const uint32_t* __restrict__ Hs, int shift, const uint32_t* __restrict__ only_if, uint32_t top_bits_per,
                const uint64_t* __restrict__ key_in, uint64_t* __restrict__ key_out,
                const int64_t* __restrict__ exec_in, int64_t* __restrict__ exec_out,
                const int64_t* __restrict__ gap_in, int64_t* __restrict__ gap_out) {
@@ -284,6 +284,14 @@ k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_
   const uint64_t end = off[t + 1];
   const uint32_t m = static_cast<uint32_t>(end - start < TILE ? end - start : TILE);
   const uint32_t tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  if (only_if && !only_if[t]) return;   // partition pass: the task was left to the general path
+  if (top_bits_per) {
+    // partition pass: the digit is the task's top ID bits (about one bucket per top_bits_per launches)
+    const uint64_t want = (end - task_start + top_bits_per - 1) / top_bits_per;
+    uint32_t b = 1;
+    while ((1ull << b) < want && b < 8) ++b;
+    shift = 64 - static_cast<int>(b);
+  }
 
   for (uint32_t d = lane; d < 256; d += WAVE) sm.cnt[w][d] = 0;
   __builtin_amdgcn_wave_barrier();

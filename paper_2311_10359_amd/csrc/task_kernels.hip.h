@@ -29,14 +29,12 @@ namespace fikit {
 
 constexpr uint64_t HT_EMPTY = ~0ull;
 constexpr uint32_t FUSE_SMALL_MAX = 4096;    // tasks up to this many launches: 256-thread workgroup
+constexpr uint32_t FUSE_MID_MAX = 8192;      // up to this many: 512-thread workgroup
 constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: one larger workgroup
 #ifndef FUSE_M_THREADS_V
 #define FUSE_M_THREADS_V 1024
 #define FUSE_M_DMAX_V 512
 #define FUSE_M_HIST_V 16384
-#endif
-#ifndef FUSE_ATTR
-#define FUSE_ATTR
 #endif
 constexpr int FUSE_M_THREADS = FUSE_M_THREADS_V, FUSE_M_DMAX = FUSE_M_DMAX_V, FUSE_M_HIST = FUSE_M_HIST_V;
 
@@ -117,22 +115,60 @@ __device__ __forceinline__ uint32_t identity_tag(const uint32_t (&w)[8]) {
 
 // Values are kept as 32-bit numbers in registers (a task with an execution or idle time of
 // 2^32 - 1 ns or more takes the general path), KPT launches per thread.
-template <int NT, int KPT, int DMAX, int HIST_WORDS, int LB>
-__global__ void __launch_bounds__(NT) FUSE_ATTR
-k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ off, uint32_t min_len, uint32_t max_len,
-             uint64_t* __restrict__ ids, int64_t* __restrict__ e0, int64_t* __restrict__ g0,
-             int64_t* __restrict__ stage_a, int64_t* __restrict__ stage_b, uint32_t* __restrict__ dcount,
-             uint32_t* __restrict__ gflag, Ctrl* ctrl) {
+struct FusedArgs {
+  // whole tasks read from launch records
+  const fikit_launch* rec;
+  const uint64_t* off;
+  uint32_t min_len, max_len;   // this launch handles tasks / units of min_len .. max_len launches
+  uint64_t* ids;               // receives the IDs in launch order
+  int64_t* e0;                 // per-launch values handed to the general path when a task does not fit
+  int64_t* g0;
+  // units: groups of ID buckets of a long task, already in (ID, exec, gap) arrays
+  const uint32_t* ustart;
+  const uint32_t* ulen;
+  const uint32_t* utask;
+  const uint64_t* skey;
+  uint32_t* mflag;             // cleared when a unit sends its task to the general path
+  // both
+  int64_t* stage_a;            // rows are staged in the task's / unit's own slice of these two arrays
+  int64_t* stage_b;            // (for units they are also the source of exec and gap values)
+  uint32_t* dcount;            // rows per task / per unit
+  uint32_t* gflag;             // task takes the general path
+  Ctrl* ctrl;
+};
+
+template <int NT, int KPT, int DMAX, int HIST_WORDS, int LB, bool UNITS, int WPE>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, 8)))
+k_task_fused(const FusedArgs A) {
   using Smem = FusedSmem<NT, DMAX, HIST_WORDS>;
   constexpr int HT = Smem::HT;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
+  Ctrl* ctrl = A.ctrl;
   if (ctrl->status & ERR_OFFSETS) return;
-  const uint32_t t = blockIdx.x;
-  const uint64_t base = off[t];
-  const uint64_t len64 = off[t + 1] - base;
-  if (len64 < min_len || len64 > max_len) return;
+  const uint32_t unit = blockIdx.x;
+  uint32_t t;          // owning task
+  uint64_t base;       // first launch / first sorted position
+  uint64_t len64;
+  if (UNITS) {
+    len64 = A.ulen[unit];
+    base = A.ustart[unit];
+    t = A.utask[unit];
+  } else {
+    t = unit;
+    base = A.off[t];
+    len64 = A.off[t + 1] - base;
+  }
+  if (len64 < A.min_len || len64 > A.max_len) return;
   const uint32_t m = static_cast<uint32_t>(len64);
+  const fikit_launch* __restrict__ rec = A.rec;
+  uint64_t* __restrict__ ids = A.ids;
+  int64_t* __restrict__ e0 = A.e0;
+  int64_t* __restrict__ g0 = A.g0;
+  int64_t* __restrict__ stage_a = A.stage_a;
+  int64_t* __restrict__ stage_b = A.stage_b;
+  uint32_t* __restrict__ dcount = A.dcount;
+  uint32_t* __restrict__ gflag = A.gflag;
   const uint32_t tid = threadIdx.x;
 
   for (uint32_t i = tid; i < HT; i += NT) {
@@ -148,6 +184,43 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
   bool bad = false, wide = false;
 #pragma unroll
   for (int r = 0; r < KPT; ++r) { ev[r] = 0; gv[r] = NONE32; sl[r] = 0; }
+  if (UNITS) {
+    // values come from the partitioned arrays; IDs go straight into the ID table
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+      const uint32_t i = r * NT + tid;
+      if (i < m) {
+        const uint64_t id = A.skey[base + i];
+        const uint64_t e64 = static_cast<uint64_t>(stage_a[base + i]);
+        const int64_t g64 = stage_b[base + i];
+        wide |= (e64 >= NONE32);
+        ev[r] = static_cast<uint32_t>(e64);
+        my_maxe = ev[r] > my_maxe ? ev[r] : my_maxe;
+        if (g64 != GAP_NONE) {
+          wide |= (static_cast<uint64_t>(g64) >= NONE32);
+          gv[r] = static_cast<uint32_t>(g64);
+          my_maxg = gv[r] > my_maxg ? gv[r] : my_maxg;
+        }
+        uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (HT - 1);
+        bool placed = false;
+        if (id != HT_EMPTY) {
+          for (int probe = 0; probe < HT; ++probe) {
+            const uint64_t k = __hip_atomic_load(&sm.ht_key[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (k == id) { placed = true; break; }
+            if (k == HT_EMPTY) {
+              const uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(&sm.ht_key[h]), HT_EMPTY, id);
+              if (old == HT_EMPTY) { atomicAdd(&sm.ndist, 1u); placed = true; break; }
+              if (old == id) { placed = true; break; }
+            }
+            h = (h + 1) & (HT - 1);
+          }
+        }
+        if (!placed) atomicOr(&sm.fallback, 1u);
+        atomicAdd(&sm.ht_cnt[h], 1u);
+        sl[r] = h;
+      }
+    }
+  } else {
   // LB rounds of loads are issued before the first of them is used, to keep more bytes in flight
 #pragma unroll
   for (int r0 = 0; r0 < KPT; r0 += LB) {
@@ -269,6 +342,7 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
       }
     }
   }
+  }
   if (bad) atomicOr(&ctrl->status, ERR_BAD_RECORD);
   if (wide) atomicOr(&sm.fallback, 1u);
   my_maxe = wave_max_u32(my_maxe);
@@ -277,6 +351,14 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
   __syncthreads();
   const uint32_t D = sm.ndist;
   if (sm.fallback || D > DMAX || D > 2 * (m >> 4)) {
+    if (UNITS) {
+      // the whole task goes to the general path (its per-launch values are still in e0 / g0)
+      if (tid == 0 && atomicExch(&A.mflag[t], 0u) == 1u) {
+        gflag[t] = 1;
+        atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), 1ull);
+      }
+      return;
+    }
     // general path: hand over the per-launch values (recomputed at full width)
     for (uint32_t i = tid; i < m; i += NT) {
       const fikit_launch* q = rec + base + i;
@@ -528,7 +610,7 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
           }
         }
       }
-      if (tid == 0) dcount[t] = D;
+      if (tid == 0) dcount[unit] = D;
       return;
     }
   }
@@ -651,15 +733,17 @@ k_task_fused(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
     row[6] = pf.x; row[7] = pf.y;
     row[12] = pf.z; row[13] = pf.w;
   }
-  if (tid == 0) dcount[t] = D;
+  if (tid == 0) dcount[unit] = D;
 }
 
 // Moves a task's staged rows to their final place once the row offsets are known.
 __global__ void __launch_bounds__(256)
 k_gather_rows(const uint64_t* __restrict__ off, const uint32_t* __restrict__ row_off32, const uint32_t* __restrict__ gflag,
-              const int64_t* __restrict__ stage_a, const int64_t* __restrict__ stage_b, fikit_row* __restrict__ rows) {
+              const uint32_t* __restrict__ long_prefix, int have_long, const int64_t* __restrict__ stage_a,
+              const int64_t* __restrict__ stage_b, fikit_row* __restrict__ rows) {
   const uint32_t t = blockIdx.x;
   if (gflag[t]) return;
+  if (have_long && long_prefix[t + 1] != long_prefix[t]) return;   // a long task: its units are gathered separately
   const uint32_t r0 = row_off32[t], D = row_off32[t + 1] - r0;
   if (D == 0) return;
   const uint64_t base = off[t];
