@@ -32,7 +32,7 @@ struct Ctrl {
   uint64_t n_general;     // tasks that take the general sort-based path
   uint64_t n_long;        // tasks too long for the one-workgroup path
   uint64_t n_heads;       // rows found by the general path
-  uint64_t pad1[2];
+  uint32_t n_class[4];    // length of the work lists (small, mid, medium tasks or units; spare)
 };
 static_assert(sizeof(Ctrl) == 64, "control block is 64 bytes");
 
@@ -154,6 +154,29 @@ __device__ __forceinline__ uint32_t heads_before(const uint64_t* __restrict__ bi
   if (pos >= n) return n_heads;
   const uint64_t w = pos >> 6;
   return word_prefix[w] + static_cast<uint32_t>(__popcll(bits[w] & ((1ull << (pos & 63)) - 1ull)));
+}
+
+// Appends one item per lane with `want` set to a list whose length lives at *counter; returns the
+// lane's position (undefined for lanes without `want`).  One atomic per wave.  Call from all lanes.
+__device__ __forceinline__ uint32_t wave_append(uint32_t* counter, bool want) {
+  const uint64_t mask = ballot(want);
+  if (mask == 0) return 0;
+  const int leader = __builtin_ctzll(mask);
+  uint32_t base = 0;
+  if (lane_id() == static_cast<uint32_t>(leader)) base = atomicAdd(counter, static_cast<uint32_t>(__popcll(mask)));
+  base = __shfl(base, leader, WAVE);
+  return base + popc_below(mask);
+}
+
+// Workgroups are handed to the eight accelerator dies (XCDs) round robin by workgroup number.  Where
+// one workgroup handles one task and neighbouring tasks differ a lot in cost (or alternate between
+// "mine" and "not mine"), that would load the dies unevenly; this map gives every die a contiguous
+// eighth of the items instead.  Launch xcd_grid(n) workgroups; items >= n do not exist.
+constexpr uint32_t N_XCD = 8;
+__host__ __device__ inline uint32_t xcd_grid(uint32_t n) { return ((n + N_XCD - 1) / N_XCD) * N_XCD; }
+__device__ __forceinline__ uint32_t xcd_item(uint32_t block, uint32_t n) {
+  const uint32_t per = (n + N_XCD - 1) / N_XCD;
+  return (block % N_XCD) * per + block / N_XCD;
 }
 
 // Largest t in [0, n_tasks) with off[t] <= pos, skipping empty tasks to the one that owns pos

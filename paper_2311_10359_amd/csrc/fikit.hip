@@ -45,7 +45,7 @@ struct Carver {
 
 struct ProfileLayout {
   uint64_t ctrl, k0, k1, k2, e0, e1, g0, g1, tiles, hist, sums, bits, word_prefix, gflag, dcount, total;
-  uint64_t is_long, mtiles, mflag, units;   // long-task partition path
+  uint64_t is_long, mtiles, mflag, units, lists;   // long-task partition path; work lists
   uint64_t max_tiles, n_words, max_units;
 };
 
@@ -81,6 +81,10 @@ ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
   if (long_tasks > n_tasks) long_tasks = n_tasks;
   L.max_units = long_tasks * MSD_SLOTS;
   L.units = c.take(L.max_units * 4 * 5);   // start, length, task, row count, first row
+  {
+    const uint64_t longest_list = L.max_units > n_tasks ? L.max_units : n_tasks;
+    L.lists = c.take(longest_list * 4 * 3);
+  }
   L.total = c.at;
   return L;
 }
@@ -243,8 +247,9 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
 
   // Short tasks with few distinct IDs: one workgroup each, records read once, rows staged.
   tr.mark("plan");
+  uint32_t* lists = reinterpret_cast<uint32_t*>(ws + L.lists);
   hipLaunchKernelGGL(k_classify, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st, d_task_offsets,
-                     n_tasks, FUSE_MAX, gflag, dcount, ctrl);
+                     n_tasks, FUSE_SMALL_MAX, FUSE_MID_MAX, FUSE_MAX, gflag, dcount, lists, ctrl);
   uint32_t* is_long = reinterpret_cast<uint32_t*>(ws + L.is_long);
   uint32_t* mtiles = reinterpret_cast<uint32_t*>(ws + L.mtiles);
   uint32_t* mflag = reinterpret_cast<uint32_t*>(ws + L.mflag);
@@ -253,16 +258,16 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   uint32_t* utask = ulen + L.max_units;
   uint32_t* udcount = utask + L.max_units;
   uint32_t* urow = udcount + L.max_units;
-  auto small = k_task_fused<256, 16, 256, 7168, 4, false, 3>;
+  auto small = k_task_fused<FUSE_S_THREADS, FUSE_SMALL_MAX / FUSE_S_THREADS, 256, 7168, 4, false, FUSE_S_WPE>;
   auto medium = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, false, 4>;
   auto mid = k_task_fused<512, 16, 256, 7168, 2, false, 4>;
-  auto small_u = k_task_fused<256, 16, 256, 7168, 4, true, 3>;
+  auto small_u = k_task_fused<FUSE_S_THREADS, FUSE_SMALL_MAX / FUSE_S_THREADS, 256, 7168, 4, true, FUSE_S_WPE>;
   auto mid_u = k_task_fused<512, 16, 256, 7168, 4, true, 4>;
   auto medium_u = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, true, 4>;
   constexpr size_t mid_lds = sizeof(FusedSmem<512, 256, 7168>);
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
-  constexpr size_t small_lds = sizeof(FusedSmem<256, 256, 7168>),
+  constexpr size_t small_lds = sizeof(FusedSmem<FUSE_S_THREADS, 256, 7168>),
                    medium_lds = sizeof(FusedSmem<FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST>);
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(small_lds)));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(medium), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(medium_lds)));
@@ -273,13 +278,13 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   fa.stage_a = e1; fa.stage_b = g1; fa.dcount = dcount; fa.gflag = gflag; fa.ctrl = ctrl;
   {
     tr.mark("k_task_fused_small");
-    fa.min_len = 1; fa.max_len = FUSE_SMALL_MAX;
-    hipLaunchKernelGGL(small, dim3(n_tasks), dim3(256), small_lds, st, fa);
+    fa.list = lists; fa.count = &ctrl->n_class[0]; fa.max_len = FUSE_SMALL_MAX;
+    hipLaunchKernelGGL(small, dim3(n_tasks), dim3(FUSE_S_THREADS), small_lds, st, fa);
     tr.mark("k_task_fused_mid");
-    fa.min_len = FUSE_SMALL_MAX + 1; fa.max_len = FUSE_MID_MAX;
+    fa.list = lists + n_tasks; fa.count = &ctrl->n_class[1]; fa.max_len = FUSE_MID_MAX;
     hipLaunchKernelGGL(mid, dim3(n_tasks), dim3(512), mid_lds, st, fa);
     tr.mark("k_task_fused_medium");
-    fa.min_len = FUSE_MID_MAX + 1; fa.max_len = FUSE_MAX;
+    fa.list = lists + 2 * static_cast<uint64_t>(n_tasks); fa.count = &ctrl->n_class[2]; fa.max_len = FUSE_MAX;
     hipLaunchKernelGGL(medium, dim3(n_tasks), dim3(FUSE_M_THREADS), medium_lds, st, fa);
     FIKIT_HIP(hipGetLastError());
   }
@@ -307,21 +312,22 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     tr.mark("scan_tile_hist");
     if (int rc = scan_u32(hist, n_msd_tiles * 256, sums, nullptr, st)) return rc;
     tr.mark("plan");
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, &ctrl->n_class[0], static_cast<uint64_t>(4), 0u);   // the lists are reused for units
     hipLaunchKernelGGL(k_msd_units, dim3(blocks_for(n_tasks, 64)), dim3(64), 0, st, d_task_offsets, n_tasks, is_long, mtiles, hist,
-                       ustart, ulen, utask, udcount, mflag, gflag, ctrl);
+                       ustart, ulen, utask, udcount, mflag, gflag, lists, static_cast<uint32_t>(n_units), ctrl);
     tr.mark("k_tile_scatter");
     hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets, n_tasks,
                        mtiles, hist, 0, mflag, FUSE_SMALL_MAX, ids, k1, e0, e1, g0, g1);
     FusedArgs ua = fa;
     ua.ustart = ustart; ua.ulen = ulen; ua.utask = utask; ua.skey = k1; ua.mflag = mflag; ua.dcount = udcount;
     tr.mark("k_unit_fused_small");
-    ua.min_len = 1; ua.max_len = FUSE_SMALL_MAX;
-    hipLaunchKernelGGL(small_u, dim3(static_cast<uint32_t>(n_units)), dim3(256), small_lds, st, ua);
+    ua.list = lists; ua.count = &ctrl->n_class[0]; ua.max_len = FUSE_SMALL_MAX;
+    hipLaunchKernelGGL(small_u, dim3(static_cast<uint32_t>(n_units)), dim3(FUSE_S_THREADS), small_lds, st, ua);
     tr.mark("k_unit_fused_mid");
-    ua.min_len = FUSE_SMALL_MAX + 1; ua.max_len = FUSE_MID_MAX;
+    ua.list = lists + n_units; ua.count = &ctrl->n_class[1]; ua.max_len = FUSE_MID_MAX;
     hipLaunchKernelGGL(mid_u, dim3(static_cast<uint32_t>(n_units)), dim3(512), mid_lds, st, ua);
     tr.mark("k_unit_fused_medium");
-    ua.min_len = FUSE_MID_MAX + 1; ua.max_len = FUSE_MAX;
+    ua.list = lists + 2 * n_units; ua.count = &ctrl->n_class[2]; ua.max_len = FUSE_MAX;
     hipLaunchKernelGGL(medium_u, dim3(static_cast<uint32_t>(n_units)), dim3(FUSE_M_THREADS), medium_lds, st, ua);
     tr.mark("plan");
     hipLaunchKernelGGL(k_msd_task_rows, dim3(blocks_for(n_tasks, 64)), dim3(64), 0, st, n_tasks, is_long, mflag, udcount, urow, dcount);
@@ -350,7 +356,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_leaf_sort), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   static_cast<int>(sizeof(LeafSmem))));
     tr.mark("k_leaf_sort");
-    hipLaunchKernelGGL(k_leaf_sort, dim3(n_tasks), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, gflag, ids,
+    hipLaunchKernelGGL(k_leaf_sort, dim3(xcd_grid(n_tasks)), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, gflag, ids,
                        k2, e0, g0, ctrl);
     FIKIT_HIP(hipGetLastError());
     if (n_big_tiles > 0) {
@@ -398,11 +404,11 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   if (n_rows > row_capacity) return FIKIT_ROW_CAPACITY;
 
   tr.mark("k_gather_rows");
-  hipLaunchKernelGGL(k_gather_rows, dim3(n_tasks), dim3(256), 0, st, d_task_offsets, dcount, gflag, is_long, n_units > 0 ? 1 : 0, e1,
-                     g1, d_rows_out);
+  hipLaunchKernelGGL(k_gather_rows, dim3(xcd_grid(n_tasks)), dim3(256), 0, st, d_task_offsets, dcount, gflag, is_long,
+                     n_units > 0 ? 1 : 0, e1, g1, n_tasks, d_rows_out);
   if (n_units > 0)
-    hipLaunchKernelGGL(k_gather_units, dim3(static_cast<uint32_t>(n_units)), dim3(256), 0, st, ustart, ulen, utask, udcount, urow,
-                       mflag, dcount, e1, g1, d_rows_out);
+    hipLaunchKernelGGL(k_gather_units, dim3(xcd_grid(static_cast<uint32_t>(n_units))), dim3(256), 0, st, ustart, ulen, utask,
+                       udcount, urow, mflag, dcount, e1, g1, static_cast<uint32_t>(n_units), d_rows_out);
   if (any_general && n_heads > 0) {
     tr.mark("seg_starts");
     hipLaunchKernelGGL(k_seg_starts, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, word_prefix, L.n_words, n, n_heads,
@@ -425,6 +431,7 @@ size_t fikit_gapfill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t 
   Carver c;
   c.take(256);
   c.take(static_cast<uint64_t>(n_tasks) * 4);
+  c.take(static_cast<uint64_t>(n_tasks) * 4 * 2);
   c.take(n_ids * 8);
   c.take(n_ids * 8);
   c.take(n_ids * 8);
@@ -462,6 +469,7 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   Carver c;
   Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
   uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
+  uint32_t* glists = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4 * 2));
   int64_t* pe = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
   int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
   int64_t* open = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
@@ -474,8 +482,10 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   hipLaunchKernelGGL(k_gf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
                      d_lp_task, n_scenarios, d_gap_offsets, role, ctrl);
   tr.mark("k_gf_predict");
+  hipLaunchKernelGGL(k_gf_lists, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, role, 8192u, glists,
+                     ctrl);
   hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                     d_task_row_offsets, role, pe, pg, open, ctrl);
+                     d_task_row_offsets, role, glists, pe, pg, open, ctrl);
 #ifndef FIKIT_WALK_GW
 #define FIKIT_WALK_GW 16
 #define FIKIT_WALK_WINDOW false

@@ -31,6 +31,20 @@ __global__ void k_gf_scenarios(const uint64_t* __restrict__ off, uint32_t n_task
   atomicOr(&role[lp], ROLE_LP);
 }
 
+// Work list of the predict kernel: tasks that play a role, short traces first, long ones after, so
+// that workgroups started next to each other have work of similar size.
+__global__ void k_gf_lists(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ role,
+                           uint32_t split_len, uint32_t* __restrict__ lists, Ctrl* ctrl) {
+  if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
+  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  uint32_t c = 2;
+  if (t < n_tasks && role[t]) c = (off[t + 1] - off[t]) <= split_len ? 0u : 1u;
+  for (uint32_t k = 0; k < 2; ++k) {
+    const uint32_t pos = wave_append(&ctrl->n_class[k], c == k);
+    if (c == k) lists[static_cast<uint64_t>(k) * n_tasks + pos] = static_cast<uint32_t>(t);
+  }
+}
+
 constexpr int PRED_THREADS = 256;
 constexpr int PRED_KPT = 8;                       // consecutive launches per thread and chunk
 constexpr int PRED_CHUNK = PRED_THREADS * PRED_KPT;
@@ -73,11 +87,14 @@ __device__ __forceinline__ bool predict_one(uint64_t id, bool in_lds, const Pred
 __global__ void __launch_bounds__(PRED_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8)))
 k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
              const fikit_row* __restrict__ rows, const uint64_t* __restrict__ row_off, const uint32_t* __restrict__ role,
-             int64_t* __restrict__ pe, int64_t* __restrict__ pg, int64_t* __restrict__ open, Ctrl* ctrl) {
+             const uint32_t* __restrict__ lists, int64_t* __restrict__ pe, int64_t* __restrict__ pg,
+             int64_t* __restrict__ open, Ctrl* ctrl) {
   __shared__ PredTable tb;
   // only bits that earlier kernels set: the decision must be the same for the whole workgroup
   if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
-  const uint32_t t = blockIdx.x;
+  const uint32_t n_short = ctrl->n_class[0], n_longer = ctrl->n_class[1];   // final: set by an earlier kernel
+  if (blockIdx.x >= n_short + n_longer) return;
+  const uint32_t t = blockIdx.x < n_short ? lists[blockIdx.x] : lists[static_cast<uint64_t>(n_tasks) + (blockIdx.x - n_short)];
   const uint32_t rl = role[t];
   if (rl == 0) return;
   const uint64_t base = off[t], len = off[t + 1] - base;

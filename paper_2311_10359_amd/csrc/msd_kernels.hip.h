@@ -94,7 +94,8 @@ k_hash_tiles(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
 __global__ void k_msd_units(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ long_prefix,
                             const uint32_t* __restrict__ tile_prefix, const uint32_t* __restrict__ Hs,
                             uint32_t* __restrict__ ustart, uint32_t* __restrict__ ulen, uint32_t* __restrict__ utask,
-                            uint32_t* __restrict__ udcount, uint32_t* __restrict__ mflag, uint32_t* __restrict__ gflag, Ctrl* ctrl) {
+                            uint32_t* __restrict__ udcount, uint32_t* __restrict__ mflag, uint32_t* __restrict__ gflag,
+                            uint32_t* __restrict__ lists, uint32_t list_stride, Ctrl* ctrl) {
   const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (t >= n_tasks) return;
   mflag[t] = 0;
@@ -131,6 +132,13 @@ __global__ void k_msd_units(const uint64_t* __restrict__ off, uint32_t n_tasks, 
     mflag[t] = 1;
     gflag[t] = 0;
     atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), ~0ull);   // one general task fewer
+    // work lists of units by size class (see k_classify)
+    for (u = o * MSD_SLOTS; u < u_end; ++u) {
+      const uint32_t l = ulen[u];
+      if (l == 0) continue;
+      const uint32_t c = l <= FUSE_SMALL_MAX ? 0u : (l <= FUSE_MID_MAX ? 1u : 2u);
+      lists[static_cast<uint64_t>(c) * list_stride + atomicAdd(&ctrl->n_class[c], 1u)] = u;
+    }
   } else {
     for (u = o * MSD_SLOTS; u < u_end; ++u) ulen[u] = 0;
   }
@@ -152,8 +160,9 @@ __global__ void __launch_bounds__(256)
 k_gather_units(const uint32_t* __restrict__ ustart, const uint32_t* __restrict__ ulen, const uint32_t* __restrict__ utask,
                const uint32_t* __restrict__ udcount, const uint32_t* __restrict__ urow, const uint32_t* __restrict__ mflag,
                const uint32_t* __restrict__ row_off32, const int64_t* __restrict__ stage_a, const int64_t* __restrict__ stage_b,
-               fikit_row* __restrict__ rows) {
-  const uint32_t u = blockIdx.x;
+               uint32_t n_units, fikit_row* __restrict__ rows) {
+  const uint32_t u = xcd_item(blockIdx.x, n_units);
+  if (u >= n_units) return;
   const uint32_t m = ulen[u];
   if (m == 0) return;
   const uint32_t t = utask[u];

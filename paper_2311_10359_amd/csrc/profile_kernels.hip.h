@@ -33,19 +33,33 @@ __global__ void k_validate_offsets(const uint64_t* __restrict__ off, uint32_t n_
   if (bad) atomicOr(&ctrl->status, ERR_OFFSETS);
 }
 
-// Tasks longer than max_fused launches take the general sort-based path from the start.
-__global__ void k_classify(const uint64_t* __restrict__ off, uint32_t n_tasks, uint32_t max_fused, uint32_t* __restrict__ gflag,
-                           uint32_t* __restrict__ dcount, Ctrl* ctrl) {
+// Sorts tasks into work lists by length: lists[c * n_tasks ...] for c = 0 (up to len_small launches),
+// 1 (up to len_mid), 2 (up to len_max); longer tasks start on the long-task path (gflag 1).  A kernel
+// that handles one class is launched over that class's list, so that every workgroup it starts has
+// work of similar size (workgroups are handed to compute units in turn: a launch in which busy and
+// idle workgroups alternate would keep only some of the units busy).  Order inside a list is arbitrary.
+__global__ void k_classify(const uint64_t* __restrict__ off, uint32_t n_tasks, uint32_t len_small, uint32_t len_mid,
+                           uint32_t len_max, uint32_t* __restrict__ gflag, uint32_t* __restrict__ dcount,
+                           uint32_t* __restrict__ lists, Ctrl* ctrl) {
   if (ctrl->status & ERR_OFFSETS) return;
   const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (t > n_tasks) return;
-  dcount[t] = 0;
-  if (t == n_tasks) return;
-  const bool is_long = (off[t + 1] - off[t]) > max_fused;
-  gflag[t] = is_long ? 1u : 0u;
-  if (is_long) {
-    atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), 1ull);
-    atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_long), 1ull);
+  uint32_t c = 3;   // 0, 1, 2: work list; 3: none
+  bool is_long = false;
+  if (t <= n_tasks) dcount[t] = 0;
+  if (t < n_tasks) {
+    const uint64_t len = off[t + 1] - off[t];
+    is_long = len > len_max;
+    gflag[t] = is_long ? 1u : 0u;
+    if (!is_long && len > 0) c = len <= len_small ? 0u : (len <= len_mid ? 1u : 2u);
+  }
+  for (uint32_t k = 0; k < 3; ++k) {
+    const uint32_t pos = wave_append(&ctrl->n_class[k], c == k);
+    if (c == k) lists[static_cast<uint64_t>(k) * n_tasks + pos] = static_cast<uint32_t>(t);
+  }
+  const uint64_t longs = ballot(is_long);
+  if (longs && lane_id() == 0) {
+    atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), static_cast<unsigned long long>(__popcll(longs)));
+    atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_long), static_cast<unsigned long long>(__popcll(longs)));
   }
 }
 
@@ -67,48 +81,6 @@ __device__ __forceinline__ uint64_t kernel_id_of(const uint32_t (&w)[8]) {
     }
   }
   return (static_cast<uint64_t>(hi) << 32) | lo;
-}
-
-// One launch record per thread: Kernel ID, execution time K = end - start, and the idle time
-// G = max(0, start of the following record - end).  Whether the following record belongs to the
-// same task is settled afterwards by k_mark_task_ends, which overwrites the G of every task's
-// last launch with GAP_NONE.
-constexpr int HASH_BLOCK = 256;
-__global__ void __launch_bounds__(HASH_BLOCK)
-k_hash_measure(const fikit_launch* __restrict__ rec, uint64_t n, uint64_t* __restrict__ ids,
-               int64_t* __restrict__ exec_out, int64_t* __restrict__ gap_out, Ctrl* ctrl) {
-  const uint64_t i = static_cast<uint64_t>(blockIdx.x) * HASH_BLOCK + threadIdx.x;
-  if (i >= n) return;
-  const uint4* p = reinterpret_cast<const uint4*>(rec + i);
-  const uint4 a = p[0];
-  const uint4 b = p[1];
-  const uint4 c = p[2];  // start_ns, end_ns
-  int64_t next_start = 0;
-  const bool has_next = (i + 1 < n);
-  if (has_next) next_start = rec[i + 1].start_ns;
-  const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-  const uint64_t id = kernel_id_of(w);
-  const int64_t start = static_cast<int64_t>((static_cast<uint64_t>(c.y) << 32) | c.x);
-  const int64_t end = static_cast<int64_t>((static_cast<uint64_t>(c.w) << 32) | c.z);
-  if (end < start) atomicOr(&ctrl->status, ERR_BAD_RECORD);
-  int64_t gap = GAP_NONE;
-  if (has_next) {
-    gap = next_start - end;
-    if (gap < 0) gap = 0;
-  }
-  ids[i] = id;
-  exec_out[i] = end - start;
-  gap_out[i] = gap;
-}
-
-// The last launch of every non-empty task has no idle time after it.
-__global__ void k_mark_task_ends(const uint64_t* __restrict__ off, uint32_t n_tasks, int64_t* __restrict__ gap,
-                                 const Ctrl* ctrl) {
-  if (ctrl->status & ERR_OFFSETS) return;
-  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (t >= n_tasks) return;
-  const uint64_t a = off[t], b = off[t + 1];
-  if (b > a) gap[b - 1] = GAP_NONE;
 }
 
 }  // namespace fikit

@@ -166,8 +166,8 @@ k_leaf_sort(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* 
   extern __shared__ __align__(16) unsigned char smem_raw[];
   LeafSmem& sm = *reinterpret_cast<LeafSmem*>(smem_raw);
   if (ctrl->status & ERR_OFFSETS) return;
-  const uint32_t t = blockIdx.x;
-  if (!gflag[t]) return;
+  const uint32_t t = xcd_item(blockIdx.x, n_tasks);
+  if (t >= n_tasks || !gflag[t]) return;
   const uint64_t base = off[t];
   const uint64_t len64 = off[t + 1] - base;
   if (len64 == 0 || len64 > LEAF) return;

@@ -36,6 +36,11 @@ constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: 
 #define FUSE_M_DMAX_V 512
 #define FUSE_M_HIST_V 16384
 #endif
+#ifndef FUSE_S_THREADS_V
+#define FUSE_S_THREADS_V 256
+#define FUSE_S_WPE_V 3
+#endif
+constexpr int FUSE_S_THREADS = FUSE_S_THREADS_V, FUSE_S_WPE = FUSE_S_WPE_V;
 constexpr int FUSE_M_THREADS = FUSE_M_THREADS_V, FUSE_M_DMAX = FUSE_M_DMAX_V, FUSE_M_HIST = FUSE_M_HIST_V;
 
 template <int NT>
@@ -119,7 +124,9 @@ struct FusedArgs {
   // whole tasks read from launch records
   const fikit_launch* rec;
   const uint64_t* off;
-  uint32_t min_len, max_len;   // this launch handles tasks / units of min_len .. max_len launches
+  const uint32_t* list;        // work list of this launch: task numbers / unit numbers ...
+  const uint32_t* count;       // ... and its length (workgroups beyond it have nothing to do)
+  uint32_t max_len;            // capacity of this kernel shape (launches)
   uint64_t* ids;               // receives the IDs in launch order
   int64_t* e0;                 // per-launch values handed to the general path when a task does not fit
   int64_t* g0;
@@ -146,7 +153,8 @@ k_task_fused(const FusedArgs A) {
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
   Ctrl* ctrl = A.ctrl;
   if (ctrl->status & ERR_OFFSETS) return;
-  const uint32_t unit = blockIdx.x;
+  if (blockIdx.x >= *A.count) return;
+  const uint32_t unit = A.list[blockIdx.x];
   uint32_t t;          // owning task
   uint64_t base;       // first launch / first sorted position
   uint64_t len64;
@@ -159,7 +167,7 @@ k_task_fused(const FusedArgs A) {
     base = A.off[t];
     len64 = A.off[t + 1] - base;
   }
-  if (len64 < A.min_len || len64 > A.max_len) return;
+  if (len64 == 0 || len64 > A.max_len) return;   // (cannot happen for a listed item)
   const uint32_t m = static_cast<uint32_t>(len64);
   const fikit_launch* __restrict__ rec = A.rec;
   uint64_t* __restrict__ ids = A.ids;
@@ -632,20 +640,6 @@ k_task_fused(const FusedArgs A) {
   const uint32_t P = 4 * D;  // (ID, percentile) pairs
   const int passes_e = (nbits_e + B - 1) / B, passes_g = (nbits_g + B - 1) / B;
   const int passes = passes_e > passes_g ? passes_e : passes_g;
-  // per launch: passes its ID needs (4 bits for execution time, 4 for idle time), packed 4 launches per register
-  uint32_t np[KPT / 4];
-#pragma unroll
-  for (int r4 = 0; r4 < KPT / 4; ++r4) np[r4] = 0;
-#pragma unroll
-  for (int r = 0; r < KPT; ++r) {
-    const uint32_t j = sl[r];
-    const uint32_t v = static_cast<uint32_t>(sm.npass[0][j]) | (static_cast<uint32_t>(sm.npass[1][j]) << 4);
-    np[r / 4] |= v << (8 * (r % 4));
-  }
-  // one bit per (launch, percentile): still a candidate?
-  uint64_t alive[(KPT + 15) / 16];
-#pragma unroll
-  for (int a16 = 0; a16 < (KPT + 15) / 16; ++a16) alive[a16] = ~0ull;
   __syncthreads();
   for (int p = passes - 1; p >= 0; --p) {
     const int shift = p * B;
@@ -653,36 +647,29 @@ k_task_fused(const FusedArgs A) {
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
       const uint32_t i = r * NT + tid;
-      const uint32_t npr = (np[r / 4] >> (8 * (r % 4))) & 0xffu;
-      const bool on_e = static_cast<uint32_t>(p) < (npr & 15u), on_g = static_cast<uint32_t>(p) < (npr >> 4) && gv[r] != NONE32;
-      const uint32_t live = static_cast<uint32_t>(alive[r / 16] >> (4 * (r % 16))) & ((on_e ? 3u : 0u) | (on_g ? 12u : 0u));
-      if (i < m && live) {
+      if (i < m) {
         uint32_t j = sl[r];
-        asm volatile("" : "+v"(j));  // keep address arithmetic inside the pass (hoisting it costs 16 launches' worth of registers)
+        asm volatile("" : "+v"(j));  // keep address arithmetic inside the pass
         const uint4 pf = sm.pref[j];
-        uint32_t dead = 0;
         // execution time: p50 (pair j) and p95 (pair D + j); one count serves both while their digits agree
-        if (live & 3u) {
+        if (static_cast<uint32_t>(p) < sm.npass[0][j]) {
           const uint32_t v = ev[r];
-          const bool m50 = (live & 1u) && (hi >= 32 || ((v ^ pf.x) >> hi) == 0);
-          const bool m95 = (live & 2u) && (hi >= 32 || ((v ^ pf.y) >> hi) == 0);
-          dead |= ((live & 1u) && !m50 ? 1u : 0u) | ((live & 2u) && !m95 ? 2u : 0u);
+          const bool m50 = hi >= 32 || ((v ^ pf.x) >> hi) == 0;
+          const bool m95 = hi >= 32 || ((v ^ pf.y) >> hi) == 0;
           const uint32_t digit = (v >> shift) & (bins - 1);
           const uint32_t at = __umul24(digit >> 1, P) + j, inc = (digit & 1u) ? 0x10000u : 1u;
           if (m50) atomicAdd(&sm.u.hist[at], inc);
           if (m95 && pf.x != pf.y) atomicAdd(&sm.u.hist[at + D], inc);
         }
-        if (live & 12u) {
+        if (gv[r] != NONE32 && static_cast<uint32_t>(p) < sm.npass[1][j]) {
           const uint32_t v = gv[r];
-          const bool m50 = (live & 4u) && (hi >= 32 || ((v ^ pf.z) >> hi) == 0);
-          const bool m95 = (live & 8u) && (hi >= 32 || ((v ^ pf.w) >> hi) == 0);
-          dead |= ((live & 4u) && !m50 ? 4u : 0u) | ((live & 8u) && !m95 ? 8u : 0u);
+          const bool m50 = hi >= 32 || ((v ^ pf.z) >> hi) == 0;
+          const bool m95 = hi >= 32 || ((v ^ pf.w) >> hi) == 0;
           const uint32_t digit = (v >> shift) & (bins - 1);
           const uint32_t at = __umul24(digit >> 1, P) + 2 * D + j, inc = (digit & 1u) ? 0x10000u : 1u;
           if (m50) atomicAdd(&sm.u.hist[at], inc);
           if (m95 && pf.z != pf.w) atomicAdd(&sm.u.hist[at + D], inc);
         }
-        alive[r / 16] &= ~(static_cast<uint64_t>(dead) << (4 * (r % 16)));
       }
       __builtin_amdgcn_sched_barrier(0);  // keep the unrolled iterations apart: they would only cost registers
     }
@@ -740,9 +727,9 @@ k_task_fused(const FusedArgs A) {
 __global__ void __launch_bounds__(256)
 k_gather_rows(const uint64_t* __restrict__ off, const uint32_t* __restrict__ row_off32, const uint32_t* __restrict__ gflag,
               const uint32_t* __restrict__ long_prefix, int have_long, const int64_t* __restrict__ stage_a,
-              const int64_t* __restrict__ stage_b, fikit_row* __restrict__ rows) {
-  const uint32_t t = blockIdx.x;
-  if (gflag[t]) return;
+              const int64_t* __restrict__ stage_b, uint32_t n_tasks, fikit_row* __restrict__ rows) {
+  const uint32_t t = xcd_item(blockIdx.x, n_tasks);
+  if (t >= n_tasks || gflag[t]) return;
   if (have_long && long_prefix[t + 1] != long_prefix[t]) return;   // a long task: its units are gathered separately
   const uint32_t r0 = row_off32[t], D = row_off32[t + 1] - r0;
   if (D == 0) return;
