@@ -259,16 +259,16 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   uint32_t* udcount = utask + L.max_units;
   uint32_t* urow = udcount + L.max_units;
   auto small = k_task_fused<FUSE_S_THREADS, FUSE_SMALL_MAX / FUSE_S_THREADS, 256, 7168, 4, false, FUSE_S_WPE>;
-  auto medium = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, false, 4>;
+  auto medium = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, false, 4, FUSE_M_ESTATS>;
   auto mid = k_task_fused<512, 16, 256, 7168, 2, false, 4>;
   auto small_u = k_task_fused<FUSE_S_THREADS, FUSE_SMALL_MAX / FUSE_S_THREADS, 256, 7168, 4, true, FUSE_S_WPE>;
   auto mid_u = k_task_fused<512, 16, 256, 7168, 4, true, 4>;
-  auto medium_u = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, true, 4>;
+  auto medium_u = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, true, 4, FUSE_M_ESTATS>;
   constexpr size_t mid_lds = sizeof(FusedSmem<512, 256, 7168>);
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
   constexpr size_t small_lds = sizeof(FusedSmem<FUSE_S_THREADS, 256, 7168>),
-                   medium_lds = sizeof(FusedSmem<FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST>);
+                   medium_lds = sizeof(FusedSmem<FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, FUSE_M_ESTATS>);
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(small_lds)));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(medium), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(medium_lds)));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(small_lds)));

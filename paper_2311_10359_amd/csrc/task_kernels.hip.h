@@ -40,6 +40,10 @@ constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: 
 #define FUSE_S_THREADS_V 256
 #define FUSE_S_WPE_V 3
 #endif
+#ifndef FUSE_M_ESTATS_V
+#define FUSE_M_ESTATS_V true
+#endif
+constexpr bool FUSE_M_ESTATS = FUSE_M_ESTATS_V;
 constexpr int FUSE_S_THREADS = FUSE_S_THREADS_V, FUSE_S_WPE = FUSE_S_WPE_V;
 constexpr int FUSE_M_THREADS = FUSE_M_THREADS_V, FUSE_M_DMAX = FUSE_M_DMAX_V, FUSE_M_HIST = FUSE_M_HIST_V;
 
@@ -72,9 +76,12 @@ struct MemoEntry {
 };
 static_assert(sizeof(MemoEntry) == 48, "memo entry is 48 bytes");
 
-template <int NT, int DMAX, int HIST_WORDS>
+// With ESTATS the sums, minima and maxima are gathered while the records are being read (per slot
+// of the ID table, since ranks are not known yet): the memory pipe is the busy one then, LDS is idle.
+template <int NT, int DMAX, int HIST_WORDS, bool ESTATS = false>
 struct FusedSmem {
   static constexpr int HT = 2 * DMAX;
+  static constexpr int HE = ESTATS ? HT : 1;
   uint64_t ht_key[HT];       // ID table (open addressing): the task's unique IDs
   uint32_t ht_cnt[HT];       // launches per ID
   uint16_t slot_rank[HT];    // slot -> rank of its ID among the task's IDs
@@ -95,6 +102,9 @@ struct FusedSmem {
   uint32_t maxe, maxg;
   uint32_t ndist;
   uint32_t fallback;
+  uint32_t last_rank;        // rank of the ID whose launch has no idle time after it (the task's last), or NONE32
+  struct { uint64_t esum[HE], gsum[HE]; uint32_t emin[HE], emax[HE], gmin[HE], gmax[HE]; } early;   // by slot
+  uint16_t rslot[ESTATS ? DMAX : 1];   // rank -> slot
 };
 
 constexpr uint32_t NONE32 = 0xffffffffu;   // "no idle time after this launch" in the 32-bit value registers
@@ -116,6 +126,34 @@ __device__ __forceinline__ uint32_t identity_tag(const uint32_t (&w)[8]) {
   t = t * 0x2c1b3c6du;
   t ^= t >> 13;
   return t | 1u;
+}
+
+// log2 of the number of bins the fast percentile path cuts an ID's value range into: about one bin
+// per WINDOW_SAMPLES_PER_BIN samples (the bin that holds a wanted rank is ranked directly afterwards), at least 2,
+// at most 2^max_log2.
+#ifndef WINDOW_SAMPLES_PER_BIN_V
+#define WINDOW_SAMPLES_PER_BIN_V 1
+#endif
+constexpr uint32_t WINDOW_SAMPLES_PER_BIN = WINDOW_SAMPLES_PER_BIN_V;
+__device__ __forceinline__ uint32_t window_bins_log2(uint32_t count, uint32_t max_log2) {
+  const uint32_t want = count / WINDOW_SAMPLES_PER_BIN;
+  const uint32_t lg = want <= 2 ? 1u : 32u - __builtin_clz(want - 1);
+  return lg < max_log2 ? lg : max_log2;
+}
+
+// Number of samples of list[0 .. n) that sort before sample x (value v): smaller ones, and equal ones
+// that stand earlier in the list.  Four independent reads per step.
+__device__ __forceinline__ uint32_t list_rank(const uint32_t* list, uint32_t n, uint32_t v, uint32_t x) {
+  uint32_t rank = 0;
+  for (uint32_t y = 0; y < n; y += 4) {
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) {
+      const uint32_t yy = y + u;
+      const uint32_t o = list[yy < n ? yy : n - 1];
+      rank += (yy < n && (o < v || (o == v && yy < x))) ? 1u : 0u;
+    }
+  }
+  return rank;
 }
 
 // Values are kept as 32-bit numbers in registers (a task with an execution or idle time of
@@ -144,10 +182,23 @@ struct FusedArgs {
   Ctrl* ctrl;
 };
 
-template <int NT, int KPT, int DMAX, int HIST_WORDS, int LB, bool UNITS, int WPE>
+// Adds one launch's execution time and (if it has one) idle time to the sums, minima and maxima of ID-table slot s.
+template <typename Smem>
+__device__ __forceinline__ void early_stats(Smem& sm, uint32_t s, uint32_t e, uint32_t g) {
+  atomicAdd(reinterpret_cast<unsigned long long*>(&sm.early.esum[s]), static_cast<unsigned long long>(e));
+  atomicMin(&sm.early.emin[s], e);
+  atomicMax(&sm.early.emax[s], e);
+  if (g != NONE32) {
+    atomicAdd(reinterpret_cast<unsigned long long*>(&sm.early.gsum[s]), static_cast<unsigned long long>(g));
+    atomicMin(&sm.early.gmin[s], g);
+    atomicMax(&sm.early.gmax[s], g);
+  }
+}
+
+template <int NT, int KPT, int DMAX, int HIST_WORDS, int LB, bool UNITS, int WPE, bool ESTATS = false>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, 8)))
 k_task_fused(const FusedArgs A) {
-  using Smem = FusedSmem<NT, DMAX, HIST_WORDS>;
+  using Smem = FusedSmem<NT, DMAX, HIST_WORDS, ESTATS>;
   constexpr int HT = Smem::HT;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
@@ -181,8 +232,12 @@ k_task_fused(const FusedArgs A) {
 
   for (uint32_t i = tid; i < HT; i += NT) {
     sm.ht_key[i] = HT_EMPTY; sm.ht_cnt[i] = 0; sm.memo_claim[i] = 0; sm.u.memo[i].ready = 0;
+    if (ESTATS) {
+      sm.early.esum[i] = 0; sm.early.emin[i] = ~0u; sm.early.emax[i] = 0;
+      sm.early.gsum[i] = 0; sm.early.gmin[i] = ~0u; sm.early.gmax[i] = 0;
+    }
   }
-  if (tid == 0) { sm.ndist = 0; sm.fallback = 0; sm.maxe = 0; sm.maxg = 0; }
+  if (tid == 0) { sm.ndist = 0; sm.fallback = 0; sm.maxe = 0; sm.maxg = 0; sm.last_rank = NONE32; }
   __syncthreads();
 
   // ---- 1. read, identify, measure ------------------------------------------------------------
@@ -225,6 +280,7 @@ k_task_fused(const FusedArgs A) {
         }
         if (!placed) atomicOr(&sm.fallback, 1u);
         atomicAdd(&sm.ht_cnt[h], 1u);
+        if (ESTATS) early_stats(sm, h, ev[r], gv[r]);
         sl[r] = h;
       }
     }
@@ -344,6 +400,7 @@ k_task_fused(const FusedArgs A) {
           }
           ids[base + i] = id;
           atomicAdd(&sm.ht_cnt[slot], 1u);
+          if (ESTATS) early_stats(sm, slot, ev[r], gv[r]);
           sl[r] = slot;
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -403,6 +460,7 @@ k_task_fused(const FusedArgs A) {
       for (uint32_t i = 0; i < D; ++i) rank += (sm.u.tmp.ckey[i] < k);
       const uint32_t s = sm.u.tmp.cslot[j];
       sm.slot_rank[s] = static_cast<uint16_t>(rank);
+      if (ESTATS) sm.rslot[rank] = static_cast<uint16_t>(s);
       sm.rkey[rank] = k;
       sm.rcnt[rank] = sm.ht_cnt[s];
     }
@@ -413,52 +471,73 @@ k_task_fused(const FusedArgs A) {
   __syncthreads();  // tmp is dead from here on; acc reuses the space
 
   // ---- 3. count / sum / min / max per ID ------------------------------------------------------
-  for (uint32_t j = tid; j < D; j += NT) {
-    sm.u.acc.esum[j] = 0; sm.u.acc.emin[j] = ~0u; sm.u.acc.emax[j] = 0;
-    sm.u.acc.gsum[j] = 0; sm.u.acc.gmin[j] = ~0u; sm.u.acc.gmax[j] = 0;
-    sm.gcnt[j] = 0;
-  }
-  __syncthreads();
+  if (ESTATS) {
+    // (gathered while reading; what is left is the number of idle times: every launch but the task's last has one)
 #pragma unroll
-  for (int r = 0; r < KPT; ++r) {
-    const uint32_t i = r * NT + tid;
-    if (i < m) {
-      const uint32_t j = sl[r];
-      atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.esum[j]), static_cast<unsigned long long>(ev[r]));
-      atomicMin(&sm.u.acc.emin[j], ev[r]);
-      atomicMax(&sm.u.acc.emax[j], ev[r]);
-      if (gv[r] != NONE32) {
-        atomicAdd(&sm.gcnt[j], 1u);
-        atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.gsum[j]), static_cast<unsigned long long>(gv[r]));
-        atomicMin(&sm.u.acc.gmin[j], gv[r]);
-        atomicMax(&sm.u.acc.gmax[j], gv[r]);
+    for (int r = 0; r < KPT; ++r)
+      if (r * NT + tid < m && gv[r] == NONE32) sm.last_rank = sl[r];
+  } else {
+    for (uint32_t j = tid; j < D; j += NT) {
+      sm.u.acc.esum[j] = 0; sm.u.acc.emin[j] = ~0u; sm.u.acc.emax[j] = 0;
+      sm.u.acc.gsum[j] = 0; sm.u.acc.gmin[j] = ~0u; sm.u.acc.gmax[j] = 0;
+      sm.gcnt[j] = 0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+      const uint32_t i = r * NT + tid;
+      if (i < m) {
+        const uint32_t j = sl[r];
+        atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.esum[j]), static_cast<unsigned long long>(ev[r]));
+        atomicMin(&sm.u.acc.emin[j], ev[r]);
+        atomicMax(&sm.u.acc.emax[j], ev[r]);
+        if (gv[r] != NONE32) {
+          atomicAdd(&sm.gcnt[j], 1u);
+          atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.gsum[j]), static_cast<unsigned long long>(gv[r]));
+          atomicMin(&sm.u.acc.gmin[j], gv[r]);
+          atomicMax(&sm.u.acc.gmax[j], gv[r]);
+        }
       }
     }
   }
   __syncthreads();
   for (uint32_t j = tid; j < D; j += NT) {
     uint64_t* row = staged_row(stage_a, stage_b, base, m, j);
-    const uint32_t ec = sm.rcnt[j], gc = sm.gcnt[j];
+    const uint32_t ec = sm.rcnt[j];
+    uint32_t gc, emin, emax, gmin, gmax;
+    uint64_t esum, gsum;
+    if (ESTATS) {
+      const uint32_t s = sm.rslot[j];
+      gc = ec - (sm.last_rank == j ? 1u : 0u);
+      sm.gcnt[j] = gc;
+      esum = sm.early.esum[s]; emin = sm.early.emin[s]; emax = sm.early.emax[s];
+      gsum = sm.early.gsum[s]; gmin = sm.early.gmin[s]; gmax = sm.early.gmax[s];
+    } else {
+      gc = sm.gcnt[j];
+      esum = sm.u.acc.esum[j]; emin = sm.u.acc.emin[j]; emax = sm.u.acc.emax[j];
+      gsum = sm.u.acc.gsum[j]; gmin = sm.u.acc.gmin[j]; gmax = sm.u.acc.gmax[j];
+    }
     row[0] = sm.rkey[j];
     row[1] = t;
-    row[2] = ec; row[3] = sm.u.acc.esum[j]; row[4] = sm.u.acc.emin[j]; row[5] = sm.u.acc.emax[j];
-    row[8] = gc; row[9] = sm.u.acc.gsum[j];
-    row[10] = gc ? sm.u.acc.gmin[j] : 0; row[11] = gc ? sm.u.acc.gmax[j] : 0;
+    row[2] = ec; row[3] = esum; row[4] = emin; row[5] = emax;
+    row[8] = gc; row[9] = gsum;
+    row[10] = gc ? gmin : 0; row[11] = gc ? gmax : 0;
     row[14] = 0; row[15] = 0;
     sm.kth[0][j] = static_cast<uint16_t>(rank_index_u32(50, ec));
     sm.kth[1][j] = static_cast<uint16_t>(rank_index_u32(95, ec));
     sm.kth[2][j] = static_cast<uint16_t>(gc ? rank_index_u32(50, gc) : 0);
     sm.kth[3][j] = static_cast<uint16_t>(gc ? rank_index_u32(95, gc) : 0);
     sm.pref[j] = make_uint4(0, 0, 0, 0);
-    const uint32_t mxe = sm.u.acc.emax[j], mxg = gc ? sm.u.acc.gmax[j] : 0;
+    const uint32_t mxe = emax, mxg = gc ? gmax : 0;
     {
-      // window of the fast percentile path: the ID's own value range, cut into 2^B1 bins
+      // window of the fast percentile path: the ID's own value range, cut into bins
       uint2* sel0 = reinterpret_cast<uint2*>(sm.ht_key);   // the ID table is dead by now
-      const uint32_t lo_e = sm.u.acc.emin[j], lo_g = gc ? sm.u.acc.gmin[j] : 0;
+      const uint32_t lo_e = emin, lo_g = gc ? gmin : 0;
       const uint32_t re = mxe - lo_e, rg = mxg - lo_g;
       const uint32_t we = re ? 32 - __builtin_clz(re) : 0, wg = rg ? 32 - __builtin_clz(rg) : 0;
-      sel0[j] = make_uint2(lo_e, we > static_cast<uint32_t>(B1) ? we - B1 : 0);
-      sel0[D + j] = make_uint2(lo_g, wg > static_cast<uint32_t>(B1) ? wg - B1 : 0);
+      const uint32_t be = window_bins_log2(ec, B1), bg = window_bins_log2(gc, B1);
+      sel0[j] = make_uint2(lo_e, we > be ? we - be : 0);
+      sel0[D + j] = make_uint2(lo_g, wg > bg ? wg - bg : 0);
     }
     sm.npass[0][j] = static_cast<uint8_t>(((mxe ? 32 - __builtin_clz(mxe) : 1) + B - 1) / B);
     sm.npass[1][j] = static_cast<uint8_t>(((mxg ? 32 - __builtin_clz(mxg) : 1) + B - 1) / B);
@@ -477,7 +556,6 @@ k_task_fused(const FusedArgs A) {
   constexpr uint32_t LIST_MAX = 64;
   const uint32_t bins = 1u << B;
   const uint32_t P2 = 2 * D;   // (ID, array) pairs
-  const uint32_t bins1 = 1u << B1;
   for (uint32_t i = tid; i < HIST_WORDS; i += NT) sm.u.hist[i] = 0;
   if (tid == 0) sm.fallback = 0;
   __syncthreads();
@@ -498,40 +576,75 @@ k_task_fused(const FusedArgs A) {
     }
   }
   __syncthreads();
-  for (uint32_t q = tid; q < P2; q += NT) {
-    const uint32_t arr = q >= D ? 1u : 0u, j = q - arr * D;
-    const uint32_t k50 = sm.kth[2 * arr][j], k95 = sm.kth[2 * arr + 1][j];
-    const uint32_t cnt_all = arr ? sm.gcnt[j] : sm.rcnt[j];
-    uint32_t cum = 0, d50 = 0, d95 = 0, n50 = 0, n95 = 0, c50 = 0, c95 = 0;
-    bool f50 = false, f95 = false;
-    for (uint32_t wd = 0; wd < (bins1 >> 1); ++wd) {
-      const uint32_t pair = sm.u.hist[wd * P2 + q];
-      sm.u.hist[wd * P2 + q] = 0;
-      const uint32_t c0 = pair & 0xffffu, c1 = pair >> 16;
-      if (!f50 && k50 < cum + c0) { f50 = true; d50 = 2 * wd; n50 = k50 - cum; c50 = c0; }
-      if (!f95 && k95 < cum + c0) { f95 = true; d95 = 2 * wd; n95 = k95 - cum; c95 = c0; }
-      cum += c0;
-      if (!f50 && k50 < cum + c1) { f50 = true; d50 = 2 * wd + 1; n50 = k50 - cum; c50 = c1; }
-      if (!f95 && k95 < cum + c1) { f95 = true; d95 = 2 * wd + 1; n95 = k95 - cum; c95 = c1; }
-      cum += c1;
-    }
-    const uint2 se = sel[q];
-    uint32_t la = 0, lb = 0;
-    if (cnt_all == 0) {
-      // no samples: both percentiles are 0, nothing to collect (bins 0xff never match a digit)
-      sel[q] = make_uint2(se.x, se.y | (0xffu << 8) | (0xffu << 16));
-    } else {
-      sel[q] = make_uint2(se.x, se.y | (d50 << 8) | (d95 << 16));
-      if (se.y != 0) {   // (bins one value wide: the bin is the answer, nothing to collect)
-        la = c50;
-        lb = (d95 != d50) ? c95 : 0;
-        if (la > LIST_MAX || lb > LIST_MAX) atomicOr(&sm.fallback, 1u);
-        sm.kth[2 * arr][j] = static_cast<uint16_t>(n50);
-        sm.kth[2 * arr + 1][j] = static_cast<uint16_t>(n95);
+  {
+    // 1, 2, 4 or 8 lanes per (ID, array), as many as there are threads for: each sums its slice of the
+    // pair's bins, a prefix sum over the slices tells which lane's slice holds each wanted rank, and
+    // that lane finds the bin.  (Groups of lanes are aligned inside the rows of 16 lanes.)
+    const uint32_t per = static_cast<uint32_t>(NT) / P2;
+    const uint32_t wg_log2 = per >= 8 ? 3u : (per >= 4 ? 2u : (per >= 2 ? 1u : 0u)), WG = 1u << wg_log2;
+    const uint32_t gl = tid & (WG - 1);
+    for (uint32_t q0 = 0; q0 < P2; q0 += NT >> wg_log2) {   // (trip count is the same for all lanes of a wave)
+      const uint32_t q = q0 + (tid >> wg_log2);
+      const bool live = q < P2;
+      const uint32_t arr = (live && q >= D) ? 1u : 0u, j = live ? q - arr * D : 0u;
+      const uint32_t k50 = sm.kth[2 * arr][j], k95 = sm.kth[2 * arr + 1][j];
+      const uint32_t cnt_all = arr ? sm.gcnt[j] : sm.rcnt[j];
+      const uint32_t sh = live ? (sel[q].y & 0xffu) : 0u;
+      const uint32_t words = live ? (1u << window_bins_log2(cnt_all, B1)) >> 1 : 0u, wpl = (words + WG - 1) >> wg_log2;
+      const uint32_t w_lo = gl * wpl < words ? gl * wpl : words, w_hi = w_lo + wpl < words ? w_lo + wpl : words;
+      uint32_t mine = 0, incl = 0;
+      if (WG > 1) {
+        for (uint32_t w = w_lo; w < w_hi; ++w) {
+          const uint32_t pair = sm.u.hist[w * P2 + q];
+          mine += (pair & 0xffffu) + (pair >> 16);
+        }
+        uint32_t up;
+        incl = mine;
+        up = dpp_or_zero<0x111, 0xf>(incl); incl += gl >= 1 ? up : 0u;
+        if (WG > 2) { up = dpp_or_zero<0x112, 0xf>(incl); incl += gl >= 2 ? up : 0u; }
+        if (WG > 4) { up = dpp_or_zero<0x114, 0xf>(incl); incl += gl >= 4 ? up : 0u; }
+      }
+      // bins of this lane's slice that hold the wanted ranks (if any): bin number, rank inside it, its count
+      uint32_t cum = incl - mine, bin50 = 0, n50 = 0, c50 = 0, bin95 = 0, n95 = 0, c95 = 0;
+      bool has50 = false, has95 = false, same_bin = false;
+      for (uint32_t w = w_lo; w < w_hi; ++w) {
+        const uint32_t pair = sm.u.hist[w * P2 + q];
+        sm.u.hist[w * P2 + q] = 0;
+#pragma unroll
+        for (uint32_t h = 0; h < 2; ++h) {
+          const uint32_t c = h ? pair >> 16 : pair & 0xffffu;
+          const bool f50 = k50 >= cum && k50 < cum + c, f95 = k95 >= cum && k95 < cum + c;
+          if (f50) { has50 = true; bin50 = 2 * w + h; n50 = k50 - cum; c50 = c; }
+          if (f95) { has95 = true; bin95 = 2 * w + h; n95 = k95 - cum; c95 = c; same_bin = k50 >= cum; }
+          cum += c;
+        }
+      }
+      if (live && cnt_all == 0) {
+        if (gl == 0) {
+          // no samples: both percentiles are 0, nothing to collect (bins 0xff never match a digit)
+          sel[q].y = sh | (0xffu << 8) | (0xffu << 16);
+          lcnt[(2 * arr) * DMAX + j] = 0;
+          lcnt[(2 * arr + 1) * DMAX + j] = 0;
+        }
+      } else if (live) {
+        // (bins one value wide, shift 0: the bin is the answer, nothing to collect)
+        if (has50) {
+          const uint32_t la = sh ? c50 : 0u;
+          atomicOr(&sel[q].y, bin50 << 8);
+          lcnt[(2 * arr) * DMAX + j] = static_cast<uint16_t>(la);
+          if (sh) sm.kth[2 * arr][j] = static_cast<uint16_t>(n50);
+          if (la > LIST_MAX) atomicOr(&sm.fallback, 1u);
+        }
+        if (has95) {
+          // (the lower rank may lie in this bin too: then one list serves both)
+          const uint32_t lb = (sh && !same_bin) ? c95 : 0u;
+          atomicOr(&sel[q].y, bin95 << 16);
+          lcnt[(2 * arr + 1) * DMAX + j] = static_cast<uint16_t>(lb);
+          if (sh) sm.kth[2 * arr + 1][j] = static_cast<uint16_t>(n95);
+          if (lb > LIST_MAX) atomicOr(&sm.fallback, 1u);
+        }
       }
     }
-    lcnt[(2 * arr) * DMAX + j] = static_cast<uint16_t>(la);
-    lcnt[(2 * arr + 1) * DMAX + j] = static_cast<uint16_t>(lb);
   }
   __syncthreads();
   const bool use_lists = (sm.fallback == 0);
@@ -603,8 +716,7 @@ k_task_fused(const FusedArgs A) {
         const uint32_t* la = lists + loff[(2 * arr) * DMAX + j];
         for (uint32_t x = gl; x < ca; x += GS) {
           const uint32_t v = la[x];
-          uint32_t rank = 0;
-          for (uint32_t y = 0; y < ca; ++y) { const uint32_t o = la[y]; rank += (o < v || (o == v && y < x)) ? 1u : 0u; }
+          const uint32_t rank = list_rank(la, ca, v, x);
           if (rank == k50) row[arr ? 12 : 6] = v;
           if (cb == 0 && rank == k95) row[arr ? 13 : 7] = v;
         }
@@ -612,8 +724,7 @@ k_task_fused(const FusedArgs A) {
           const uint32_t* lb = lists + loff[(2 * arr + 1) * DMAX + j];
           for (uint32_t x = gl; x < cb; x += GS) {
             const uint32_t v = lb[x];
-            uint32_t rank = 0;
-            for (uint32_t y = 0; y < cb; ++y) { const uint32_t o = lb[y]; rank += (o < v || (o == v && y < x)) ? 1u : 0u; }
+            const uint32_t rank = list_rank(lb, cb, v, x);
             if (rank == k95) row[arr ? 13 : 7] = v;
           }
         }
