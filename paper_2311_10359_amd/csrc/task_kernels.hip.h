@@ -66,15 +66,17 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* aux, u
   return base + incl - v;
 }
 
-// One remembered kernel identity: the 32 identity bytes, the Kernel ID they hash to and the
-// slot that ID occupies in the ID table.  `ready` holds the entry's tag once the rest is valid.
-struct MemoEntry {
-  uint32_t w[8];
-  uint64_t id;
-  uint32_t slot;
-  uint32_t ready;
+// Remembered kernel identities: the 32 identity bytes (two 16-byte halves), the Kernel ID they hash to
+// and the slot that ID occupies in the ID table; `ready` holds the entry's tag once the rest is valid.
+// One array per field: lanes that look at different entries then fall on different LDS banks
+// (48-byte records would put every entry on one of only eight bank groups).
+template <int HT>
+struct Memo {
+  uint4 wa[HT], wb[HT];
+  uint64_t id[HT];
+  uint32_t slot[HT];
+  uint32_t ready[HT];
 };
-static_assert(sizeof(MemoEntry) == 48, "memo entry is 48 bytes");
 
 // With ESTATS the sums, minima and maxima are gathered while the records are being read (per slot
 // of the ID table, since ranks are not known yet): the memory pipe is the busy one then, LDS is idle.
@@ -93,7 +95,7 @@ struct FusedSmem {
   uint8_t npass[2][DMAX];    //                  passes this ID's execution / idle times need (from their max)
   uint32_t memo_claim[HT];   // 0 = free, else the tag of the claiming identity
   union {
-    MemoEntry memo[HT];      // phase 1
+    Memo<HT> memo;           // phase 1
     struct { uint64_t ckey[DMAX]; uint32_t cslot[DMAX]; } tmp;   // phase 2
     struct { uint64_t esum[DMAX], gsum[DMAX]; uint32_t emin[DMAX], emax[DMAX], gmin[DMAX], gmax[DMAX]; } acc;  // phase 3
     uint32_t hist[HIST_WORDS];  // phase 4
@@ -231,7 +233,7 @@ k_task_fused(const FusedArgs A) {
   const uint32_t tid = threadIdx.x;
 
   for (uint32_t i = tid; i < HT; i += NT) {
-    sm.ht_key[i] = HT_EMPTY; sm.ht_cnt[i] = 0; sm.memo_claim[i] = 0; sm.u.memo[i].ready = 0;
+    sm.ht_key[i] = HT_EMPTY; sm.ht_cnt[i] = 0; sm.memo_claim[i] = 0; sm.u.memo.ready[i] = 0;
     if (ESTATS) {
       sm.early.esum[i] = 0; sm.early.emin[i] = ~0u; sm.early.emax[i] = 0;
       sm.early.gsum[i] = 0; sm.early.gmin[i] = ~0u; sm.early.gmax[i] = 0;
@@ -333,14 +335,14 @@ k_task_fused(const FusedArgs A) {
           bool hit = false;
 #pragma unroll 1
           for (int probe = 0; probe < 4; ++probe) {
-            const uint32_t rd = __hip_atomic_load(&sm.u.memo[mh].ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const uint32_t rd = __hip_atomic_load(&sm.u.memo.ready[mh], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
             if (rd == tag) {
-              const uint4 ma = *reinterpret_cast<const uint4*>(&sm.u.memo[mh].w[0]);
-              const uint4 mb = *reinterpret_cast<const uint4*>(&sm.u.memo[mh].w[4]);
+              const uint4 ma = sm.u.memo.wa[mh];
+              const uint4 mb = sm.u.memo.wb[mh];
               if (ma.x == a.x && ma.y == a.y && ma.z == a.z && ma.w == a.w && mb.x == b.x && mb.y == b.y && mb.z == b.z &&
                   mb.w == b.w) {
-                id = sm.u.memo[mh].id;
-                slot = sm.u.memo[mh].slot;
+                id = sm.u.memo.id[mh];
+                slot = sm.u.memo.slot[mh];
                 hit = true;
                 break;
               }
@@ -375,21 +377,20 @@ k_task_fused(const FusedArgs A) {
               for (int probe = 0; probe < 4; ++probe) {
                 const uint32_t old = atomicCAS(&sm.memo_claim[ch], 0u, tag);
                 if (old == 0) {
-                  MemoEntry& me = sm.u.memo[ch];
-                  *reinterpret_cast<uint4*>(&me.w[0]) = a;
-                  *reinterpret_cast<uint4*>(&me.w[4]) = b;
-                  me.id = id;
-                  me.slot = slot;
-                  __hip_atomic_store(&me.ready, tag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                  sm.u.memo.wa[ch] = a;
+                  sm.u.memo.wb[ch] = b;
+                  sm.u.memo.id[ch] = id;
+                  sm.u.memo.slot[ch] = slot;
+                  __hip_atomic_store(&sm.u.memo.ready[ch], tag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                   break;
                 }
                 if (old == tag) {
                   // same tag: the same identity is being (or has been) remembered by someone else, or a
                   // different identity shares the tag; either way leave this one out if it is the former
-                  const uint32_t rd = __hip_atomic_load(&sm.u.memo[ch].ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                  const uint32_t rd = __hip_atomic_load(&sm.u.memo.ready[ch], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
                   if (rd == 0) break;  // being written right now: do not wait for it
-                  const uint4 ma = *reinterpret_cast<const uint4*>(&sm.u.memo[ch].w[0]);
-                  const uint4 mb = *reinterpret_cast<const uint4*>(&sm.u.memo[ch].w[4]);
+                  const uint4 ma = sm.u.memo.wa[ch];
+                  const uint4 mb = sm.u.memo.wb[ch];
                   if (ma.x == a.x && ma.y == a.y && ma.z == a.z && ma.w == a.w && mb.x == b.x && mb.y == b.y &&
                       mb.z == b.z && mb.w == b.w)
                     break;
