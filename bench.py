@@ -38,7 +38,7 @@ ALGO_BYTES_PER_RECORD = {
     "k_tile_scatter": 24 + 24,
     "k_unit_fused": 24,
 }
-GAPFILL_KERNELS = ("k_gf_predict", "k_gf_walk")
+GAPFILL_KERNELS = ("k_gf_predict", "k_gf_walk", "k_gf_predict32", "k_gf_walk_lanes")
 
 
 def source_hash():
@@ -236,11 +236,14 @@ def main():
     avg_ms = dom_ms / dom_cnt
     if dom in ALGO_BYTES_PER_RECORD:
         algo_bytes = ALGO_BYTES_PER_RECORD[dom] * units[dom]
-    elif dom == "k_gf_predict":
+    elif dom == "k_gf_predict":      # IDs read; prefix sums, idle times and gap-open times written (8 bytes each)
         algo_bytes = 8 * (n_hp + n_lp) + 8 * n_lp + 16 * n_hp
-    else:
-        algo_bytes = 8 * n_hp * (n_scen // max(1, len(np.unique(hp)))) + 8 * n_lp * (n_scen // max(1, len(np.unique(lp)))) \
-            + 12 * n_gaps
+    elif dom == "k_gf_predict32":    # IDs read; 32-bit execution times (queue) and (execution, idle) pairs (trace) written
+        algo_bytes = 8 * (n_hp + n_lp) + 4 * n_lp + 8 * n_hp
+    else:                            # every scenario reads its trace and its queue once and writes 12 bytes per gap
+        per_hp, per_lp = (8, 8) if dom == "k_gf_walk" else (8, 4)
+        algo_bytes = per_hp * n_hp * (n_scen // max(1, len(np.unique(hp)))) \
+            + per_lp * n_lp * (n_scen // max(1, len(np.unique(lp)))) + 12 * n_gaps
     achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
     roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": stored_traffic(dom, name),

@@ -425,6 +425,11 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   return FIKIT_OK;
 }
 
+// The per-launch arrays of the gap fill are read in 64-byte pieces that may reach past the last launch.
+constexpr uint64_t GF_PAD = 256;
+// One lane per scenario pays off once there are about as many scenarios as the GPU has lanes to run at a time.
+constexpr uint64_t GF_LANES_MIN_SCENARIOS = 4096;
+
 size_t fikit_gapfill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios) {
   (void)n_scenarios;
   if (n_ids >= MAX_ELEMS) return 0;
@@ -432,8 +437,9 @@ size_t fikit_gapfill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t 
   c.take(256);
   c.take(static_cast<uint64_t>(n_tasks) * 4);
   c.take(static_cast<uint64_t>(n_tasks) * 4 * 2);
-  c.take(n_ids * 8);
-  c.take(n_ids * 8);
+  c.take(static_cast<uint64_t>(n_tasks) * 8);
+  c.take(n_ids * 8 + GF_PAD);
+  c.take(n_ids * 8 + GF_PAD);
   c.take(n_ids * 8);
   return static_cast<size_t>(c.at);
 }
@@ -470,9 +476,13 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
   uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
   uint32_t* glists = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4 * 2));
-  int64_t* pe = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
-  int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
+  uint64_t* lp_total = reinterpret_cast<uint64_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 8));
+  int64_t* pe = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
+  int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
   int64_t* open = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
+  // the 32-bit arrays of the one-lane-per-scenario kernels share the space of the 64-bit ones
+  uint32_t* lp_e = reinterpret_cast<uint32_t*>(pe);
+  uint2* hp_eg = reinterpret_cast<uint2*>(pg);
 
   Tracer tr(st);
   tr.mark("gf_setup");
@@ -481,11 +491,29 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_ids, ctrl);
   hipLaunchKernelGGL(k_gf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
                      d_lp_task, n_scenarios, d_gap_offsets, role, ctrl);
-  tr.mark("k_gf_predict");
+  tr.mark("gf_lists");
   hipLaunchKernelGGL(k_gf_lists, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, role, 8192u, glists,
                      ctrl);
+  // Many scenarios: one lane per scenario on 32-bit predictions; the 64-bit kernels then only run if a
+  // prediction did not fit (they check Ctrl::wide).  Few scenarios: the 64-bit kernels, a group of lanes each.
+  const bool lanes = n_scenarios >= GF_LANES_MIN_SCENARIOS && n_gaps < MAX_ELEMS;
+  if (lanes) {
+    tr.mark("k_gf_predict32");
+    hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                       d_task_row_offsets, role, glists, lp_e, hp_eg, lp_total, ctrl);
+    tr.mark("k_gf_walk_lanes");
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  static_cast<int>(sizeof(LaneWalkSmem))));
+    const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
+    hipLaunchKernelGGL(k_gf_walk_lanes, dim3(blocks_for(n_scenarios, LW_THREADS)), dim3(LW_THREADS), sizeof(LaneWalkSmem), st,
+                       d_task_offsets, d_hp_task, d_lp_task, n_scenarios, d_gap_offsets, lp_e, hp_eg, lp_total,
+                       h_params->margin_ns, h_params->min_gap_ns, d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed,
+                       vec_ok, ctrl);
+  }
+  const uint32_t only_if_wide = lanes ? 1u : 0u;
+  tr.mark("k_gf_predict");
   hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                     d_task_row_offsets, role, glists, pe, pg, open, ctrl);
+                     d_task_row_offsets, role, glists, pe, pg, open, only_if_wide, ctrl);
 #ifndef FIKIT_WALK_GW
 #define FIKIT_WALK_GW 16
 #define FIKIT_WALK_WINDOW false
@@ -494,7 +522,7 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   tr.mark("k_gf_walk");
   hipLaunchKernelGGL((k_gf_walk<GW, FIKIT_WALK_WINDOW>), dim3(blocks_for(n_scenarios, 256 / GW)), dim3(256), 0, st, d_task_offsets, d_hp_task,
                      d_lp_task, n_scenarios, d_gap_offsets, pe, pg, open, h_params->margin_ns, h_params->min_gap_ns,
-                     d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed, ctrl);
+                     d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed, only_if_wide, ctrl);
   FIKIT_HIP(hipGetLastError());
   tr.mark("host_sync");
   Ctrl h{};

@@ -88,10 +88,11 @@ __global__ void __launch_bounds__(PRED_THREADS) __attribute__((amdgpu_waves_per_
 k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
              const fikit_row* __restrict__ rows, const uint64_t* __restrict__ row_off, const uint32_t* __restrict__ role,
              const uint32_t* __restrict__ lists, int64_t* __restrict__ pe, int64_t* __restrict__ pg,
-             int64_t* __restrict__ open, Ctrl* ctrl) {
+             int64_t* __restrict__ open, uint32_t only_if_wide, Ctrl* ctrl) {
   __shared__ PredTable tb;
   // only bits that earlier kernels set: the decision must be the same for the whole workgroup
   if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
+  if (only_if_wide && !ctrl->wide) return;
   const uint32_t n_short = ctrl->n_class[0], n_longer = ctrl->n_class[1];   // final: set by an earlier kernel
   if (blockIdx.x >= n_short + n_longer) return;
   const uint32_t t = blockIdx.x < n_short ? lists[blockIdx.x] : lists[static_cast<uint64_t>(n_tasks) + (blockIdx.x - n_short)];
@@ -198,8 +199,9 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
           uint64_t n_scen, const uint64_t* __restrict__ gap_off, const int64_t* __restrict__ pe,
           const int64_t* __restrict__ pg, const int64_t* __restrict__ open, int64_t margin, int64_t min_gap,
           uint32_t* __restrict__ fill_count, int64_t* __restrict__ filled_ns, int64_t* __restrict__ completion_out,
-          uint64_t* __restrict__ placed_out, const Ctrl* ctrl) {
+          uint64_t* __restrict__ placed_out, uint32_t only_if_wide, const Ctrl* ctrl) {
   if (ctrl->status) return;
+  if (only_if_wide && !ctrl->wide) return;
   constexpr int GROUPS_PER_BLOCK = 256 / GW;
   const uint64_t s = static_cast<uint64_t>(blockIdx.x) * GROUPS_PER_BLOCK + threadIdx.x / GW;
   if (s >= n_scen) return;  // whole groups leave together
@@ -291,5 +293,296 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
     placed_out[s] = p;
   }
 }
+
+// ---------------------------------------------------------------------------------------------
+// One lane per scenario.
+//
+// When there are many scenarios, the cheapest way to run Algorithm 1 is its literal form, one lane per
+// scenario: keep what is left of the current gap, and issue the head of the low-priority queue while
+// its predicted duration fits.  A lane needs the predicted execution time of every low-priority
+// launch once, in order, and the predicted (execution time, idle time) of every high-priority launch
+// once, in order: two streams per lane.  They are stored as 32-bit numbers (4 and 8 bytes per launch
+// instead of three 8-byte arrays); a prediction that does not fit 32 bits sets Ctrl::wide and the
+// call is redone with the 64-bit kernels above.
+//
+// Each lane steps through its own scenario: a step either opens the next gap or tries the next queue
+// entry, so lanes of a wave do not wait for the slowest gap.  Streams are read 64 bytes per lane at a
+// time into registers and parked in per-lane LDS rings one period (LW_PERIOD steps) later, which
+// hides the memory latency; a lane whose ring is empty simply idles for a step.  Results are staged
+// in LDS and written 8 gaps at a time.
+
+constexpr uint32_t WIDE32 = 0xffffffffu;   // 32-bit predictions must be below this
+
+// Predicted values of every launch of the tasks that take part, in 32 bits:
+//   lp_e[i]  execution time, for tasks used as low-priority queue; lp_total[t] their sum
+//   hp_eg[i] (execution time, idle time), for tasks used as high-priority trace
+__global__ void __launch_bounds__(PRED_THREADS)
+k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
+               const fikit_row* __restrict__ rows, const uint64_t* __restrict__ row_off, const uint32_t* __restrict__ role,
+               const uint32_t* __restrict__ lists, uint32_t* __restrict__ lp_e, uint2* __restrict__ hp_eg,
+               uint64_t* __restrict__ lp_total, Ctrl* ctrl) {
+  __shared__ PredTable tb;
+  __shared__ uint64_t wave_tot[PRED_THREADS / WAVE];
+  if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
+  const uint32_t n_short = ctrl->n_class[0], n_longer = ctrl->n_class[1];   // final: set by an earlier kernel
+  if (blockIdx.x >= n_short + n_longer) return;
+  const uint32_t t = blockIdx.x < n_short ? lists[blockIdx.x] : lists[static_cast<uint64_t>(n_tasks) + (blockIdx.x - n_short)];
+  const uint32_t rl = role[t];
+  if (rl == 0) return;
+  const uint64_t base = off[t], len = off[t + 1] - base;
+  const uint64_t r0 = row_off[t], nr = row_off[t + 1] - r0;
+  const uint32_t tid = threadIdx.x;
+  const bool in_lds = nr <= PRED_ROWS && (nr == 0 || rows[r0 + nr - 1].kernel_id != ~0ull);
+  if (in_lds) {
+    for (uint32_t h = tid; h < PRED_HT; h += PRED_THREADS) tb.key[h] = ~0ull;
+    __syncthreads();
+    for (uint32_t r = tid; r < nr; r += PRED_THREADS) {
+      const fikit_row* row = rows + r0 + r;
+      const uint64_t id = row->kernel_id;
+      uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (PRED_HT - 1);
+      for (;;) {   // IDs of a task are distinct and fill at most half the table: a free slot exists
+        const uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(&tb.key[h]), ~0ull, id);
+        if (old == ~0ull) break;
+        h = (h + 1) & (PRED_HT - 1);
+      }
+      tb.e[h] = row->exec.p50;
+      tb.g[h] = row->gap.p50;
+    }
+  }
+  __syncthreads();
+  bool unknown = false, wide = false;
+  uint64_t total = 0;
+  const bool even = ((base & 1) == 0);   // 16-byte accesses need an even first index
+  for (uint64_t i0 = 2 * static_cast<uint64_t>(tid); i0 < len; i0 += 2 * PRED_THREADS) {
+    uint64_t id0 = 0, id1 = 0;
+    const bool two = i0 + 1 < len;
+    if (even && two) {
+      const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(ids + base + i0);
+      id0 = v.x; id1 = v.y;
+    } else {
+      id0 = ids[base + i0];
+      if (two) id1 = ids[base + i0 + 1];
+    }
+    int64_t e0 = 0, g0 = 0, e1 = 0, g1 = 0;
+    unknown |= !predict_one(id0, in_lds, tb, rows, r0, nr, e0, g0);
+    if (two) unknown |= !predict_one(id1, in_lds, tb, rows, r0, nr, e1, g1);
+    wide |= static_cast<uint64_t>(e0) >= WIDE32 || static_cast<uint64_t>(g0) >= WIDE32 || static_cast<uint64_t>(e1) >= WIDE32 ||
+            static_cast<uint64_t>(g1) >= WIDE32;
+    const uint32_t a0 = static_cast<uint32_t>(e0), b0 = static_cast<uint32_t>(g0), a1 = static_cast<uint32_t>(e1),
+                   b1 = static_cast<uint32_t>(g1);
+    total += static_cast<uint64_t>(a0) + a1;
+    if (even && two) {
+      if (rl & ROLE_LP) *reinterpret_cast<uint2*>(lp_e + base + i0) = make_uint2(a0, a1);
+      if (rl & ROLE_HP) *reinterpret_cast<uint4*>(hp_eg + base + i0) = make_uint4(a0, b0, a1, b1);
+    } else {
+      if (rl & ROLE_LP) { lp_e[base + i0] = a0; if (two) lp_e[base + i0 + 1] = a1; }
+      if (rl & ROLE_HP) { hp_eg[base + i0] = make_uint2(a0, b0); if (two) hp_eg[base + i0 + 1] = make_uint2(a1, b1); }
+    }
+  }
+  total = wave_sum_u64(total);
+  if (lane_id() == 0) wave_tot[tid >> 6] = total;
+  __syncthreads();
+  if (tid == 0) {
+    uint64_t sum = 0;
+    for (int w = 0; w < PRED_THREADS / WAVE; ++w) sum += wave_tot[w];
+    lp_total[t] = sum;
+  }
+  if (unknown) atomicOr(&ctrl->status, ERR_UNKNOWN_ID);
+  if (wide) atomicOr(&ctrl->wide, 1u);
+}
+
+constexpr int LW_THREADS = 256;
+constexpr uint32_t LW_PERIOD = 16;                 // steps between two rounds of stream reads / result writes
+constexpr uint32_t LW_LP_CHUNK = 16, LW_LP_CAP = 32;   // low-priority ring: entries read at a time, capacity
+constexpr uint32_t LW_HP_CHUNK = 8, LW_HP_CAP = 16;    // high-priority ring
+constexpr uint32_t LW_OUT_CHUNK = 8, LW_OUT_CAP = 32;  // staged results
+
+struct LaneWalkSmem {   // [entry][lane]: a lane's entries fall on one bank whatever position it is at
+  uint32_t lp[LW_LP_CAP][LW_THREADS];
+  uint32_t hp_e[LW_HP_CAP][LW_THREADS];
+  uint32_t hp_g[LW_HP_CAP][LW_THREADS];
+  uint32_t out_c[LW_OUT_CAP][LW_THREADS];
+  uint32_t out_f[LW_OUT_CAP][LW_THREADS];
+};
+
+// Writes the staged results of gaps [first, first + count) (global gap numbers) of the calling lane.
+__device__ __forceinline__ void lw_store_scalar(const LaneWalkSmem& sm, uint32_t tid, uint32_t first, uint32_t count,
+                                                uint32_t* __restrict__ fill_count, int64_t* __restrict__ filled_ns) {
+  for (uint32_t k = 0; k < count; ++k) {
+    const uint32_t at = first + k;
+    fill_count[at] = sm.out_c[at & (LW_OUT_CAP - 1)][tid];
+    filled_ns[at] = static_cast<int64_t>(sm.out_f[at & (LW_OUT_CAP - 1)][tid]);
+  }
+}
+
+__global__ void __launch_bounds__(LW_THREADS)
+k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task, const uint32_t* __restrict__ lp_task,
+                uint64_t n_scen, const uint64_t* __restrict__ gap_off, const uint32_t* __restrict__ lp_e,
+                const uint2* __restrict__ hp_eg, const uint64_t* __restrict__ lp_total, int64_t margin, int64_t min_gap,
+                uint32_t* __restrict__ fill_count, int64_t* __restrict__ filled_ns, int64_t* __restrict__ completion_out,
+                uint64_t* __restrict__ placed_out, uint32_t vec_ok, const Ctrl* ctrl) {
+  extern __shared__ __align__(16) unsigned char lw_raw[];
+  LaneWalkSmem& sm = *reinterpret_cast<LaneWalkSmem*>(lw_raw);
+  if (ctrl->status || ctrl->wide) return;
+  const uint32_t tid = threadIdx.x;
+  const uint64_t s = static_cast<uint64_t>(blockIdx.x) * LW_THREADS + tid;
+  const bool valid = s < n_scen;
+
+  // positions are global element numbers (all below 2^32)
+  uint32_t h0 = 0, hp_end = 0, l0 = 0, lp_end = 0, g_first = 0, n_gaps = 0;
+  uint64_t total_lp = 0;
+  if (valid) {
+    const uint32_t hp = hp_task[s], lp = lp_task[s];
+    h0 = static_cast<uint32_t>(off[hp]); hp_end = static_cast<uint32_t>(off[hp + 1]);
+    l0 = static_cast<uint32_t>(off[lp]); lp_end = static_cast<uint32_t>(off[lp + 1]);
+    g_first = static_cast<uint32_t>(gap_off[s]);
+    n_gaps = hp_end > h0 ? hp_end - h0 - 1 : 0;
+    total_lp = lp_end > l0 ? lp_total[lp] : 0;
+  }
+  uint32_t hp_pos = h0, lp_pos = l0;                    // next entry of either stream
+  uint32_t hp_landed = h0 & ~(LW_HP_CHUNK - 1), lp_landed = l0 & ~(LW_LP_CHUNK - 1);   // ring holds entries below these
+  uint32_t hp_req = 0, lp_req = 0;
+  bool hp_fly = false, lp_fly = false;
+  uint4 hr[4], lr[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) hr[k] = lr[k] = make_uint4(0, 0, 0, 0);
+
+  uint32_t g = g_first;              // global number of the next gap to report
+  uint32_t flushed = g_first;        // results below this are in memory
+  const uint32_t g_end = g_first + n_gaps;
+  int64_t t_open = 0;                // predicted time line of the high-priority task
+  int64_t cur_open = 0, completion = 0;
+  uint64_t consumed = 0;
+  uint32_t c = 0, f = 0, rem = 0;
+  // a gap is used if it is at least min_gap and at least the margin long (32-bit idle times are below WIDE32)
+  const int64_t floor64 = min_gap > margin ? min_gap : margin;
+  const uint32_t gap_floor = floor64 >= static_cast<int64_t>(WIDE32) ? WIDE32 : static_cast<uint32_t>(floor64);
+  const uint32_t margin32 = margin >= static_cast<int64_t>(WIDE32) ? WIDE32 : static_cast<uint32_t>(margin);
+  bool in_gap = false;
+  bool done = valid && (lp_end == l0);     // the whole queue has been issued
+  bool finished = !valid || done;          // nothing left to step through (remaining gaps, if any, get zeros)
+
+  for (;;) {
+    // ---- once per period: park what was read, read on, write complete groups of results ----
+    if (hp_fly) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t at = (hp_req + 2 * k) & (LW_HP_CAP - 1);
+        sm.hp_e[at][tid] = hr[k].x; sm.hp_g[at][tid] = hr[k].y;
+        sm.hp_e[at + 1][tid] = hr[k].z; sm.hp_g[at + 1][tid] = hr[k].w;
+      }
+      hp_landed = hp_req + LW_HP_CHUNK;
+      hp_fly = false;
+    }
+    if (lp_fly) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t at = (lp_req + 4 * k) & (LW_LP_CAP - 1);
+        sm.lp[at][tid] = lr[k].x; sm.lp[at + 1][tid] = lr[k].y; sm.lp[at + 2][tid] = lr[k].z; sm.lp[at + 3][tid] = lr[k].w;
+      }
+      lp_landed = lp_req + LW_LP_CHUNK;
+      lp_fly = false;
+    }
+    if (!finished && hp_landed < hp_end && static_cast<int32_t>(hp_landed - hp_pos) <= static_cast<int32_t>(LW_HP_CAP - LW_HP_CHUNK)) {
+      const uint4* src = reinterpret_cast<const uint4*>(hp_eg + hp_landed);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) hr[k] = src[k];
+      hp_req = hp_landed;
+      hp_fly = true;
+    }
+    if (!finished && lp_landed < lp_end && static_cast<int32_t>(lp_landed - lp_pos) <= static_cast<int32_t>(LW_LP_CAP - LW_LP_CHUNK)) {
+      const uint4* src = reinterpret_cast<const uint4*>(lp_e + lp_landed);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) lr[k] = src[k];
+      lp_req = lp_landed;
+      lp_fly = true;
+    }
+    if (flushed < g && (flushed & (LW_OUT_CHUNK - 1))) {   // (first results of a scenario, up to a multiple of 8)
+      const uint32_t to8 = LW_OUT_CHUNK - (flushed & (LW_OUT_CHUNK - 1));
+      const uint32_t cnt = g - flushed < to8 ? g - flushed : to8;
+      lw_store_scalar(sm, tid, flushed, cnt, fill_count, filled_ns);
+      flushed += cnt;
+    }
+    while (flushed + LW_OUT_CHUNK <= g) {
+      if (vec_ok) {
+        const uint32_t at = flushed & (LW_OUT_CAP - 1);
+        uint32_t cc[LW_OUT_CHUNK], ff[LW_OUT_CHUNK];
+#pragma unroll
+        for (uint32_t k = 0; k < LW_OUT_CHUNK; ++k) { cc[k] = sm.out_c[at + k][tid]; ff[k] = sm.out_f[at + k][tid]; }
+        uint4* oc = reinterpret_cast<uint4*>(fill_count + flushed);
+        oc[0] = make_uint4(cc[0], cc[1], cc[2], cc[3]);
+        oc[1] = make_uint4(cc[4], cc[5], cc[6], cc[7]);
+        uint4* of = reinterpret_cast<uint4*>(filled_ns + flushed);
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) of[k] = make_uint4(ff[2 * k], 0u, ff[2 * k + 1], 0u);
+      } else {
+        lw_store_scalar(sm, tid, flushed, LW_OUT_CHUNK, fill_count, filled_ns);
+      }
+      flushed += LW_OUT_CHUNK;
+    }
+    if (__all(finished)) break;
+
+    // ---- LW_PERIOD steps, written without branches: a lane either tries the head of the queue
+    // (in a gap) or takes the next high-priority launch (between gaps), or idles when its ring is empty ----
+#pragma unroll
+    for (uint32_t step = 0; step < LW_PERIOD; ++step) {
+      const uint32_t d = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid];
+      const uint32_t E = sm.hp_e[hp_pos & (LW_HP_CAP - 1)][tid], G = sm.hp_g[hp_pos & (LW_HP_CAP - 1)][tid];
+      const bool act = !finished, was_in_gap = in_gap;
+      // in a gap: does the head of the queue fit into what is left?
+      const bool tryq = act && in_gap && lp_pos < lp_landed;
+      const bool fits = tryq && d <= rem;
+      const uint32_t dd = fits ? d : 0u;
+      rem -= dd; f += dd; consumed += dd;
+      c += fits ? 1u : 0u;
+      lp_pos += fits ? 1u : 0u;
+      const bool emptied = fits && lp_pos == lp_end;          // the whole queue has been issued
+      const bool close = (tryq && !fits) || emptied;
+      // between gaps: the next high-priority launch runs, then its gap opens (the last launch has none)
+      const bool idle = act && !in_gap;
+      const bool at_end = idle && hp_pos == hp_end;
+      const bool take = idle && !at_end && hp_pos < hp_landed;
+      hp_pos += take ? 1u : 0u;
+      t_open += take ? static_cast<int64_t>(E) : 0;
+      const bool last = take && hp_pos == hp_end;
+      const bool gap = take && !last;
+      cur_open = gap ? t_open : cur_open;
+      t_open += gap ? static_cast<int64_t>(G) : 0;
+      const bool usable = gap && G >= gap_floor;
+      const bool skip = gap && !usable;
+      // the result of the gap that closes (or is skipped) goes to the staging slot; a slot that is
+      // written early is simply written again
+      sm.out_c[g & (LW_OUT_CAP - 1)][tid] = was_in_gap ? c : 0u;
+      sm.out_f[g & (LW_OUT_CAP - 1)][tid] = was_in_gap ? f : 0u;
+      g += (close || skip) ? 1u : 0u;
+      completion = emptied ? cur_open + static_cast<int64_t>(f) : completion;
+      done = done || emptied;
+      in_gap = (in_gap && !close) || usable;
+      rem = usable ? G - margin32 : rem;
+      c = usable ? 0u : c;
+      f = usable ? 0u : f;
+      finished = finished || emptied || at_end || last;
+    }
+  }
+
+  if (!valid) return;
+  // what is still staged, then zeros for the gaps after the queue ran empty
+  lw_store_scalar(sm, tid, flushed, g - flushed, fill_count, filled_ns);
+  uint32_t z = g;
+  while (z < g_end && (z & (LW_OUT_CHUNK - 1))) { fill_count[z] = 0; filled_ns[z] = 0; ++z; }
+  if (vec_ok) {
+    for (; z + LW_OUT_CHUNK <= g_end; z += LW_OUT_CHUNK) {
+      uint4* oc = reinterpret_cast<uint4*>(fill_count + z);
+      oc[0] = oc[1] = make_uint4(0, 0, 0, 0);
+      uint4* of = reinterpret_cast<uint4*>(filled_ns + z);
+      of[0] = of[1] = of[2] = of[3] = make_uint4(0, 0, 0, 0);
+    }
+  }
+  for (; z < g_end; ++z) { fill_count[z] = 0; filled_ns[z] = 0; }
+  if (!done) completion = t_open + static_cast<int64_t>(total_lp - consumed);
+  completion_out[s] = completion;
+  placed_out[s] = lp_pos - l0;
+}
+
 
 }  // namespace fikit

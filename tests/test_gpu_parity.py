@@ -104,6 +104,71 @@ def test_ragged_and_degenerate_tasks(lens, n_kernels):
     check_gapfill(prof, d_off, off, o_prof, hp, lp, 0, 5000)
 
 
+def all_pairs(tasks):
+    t = np.asarray(tasks, dtype=np.uint32)
+    return np.repeat(t, t.size), np.tile(t, t.size)
+
+
+def test_many_scenarios_take_one_lane_each():
+    """Thousands of scenarios over shared tasks (every ordered pair, a task against itself included):
+    the one-lane-per-scenario kernels, with and without a margin and a minimum gap."""
+    cfg = traces.config(4, n_tasks=72, hp_launches=301, lp_launches=1203)
+    rec, off = traces.build(cfg, threads=4)
+    prof, d_off, o_prof = check_profile(rec, off)
+    hp, lp = all_pairs(range(cfg.n_tasks))
+    assert hp.size >= 4096
+    for margin, min_gap in ((cfg.margin_ns, cfg.min_gap_ns), (0, 100000), (40000, 0)):
+        print(f"{hp.size} scenarios, margin {margin}, min gap {min_gap}", flush=True)
+        check_gapfill(prof, d_off, off, o_prof, hp, lp, margin, min_gap)
+
+
+def test_many_scenarios_ragged_tasks_and_unaligned_outputs():
+    """Empty, one-launch and odd-length tasks in both roles; result buffers that are not 16-byte aligned."""
+    lens = [0, 1, 2, 3, 7, 8, 9, 15, 16, 17, 31, 33, 63, 64, 65, 100, 127, 129, 255, 257, 500, 1000, 1001, 2047,
+            0, 5, 6, 40, 41, 42, 43, 44] + [11 * k + 1 for k in range(32)]
+    rec, off = ragged_trace(4242, lens, 9)
+    prof, d_off, o_prof = check_profile(rec, off)
+    hp, lp = all_pairs(range(len(lens)))
+    assert hp.size >= 4096
+    print(f"{hp.size} scenarios over {len(lens)} ragged tasks", flush=True)
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 300, 0)
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 0, 5000)
+    # the same through buffers that start 4 / 8 bytes past a 16-byte boundary
+    go = traces.gap_offsets(off, hp)
+    n_gaps = int(go[-1])
+    o_ids, o_rows, o_tro = o_prof
+    exp = oracle.gapfill(o_ids, off, o_rows, o_tro, hp, lp, 300, 0, go)
+    out = binding.GapFill(torch.empty(n_gaps + 1, dtype=torch.int32, device=DEV)[1:],
+                          torch.empty(n_gaps + 1, dtype=torch.int64, device=DEV)[1:],
+                          torch.empty(hp.size, dtype=torch.int64, device=DEV),
+                          torch.empty(hp.size, dtype=torch.int64, device=DEV))
+    got = binding.fikit_gapfill(prof.ids, d_off, prof.rows, prof.task_row_offsets, binding.to_device_u32(hp, DEV),
+                                binding.to_device_u32(lp, DEV), binding.to_device_u64(go, DEV), margin_ns=300,
+                                min_gap_ns=0, n_gaps=n_gaps, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(binding.u32_to_numpy(got.fill_count), exp[0])
+    assert np.array_equal(got.filled_ns.cpu().numpy(), exp[1])
+    assert np.array_equal(got.lp_completion_ns.cpu().numpy(), exp[2])
+    assert np.array_equal(binding.u64_to_numpy(got.lp_placed), exp[3])
+
+
+def test_many_scenarios_with_predictions_beyond_32_bits():
+    """A kernel that runs for more than 2^32 ns and an idle time of more than 2^32 ns: the 64-bit kernels take over."""
+    lens = [40 + k for k in range(64)]
+    rec, off = ragged_trace(99, lens, 4)
+    slow = rec["name_id"] == 1
+    ex = (rec["end_ns"] - rec["start_ns"]).astype(np.int64)
+    ex[slow] += 5_000_000_000
+    gp = np.full(rec.shape[0], 1000, dtype=np.int64)
+    gp[rec["name_id"] == 2] = 6_000_000_000
+    start = np.cumsum(ex + gp) - (ex + gp)
+    rec["start_ns"] = start
+    rec["end_ns"] = start + ex
+    prof, d_off, o_prof = check_profile(rec, off)
+    hp, lp = all_pairs(range(len(lens)))
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 300, 0)
+
+
 def test_all_distinct_ids_one_row_per_launch():
     n = 20000
     rec = np.zeros(n, dtype=traces.LAUNCH_DTYPE)
