@@ -305,10 +305,10 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
 // instead of three 8-byte arrays); a prediction that does not fit 32 bits sets Ctrl::wide and the
 // call is redone with the 64-bit kernels above.
 //
-// Each lane steps through its own scenario: a step either opens the next gap or tries the next queue
-// entry, so lanes of a wave do not wait for the slowest gap.  Streams are read 64 bytes per lane at a
-// time into registers and parked in per-lane LDS rings one period (LW_PERIOD steps) later, which
-// hides the memory latency; a lane whose ring is empty simply idles for a step.  Results are staged
+// Each lane steps through its own scenario: a sub-step either opens the next gap or tries the next
+// queue entry, so lanes of a wave do not wait for the slowest gap.  Streams are read 64 bytes per lane
+// at a time into registers and parked in per-lane LDS rings one period later, which hides the memory
+// latency; a lane whose ring is empty simply idles for a sub-step.  Results are staged
 // in LDS and written 8 gaps at a time.
 
 constexpr uint32_t WIDE32 = 0xffffffffu;   // 32-bit predictions must be below this
@@ -392,7 +392,8 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
 }
 
 constexpr int LW_THREADS = 256;
-constexpr uint32_t LW_PERIOD = 16;                 // steps between two rounds of stream reads / result writes
+constexpr uint32_t LW_OPENS = 4, LW_TRIES = 4;     // per period (between two rounds of stream reads / result writes):
+                                                   // gaps opened, and queue entries tried per gap opened
 constexpr uint32_t LW_LP_CHUNK = 16, LW_LP_CAP = 32;   // low-priority ring: entries read at a time, capacity
 constexpr uint32_t LW_HP_CHUNK = 8, LW_HP_CAP = 16;    // high-priority ring
 constexpr uint32_t LW_OUT_CHUNK = 8, LW_OUT_CAP = 32;  // staged results
@@ -522,46 +523,55 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     }
     if (__all(finished)) break;
 
-    // ---- LW_PERIOD steps, written without branches: a lane either tries the head of the queue
-    // (in a gap) or takes the next high-priority launch (between gaps), or idles when its ring is empty ----
+    // ---- one period: LW_OPENS times { take the next high-priority launch and open its gap; LW_TRIES
+    // times try the head of the queue }.  Written without branches; a lane whose ring is empty, or whose
+    // gap is still open when a new one could be taken, simply idles in that sub-step. ----
 #pragma unroll
-    for (uint32_t step = 0; step < LW_PERIOD; ++step) {
-      const uint32_t d = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid];
-      const uint32_t E = sm.hp_e[hp_pos & (LW_HP_CAP - 1)][tid], G = sm.hp_g[hp_pos & (LW_HP_CAP - 1)][tid];
-      const bool act = !finished, was_in_gap = in_gap;
-      // in a gap: does the head of the queue fit into what is left?
-      const bool tryq = act && in_gap && lp_pos < lp_landed;
-      const bool fits = tryq && d <= rem;
-      const uint32_t dd = fits ? d : 0u;
-      rem -= dd; f += dd; consumed += dd;
-      c += fits ? 1u : 0u;
-      lp_pos += fits ? 1u : 0u;
-      const bool emptied = fits && lp_pos == lp_end;          // the whole queue has been issued
-      const bool close = (tryq && !fits) || emptied;
-      // between gaps: the next high-priority launch runs, then its gap opens (the last launch has none)
-      const bool idle = act && !in_gap;
-      const bool at_end = idle && hp_pos == hp_end;
-      const bool take = idle && !at_end && hp_pos < hp_landed;
-      hp_pos += take ? 1u : 0u;
-      t_open += take ? static_cast<int64_t>(E) : 0;
-      const bool last = take && hp_pos == hp_end;
-      const bool gap = take && !last;
-      cur_open = gap ? t_open : cur_open;
-      t_open += gap ? static_cast<int64_t>(G) : 0;
-      const bool usable = gap && G >= gap_floor;
-      const bool skip = gap && !usable;
-      // the result of the gap that closes (or is skipped) goes to the staging slot; a slot that is
-      // written early is simply written again
-      sm.out_c[g & (LW_OUT_CAP - 1)][tid] = was_in_gap ? c : 0u;
-      sm.out_f[g & (LW_OUT_CAP - 1)][tid] = was_in_gap ? f : 0u;
-      g += (close || skip) ? 1u : 0u;
-      completion = emptied ? cur_open + static_cast<int64_t>(f) : completion;
-      done = done || emptied;
-      in_gap = (in_gap && !close) || usable;
-      rem = usable ? G - margin32 : rem;
-      c = usable ? 0u : c;
-      f = usable ? 0u : f;
-      finished = finished || emptied || at_end || last;
+    for (uint32_t o = 0; o < LW_OPENS; ++o) {
+      {
+        const uint32_t E = sm.hp_e[hp_pos & (LW_HP_CAP - 1)][tid], G = sm.hp_g[hp_pos & (LW_HP_CAP - 1)][tid];
+        // between gaps: the next high-priority launch runs, then its gap opens (the last launch has none)
+        const bool idle = !finished && !in_gap;
+        const bool at_end = idle && hp_pos == hp_end;
+        const bool take = idle && !at_end && hp_pos < hp_landed;
+        hp_pos += take ? 1u : 0u;
+        t_open += take ? static_cast<int64_t>(E) : 0;
+        const bool last = take && hp_pos == hp_end;
+        const bool gap = take && !last;
+        cur_open = gap ? t_open : cur_open;
+        t_open += gap ? static_cast<int64_t>(G) : 0;
+        const bool usable = gap && G >= gap_floor;
+        const bool skip = gap && !usable;
+        // a skipped gap reports zeros (a staging slot that is written early is simply written again)
+        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = 0u;
+        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = 0u;
+        g += skip ? 1u : 0u;
+        in_gap = in_gap || usable;
+        rem = usable ? G - margin32 : rem;
+        c = usable ? 0u : c;
+        f = usable ? 0u : f;
+        finished = finished || at_end || last;
+      }
+#pragma unroll
+      for (uint32_t k = 0; k < LW_TRIES; ++k) {
+        // in a gap: does the head of the queue fit into what is left?
+        const uint32_t d = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid];
+        const bool tryq = in_gap && lp_pos < lp_landed;
+        const bool fits = tryq && d <= rem;
+        const uint32_t dd = fits ? d : 0u;
+        rem -= dd; f += dd; consumed += dd;
+        c += fits ? 1u : 0u;
+        lp_pos += fits ? 1u : 0u;
+        const bool emptied = fits && lp_pos == lp_end;          // the whole queue has been issued
+        const bool close = (tryq && !fits) || emptied;
+        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
+        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
+        g += close ? 1u : 0u;
+        completion = emptied ? cur_open + static_cast<int64_t>(f) : completion;
+        done = done || emptied;
+        finished = finished || emptied;
+        in_gap = in_gap && !close;
+      }
     }
   }
 

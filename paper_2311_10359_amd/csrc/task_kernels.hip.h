@@ -28,8 +28,8 @@
 namespace fikit {
 
 constexpr uint64_t HT_EMPTY = ~0ull;
-constexpr uint32_t FUSE_SMALL_MAX = 4096;    // tasks up to this many launches: 256-thread workgroup
-constexpr uint32_t FUSE_MID_MAX = 8192;      // up to this many: 512-thread workgroup
+constexpr uint32_t FUSE_SMALL_MAX = 4096;    // tasks up to this many launches: 512-thread workgroup, 8 launches per thread
+constexpr uint32_t FUSE_MID_MAX = 8192;      // up to this many: 512-thread workgroup, 16 launches per thread
 constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: one larger workgroup
 #ifndef FUSE_M_THREADS_V
 #define FUSE_M_THREADS_V 1024
@@ -37,8 +37,8 @@ constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: 
 #define FUSE_M_HIST_V 16384
 #endif
 #ifndef FUSE_S_THREADS_V
-#define FUSE_S_THREADS_V 256
-#define FUSE_S_WPE_V 3
+#define FUSE_S_THREADS_V 512
+#define FUSE_S_WPE_V 6
 #endif
 #ifndef FUSE_M_ESTATS_V
 #define FUSE_M_ESTATS_V true
