@@ -258,7 +258,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   uint32_t* utask = ulen + L.max_units;
   uint32_t* udcount = utask + L.max_units;
   uint32_t* urow = udcount + L.max_units;
-  auto small = k_task_fused<FUSE_S_THREADS, FUSE_SMALL_MAX / FUSE_S_THREADS, 256, 7168, 4, false, FUSE_S_WPE>;
+  auto small = k_task_fused<FUSE_S_THREADS, FUSE_SMALL_MAX / FUSE_S_THREADS, 256, 7168, FUSE_S_LB, false, FUSE_S_WPE>;
   auto medium = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, false, 4, FUSE_M_ESTATS>;
   auto mid = k_task_fused<512, 16, 256, 7168, 2, false, 4>;
   auto small_u = k_task_fused<FUSE_S_THREADS, FUSE_SMALL_MAX / FUSE_S_THREADS, 256, 7168, 4, true, FUSE_S_WPE>;

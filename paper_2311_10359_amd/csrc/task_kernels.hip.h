@@ -40,6 +40,10 @@ constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: 
 #define FUSE_S_THREADS_V 512
 #define FUSE_S_WPE_V 6
 #endif
+#ifndef FUSE_S_LB_V
+#define FUSE_S_LB_V 1
+#endif
+constexpr int FUSE_S_LB = FUSE_S_LB_V;
 #ifndef FUSE_M_ESTATS_V
 #define FUSE_M_ESTATS_V true
 #endif
