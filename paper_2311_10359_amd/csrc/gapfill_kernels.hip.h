@@ -452,7 +452,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
   uint32_t flushed = g_first;        // results below this are in memory
   const uint32_t g_end = g_first + n_gaps;
   int64_t t_open = 0;                // predicted time line of the high-priority task
-  int64_t cur_open = 0, completion = 0;
+  int64_t cur_open = 0, completion;
   uint64_t consumed = 0;
   uint32_t c = 0, f = 0, rem = 0;
   // a gap is used if it is at least min_gap and at least the margin long (32-bit idle times are below WIDE32)
@@ -460,6 +460,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
   const uint32_t gap_floor = floor64 >= static_cast<int64_t>(WIDE32) ? WIDE32 : static_cast<uint32_t>(floor64);
   const uint32_t margin32 = margin >= static_cast<int64_t>(WIDE32) ? WIDE32 : static_cast<uint32_t>(margin);
   bool in_gap = false;
+  bool pending = false;               // a gap has closed and its result (c, f) is not staged yet
   bool done = valid && (lp_end == l0);     // the whole queue has been issued
   bool finished = !valid || done;          // nothing left to step through (remaining gaps, if any, get zeros)
 
@@ -523,12 +524,19 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     }
     if (__all(finished)) break;
 
-    // ---- one period: LW_OPENS times { take the next high-priority launch and open its gap; LW_TRIES
-    // times try the head of the queue }.  Written without branches; a lane whose ring is empty, or whose
-    // gap is still open when a new one could be taken, simply idles in that sub-step. ----
+    // ---- one period: LW_OPENS times { stage the result of the gap that closed, take the next
+    // high-priority launch and open its gap; LW_TRIES times try the head of the queue }.  Written
+    // without branches; a lane whose ring is empty, or whose gap is still open when a new one could be
+    // taken, simply idles in that sub-step. ----
 #pragma unroll
     for (uint32_t o = 0; o < LW_OPENS; ++o) {
       {
+        // (a staging slot that is written early is simply written again)
+        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
+        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
+        g += pending ? 1u : 0u;
+        consumed += pending ? f : 0u;
+        pending = false;
         const uint32_t E = sm.hp_e[hp_pos & (LW_HP_CAP - 1)][tid], G = sm.hp_g[hp_pos & (LW_HP_CAP - 1)][tid];
         // between gaps: the next high-priority launch runs, then its gap opens (the last launch has none)
         const bool idle = !finished && !in_gap;
@@ -542,7 +550,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         t_open += gap ? static_cast<int64_t>(G) : 0;
         const bool usable = gap && G >= gap_floor;
         const bool skip = gap && !usable;
-        // a skipped gap reports zeros (a staging slot that is written early is simply written again)
+        // a skipped gap reports zeros
         sm.out_c[g & (LW_OUT_CAP - 1)][tid] = 0u;
         sm.out_f[g & (LW_OUT_CAP - 1)][tid] = 0u;
         g += skip ? 1u : 0u;
@@ -559,16 +567,13 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         const bool tryq = in_gap && lp_pos < lp_landed;
         const bool fits = tryq && d <= rem;
         const uint32_t dd = fits ? d : 0u;
-        rem -= dd; f += dd; consumed += dd;
+        rem -= dd; f += dd;
         c += fits ? 1u : 0u;
         lp_pos += fits ? 1u : 0u;
         const bool emptied = fits && lp_pos == lp_end;          // the whole queue has been issued
         const bool close = (tryq && !fits) || emptied;
-        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
-        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
-        g += close ? 1u : 0u;
-        completion = emptied ? cur_open + static_cast<int64_t>(f) : completion;
-        done = done || emptied;
+        pending = pending || close;
+        done = done || emptied;          // (cur_open and f stay as they are from here on)
         finished = finished || emptied;
         in_gap = in_gap && !close;
       }
@@ -576,6 +581,12 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
   }
 
   if (!valid) return;
+  if (pending) {
+    sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
+    sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
+    ++g;
+    consumed += f;
+  }
   // what is still staged, then zeros for the gaps after the queue ran empty
   lw_store_scalar(sm, tid, flushed, g - flushed, fill_count, filled_ns);
   uint32_t z = g;
@@ -589,7 +600,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     }
   }
   for (; z < g_end; ++z) { fill_count[z] = 0; filled_ns[z] = 0; }
-  if (!done) completion = t_open + static_cast<int64_t>(total_lp - consumed);
+  completion = done ? cur_open + static_cast<int64_t>(f) : t_open + static_cast<int64_t>(total_lp - consumed);
   completion_out[s] = completion;
   placed_out[s] = lp_pos - l0;
 }
