@@ -59,6 +59,11 @@ def _load():
         lib.oracle_gapfill.restype = ctypes.c_int
         lib.oracle_gapfill.argtypes = [vp, vp, u32, vp, vp, vp, vp, u64, i64, i64, vp, vp, vp, vp,
                                        vp, vp, vp]
+        lib.oracle_measure.restype = ctypes.c_int
+        lib.oracle_measure.argtypes = [vp, u64, vp, u32, vp, vp]
+        lib.oracle_replay.restype = ctypes.c_int
+        lib.oracle_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, i64, i64, ctypes.c_int, vp, vp, vp,
+                                      vp, vp]
         _lib = lib
     return _lib
 
@@ -130,3 +135,44 @@ def gapfill(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_ro
     if want_assign:
         return fill_count, filled_ns, completion, placed, assign, assign_off
     return fill_count, filled_ns, completion, placed
+
+
+def measure(records: np.ndarray, task_offsets: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """-> (exec_ns[n], gap_ns[n]); gap_ns is -1 for the last launch of a task."""
+    assert records.dtype.itemsize == 64
+    records = np.ascontiguousarray(records)
+    task_offsets = np.ascontiguousarray(task_offsets, dtype=np.uint64)
+    n = records.shape[0]
+    ex = np.zeros(n, dtype=np.int64)
+    gp = np.zeros(n, dtype=np.int64)
+    st = _load().oracle_measure(_p(records), n, _p(task_offsets), task_offsets.shape[0] - 1, _p(ex), _p(gp))
+    if st != OK:
+        raise OracleError(st)
+    return ex, gp
+
+
+def replay(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_row_offsets: np.ndarray,
+           actual_gap_ns: np.ndarray, hp_task: np.ndarray, lp_task: np.ndarray, margin_ns: int, min_gap_ns: int,
+           feedback: bool, gap_offsets: np.ndarray):
+    """-> (fill_count, filled_ns, hp_delay_ns, lp_placed)."""
+    ids = np.ascontiguousarray(ids, dtype=np.uint64)
+    task_offsets = np.ascontiguousarray(task_offsets, dtype=np.uint64)
+    rows = np.ascontiguousarray(rows)
+    assert rows.dtype.itemsize == 128
+    tro = np.ascontiguousarray(task_row_offsets, dtype=np.uint64)
+    ag = np.ascontiguousarray(actual_gap_ns, dtype=np.int64)
+    hp = np.ascontiguousarray(hp_task, dtype=np.uint32)
+    lp = np.ascontiguousarray(lp_task, dtype=np.uint32)
+    go = np.ascontiguousarray(gap_offsets, dtype=np.uint64)
+    s = hp.shape[0]
+    n_gaps = int(go[-1]) if s else 0
+    fill_count = np.zeros(n_gaps, dtype=np.uint32)
+    filled_ns = np.zeros(n_gaps, dtype=np.int64)
+    delay = np.zeros(s, dtype=np.int64)
+    placed = np.zeros(s, dtype=np.uint64)
+    st = _load().oracle_replay(_p(ids), _p(task_offsets), task_offsets.shape[0] - 1, _p(rows), _p(tro), _p(ag),
+                               _p(hp), _p(lp), s, margin_ns, min_gap_ns, 1 if feedback else 0, _p(go),
+                               _p(fill_count), _p(filled_ns), _p(delay), _p(placed))
+    if st != OK:
+        raise OracleError(st)
+    return fill_count, filled_ns, delay, placed

@@ -23,6 +23,16 @@
 //                       task's waiting queue then holds exactly one request at a time, its next
 //                       kernel, so "best fit" degenerates to first-in-first-out and a gap ends
 //                       as soon as that head request does not fit.
+//   oracle_measure    - the two per-launch measurements of Section 3.2 ("Measuring the execution
+//                       and idle time of kernel"): execution time K and the idle time G that
+//                       follows a launch, as they stand in the trace.
+//   oracle_replay     - the same filling procedure played against the idle times that actually
+//                       occurred ("Real time feedback to stop error propagation", end of the
+//                       scheduling section, Figure "Runtime Feedback"): without feedback every
+//                       kernel that fits the predicted gap is issued and what runs past the
+//                       actual gap delays the high-priority task (overhead 1); with feedback the
+//                       controller stops issuing once the next high-priority request has
+//                       arrived, and only the kernel already issued can run over (overhead 2).
 //
 // All quantities are integers (nanoseconds, counts); nothing is floating point.
 
@@ -268,5 +278,102 @@ int oracle_gapfill(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n
   }
   return OK;
 }
+
+// Execution time K = end - start of every launch, and the idle time G = max(0, next start - end)
+// that follows it inside its task; the last launch of a task has no idle time: -1.
+int oracle_measure(const void* records_v, uint64_t n_records, const uint64_t* task_offsets,
+                   uint32_t n_tasks, int64_t* exec_ns, int64_t* gap_ns) {
+  const Launch* rec = static_cast<const Launch*>(records_v);
+  if (n_records && (!rec || !exec_ns || !gap_ns)) return INVALID_ARG;
+  if (!offsets_ok(task_offsets, n_tasks, n_records)) return INVALID_ARG;
+  for (uint32_t t = 0; t < n_tasks; ++t) {
+    const uint64_t lo = task_offsets[t], hi = task_offsets[t + 1];
+    for (uint64_t i = lo; i < hi; ++i) {
+      if (rec[i].end_ns < rec[i].start_ns) return BAD_RECORD;
+      exec_ns[i] = rec[i].end_ns - rec[i].start_ns;
+      int64_t g = -1;
+      if (i + 1 < hi) {
+        g = rec[i + 1].start_ns - rec[i].end_ns;
+        if (g < 0) g = 0;
+      }
+      gap_ns[i] = g;
+    }
+  }
+  return OK;
+}
+
+// Gap filling replayed against the actual idle times of the high-priority trace.
+//
+// Decisions are taken as in oracle_gapfill, on predictions: a gap whose predicted length is below
+// min_gap_ns or margin_ns is skipped, and a low-priority kernel is issued only while its predicted
+// duration fits what is left of the predicted gap minus the margin.  Issued kernels run back to
+// back from the start of the gap and take their predicted duration.  actual_gap_ns[i] is the idle
+// time that really followed high-priority launch i (as oracle_measure gives it).
+//   feedback == 0: every kernel that fits the prediction is issued.
+//   feedback != 0: before each issue the controller looks whether the next high-priority request
+//                  has arrived, i.e. whether the time already filled in this gap has reached the
+//                  actual idle time; if so it stops issuing for this gap.
+// In both cases the time by which the issued kernels run past the actual idle time delays the next
+// high-priority kernel; hp_delay_ns[s] is the sum of these delays over the scenario's gaps (the
+// paper's overhead 1 without feedback, overhead 2 with it).  Each gap is charged on its own: the
+// replay does not shift later launches of the trace.
+int oracle_replay(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n_tasks,
+                  const void* rows_v, const uint64_t* task_row_offsets, const int64_t* actual_gap_ns,
+                  const uint32_t* hp_task, const uint32_t* lp_task, uint64_t n_scenarios,
+                  int64_t margin_ns, int64_t min_gap_ns, int feedback, const uint64_t* gap_offsets,
+                  uint32_t* fill_count, int64_t* filled_ns, int64_t* hp_delay_ns, uint64_t* lp_placed) {
+  const Row* rows = static_cast<const Row*>(rows_v);
+  if (!task_offsets || !task_row_offsets) return INVALID_ARG;
+  if (n_scenarios && (!hp_task || !lp_task || !gap_offsets || !hp_delay_ns || !lp_placed)) return INVALID_ARG;
+  if (margin_ns < 0 || min_gap_ns < 0) return INVALID_ARG;
+
+  for (uint64_t s = 0; s < n_scenarios; ++s) {
+    const uint32_t hp = hp_task[s], lp = lp_task[s];
+    if (hp >= n_tasks || lp >= n_tasks) return INVALID_ARG;
+    std::map<uint64_t, const Row*> hp_rows, lp_rows;
+    for (uint64_t r = task_row_offsets[hp]; r < task_row_offsets[hp + 1]; ++r) hp_rows[rows[r].kernel_id] = &rows[r];
+    for (uint64_t r = task_row_offsets[lp]; r < task_row_offsets[lp + 1]; ++r) lp_rows[rows[r].kernel_id] = &rows[r];
+    const uint64_t h0 = task_offsets[hp], H = task_offsets[hp + 1] - h0;
+    const uint64_t l0 = task_offsets[lp], L = task_offsets[lp + 1] - l0;
+    std::vector<int64_t> D(L);  // predicted duration of each low-priority kernel
+    for (uint64_t j = 0; j < L; ++j) {
+      auto it = lp_rows.find(ids[l0 + j]);
+      if (it == lp_rows.end()) return UNKNOWN_ID;
+      D[j] = it->second->exec.p50;
+    }
+    uint64_t p = 0;     // next low-priority kernel to issue (FIFO)
+    int64_t delay = 0;  // accumulated delay of the high-priority task
+    const uint64_t g0 = gap_offsets[s];
+    for (uint64_t i = 0; i + 1 < H; ++i) {
+      auto it = hp_rows.find(ids[h0 + i]);
+      if (it == hp_rows.end()) return UNKNOWN_ID;
+      const int64_t G = it->second->gap.p50;        // predicted idle time
+      const int64_t actual = actual_gap_ns[h0 + i];  // idle time that occurred
+      if (actual < 0) return INVALID_ARG;
+      uint32_t c = 0;
+      int64_t f = 0;
+      if (G >= min_gap_ns && G >= margin_ns) {
+        int64_t r = G - margin_ns;  // remaining predicted idle time
+        while (p < L && D[p] <= r) {
+          if (feedback && f >= actual) break;  // the next high-priority request is already there
+          r -= D[p];
+          f += D[p];
+          ++p;
+          ++c;
+        }
+        if (f > actual) delay += f - actual;
+      }
+      fill_count[g0 + i] = c;
+      filled_ns[g0 + i] = f;
+    }
+    if (H > 0) {  // the last launch must be known too, as in oracle_gapfill
+      if (hp_rows.find(ids[h0 + H - 1]) == hp_rows.end()) return UNKNOWN_ID;
+    }
+    hp_delay_ns[s] = delay;
+    lp_placed[s] = p;
+  }
+  return OK;
+}
+
 
 }  // extern "C"

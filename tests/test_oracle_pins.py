@@ -6,6 +6,8 @@ P2  the paper's closed forms SK_j, SG_j (Section 3.2) evaluated with the Kroneck
 P3  invariants that hold for any trace.
 P4  brute-force enumeration of every first-in-first-out schedule on tiny traces.
 P5  special cases that reduce to library routines (numpy.sort, numpy.unique) or closed forms.
+P6  per-launch measurement and the replay against actual idle times: hand-worked example
+    (tests/golden/p6_replay_hand_worked.json), ties to the pinned gap fill, closed form by prefix sums.
 """
 import itertools
 import json
@@ -460,6 +462,128 @@ def test_p5_gapfill_equal_durations_closed_form():
 
 
 # ---------------------------------------------------------------- error statuses
+# ---------------------------------------------------------------- P6
+def test_p6_measure_is_end_minus_start_and_next_start_minus_end():
+    rec = make_records([(1, (1, 1, 1), (64, 1, 1), 0, 10, 25), (2, (1, 1, 1), (64, 1, 1), 0, 30, 31),
+                        (1, (1, 1, 1), (64, 1, 1), 0, 29, 40),       # starts before the previous one ends
+                        (3, (1, 1, 1), (64, 1, 1), 0, 100, 100), (3, (1, 1, 1), (64, 1, 1), 0, 107, 110)])
+    off = np.array([0, 3, 3, 5], dtype=np.uint64)
+    ex, gp = oracle.measure(rec, off)
+    assert ex.tolist() == [15, 1, 11, 0, 3]
+    assert gp.tolist() == [5, 0, -1, 7, -1]
+    cfg = traces.config(0)
+    rec, off = traces.build(cfg)
+    ex, gp = oracle.measure(rec, off)
+    assert np.array_equal(ex, rec["end_ns"] - rec["start_ns"])
+    nxt = np.roll(rec["start_ns"], -1) - rec["end_ns"]
+    last = np.zeros(rec.shape[0], dtype=bool)
+    last[(off[1:][off[1:] > off[:-1]] - 1).astype(np.int64)] = True
+    assert np.array_equal(gp, np.where(last, -1, np.maximum(nxt, 0)))
+
+
+def replay_inputs(golden):
+    hp_ids, lp_ids = golden["hp_ids"], golden["lp_ids"]
+    ids = np.array(hp_ids + lp_ids, dtype=np.uint64)
+    off = np.array([0, len(hp_ids), len(ids)], dtype=np.uint64)
+    rows = np.zeros(len(golden["rows"]), dtype=oracle.ROW_DTYPE)
+    for k, r in enumerate(golden["rows"]):
+        rows[k]["kernel_id"] = r["kernel_id"]
+        rows[k]["task"] = r["task"]
+        rows[k]["exec"]["p50"] = r["exec_p50"]
+        rows[k]["gap"]["p50"] = r["gap_p50"]
+    tro = np.array([0, 2, 3], dtype=np.uint64)
+    return ids, off, rows, tro
+
+
+def test_p6_replay_hand_worked(golden_dir):
+    with open(os.path.join(golden_dir, "p6_replay_hand_worked.json")) as f:
+        golden = json.load(f)
+    ids, off, rows, tro = replay_inputs(golden)
+    hp, lp = np.array([0], dtype=np.uint32), np.array([1], dtype=np.uint32)
+    go = traces.gap_offsets(off, hp)
+    for case in golden["cases"]:
+        actual = np.array(case["actual_gap_ns"] + [-1] + [1] * (len(golden["lp_ids"]) - 1) + [-1], dtype=np.int64)
+        for feedback, key in ((False, "no_feedback"), (True, "feedback")):
+            fc, fn, delay, placed = oracle.replay(ids, off, rows, tro, actual, hp, lp, case["margin_ns"],
+                                                  case["min_gap_ns"], feedback, go)
+            exp = case[key]
+            assert fc.tolist() == exp["fill_count"], (case, key)
+            assert fn.tolist() == exp["filled_ns"], (case, key)
+            assert int(delay[0]) == exp["hp_delay_ns"], (case, key)
+            assert int(placed[0]) == exp["lp_placed"], (case, key)
+
+
+def replay_by_prefix_sums(E_pred_gap, actual, D, margin, min_gap, feedback):
+    """The replay of one scenario written with prefix sums and searches instead of a kernel-by-kernel loop."""
+    ps = np.concatenate([[0], np.cumsum(np.asarray(D, dtype=np.int64))])
+    p, delay, fills, filled = 0, 0, [], []
+    for G, A in zip(E_pred_gap, actual):
+        c = 0
+        if G >= min_gap and G >= margin:
+            # kernels p .. p+c-1 fit the predicted budget: largest c with ps[p+c] - ps[p] <= G - margin
+            c = int(np.searchsorted(ps, ps[p] + (G - margin), side="right")) - 1 - p
+            if feedback:
+                # kernel p+k is issued only if the time filled before it, ps[p+k] - ps[p], is below the actual gap
+                started = int(np.searchsorted(ps[p:p + c] - ps[p], A, side="left"))
+                c = min(c, started)
+        f = int(ps[p + c] - ps[p])
+        fills.append(c)
+        filled.append(f)
+        delay += max(0, f - A)
+        p += c
+    return fills, filled, delay, p
+
+
+@pytest.mark.parametrize("cfg", small_configs(), ids=lambda c: c.name)
+def test_p6_replay_ties(cfg):
+    rec, off = traces.build(cfg)
+    ids, rows, tro = oracle.profile(rec, off)
+    _, gap = oracle.measure(rec, off)
+    hp, lp = traces.scenarios(cfg)
+    if hp.size == 0:
+        return
+    go = traces.gap_offsets(off, hp)
+    for margin, min_gap in ((cfg.margin_ns, 0), (0, 20000)):
+        ref = oracle.gapfill(ids, off, rows, tro, hp, lp, margin, min_gap, go)
+        # without feedback the decisions are those of the gap fill; the delay is what runs past the actual gap
+        fc, fn, delay, placed = oracle.replay(ids, off, rows, tro, gap, hp, lp, margin, min_gap, False, go)
+        assert np.array_equal(fc, ref[0]) and np.array_equal(fn, ref[1]) and np.array_equal(placed, ref[3])
+        for s in range(hp.size):
+            h0 = int(off[hp[s]])
+            n_g = int(go[s + 1] - go[s])
+            a = gap[h0:h0 + n_g]
+            assert int(delay[s]) == int(np.maximum(fn[int(go[s]):int(go[s + 1])] - a, 0).sum())
+        # gaps that never end early: feedback changes nothing and nothing is delayed
+        huge = np.where(gap < 0, -1, np.int64(1) << 60)
+        for fb in (False, True):
+            fc2, fn2, delay2, placed2 = oracle.replay(ids, off, rows, tro, huge, hp, lp, margin, min_gap, fb, go)
+            assert np.array_equal(fc2, ref[0]) and np.array_equal(fn2, ref[1]) and not delay2.any()
+        # gaps that end at once: with feedback nothing is issued
+        zero = np.where(gap < 0, -1, 0)
+        fc3, fn3, delay3, placed3 = oracle.replay(ids, off, rows, tro, zero, hp, lp, margin, min_gap, True, go)
+        assert not fc3.any() and not fn3.any() and not delay3.any() and not placed3.any()
+        # with feedback, a gap's overrun is shorter than the last kernel issued into it, and the closed form agrees
+        fc4, fn4, delay4, placed4 = oracle.replay(ids, off, rows, tro, gap, hp, lp, margin, min_gap, True, go)
+        for s in range(min(hp.size, 8)):
+            h0, l0, l1 = int(off[hp[s]]), int(off[lp[s]]), int(off[lp[s] + 1])
+            n_g = int(go[s + 1] - go[s])
+            lut_e = {int(r["kernel_id"]): int(r["exec"]["p50"]) for r in rows[int(tro[lp[s]]):int(tro[lp[s] + 1])]}
+            lut_g = {int(r["kernel_id"]): int(r["gap"]["p50"]) for r in rows[int(tro[hp[s]]):int(tro[hp[s] + 1])]}
+            D = [lut_e[int(i)] for i in ids[l0:l1]]
+            Gp = [lut_g[int(i)] for i in ids[h0:h0 + n_g]]
+            for fb, got in ((False, (fc, fn, delay, placed)), (True, (fc4, fn4, delay4, placed4))):
+                fills, filled, dl, p = replay_by_prefix_sums(Gp, gap[h0:h0 + n_g].tolist(), D, margin, min_gap, fb)
+                sl = slice(int(go[s]), int(go[s + 1]))
+                assert got[0][sl].tolist() == fills and got[1][sl].tolist() == filled
+                assert int(got[2][s]) == dl and int(got[3][s]) == p
+            p = 0
+            for g in range(n_g):
+                c = int(fc4[int(go[s]) + g])
+                if c:
+                    assert int(fn4[int(go[s]) + g]) - D[p + c - 1] < int(gap[h0 + g])
+                p += c
+
+
 def test_oracle_error_statuses():
     rec = make_records([(1, (1, 1, 1), (1, 1, 1), 0, 10, 5)])
     with pytest.raises(oracle.OracleError) as e:
