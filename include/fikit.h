@@ -86,7 +86,8 @@ typedef enum fikit_status {
   FIKIT_ROW_CAPACITY = -3,        /* more rows than row_capacity; *h_n_rows holds the need       */
   FIKIT_BAD_RECORD = -4,          /* some record has end_ns < start_ns                          */
   FIKIT_UNKNOWN_ID = -5,          /* a scenario launch whose ID is absent from its task's rows  */
-  FIKIT_HIP_ERROR = -6            /* the HIP runtime reported an error                          */
+  FIKIT_HIP_ERROR = -6,           /* the HIP runtime reported an error                          */
+  FIKIT_UNSUPPORTED = -7          /* fikit_gapfill_replay: a predicted time of 2^32 - 1 ns or more */
 } fikit_status;
 
 /* Bytes of device workspace fikit_profile needs for these sizes (0 on size overflow). */
@@ -155,6 +156,70 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
                   uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_lp_completion_ns,
                   uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes,
                   void* hip_stream);
+
+/* Bytes of device workspace fikit_measure needs. */
+size_t fikit_measure_workspace_bytes(void);
+
+/*
+ * The two per-launch measurements of Section 3.2 ("Measuring the execution and idle time of
+ * kernel"), as they stand in the trace.
+ *
+ *   d_records, d_task_offsets, n_tasks   as in fikit_profile.
+ *   d_exec_ns   [n_records] receives end_ns - start_ns of every launch.
+ *   d_gap_ns    [n_records] receives the idle time after the launch, max(0, start_ns of the
+ *               task's next launch - end_ns), or -1 for the last launch of a task.
+ *   d_workspace 256-byte aligned, at least fikit_measure_workspace_bytes() bytes.
+ *
+ * Buffers are the caller's; the call synchronises the stream.  Errors: INVALID_ARG,
+ * WORKSPACE_TOO_SMALL, BAD_RECORD, HIP_ERROR.
+ */
+int fikit_measure(const fikit_launch* d_records, uint64_t n_records, const uint64_t* d_task_offsets,
+                  uint32_t n_tasks, int64_t* d_exec_ns, int64_t* d_gap_ns, void* d_workspace,
+                  size_t workspace_bytes, void* hip_stream);
+
+typedef struct fikit_replay_params {
+  int64_t margin_ns;   /* as in fikit_gapfill_params                                            */
+  int64_t min_gap_ns;  /* as in fikit_gapfill_params                                            */
+  int32_t feedback;    /* 0: profile-only controller; non-zero: real-time feedback             */
+  int32_t reserved;    /* must be 0                                                             */
+} fikit_replay_params;
+
+/* Bytes of device workspace fikit_gapfill_replay needs for these sizes (0 on size overflow). */
+size_t fikit_replay_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios);
+
+/*
+ * The gap filling of fikit_gapfill replayed against the idle times that actually occurred (the
+ * paragraph "Real time feedback to stop error propagation" of the paper's scheduling section,
+ * Figure "Runtime Feedback").  Decisions are taken on predictions exactly as in fikit_gapfill;
+ * issued kernels run back to back from the start of the gap for their predicted duration.
+ *
+ *   d_actual_gap_ns  [n_ids] idle time that followed every launch (fikit_measure's d_gap_ns);
+ *                    only high-priority launches that have a gap are looked at, and theirs must be
+ *                    >= 0 (else INVALID_ARG).
+ *   h_params         host pointer.  feedback == 0: every kernel that fits the predicted gap is
+ *                    issued (the paper's profile-only controller).  feedback != 0: before each
+ *                    issue the controller checks whether the next high-priority request has
+ *                    arrived, i.e. whether the time already filled in this gap has reached the
+ *                    actual idle time, and if so issues nothing more into this gap.
+ *   d_fill_count, d_filled_ns  per gap, as in fikit_gapfill (with feedback == 0 they equal its).
+ *   d_hp_delay_ns    [n_scenarios] sum over the scenario's gaps of max(0, filled - actual idle
+ *                    time): what the high-priority task is delayed by (the paper's overhead 1
+ *                    without feedback, overhead 2 with it).  Every gap is charged on its own;
+ *                    later launches of the trace are not shifted.
+ *   d_lp_placed      [n_scenarios] number of low-priority kernels issued into gaps.
+ *   all other arguments as in fikit_gapfill.
+ *
+ * Predicted times must be below 2^32 - 1 ns (about 4.29 s), else FIKIT_UNSUPPORTED.
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNKNOWN_ID, UNSUPPORTED, HIP_ERROR.
+ */
+int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks,
+                         const fikit_row* d_rows, const uint64_t* d_task_row_offsets,
+                         const int64_t* d_actual_gap_ns, const uint32_t* d_hp_task,
+                         const uint32_t* d_lp_task, uint64_t n_scenarios,
+                         const fikit_replay_params* h_params, const uint64_t* d_gap_offsets,
+                         uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_hp_delay_ns,
+                         uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes,
+                         void* hip_stream);
 
 const char* fikit_status_string(int status);
 int fikit_version(void);

@@ -22,9 +22,11 @@ FIKIT_ROW_CAPACITY = -3
 FIKIT_BAD_RECORD = -4
 FIKIT_UNKNOWN_ID = -5
 FIKIT_HIP_ERROR = -6
+FIKIT_UNSUPPORTED = -7
 
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
-           "fikit_gapfill", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
+           "fikit_gapfill", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
+           "fikit_gapfill_replay", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
 
 # Layout of a profile row as seen from numpy (128 bytes; see fikit_row in fikit.h).
 STATS_DTYPE = np.dtype([("count", "<u8"), ("sum", "<u8"), ("min", "<i8"), ("max", "<i8"),
@@ -44,6 +46,11 @@ class FikitError(RuntimeError):
 
 class _GapfillParams(ctypes.Structure):
     _fields_ = [("margin_ns", ctypes.c_int64), ("min_gap_ns", ctypes.c_int64)]
+
+
+class _ReplayParams(ctypes.Structure):
+    _fields_ = [("margin_ns", ctypes.c_int64), ("min_gap_ns", ctypes.c_int64), ("feedback", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 _lib = None
@@ -71,6 +78,15 @@ def load() -> ctypes.CDLL:
         lib.fikit_gapfill.restype = ctypes.c_int
         lib.fikit_gapfill.argtypes = [vp, vp, u32, vp, vp, vp, vp, u64, ctypes.POINTER(_GapfillParams), vp,
                                       vp, vp, vp, vp, vp, sz, vp]
+        lib.fikit_measure_workspace_bytes.restype = sz
+        lib.fikit_measure_workspace_bytes.argtypes = []
+        lib.fikit_measure.restype = ctypes.c_int
+        lib.fikit_measure.argtypes = [vp, u64, vp, u32, vp, vp, vp, sz, vp]
+        lib.fikit_replay_workspace_bytes.restype = sz
+        lib.fikit_replay_workspace_bytes.argtypes = [u64, u32, u64]
+        lib.fikit_gapfill_replay.restype = ctypes.c_int
+        lib.fikit_gapfill_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, ctypes.POINTER(_ReplayParams), vp,
+                                             vp, vp, vp, vp, vp, sz, vp]
         lib.fikit_status_string.restype = ctypes.c_char_p
         lib.fikit_status_string.argtypes = [ctypes.c_int]
         lib.fikit_version.restype = ctypes.c_int
@@ -209,6 +225,82 @@ def fikit_gapfill(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Ten
                                _stream_handle(stream))
     if st != FIKIT_OK:
         raise FikitError(st, "fikit_gapfill")
+    return out
+
+
+def fikit_measure_workspace_bytes() -> int:
+    return int(load().fikit_measure_workspace_bytes())
+
+
+def fikit_measure(records: torch.Tensor, task_offsets: torch.Tensor, *, exec_out: Optional[torch.Tensor] = None,
+                  gap_out: Optional[torch.Tensor] = None, workspace_buf: Optional[torch.Tensor] = None,
+                  stream: Optional[torch.cuda.Stream] = None):
+    """-> (exec_ns, gap_ns): int64 [n] device tensors (gap_ns is -1 for the last launch of a task)."""
+    lib = load()
+    dev = records.device
+    assert records.dtype == torch.uint8 and records.is_contiguous()
+    n = records.numel() // LAUNCH_BYTES
+    assert task_offsets.dtype == torch.int64 and task_offsets.is_contiguous() and task_offsets.device == dev
+    n_tasks = task_offsets.numel() - 1
+    if exec_out is None:
+        exec_out = torch.empty(n, dtype=torch.int64, device=dev)
+    if gap_out is None:
+        gap_out = torch.empty(n, dtype=torch.int64, device=dev)
+    if workspace_buf is None:
+        workspace_buf = workspace(fikit_measure_workspace_bytes(), dev)
+    with torch.cuda.device(dev):
+        st = lib.fikit_measure(_ptr(records), n, _ptr(task_offsets), n_tasks, _ptr(exec_out), _ptr(gap_out),
+                               _ptr(workspace_buf), workspace_buf.numel(), _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_measure")
+    return exec_out, gap_out
+
+
+class Replay(NamedTuple):
+    fill_count: torch.Tensor   # int32 view of uint32 [n_gaps]
+    filled_ns: torch.Tensor    # int64 [n_gaps]
+    hp_delay_ns: torch.Tensor  # int64 [S]
+    lp_placed: torch.Tensor    # int64 view of uint64 [S]
+
+
+def fikit_replay_workspace_bytes(n_ids: int, n_tasks: int, n_scenarios: int) -> int:
+    return int(load().fikit_replay_workspace_bytes(n_ids, n_tasks, n_scenarios))
+
+
+def fikit_gapfill_replay(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Tensor, task_row_offsets: torch.Tensor,
+                         actual_gap_ns: torch.Tensor, hp_task: torch.Tensor, lp_task: torch.Tensor,
+                         gap_offsets: torch.Tensor, *, margin_ns: int, min_gap_ns: int, feedback: bool,
+                         n_gaps: Optional[int] = None, n_ids: Optional[int] = None, out: Optional[Replay] = None,
+                         workspace_buf: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> Replay:
+    """As fikit_gapfill, plus actual_gap_ns: int64 [n_ids] (fikit_measure's gap_ns)."""
+    lib = load()
+    dev = task_offsets.device
+    n_tasks = task_offsets.numel() - 1
+    s = hp_task.numel()
+    assert hp_task.dtype == torch.int32 and lp_task.dtype == torch.int32 and lp_task.numel() == s
+    assert gap_offsets.dtype == torch.int64 and gap_offsets.numel() == s + 1
+    assert actual_gap_ns.dtype == torch.int64
+    for t in (ids, task_offsets, rows, task_row_offsets, actual_gap_ns, hp_task, lp_task, gap_offsets):
+        assert t.is_contiguous() and t.device == dev
+    if n_gaps is None:
+        n_gaps = int(gap_offsets[-1].item()) if s else 0
+    if n_ids is None:
+        n_ids = ids.numel()
+    if out is None:
+        out = Replay(torch.empty(n_gaps, dtype=torch.int32, device=dev), torch.empty(n_gaps, dtype=torch.int64, device=dev),
+                     torch.empty(s, dtype=torch.int64, device=dev), torch.empty(s, dtype=torch.int64, device=dev))
+    if workspace_buf is None:
+        workspace_buf = workspace(fikit_replay_workspace_bytes(n_ids, n_tasks, s), dev)
+    params = _ReplayParams(margin_ns, min_gap_ns, 1 if feedback else 0, 0)
+    with torch.cuda.device(dev):
+        st = lib.fikit_gapfill_replay(_ptr(ids), _ptr(task_offsets), n_tasks, _ptr(rows), _ptr(task_row_offsets),
+                                      _ptr(actual_gap_ns), _ptr(hp_task), _ptr(lp_task), s, ctypes.byref(params),
+                                      _ptr(gap_offsets), _ptr(out.fill_count), _ptr(out.filled_ns), _ptr(out.hp_delay_ns),
+                                      _ptr(out.lp_placed), _ptr(workspace_buf), workspace_buf.numel(),
+                                      _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_gapfill_replay")
     return out
 
 

@@ -21,6 +21,7 @@ enum : uint32_t {
   ERR_UNKNOWN_ID = 1u << 2,  // launch ID without a row in its task's profile
   ERR_TASK_INDEX = 1u << 3,  // scenario names a task >= n_tasks
   ERR_GAP_OFFSETS = 1u << 4, // scenario gap offsets do not match the trace lengths
+  ERR_ACTUAL_GAP = 1u << 5,  // replay: negative actual idle time after a launch that has a gap
 };
 
 // Control block at the start of the workspace; cleared by k_clear_ctrl at the start of a call.

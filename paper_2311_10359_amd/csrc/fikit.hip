@@ -145,7 +145,7 @@ struct Tracer {
 };
 
 int status_from_bits(uint32_t bits) {
-  if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return FIKIT_INVALID_ARG;
+  if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS | ERR_ACTUAL_GAP)) return FIKIT_INVALID_ARG;
   if (bits & ERR_BAD_RECORD) return FIKIT_BAD_RECORD;
   if (bits & ERR_UNKNOWN_ID) return FIKIT_UNKNOWN_ID;
   return FIKIT_OK;
@@ -186,6 +186,7 @@ const char* fikit_status_string(int status) {
     case FIKIT_BAD_RECORD: return "record with end_ns < start_ns";
     case FIKIT_UNKNOWN_ID: return "launch ID missing from its task's profile";
     case FIKIT_HIP_ERROR: return "HIP runtime error";
+    case FIKIT_UNSUPPORTED: return "a predicted time of 2^32 - 1 ns or more (replay)";
     default: return "unknown status";
   }
 }
@@ -500,12 +501,12 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   if (lanes) {
     tr.mark("k_gf_predict32");
     hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                       d_task_row_offsets, role, glists, lp_e, hp_eg, lp_total, ctrl);
+                       d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total, ctrl);
     tr.mark("k_gf_walk_lanes");
-    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  static_cast<int>(sizeof(LaneWalkSmem))));
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes<LW_PLAN>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(LaneWalkSmem))));
     const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
-    hipLaunchKernelGGL(k_gf_walk_lanes, dim3(blocks_for(n_scenarios, LW_THREADS)), dim3(LW_THREADS), sizeof(LaneWalkSmem), st,
+    hipLaunchKernelGGL(k_gf_walk_lanes<LW_PLAN>, dim3(blocks_for(n_scenarios, LW_THREADS)), dim3(LW_THREADS), sizeof(LaneWalkSmem), st,
                        d_task_offsets, d_hp_task, d_lp_task, n_scenarios, d_gap_offsets, lp_e, hp_eg, lp_total,
                        h_params->margin_ns, h_params->min_gap_ns, d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed,
                        vec_ok, ctrl);
@@ -528,6 +529,116 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   Ctrl h{};
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   return status_from_bits(h.status);
+}
+
+size_t fikit_measure_workspace_bytes(void) { return 256; }
+
+int fikit_measure(const fikit_launch* d_records, uint64_t n_records, const uint64_t* d_task_offsets, uint32_t n_tasks,
+                  int64_t* d_exec_ns, int64_t* d_gap_ns, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!d_task_offsets || !d_workspace) return FIKIT_INVALID_ARG;
+  if (n_records >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_records > 0 && (!d_records || !d_exec_ns || !d_gap_ns || n_tasks == 0)) return FIKIT_INVALID_ARG;
+  if (!aligned(d_records, 8) || !aligned(d_task_offsets, 8) || !aligned(d_exec_ns, 8) || !aligned(d_gap_ns, 8) ||
+      !aligned(d_workspace, 256))
+    return FIKIT_INVALID_ARG;
+  if (workspace_bytes < fikit_measure_workspace_bytes()) return FIKIT_WORKSPACE_TOO_SMALL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  Ctrl* ctrl = static_cast<Ctrl*>(d_workspace);
+  Tracer tr(st);
+  tr.mark("k_measure");
+  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_records,
+                     ctrl);
+  if (n_records > 0) {
+    hipLaunchKernelGGL(k_measure, dim3(blocks_for(n_records, 256)), dim3(256), 0, st, d_records, n_records, d_exec_ns, d_gap_ns,
+                       ctrl);
+    hipLaunchKernelGGL(k_measure_task_ends, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_gap_ns,
+                       ctrl);
+  }
+  FIKIT_HIP(hipGetLastError());
+  tr.mark("host_sync");
+  Ctrl h{};
+  if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+  return status_from_bits(h.status);
+}
+
+size_t fikit_replay_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios) {
+  return fikit_gapfill_workspace_bytes(n_ids, n_tasks, n_scenarios);
+}
+
+int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks, const fikit_row* d_rows,
+                         const uint64_t* d_task_row_offsets, const int64_t* d_actual_gap_ns, const uint32_t* d_hp_task,
+                         const uint32_t* d_lp_task, uint64_t n_scenarios, const fikit_replay_params* h_params,
+                         const uint64_t* d_gap_offsets, uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_hp_delay_ns,
+                         uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!h_params || h_params->margin_ns < 0 || h_params->min_gap_ns < 0 || h_params->reserved != 0) return FIKIT_INVALID_ARG;
+  if (!d_task_offsets || !d_task_row_offsets || !d_workspace) return FIKIT_INVALID_ARG;
+  if (n_scenarios >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_scenarios > 0 && (!d_hp_task || !d_lp_task || !d_gap_offsets || !d_hp_delay_ns || !d_lp_placed || n_tasks == 0))
+    return FIKIT_INVALID_ARG;
+  if (!aligned(d_ids, 8) || !aligned(d_task_offsets, 8) || !aligned(d_rows, 16) || !aligned(d_task_row_offsets, 8) ||
+      !aligned(d_actual_gap_ns, 8) || !aligned(d_hp_task, 4) || !aligned(d_lp_task, 4) || !aligned(d_gap_offsets, 8) ||
+      !aligned(d_fill_count, 4) || !aligned(d_filled_ns, 8) || !aligned(d_hp_delay_ns, 8) || !aligned(d_lp_placed, 8) ||
+      !aligned(d_workspace, 256))
+    return FIKIT_INVALID_ARG;
+  if (n_scenarios == 0) return FIKIT_OK;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint64_t n_ids = 0, n_gaps = 0;
+  FIKIT_HIP(hipMemcpyAsync(&n_ids, d_task_offsets + n_tasks, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipMemcpyAsync(&n_gaps, d_gap_offsets + n_scenarios, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipStreamSynchronize(st));
+  if (n_ids >= MAX_ELEMS || n_gaps >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_ids > 0 && (!d_ids || !d_rows || !d_actual_gap_ns)) return FIKIT_INVALID_ARG;
+  if (n_gaps > 0 && (!d_fill_count || !d_filled_ns)) return FIKIT_INVALID_ARG;
+  if (workspace_bytes < fikit_replay_workspace_bytes(n_ids, n_tasks, n_scenarios)) return FIKIT_WORKSPACE_TOO_SMALL;
+
+  unsigned char* ws = static_cast<unsigned char*>(d_workspace);
+  Carver c;   // (same layout as fikit_gapfill; only the 32-bit arrays are used)
+  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
+  uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
+  uint32_t* glists = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4 * 2));
+  uint64_t* lp_total = reinterpret_cast<uint64_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 8));
+  uint32_t* lp_e = reinterpret_cast<uint32_t*>(ws + c.take(n_ids * 8 + GF_PAD));
+  uint2* hp_eg = reinterpret_cast<uint2*>(ws + c.take(n_ids * 8 + GF_PAD));
+
+  Tracer tr(st);
+  tr.mark("gf_setup");
+  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+  hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, role, static_cast<uint64_t>(n_tasks), 0u);
+  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_ids, ctrl);
+  hipLaunchKernelGGL(k_gf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
+                     d_lp_task, n_scenarios, d_gap_offsets, role, ctrl);
+  tr.mark("gf_lists");
+  hipLaunchKernelGGL(k_gf_lists, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, role, 8192u, glists,
+                     ctrl);
+  tr.mark("k_gf_predict32");
+  hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                     d_task_row_offsets, role, glists, d_actual_gap_ns, lp_e, hp_eg, lp_total, ctrl);
+  const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
+  const dim3 grid(blocks_for(n_scenarios, LW_THREADS)), block(LW_THREADS);
+  if (h_params->feedback) {
+    tr.mark("k_gf_replay_feedback");
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes<LW_REPLAY_FEEDBACK>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(LaneWalkSmem))));
+    hipLaunchKernelGGL(k_gf_walk_lanes<LW_REPLAY_FEEDBACK>, grid, block, sizeof(LaneWalkSmem), st, d_task_offsets, d_hp_task,
+                       d_lp_task, n_scenarios, d_gap_offsets, lp_e, hp_eg, lp_total, h_params->margin_ns, h_params->min_gap_ns,
+                       d_fill_count, d_filled_ns, d_hp_delay_ns, d_lp_placed, vec_ok, ctrl);
+  } else {
+    tr.mark("k_gf_replay");
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes<LW_REPLAY>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(LaneWalkSmem))));
+    hipLaunchKernelGGL(k_gf_walk_lanes<LW_REPLAY>, grid, block, sizeof(LaneWalkSmem), st, d_task_offsets, d_hp_task, d_lp_task,
+                       n_scenarios, d_gap_offsets, lp_e, hp_eg, lp_total, h_params->margin_ns, h_params->min_gap_ns,
+                       d_fill_count, d_filled_ns, d_hp_delay_ns, d_lp_placed, vec_ok, ctrl);
+  }
+  FIKIT_HIP(hipGetLastError());
+  tr.mark("host_sync");
+  Ctrl h{};
+  if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+  if (int rc = status_from_bits(h.status)) return rc;
+  // (the walk has not run in this case: its outputs are undefined)
+  return h.wide ? FIKIT_UNSUPPORTED : FIKIT_OK;
 }
 
 }  // extern "C"

@@ -316,11 +316,13 @@ constexpr uint32_t WIDE32 = 0xffffffffu;   // 32-bit predictions must be below t
 // Predicted values of every launch of the tasks that take part, in 32 bits:
 //   lp_e[i]  execution time, for tasks used as low-priority queue; lp_total[t] their sum
 //   hp_eg[i] (execution time, idle time), for tasks used as high-priority trace
+// For the replay against actual idle times (actual != nullptr) the first word of hp_eg[i] holds the idle
+// time that really followed launch i instead (clamped to WIDE32, which no filled time can reach).
 __global__ void __launch_bounds__(PRED_THREADS)
 k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
                const fikit_row* __restrict__ rows, const uint64_t* __restrict__ row_off, const uint32_t* __restrict__ role,
-               const uint32_t* __restrict__ lists, uint32_t* __restrict__ lp_e, uint2* __restrict__ hp_eg,
-               uint64_t* __restrict__ lp_total, Ctrl* ctrl) {
+               const uint32_t* __restrict__ lists, const int64_t* __restrict__ actual, uint32_t* __restrict__ lp_e,
+               uint2* __restrict__ hp_eg, uint64_t* __restrict__ lp_total, Ctrl* ctrl) {
   __shared__ PredTable tb;
   __shared__ uint64_t wave_tot[PRED_THREADS / WAVE];
   if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
@@ -350,7 +352,7 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
     }
   }
   __syncthreads();
-  bool unknown = false, wide = false;
+  bool unknown = false, wide = false, bad_actual = false;
   uint64_t total = 0;
   const bool even = ((base & 1) == 0);   // 16-byte accesses need an even first index
   for (uint64_t i0 = 2 * static_cast<uint64_t>(tid); i0 < len; i0 += 2 * PRED_THREADS) {
@@ -371,12 +373,20 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
     const uint32_t a0 = static_cast<uint32_t>(e0), b0 = static_cast<uint32_t>(g0), a1 = static_cast<uint32_t>(e1),
                    b1 = static_cast<uint32_t>(g1);
     total += static_cast<uint64_t>(a0) + a1;
+    uint32_t h0w = a0, h1w = a1;   // first word of the high-priority entries
+    if (actual && (rl & ROLE_HP)) {
+      // (the task's last launch has no idle time after it and its entry is never used as a gap)
+      const int64_t x0 = i0 + 1 < len ? actual[base + i0] : 0, x1 = i0 + 2 < len ? actual[base + i0 + 1] : 0;
+      bad_actual |= x0 < 0 || x1 < 0;
+      h0w = static_cast<uint64_t>(x0) >= WIDE32 ? WIDE32 : static_cast<uint32_t>(x0);
+      h1w = static_cast<uint64_t>(x1) >= WIDE32 ? WIDE32 : static_cast<uint32_t>(x1);
+    }
     if (even && two) {
       if (rl & ROLE_LP) *reinterpret_cast<uint2*>(lp_e + base + i0) = make_uint2(a0, a1);
-      if (rl & ROLE_HP) *reinterpret_cast<uint4*>(hp_eg + base + i0) = make_uint4(a0, b0, a1, b1);
+      if (rl & ROLE_HP) *reinterpret_cast<uint4*>(hp_eg + base + i0) = make_uint4(h0w, b0, h1w, b1);
     } else {
       if (rl & ROLE_LP) { lp_e[base + i0] = a0; if (two) lp_e[base + i0 + 1] = a1; }
-      if (rl & ROLE_HP) { hp_eg[base + i0] = make_uint2(a0, b0); if (two) hp_eg[base + i0 + 1] = make_uint2(a1, b1); }
+      if (rl & ROLE_HP) { hp_eg[base + i0] = make_uint2(h0w, b0); if (two) hp_eg[base + i0 + 1] = make_uint2(h1w, b1); }
     }
   }
   total = wave_sum_u64(total);
@@ -388,6 +398,7 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
     lp_total[t] = sum;
   }
   if (unknown) atomicOr(&ctrl->status, ERR_UNKNOWN_ID);
+  if (bad_actual) atomicOr(&ctrl->status, ERR_ACTUAL_GAP);
   if (wide) atomicOr(&ctrl->wide, 1u);
 }
 
@@ -416,6 +427,15 @@ __device__ __forceinline__ void lw_store_scalar(const LaneWalkSmem& sm, uint32_t
   }
 }
 
+// MODE 0: the plan on predictions (fill counts, filled time, completion time of the low-priority task).
+// MODE 1 / 2: the same decisions replayed against the idle times that occurred, without / with real-time
+// feedback (the runtime-feedback paragraph of the paper's scheduling section): the first word of a
+// high-priority entry is then the actual idle time; with feedback nothing more is issued into a gap once
+// the time filled has reached it; what runs past it delays the high-priority task, and the sum of these
+// delays is written in place of the completion time.
+enum : int { LW_PLAN = 0, LW_REPLAY = 1, LW_REPLAY_FEEDBACK = 2 };
+
+template <int MODE>
 __global__ void __launch_bounds__(LW_THREADS)
 k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task, const uint32_t* __restrict__ lp_task,
                 uint64_t n_scen, const uint64_t* __restrict__ gap_off, const uint32_t* __restrict__ lp_e,
@@ -438,7 +458,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     l0 = static_cast<uint32_t>(off[lp]); lp_end = static_cast<uint32_t>(off[lp + 1]);
     g_first = static_cast<uint32_t>(gap_off[s]);
     n_gaps = hp_end > h0 ? hp_end - h0 - 1 : 0;
-    total_lp = lp_end > l0 ? lp_total[lp] : 0;
+    total_lp = (MODE == LW_PLAN && lp_end > l0) ? lp_total[lp] : 0;
   }
   uint32_t hp_pos = h0, lp_pos = l0;                    // next entry of either stream
   uint32_t hp_landed = h0 & ~(LW_HP_CHUNK - 1), lp_landed = l0 & ~(LW_LP_CHUNK - 1);   // ring holds entries below these
@@ -455,6 +475,8 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
   int64_t cur_open = 0, completion;
   uint64_t consumed = 0;
   uint32_t c = 0, f = 0, rem = 0;
+  uint32_t ga = 0;                   // replay: the idle time that occurred after the launch whose gap is open
+  int64_t delay = 0;                 // replay: by how much issued kernels ran past the gaps so far
   // a gap is used if it is at least min_gap and at least the margin long (32-bit idle times are below WIDE32)
   const int64_t floor64 = min_gap > margin ? min_gap : margin;
   const uint32_t gap_floor = floor64 >= static_cast<int64_t>(WIDE32) ? WIDE32 : static_cast<uint32_t>(floor64);
@@ -536,6 +558,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
         g += pending ? 1u : 0u;
         consumed += pending ? f : 0u;
+        if (MODE != LW_PLAN) delay += (pending && f > ga) ? static_cast<int64_t>(f - ga) : 0;
         pending = false;
         const uint32_t E = sm.hp_e[hp_pos & (LW_HP_CAP - 1)][tid], G = sm.hp_g[hp_pos & (LW_HP_CAP - 1)][tid];
         // between gaps: the next high-priority launch runs, then its gap opens (the last launch has none)
@@ -543,12 +566,15 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         const bool at_end = idle && hp_pos == hp_end;
         const bool take = idle && !at_end && hp_pos < hp_landed;
         hp_pos += take ? 1u : 0u;
-        t_open += take ? static_cast<int64_t>(E) : 0;
         const bool last = take && hp_pos == hp_end;
         const bool gap = take && !last;
-        cur_open = gap ? t_open : cur_open;
-        t_open += gap ? static_cast<int64_t>(G) : 0;
+        if (MODE == LW_PLAN) {
+          t_open += take ? static_cast<int64_t>(E) : 0;
+          cur_open = gap ? t_open : cur_open;
+          t_open += gap ? static_cast<int64_t>(G) : 0;
+        }
         const bool usable = gap && G >= gap_floor;
+        if (MODE != LW_PLAN) ga = usable ? E : ga;
         const bool skip = gap && !usable;
         // a skipped gap reports zeros
         sm.out_c[g & (LW_OUT_CAP - 1)][tid] = 0u;
@@ -565,7 +591,8 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         // in a gap: does the head of the queue fit into what is left?
         const uint32_t d = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid];
         const bool tryq = in_gap && lp_pos < lp_landed;
-        const bool fits = tryq && d <= rem;
+        // (with feedback: the next high-priority request has arrived once the time filled reaches the actual gap)
+        const bool fits = tryq && d <= rem && (MODE != LW_REPLAY_FEEDBACK || f < ga);
         const uint32_t dd = fits ? d : 0u;
         rem -= dd; f += dd;
         c += fits ? 1u : 0u;
@@ -586,6 +613,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
     ++g;
     consumed += f;
+    if (MODE != LW_PLAN && f > ga) delay += static_cast<int64_t>(f - ga);
   }
   // what is still staged, then zeros for the gaps after the queue ran empty
   lw_store_scalar(sm, tid, flushed, g - flushed, fill_count, filled_ns);
@@ -601,7 +629,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
   }
   for (; z < g_end; ++z) { fill_count[z] = 0; filled_ns[z] = 0; }
   completion = done ? cur_open + static_cast<int64_t>(f) : t_open + static_cast<int64_t>(total_lp - consumed);
-  completion_out[s] = completion;
+  completion_out[s] = MODE == LW_PLAN ? completion : delay;
   placed_out[s] = lp_pos - l0;
 }
 

@@ -63,6 +63,30 @@ __global__ void k_classify(const uint64_t* __restrict__ off, uint32_t n_tasks, u
   }
 }
 
+// Execution time and idle time of every launch as they stand in the trace (Section 3.2, "Measuring the
+// execution and idle time of kernel"); task boundaries are put right by k_measure_task_ends afterwards.
+__global__ void __launch_bounds__(256)
+k_measure(const fikit_launch* __restrict__ rec, uint64_t n, int64_t* __restrict__ exec_ns, int64_t* __restrict__ gap_ns,
+          Ctrl* ctrl) {
+  if (ctrl->status & ERR_OFFSETS) return;
+  const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int64_t start = rec[i].start_ns, end = rec[i].end_ns;
+  if (end < start) atomicOr(&ctrl->status, ERR_BAD_RECORD);
+  exec_ns[i] = end - start;
+  int64_t g = GAP_NONE;
+  if (i + 1 < n) { g = rec[i + 1].start_ns - end; g = g < 0 ? 0 : g; }
+  gap_ns[i] = g;
+}
+
+// The last launch of every task has no idle time after it.
+__global__ void k_measure_task_ends(const uint64_t* __restrict__ off, uint32_t n_tasks, int64_t* __restrict__ gap_ns,
+                                    const Ctrl* ctrl) {
+  if (ctrl->status & ERR_OFFSETS) return;
+  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (t < n_tasks && off[t + 1] > off[t]) gap_ns[off[t + 1] - 1] = GAP_NONE;
+}
+
 // FNV-1a, 64 bit, over the eight little-endian 32-bit words that hold a launch's identity
 // (name id, grid x y z, block x y z, dynamic shared-memory bytes): for each byte in memory
 // order, xor it into the hash, then multiply by the FNV prime 2^40 + 0x1b3 modulo 2^64.

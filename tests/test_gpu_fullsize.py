@@ -127,7 +127,16 @@ def test_config4_batched_gapfill_full_size():
     check_global_properties(prof, off, cfg.n_tasks)
     scen = [0, 1, 777, 32768, 65534, 65535]
     check_sampled_tasks(cfg, prof, off, [t for s in scen for t in (2 * s, 2 * s + 1)])
-    del d_rec
+    # per-launch measurement at full size (the actual idle times are the replay's input further down)
+    d_exec, d_gap = binding.fikit_measure(d_rec, d_off)
+    for s in scen[:3]:
+        for t in (2 * s, 2 * s + 1):
+            rec_t = traces.task_records(cfg, t)
+            ex, gp = oracle.measure(rec_t, np.array([0, rec_t.shape[0]], dtype=np.uint64))
+            a, b = int(off[t]), int(off[t + 1])
+            assert np.array_equal(d_exec[a:b].cpu().numpy(), ex) and np.array_equal(d_gap[a:b].cpu().numpy(), gp), f"task {t}"
+    assert bool((d_exec >= 1).all())
+    del d_rec, d_exec
     hp, lp = traces.scenarios(cfg)
     go = traces.gap_offsets(off, hp)
     t0 = time.time()
@@ -154,3 +163,33 @@ def test_config4_batched_gapfill_full_size():
         assert np.array_equal(got.filled_ns[g0:g1].cpu().numpy(), exp[1]), f"scenario {s}"
         assert int(got.lp_completion_ns[s]) == int(exp[2][0]) and int(got.lp_placed[s]) == int(exp[3][0])
     say(f"  sampled scenarios {scen} match the oracle")
+    # replay against the actual idle times, without and with real-time feedback
+    d_hp, d_lp, d_go = binding.to_device_u32(hp, DEV), binding.to_device_u32(lp, DEV), binding.to_device_u64(go, DEV)
+    hp_gap = d_gap.view(-1, 4096 + 16384)[:, :4095]          # actual idle time of every gap, scenario by scenario
+    for feedback in (False, True):
+        t0 = time.time()
+        rep = binding.fikit_gapfill_replay(prof.ids, d_off, prof.rows, prof.task_row_offsets, d_gap, d_hp, d_lp, d_go,
+                                           margin_ns=cfg.margin_ns, min_gap_ns=cfg.min_gap_ns, feedback=feedback)
+        say(f"  fikit_gapfill_replay(feedback={feedback}): {hp.size} scenarios in {time.time() - t0:.2f}s")
+        fn = rep.filled_ns.view(-1, 4095)
+        assert torch.equal(rep.fill_count.view(-1, 4095).to(torch.int64).sum(dim=1), rep.lp_placed)
+        assert torch.equal(torch.clamp(fn - hp_gap, min=0).sum(dim=1), rep.hp_delay_ns)
+        if not feedback:   # the profile-only controller takes the decisions of the gap fill
+            assert torch.equal(rep.fill_count, got.fill_count) and torch.equal(rep.filled_ns, got.filled_ns)
+            assert torch.equal(rep.lp_placed, got.lp_placed)
+        for s in scen:
+            recs = [traces.task_records(cfg, 2 * s), traces.task_records(cfg, 2 * s + 1)]
+            loc_off = np.array([0, recs[0].shape[0], recs[0].shape[0] + recs[1].shape[0]], dtype=np.uint64)
+            both = np.concatenate(recs)
+            o_ids, o_rows, o_tro = oracle.profile(both, loc_off)
+            _, o_gap = oracle.measure(both, loc_off)
+            one = np.array([0], dtype=np.uint32)
+            exp = oracle.replay(o_ids, loc_off, o_rows, o_tro, o_gap, one, one + 1, cfg.margin_ns, cfg.min_gap_ns, feedback,
+                                traces.gap_offsets(loc_off, one))
+            g0, g1 = int(go[s]), int(go[s + 1])
+            assert np.array_equal(binding.u32_to_numpy(rep.fill_count[g0:g1]), exp[0]), f"scenario {s}"
+            assert np.array_equal(rep.filled_ns[g0:g1].cpu().numpy(), exp[1]), f"scenario {s}"
+            assert int(rep.hp_delay_ns[s]) == int(exp[2][0]) and int(rep.lp_placed[s]) == int(exp[3][0])
+        say(f"  replay, feedback={feedback}: mean delay of the high-priority task {float(rep.hp_delay_ns.double().mean()) / 1e6:.3f} ms; "
+            f"sampled scenarios match the oracle")
+        del rep
