@@ -106,6 +106,9 @@ def main():
                     help="processes that generate the input; 0 = generate in this process")
     ap.add_argument("--cpu-sample-tasks", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replay", action="store_true",
+                    help="after the timed steps, also time fikit_measure and fikit_gapfill_replay (reported beside "
+                         "the metric, not part of it)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware counter runs)")
     args = ap.parse_args()
@@ -240,6 +243,44 @@ def main():
     for k, (ms, cnt) in sorted(trace.items(), key=lambda kv: -kv[1][0]):
         log(f"[bench]   {k:18s} {ms / args.steps:9.3f} ms/step  {cnt // args.steps:3d} launches/step")
 
+    # ---- the replay against actual idle times (beside the metric) --------------------------------
+    replay = None
+    if args.replay and n_scen:
+        d_exec, d_gap = binding.fikit_measure(d_rec, d_off, workspace_buf=ws)
+        rp_out = binding.Replay(gf_out.fill_count, gf_out.filled_ns, gf_out.lp_completion_ns, gf_out.lp_placed)
+        replay = {}
+        for feedback in (False, True):
+            binding.fikit_gapfill_replay(ids, d_off, prof.rows, tro, d_gap, d_hp, d_lp, d_go, margin_ns=cfg.margin_ns,
+                                         min_gap_ns=cfg.min_gap_ns, feedback=feedback, n_gaps=n_gaps, n_ids=n,
+                                         out=rp_out, workspace_buf=ws)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            binding.fikit_trace_enable(True)
+            ev[0].record()
+            for _ in range(args.steps):
+                binding.fikit_gapfill_replay(ids, d_off, prof.rows, tro, d_gap, d_hp, d_lp, d_go, margin_ns=cfg.margin_ns,
+                                             min_gap_ns=cfg.min_gap_ns, feedback=feedback, n_gaps=n_gaps, n_ids=n,
+                                             out=rp_out, workspace_buf=ws)
+            ev[1].record()
+            torch.cuda.synchronize()
+            rt = binding.fikit_trace_read()
+            binding.fikit_trace_enable(False)
+            ms = ev[0].elapsed_time(ev[1]) / args.steps
+            replay["feedback" if feedback else "no_feedback"] = {
+                "ms": round(ms, 3), "scenarios_per_s": round(n_scen / (ms * 1e-3), 1),
+                "mean_hp_delay_ns": round(float(rp_out.hp_delay_ns.double().mean()), 1),
+                "kernel_ms": {k: round(v[0] / args.steps, 3) for k, v in rt.items() if k.startswith("k_gf")}}
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(args.steps):
+            binding.fikit_measure(d_rec, d_off, exec_out=d_exec, gap_out=d_gap, workspace_buf=ws)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / args.steps
+        replay["measure"] = {"ms": round(ms, 3), "records_per_s": round(n / (ms * 1e-3), 1),
+                             "algorithmic_GB/s": round(n * 80 / (ms * 1e-3) / 1e9, 1)}
+        log(f"[bench] replay: {json.dumps(replay)}")
+        del d_exec, d_gap
+
     # ---- roofline of the dominant kernel ------------------------------------------------------
     lens = np.array([cfg.launches(t) for t in range(cfg.n_tasks)], dtype=np.int64)
     n_small = int(lens[lens <= 4096].sum())
@@ -315,6 +356,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if replay:
+        out["replay"] = replay
     # whole calls against the HBM peak: counter-measured bytes of every kernel of the call / the call's time
     calls = stored_call_traffic(name)
     if calls:
