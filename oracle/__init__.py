@@ -58,12 +58,12 @@ def _load():
         lib.oracle_profile.argtypes = [vp, u64, vp, u32, vp, vp, u64, vp, vp]
         lib.oracle_gapfill.restype = ctypes.c_int
         lib.oracle_gapfill.argtypes = [vp, vp, u32, vp, vp, vp, vp, u64, i64, i64, vp, vp, vp, vp,
-                                       vp, vp, vp]
+                                       vp, vp, vp, ctypes.c_int]
         lib.oracle_measure.restype = ctypes.c_int
         lib.oracle_measure.argtypes = [vp, u64, vp, u32, vp, vp]
         lib.oracle_replay.restype = ctypes.c_int
         lib.oracle_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, i64, i64, ctypes.c_int, vp, vp, vp,
-                                      vp, vp]
+                                      vp, vp, ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -104,8 +104,9 @@ def profile(records: np.ndarray, task_offsets: np.ndarray, row_capacity: Optiona
 
 def gapfill(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_row_offsets: np.ndarray,
             hp_task: np.ndarray, lp_task: np.ndarray, margin_ns: int, min_gap_ns: int,
-            gap_offsets: np.ndarray, want_assign: bool = False):
-    """-> (fill_count, filled_ns, lp_completion_ns, lp_placed[, assign, assign_offsets])."""
+            gap_offsets: np.ndarray, want_assign: bool = False, predictor: int = 0):
+    """-> (fill_count, filled_ns, lp_completion_ns, lp_placed[, assign, assign_offsets]).
+    predictor: 0 = nearest-rank median of the ID's samples, 1 = their mean (sum // count)."""
     ids = np.ascontiguousarray(ids, dtype=np.uint64)
     task_offsets = np.ascontiguousarray(task_offsets, dtype=np.uint64)
     rows = np.ascontiguousarray(rows)
@@ -129,7 +130,7 @@ def gapfill(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_ro
         assign = np.zeros(int(assign_off[-1]), dtype=np.uint32)
     st = _load().oracle_gapfill(_p(ids), _p(task_offsets), n_tasks, _p(rows), _p(tro), _p(hp), _p(lp),
                                 s, margin_ns, min_gap_ns, _p(go), _p(fill_count), _p(filled_ns),
-                                _p(completion), _p(placed), _p(assign_off), _p(assign))
+                                _p(completion), _p(placed), _p(assign_off), _p(assign), predictor)
     if st != OK:
         raise OracleError(st)
     if want_assign:
@@ -153,7 +154,7 @@ def measure(records: np.ndarray, task_offsets: np.ndarray) -> Tuple[np.ndarray, 
 
 def replay(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_row_offsets: np.ndarray,
            actual_gap_ns: np.ndarray, hp_task: np.ndarray, lp_task: np.ndarray, margin_ns: int, min_gap_ns: int,
-           feedback: bool, gap_offsets: np.ndarray):
+           feedback: bool, gap_offsets: np.ndarray, predictor: int = 0):
     """-> (fill_count, filled_ns, hp_delay_ns, lp_placed)."""
     ids = np.ascontiguousarray(ids, dtype=np.uint64)
     task_offsets = np.ascontiguousarray(task_offsets, dtype=np.uint64)
@@ -172,7 +173,7 @@ def replay(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_row
     placed = np.zeros(s, dtype=np.uint64)
     st = _load().oracle_replay(_p(ids), _p(task_offsets), task_offsets.shape[0] - 1, _p(rows), _p(tro), _p(ag),
                                _p(hp), _p(lp), s, margin_ns, min_gap_ns, 1 if feedback else 0, _p(go),
-                               _p(fill_count), _p(filled_ns), _p(delay), _p(placed))
+                               _p(fill_count), _p(filled_ns), _p(delay), _p(placed), predictor)
     if st != OK:
         raise OracleError(st)
     return fill_count, filled_ns, delay, placed

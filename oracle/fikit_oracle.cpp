@@ -115,6 +115,14 @@ Stats stats_of(std::vector<int64_t> v) {
   return s;
 }
 
+// The predicted duration taken from a row's statistics: the nearest-rank median (predictor 0), or the
+// mean the paper defines, SK_j / SG_j of Section 3.2 = sum / count, rounded down to whole nanoseconds
+// (predictor 1; 0 if there is no sample).
+int64_t predicted(const Stats& s, int predictor) {
+  if (predictor == 0) return s.p50;
+  return s.count ? static_cast<int64_t>(s.sum / s.count) : 0;
+}
+
 struct Samples {
   std::vector<int64_t> exec;  // K: execution time of every launch with this ID
   std::vector<int64_t> gap;   // G: idle time after every launch with this ID (not the last of the task)
@@ -189,7 +197,7 @@ int oracle_profile(const void* records_v, uint64_t n_records, const uint64_t* ta
 //
 // Predictions come from the profile rows: a launch's predicted execution time is the p50
 // execution time of its ID, the predicted idle time after a high-priority launch is the p50
-// idle time of its ID.  Per high-priority gap the procedure (Algorithm 1) skips gaps below
+// idle time of its ID (predictor 0), or the means SK_j and SG_j of Section 3.2 (predictor 1).  Per high-priority gap the procedure (Algorithm 1) skips gaps below
 // min_gap_ns, reserves margin_ns at the end of the gap, and then keeps issuing the
 // low-priority task's next kernel while its predicted duration does not exceed what is left,
 // subtracting each issued kernel's duration from the remaining idle time.
@@ -205,12 +213,12 @@ int oracle_gapfill(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n
                    const uint32_t* lp_task, uint64_t n_scenarios, int64_t margin_ns,
                    int64_t min_gap_ns, const uint64_t* gap_offsets, uint32_t* fill_count,
                    int64_t* filled_ns, int64_t* lp_completion_ns, uint64_t* lp_placed,
-                   const uint64_t* assign_offsets, uint32_t* assign) {
+                   const uint64_t* assign_offsets, uint32_t* assign, int predictor) {
   const Row* rows = static_cast<const Row*>(rows_v);
   if (!task_offsets || !task_row_offsets) return INVALID_ARG;
   if (n_scenarios && (!hp_task || !lp_task || !gap_offsets || !lp_completion_ns || !lp_placed))
     return INVALID_ARG;
-  if (margin_ns < 0 || min_gap_ns < 0) return INVALID_ARG;
+  if (margin_ns < 0 || min_gap_ns < 0 || predictor < 0 || predictor > 1) return INVALID_ARG;
 
   for (uint64_t s = 0; s < n_scenarios; ++s) {
     const uint32_t hp = hp_task[s], lp = lp_task[s];
@@ -230,7 +238,7 @@ int oracle_gapfill(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n
     for (uint64_t j = 0; j < L; ++j) {
       auto it = lp_rows.find(ids[l0 + j]);
       if (it == lp_rows.end()) return UNKNOWN_ID;
-      D[j] = it->second->exec.p50;
+      D[j] = predicted(it->second->exec, predictor);
     }
 
     uint64_t p = 0;        // next low-priority kernel to issue (FIFO)
@@ -241,8 +249,8 @@ int oracle_gapfill(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n
     for (uint64_t i = 0; i < H; ++i) {
       auto it = hp_rows.find(ids[h0 + i]);
       if (it == hp_rows.end()) return UNKNOWN_ID;
-      const int64_t E = it->second->exec.p50;
-      const int64_t G = it->second->gap.p50;
+      const int64_t E = predicted(it->second->exec, predictor);
+      const int64_t G = predicted(it->second->gap, predictor);
       t += E;  // high-priority kernel i runs and ends at t
       if (i + 1 == H) break;  // no gap after the last launch
       uint32_t c = 0;
@@ -321,11 +329,12 @@ int oracle_replay(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n_
                   const void* rows_v, const uint64_t* task_row_offsets, const int64_t* actual_gap_ns,
                   const uint32_t* hp_task, const uint32_t* lp_task, uint64_t n_scenarios,
                   int64_t margin_ns, int64_t min_gap_ns, int feedback, const uint64_t* gap_offsets,
-                  uint32_t* fill_count, int64_t* filled_ns, int64_t* hp_delay_ns, uint64_t* lp_placed) {
+                  uint32_t* fill_count, int64_t* filled_ns, int64_t* hp_delay_ns, uint64_t* lp_placed,
+                  int predictor) {
   const Row* rows = static_cast<const Row*>(rows_v);
   if (!task_offsets || !task_row_offsets) return INVALID_ARG;
   if (n_scenarios && (!hp_task || !lp_task || !gap_offsets || !hp_delay_ns || !lp_placed)) return INVALID_ARG;
-  if (margin_ns < 0 || min_gap_ns < 0) return INVALID_ARG;
+  if (margin_ns < 0 || min_gap_ns < 0 || predictor < 0 || predictor > 1) return INVALID_ARG;
 
   for (uint64_t s = 0; s < n_scenarios; ++s) {
     const uint32_t hp = hp_task[s], lp = lp_task[s];
@@ -339,7 +348,7 @@ int oracle_replay(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n_
     for (uint64_t j = 0; j < L; ++j) {
       auto it = lp_rows.find(ids[l0 + j]);
       if (it == lp_rows.end()) return UNKNOWN_ID;
-      D[j] = it->second->exec.p50;
+      D[j] = predicted(it->second->exec, predictor);
     }
     uint64_t p = 0;     // next low-priority kernel to issue (FIFO)
     int64_t delay = 0;  // accumulated delay of the high-priority task
@@ -347,7 +356,7 @@ int oracle_replay(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n_
     for (uint64_t i = 0; i + 1 < H; ++i) {
       auto it = hp_rows.find(ids[h0 + i]);
       if (it == hp_rows.end()) return UNKNOWN_ID;
-      const int64_t G = it->second->gap.p50;        // predicted idle time
+      const int64_t G = predicted(it->second->gap, predictor);  // predicted idle time
       const int64_t actual = actual_gap_ns[h0 + i];  // idle time that occurred
       if (actual < 0) return INVALID_ARG;
       uint32_t c = 0;

@@ -115,7 +115,7 @@ def test_p1_ids_and_rows(p1):
     assert sum(int(r["gap"]["count"]) for r in rows[:3]) == 11
 
 
-@pytest.mark.parametrize("case", [0, 1])
+@pytest.mark.parametrize("case", [0, 1, 2])
 def test_p1_gapfill(p1, case):
     g, rec, off = p1
     exp = g["gapfill"][case]
@@ -125,7 +125,8 @@ def test_p1_gapfill(p1, case):
     go = traces.gap_offsets(off, hp)
     assert list(go) == [0, 11]
     fc, fn, comp, placed, assign, aoff = oracle.gapfill(
-        ids, off, rows, tro, hp, lp, exp["margin_ns"], exp["min_gap_ns"], go, want_assign=True)
+        ids, off, rows, tro, hp, lp, exp["margin_ns"], exp["min_gap_ns"], go, want_assign=True,
+        predictor=exp.get("predictor", 0))
     assert list(fc) == exp["fill_count"]
     assert list(fn) == exp["filled_ns"]
     assert int(placed[0]) == exp["lp_placed"]
@@ -462,6 +463,34 @@ def test_p5_gapfill_equal_durations_closed_form():
 
 
 # ---------------------------------------------------------------- error statuses
+@pytest.mark.parametrize("cfg", small_configs(), ids=lambda c: c.name)
+def test_p3_mean_predictor_is_the_median_predictor_on_rows_that_carry_the_mean(cfg):
+    """Predicting with SK_j / SG_j (sum // count) must give what the median predictor gives once the rows'
+    p50 fields are overwritten with those means: the two only differ in where the prediction is read."""
+    rec, off = traces.build(cfg)
+    ids, rows, tro = oracle.profile(rec, off)
+    _, gap = oracle.measure(rec, off)
+    hp, lp = traces.scenarios(cfg)
+    if hp.size == 0:
+        return
+    go = traces.gap_offsets(off, hp)
+    swapped = rows.copy()
+    for blk in ("exec", "gap"):
+        cnt = rows[blk]["count"].astype(np.uint64)
+        swapped[blk]["p50"] = np.where(cnt > 0, rows[blk]["sum"] // np.maximum(cnt, 1), 0).astype(np.int64)
+    a = oracle.gapfill(ids, off, rows, tro, hp, lp, cfg.margin_ns, 0, go, predictor=1)
+    b = oracle.gapfill(ids, off, swapped, tro, hp, lp, cfg.margin_ns, 0, go, predictor=0)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    assert not all(np.array_equal(x, y) for x, y in zip(a, oracle.gapfill(ids, off, rows, tro, hp, lp, cfg.margin_ns, 0, go)))
+    for fb in (False, True):
+        a = oracle.replay(ids, off, rows, tro, gap, hp, lp, cfg.margin_ns, 0, fb, go, predictor=1)
+        b = oracle.replay(ids, off, swapped, tro, gap, hp, lp, cfg.margin_ns, 0, fb, go, predictor=0)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.gapfill(ids, off, rows, tro, hp, lp, 0, 0, go, predictor=2)
+    assert e.value.status == oracle.INVALID_ARG
+
+
 # ---------------------------------------------------------------- P6
 def test_p6_measure_is_end_minus_start_and_next_start_minus_end():
     rec = make_records([(1, (1, 1, 1), (64, 1, 1), 0, 10, 25), (2, (1, 1, 1), (64, 1, 1), 0, 30, 31),
