@@ -117,9 +117,18 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records,
                   fikit_row* d_rows_out, uint64_t row_capacity, uint64_t* d_task_row_offsets,
                   uint64_t* h_n_rows, void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Where a launch's predicted execution / idle time is read in its ID's row. */
+typedef enum fikit_predictor {
+  FIKIT_PREDICT_P50 = 0,  /* nearest-rank median of the ID's samples                              */
+  FIKIT_PREDICT_MEAN = 1  /* their mean, SK_j / SG_j of Section 3.2: sum / count, rounded down
+                             to whole nanoseconds (0 if the ID has no sample)                     */
+} fikit_predictor;
+
 typedef struct fikit_gapfill_params {
   int64_t margin_ns;  /* reserved at the end of every gap; a gap shorter than this is skipped */
   int64_t min_gap_ns; /* gaps predicted shorter than this are skipped (Algorithm 1)           */
+  int32_t predictor;  /* a fikit_predictor                                                     */
+  int32_t reserved;   /* must be 0                                                             */
 } fikit_gapfill_params;
 
 /* Bytes of device workspace fikit_gapfill needs for these sizes (0 on size overflow). */
@@ -144,7 +153,7 @@ size_t fikit_gapfill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t 
  *   d_lp_placed        [n_scenarios] number of low-priority kernels issued into gaps.
  *
  * Predicted execution time of a launch = exec.p50 of its ID's row; predicted idle time after a
- * high-priority launch = gap.p50 of its ID's row.  A gap is skipped if its prediction is below
+ * high-priority launch = gap.p50 of its ID's row (or the means, see fikit_predictor).  A gap is skipped if its prediction is below
  * min_gap_ns or below margin_ns; otherwise gap - margin_ns nanoseconds may be filled.
  *
  * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNKNOWN_ID, HIP_ERROR.
@@ -181,7 +190,7 @@ typedef struct fikit_replay_params {
   int64_t margin_ns;   /* as in fikit_gapfill_params                                            */
   int64_t min_gap_ns;  /* as in fikit_gapfill_params                                            */
   int32_t feedback;    /* 0: profile-only controller; non-zero: real-time feedback             */
-  int32_t reserved;    /* must be 0                                                             */
+  int32_t predictor;   /* a fikit_predictor                                                     */
 } fikit_replay_params;
 
 /* Bytes of device workspace fikit_gapfill_replay needs for these sizes (0 on size overflow). */

@@ -23,6 +23,7 @@ FIKIT_BAD_RECORD = -4
 FIKIT_UNKNOWN_ID = -5
 FIKIT_HIP_ERROR = -6
 FIKIT_UNSUPPORTED = -7
+FIKIT_PREDICT_P50, FIKIT_PREDICT_MEAN = 0, 1
 
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
            "fikit_gapfill", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
@@ -45,12 +46,13 @@ class FikitError(RuntimeError):
 
 
 class _GapfillParams(ctypes.Structure):
-    _fields_ = [("margin_ns", ctypes.c_int64), ("min_gap_ns", ctypes.c_int64)]
+    _fields_ = [("margin_ns", ctypes.c_int64), ("min_gap_ns", ctypes.c_int64), ("predictor", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 class _ReplayParams(ctypes.Structure):
     _fields_ = [("margin_ns", ctypes.c_int64), ("min_gap_ns", ctypes.c_int64), ("feedback", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("predictor", ctypes.c_int32)]
 
 
 _lib = None
@@ -192,8 +194,8 @@ class GapFill(NamedTuple):
 
 def fikit_gapfill(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Tensor, task_row_offsets: torch.Tensor,
                   hp_task: torch.Tensor, lp_task: torch.Tensor, gap_offsets: torch.Tensor, *, margin_ns: int,
-                  min_gap_ns: int, n_gaps: Optional[int] = None, n_ids: Optional[int] = None,
-                  out: Optional[GapFill] = None, workspace_buf: Optional[torch.Tensor] = None,
+                  min_gap_ns: int, predictor: int = FIKIT_PREDICT_P50, n_gaps: Optional[int] = None,
+                  n_ids: Optional[int] = None, out: Optional[GapFill] = None, workspace_buf: Optional[torch.Tensor] = None,
                   stream: Optional[torch.cuda.Stream] = None) -> GapFill:
     """hp_task / lp_task: int32 views of the uint32 task numbers; gap_offsets: int64 [S+1]."""
     lib = load()
@@ -216,7 +218,7 @@ def fikit_gapfill(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Ten
     need = fikit_gapfill_workspace_bytes(n_ids, n_tasks, s)
     if workspace_buf is None:
         workspace_buf = workspace(need, dev)
-    params = _GapfillParams(margin_ns, min_gap_ns)
+    params = _GapfillParams(margin_ns, min_gap_ns, predictor, 0)
     with torch.cuda.device(dev):
         st = lib.fikit_gapfill(_ptr(ids), _ptr(task_offsets), n_tasks, _ptr(rows), _ptr(task_row_offsets),
                                _ptr(hp_task), _ptr(lp_task), s, ctypes.byref(params), _ptr(gap_offsets),
@@ -270,7 +272,7 @@ def fikit_replay_workspace_bytes(n_ids: int, n_tasks: int, n_scenarios: int) -> 
 def fikit_gapfill_replay(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Tensor, task_row_offsets: torch.Tensor,
                          actual_gap_ns: torch.Tensor, hp_task: torch.Tensor, lp_task: torch.Tensor,
                          gap_offsets: torch.Tensor, *, margin_ns: int, min_gap_ns: int, feedback: bool,
-                         n_gaps: Optional[int] = None, n_ids: Optional[int] = None, out: Optional[Replay] = None,
+                         predictor: int = FIKIT_PREDICT_P50, n_gaps: Optional[int] = None, n_ids: Optional[int] = None, out: Optional[Replay] = None,
                          workspace_buf: Optional[torch.Tensor] = None,
                          stream: Optional[torch.cuda.Stream] = None) -> Replay:
     """As fikit_gapfill, plus actual_gap_ns: int64 [n_ids] (fikit_measure's gap_ns)."""
@@ -292,7 +294,7 @@ def fikit_gapfill_replay(ids: torch.Tensor, task_offsets: torch.Tensor, rows: to
                      torch.empty(s, dtype=torch.int64, device=dev), torch.empty(s, dtype=torch.int64, device=dev))
     if workspace_buf is None:
         workspace_buf = workspace(fikit_replay_workspace_bytes(n_ids, n_tasks, s), dev)
-    params = _ReplayParams(margin_ns, min_gap_ns, 1 if feedback else 0, 0)
+    params = _ReplayParams(margin_ns, min_gap_ns, 1 if feedback else 0, predictor)
     with torch.cuda.device(dev):
         st = lib.fikit_gapfill_replay(_ptr(ids), _ptr(task_offsets), n_tasks, _ptr(rows), _ptr(task_row_offsets),
                                       _ptr(actual_gap_ns), _ptr(hp_task), _ptr(lp_task), s, ctypes.byref(params),

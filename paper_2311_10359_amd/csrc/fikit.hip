@@ -450,7 +450,9 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
                   uint64_t n_scenarios, const fikit_gapfill_params* h_params, const uint64_t* d_gap_offsets,
                   uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_lp_completion_ns, uint64_t* d_lp_placed,
                   void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!h_params || h_params->margin_ns < 0 || h_params->min_gap_ns < 0) return FIKIT_INVALID_ARG;
+  if (!h_params || h_params->margin_ns < 0 || h_params->min_gap_ns < 0 || h_params->reserved != 0 ||
+      h_params->predictor < FIKIT_PREDICT_P50 || h_params->predictor > FIKIT_PREDICT_MEAN)
+    return FIKIT_INVALID_ARG;
   if (!d_task_offsets || !d_task_row_offsets || !d_workspace) return FIKIT_INVALID_ARG;
   if (n_scenarios >= MAX_ELEMS) return FIKIT_INVALID_ARG;
   if (n_scenarios > 0 && (!d_hp_task || !d_lp_task || !d_gap_offsets || !d_lp_completion_ns || !d_lp_placed || n_tasks == 0))
@@ -501,7 +503,7 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   if (lanes) {
     tr.mark("k_gf_predict32");
     hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                       d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total, ctrl);
+                       d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total, static_cast<uint32_t>(h_params->predictor), ctrl);
     tr.mark("k_gf_walk_lanes");
     FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes<LW_PLAN>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(LaneWalkSmem))));
@@ -514,7 +516,7 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   const uint32_t only_if_wide = lanes ? 1u : 0u;
   tr.mark("k_gf_predict");
   hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                     d_task_row_offsets, role, glists, pe, pg, open, only_if_wide, ctrl);
+                     d_task_row_offsets, role, glists, pe, pg, open, only_if_wide, static_cast<uint32_t>(h_params->predictor), ctrl);
 #ifndef FIKIT_WALK_GW
 #define FIKIT_WALK_GW 16
 #define FIKIT_WALK_WINDOW false
@@ -571,7 +573,9 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
                          const uint32_t* d_lp_task, uint64_t n_scenarios, const fikit_replay_params* h_params,
                          const uint64_t* d_gap_offsets, uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_hp_delay_ns,
                          uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!h_params || h_params->margin_ns < 0 || h_params->min_gap_ns < 0 || h_params->reserved != 0) return FIKIT_INVALID_ARG;
+  if (!h_params || h_params->margin_ns < 0 || h_params->min_gap_ns < 0 || h_params->predictor < FIKIT_PREDICT_P50 ||
+      h_params->predictor > FIKIT_PREDICT_MEAN)
+    return FIKIT_INVALID_ARG;
   if (!d_task_offsets || !d_task_row_offsets || !d_workspace) return FIKIT_INVALID_ARG;
   if (n_scenarios >= MAX_ELEMS) return FIKIT_INVALID_ARG;
   if (n_scenarios > 0 && (!d_hp_task || !d_lp_task || !d_gap_offsets || !d_hp_delay_ns || !d_lp_placed || n_tasks == 0))
@@ -614,7 +618,8 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
                      ctrl);
   tr.mark("k_gf_predict32");
   hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                     d_task_row_offsets, role, glists, d_actual_gap_ns, lp_e, hp_eg, lp_total, ctrl);
+                     d_task_row_offsets, role, glists, d_actual_gap_ns, lp_e, hp_eg, lp_total,
+                     static_cast<uint32_t>(h_params->predictor), ctrl);
   const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
   const dim3 grid(blocks_for(n_scenarios, LW_THREADS)), block(LW_THREADS);
   if (h_params->feedback) {

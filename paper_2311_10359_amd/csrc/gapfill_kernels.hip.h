@@ -54,6 +54,12 @@ constexpr int PRED_HT = 2 * PRED_ROWS;
 // Predicted execution time and idle time of a launch: p50 values of its ID's row.  Rows of a
 // task with few IDs sit in an LDS hash table keyed by the ID; otherwise the task's sorted rows
 // are searched in memory.
+// The prediction read from a row's statistics: median, or mean = sum / count (Section 3.2: SK_j, SG_j).
+__device__ __forceinline__ int64_t predicted_of(const fikit_stats& st, uint32_t predictor) {
+  if (predictor == FIKIT_PREDICT_P50) return st.p50;
+  return st.count ? static_cast<int64_t>(st.sum / st.count) : 0;
+}
+
 struct PredTable {
   uint64_t key[PRED_HT];
   int64_t e[PRED_HT];
@@ -61,7 +67,7 @@ struct PredTable {
 };
 
 __device__ __forceinline__ bool predict_one(uint64_t id, bool in_lds, const PredTable& tb, const fikit_row* __restrict__ rows,
-                                            uint64_t r0, uint64_t nr, int64_t& e, int64_t& g) {
+                                            uint64_t r0, uint64_t nr, uint32_t predictor, int64_t& e, int64_t& g) {
   if (in_lds) {
     uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (PRED_HT - 1);
     for (int probe = 0; probe < PRED_HT; ++probe) {
@@ -74,7 +80,11 @@ __device__ __forceinline__ bool predict_one(uint64_t id, bool in_lds, const Pred
   }
   uint64_t lo = 0, hi = nr;
   while (lo < hi) { const uint64_t mid = (lo + hi) >> 1; if (rows[r0 + mid].kernel_id < id) lo = mid + 1; else hi = mid; }
-  if (lo < nr && rows[r0 + lo].kernel_id == id) { e = rows[r0 + lo].exec.p50; g = rows[r0 + lo].gap.p50; return true; }
+  if (lo < nr && rows[r0 + lo].kernel_id == id) {
+    e = predicted_of(rows[r0 + lo].exec, predictor);
+    g = predicted_of(rows[r0 + lo].gap, predictor);
+    return true;
+  }
   return false;
 }
 
@@ -88,7 +98,7 @@ __global__ void __launch_bounds__(PRED_THREADS) __attribute__((amdgpu_waves_per_
 k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
              const fikit_row* __restrict__ rows, const uint64_t* __restrict__ row_off, const uint32_t* __restrict__ role,
              const uint32_t* __restrict__ lists, int64_t* __restrict__ pe, int64_t* __restrict__ pg,
-             int64_t* __restrict__ open, uint32_t only_if_wide, Ctrl* ctrl) {
+             int64_t* __restrict__ open, uint32_t only_if_wide, uint32_t predictor, Ctrl* ctrl) {
   __shared__ PredTable tb;
   // only bits that earlier kernels set: the decision must be the same for the whole workgroup
   if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
@@ -115,8 +125,8 @@ k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off,
         if (old == ~0ull) break;
         h = (h + 1) & (PRED_HT - 1);
       }
-      tb.e[h] = row->exec.p50;
-      tb.g[h] = row->gap.p50;
+      tb.e[h] = predicted_of(row->exec, predictor);
+      tb.g[h] = predicted_of(row->gap, predictor);
     }
   }
   __syncthreads();
@@ -142,8 +152,8 @@ k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off,
         if (i0 + 1 < len) id1 = ids[base + i0 + 1];
       }
       e[2 * k] = e[2 * k + 1] = g[2 * k] = g[2 * k + 1] = 0;
-      if (i0 < len) unknown |= !predict_one(id0, in_lds, tb, rows, r0, nr, e[2 * k], g[2 * k]);
-      if (i0 + 1 < len) unknown |= !predict_one(id1, in_lds, tb, rows, r0, nr, e[2 * k + 1], g[2 * k + 1]);
+      if (i0 < len) unknown |= !predict_one(id0, in_lds, tb, rows, r0, nr, predictor, e[2 * k], g[2 * k]);
+      if (i0 + 1 < len) unknown |= !predict_one(id1, in_lds, tb, rows, r0, nr, predictor, e[2 * k + 1], g[2 * k + 1]);
       const uint64_t se = static_cast<uint64_t>(e[2 * k]) + static_cast<uint64_t>(e[2 * k + 1]);
       const uint64_t so = se + static_cast<uint64_t>(g[2 * k]) + static_cast<uint64_t>(g[2 * k + 1]);
       // a task needs the sums of the role it plays only (the branch is the same for the whole workgroup)
@@ -322,7 +332,7 @@ __global__ void __launch_bounds__(PRED_THREADS)
 k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
                const fikit_row* __restrict__ rows, const uint64_t* __restrict__ row_off, const uint32_t* __restrict__ role,
                const uint32_t* __restrict__ lists, const int64_t* __restrict__ actual, uint32_t* __restrict__ lp_e,
-               uint2* __restrict__ hp_eg, uint64_t* __restrict__ lp_total, Ctrl* ctrl) {
+               uint2* __restrict__ hp_eg, uint64_t* __restrict__ lp_total, uint32_t predictor, Ctrl* ctrl) {
   __shared__ PredTable tb;
   __shared__ uint64_t wave_tot[PRED_THREADS / WAVE];
   if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
@@ -347,8 +357,8 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
         if (old == ~0ull) break;
         h = (h + 1) & (PRED_HT - 1);
       }
-      tb.e[h] = row->exec.p50;
-      tb.g[h] = row->gap.p50;
+      tb.e[h] = predicted_of(row->exec, predictor);
+      tb.g[h] = predicted_of(row->gap, predictor);
     }
   }
   __syncthreads();
@@ -366,8 +376,8 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
       if (two) id1 = ids[base + i0 + 1];
     }
     int64_t e0 = 0, g0 = 0, e1 = 0, g1 = 0;
-    unknown |= !predict_one(id0, in_lds, tb, rows, r0, nr, e0, g0);
-    if (two) unknown |= !predict_one(id1, in_lds, tb, rows, r0, nr, e1, g1);
+    unknown |= !predict_one(id0, in_lds, tb, rows, r0, nr, predictor, e0, g0);
+    if (two) unknown |= !predict_one(id1, in_lds, tb, rows, r0, nr, predictor, e1, g1);
     wide |= static_cast<uint64_t>(e0) >= WIDE32 || static_cast<uint64_t>(g0) >= WIDE32 || static_cast<uint64_t>(e1) >= WIDE32 ||
             static_cast<uint64_t>(g1) >= WIDE32;
     const uint32_t a0 = static_cast<uint32_t>(e0), b0 = static_cast<uint32_t>(g0), a1 = static_cast<uint32_t>(e1),

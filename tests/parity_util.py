@@ -43,13 +43,13 @@ def check_profile(rec, off, **kw):
     return prof, d_off, (o_ids, o_rows, o_tro)
 
 
-def check_gapfill(prof, d_off, off, o_prof, hp, lp, margin, min_gap):
+def check_gapfill(prof, d_off, off, o_prof, hp, lp, margin, min_gap, predictor=0):
     o_ids, o_rows, o_tro = o_prof
     go = traces.gap_offsets(off, hp)
-    exp = oracle.gapfill(o_ids, off, o_rows, o_tro, hp, lp, margin, min_gap, go)
+    exp = oracle.gapfill(o_ids, off, o_rows, o_tro, hp, lp, margin, min_gap, go, predictor=predictor)
     got = binding.fikit_gapfill(prof.ids, d_off, prof.rows, prof.task_row_offsets,
                                 binding.to_device_u32(hp, DEV), binding.to_device_u32(lp, DEV),
-                                binding.to_device_u64(go, DEV), margin_ns=margin, min_gap_ns=min_gap)
+                                binding.to_device_u64(go, DEV), margin_ns=margin, min_gap_ns=min_gap, predictor=predictor)
     torch.cuda.synchronize()
     fc = binding.u32_to_numpy(got.fill_count)
     fn = got.filled_ns.cpu().numpy()

@@ -37,6 +37,8 @@ def test_profile_and_gapfill_match_oracle(name):
     if hp.size:
         for min_gap in (cfg.min_gap_ns, 100000):
             check_gapfill(prof, d_off, off, o_prof, hp, lp, cfg.margin_ns, min_gap)
+        # predictions by the means SK_j / SG_j instead of the medians
+        check_gapfill(prof, d_off, off, o_prof, hp, lp, cfg.margin_ns, cfg.min_gap_ns, predictor=binding.FIKIT_PREDICT_MEAN)
 
 
 def test_hand_worked_trace(golden_dir):
@@ -57,7 +59,8 @@ def test_hand_worked_trace(golden_dir):
     hp = np.array([0], dtype=np.uint32)
     lp = np.array([1], dtype=np.uint32)
     for exp in g["gapfill"]:
-        got = check_gapfill(prof, d_off, off, o_prof, hp, lp, exp["margin_ns"], exp["min_gap_ns"])
+        got = check_gapfill(prof, d_off, off, o_prof, hp, lp, exp["margin_ns"], exp["min_gap_ns"],
+                            predictor=exp.get("predictor", 0))
         assert binding.u32_to_numpy(got.fill_count).tolist() == exp["fill_count"]
         assert got.filled_ns.cpu().tolist() == exp["filled_ns"]
         assert int(got.lp_completion_ns[0]) == exp["lp_completion_ns"]
@@ -120,6 +123,7 @@ def test_many_scenarios_take_one_lane_each():
     for margin, min_gap in ((cfg.margin_ns, cfg.min_gap_ns), (0, 100000), (40000, 0)):
         print(f"{hp.size} scenarios, margin {margin}, min gap {min_gap}", flush=True)
         check_gapfill(prof, d_off, off, o_prof, hp, lp, margin, min_gap)
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, cfg.margin_ns, cfg.min_gap_ns, predictor=binding.FIKIT_PREDICT_MEAN)
 
 
 def test_many_scenarios_ragged_tasks_and_unaligned_outputs():

@@ -25,15 +25,15 @@ def check_measure(rec, off):
     return d_gp, gp
 
 
-def check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, margin, min_gap, out=None):
+def check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, margin, min_gap, out=None, predictor=0):
     o_ids, o_rows, o_tro = o_prof
     go = traces.gap_offsets(off, hp)
     d_hp, d_lp, d_go = binding.to_device_u32(hp, DEV), binding.to_device_u32(lp, DEV), binding.to_device_u64(go, DEV)
     for feedback in (False, True):
-        exp = oracle.replay(o_ids, off, o_rows, o_tro, gap, hp, lp, margin, min_gap, feedback, go)
+        exp = oracle.replay(o_ids, off, o_rows, o_tro, gap, hp, lp, margin, min_gap, feedback, go, predictor=predictor)
         got = binding.fikit_gapfill_replay(prof.ids, d_off, prof.rows, prof.task_row_offsets, d_gap, d_hp, d_lp, d_go,
                                            margin_ns=margin, min_gap_ns=min_gap, feedback=feedback,
-                                           n_gaps=int(go[-1]), out=out)
+                                           predictor=predictor, n_gaps=int(go[-1]), out=out)
         torch.cuda.synchronize()
         fc, fn = binding.u32_to_numpy(got.fill_count), got.filled_ns.cpu().numpy()
         bad = np.nonzero(fc != exp[0])[0]
@@ -103,6 +103,7 @@ def test_replay_many_scenarios():
     for margin, min_gap in ((cfg.margin_ns, cfg.min_gap_ns), (0, 100000), (40000, 0)):
         print(f"{hp.size} scenarios, margin {margin}, min gap {min_gap}", flush=True)
         check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, margin, min_gap)
+    check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, cfg.margin_ns, cfg.min_gap_ns, predictor=binding.FIKIT_PREDICT_MEAN)
 
 
 def test_replay_ragged_tasks_and_unaligned_outputs():
