@@ -51,15 +51,15 @@ constexpr int PRED_CHUNK = PRED_THREADS * PRED_KPT;
 constexpr int PRED_ROWS = 512;                    // rows of a task kept in an LDS hash table for the lookup
 constexpr int PRED_HT = 2 * PRED_ROWS;
 
-// Predicted execution time and idle time of a launch: p50 values of its ID's row.  Rows of a
-// task with few IDs sit in an LDS hash table keyed by the ID; otherwise the task's sorted rows
-// are searched in memory.
 // The prediction read from a row's statistics: median, or mean = sum / count (Section 3.2: SK_j, SG_j).
 __device__ __forceinline__ int64_t predicted_of(const fikit_stats& st, uint32_t predictor) {
   if (predictor == FIKIT_PREDICT_P50) return st.p50;
   return st.count ? static_cast<int64_t>(st.sum / st.count) : 0;
 }
 
+// Predicted execution time and idle time of a launch: taken from its ID's row.  Rows of a
+// task with few IDs sit in an LDS hash table keyed by the ID; otherwise the task's sorted rows
+// are searched in memory.
 struct PredTable {
   uint64_t key[PRED_HT];
   int64_t e[PRED_HT];
@@ -246,7 +246,15 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
     uint32_t my_c = 0;
     int64_t my_f = 0;
     const uint32_t steps = static_cast<uint32_t>(n_gaps - i0 < GW ? n_gaps - i0 : GW);
-    for (uint32_t k = 0; k < steps; ++k) {
+    uint32_t k = 0;
+    while (k < steps) {
+      // Gaps that the head of the queue does not fit into take nothing and change nothing: every lane tests
+      // its own gap against the head, and the group goes straight to the first gap that takes something.
+      const int64_t head = p < L ? pe[l0 + p] - consumed : INT64_MAX;
+      const bool takes = gl >= k && gl < steps && my_g >= min_gap && my_g >= margin && head <= my_g - margin;
+      const uint64_t tb = (ballot(takes) >> gbase) & gmask;
+      if (tb == 0) break;
+      k = static_cast<uint32_t>(__builtin_ctzll(tb));
       const int64_t G = static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(my_g), gbase + k));
       uint32_t c = 0;
       int64_t f = 0;
@@ -287,6 +295,7 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
         }
       }
       if (gl == k) { my_c = c; my_f = f; }
+      ++k;
     }
     if (mine < n_gaps) {
       fill_count[g0 + mine] = my_c;
