@@ -518,7 +518,7 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
                      d_task_row_offsets, role, glists, pe, pg, open, only_if_wide, static_cast<uint32_t>(h_params->predictor), ctrl);
 #ifndef FIKIT_WALK_GW
-#define FIKIT_WALK_GW 16
+#define FIKIT_WALK_GW 64
 #define FIKIT_WALK_WINDOW false
 #endif
   constexpr int GW = FIKIT_WALK_GW;
