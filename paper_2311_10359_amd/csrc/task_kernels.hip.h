@@ -84,6 +84,8 @@ struct Memo {
 
 // With ESTATS the sums, minima and maxima are gathered while the records are being read (per slot
 // of the ID table, since ranks are not known yet): the memory pipe is the busy one then, LDS is idle.
+constexpr int PRIV_IDS = 16, PRIV_COPIES = 32, PRIV_N = PRIV_IDS * PRIV_COPIES;
+
 template <int NT, int DMAX, int HIST_WORDS, bool ESTATS = false>
 struct FusedSmem {
   static constexpr int HT = 2 * DMAX;
@@ -101,7 +103,14 @@ struct FusedSmem {
   union {
     Memo<HT> memo;           // phase 1
     struct { uint64_t ckey[DMAX]; uint32_t cslot[DMAX]; } tmp;   // phase 2
-    struct { uint64_t esum[DMAX], gsum[DMAX]; uint32_t emin[DMAX], emax[DMAX], gmin[DMAX], gmax[DMAX]; } acc;  // phase 3
+    struct {
+      uint64_t esum[DMAX], gsum[DMAX]; uint32_t emin[DMAX], emax[DMAX], gmin[DMAX], gmax[DMAX];
+      // With few IDs many lanes would hit the same few addresses; every ID then gets PRIV_COPIES
+      // accumulators, one per lane modulo PRIV_COPIES (so that a wave's lanes fall on different banks),
+      // which are merged afterwards.
+      uint64_t p_esum[PRIV_N], p_gsum[PRIV_N];
+      uint32_t p_emin[PRIV_N], p_emax[PRIV_N], p_gmin[PRIV_N], p_gmax[PRIV_N], p_gcnt[PRIV_N];
+    } acc;  // phase 3
     uint32_t hist[HIST_WORDS];  // phase 4
   } u;
   uint32_t aux[NT / WAVE];
@@ -133,6 +142,15 @@ __device__ __forceinline__ uint32_t identity_tag(const uint32_t (&w)[8]) {
   t ^= t >> 13;
   return t | 1u;
 }
+
+// How the fast percentile path packs an (ID, array) pair's window into one word: the shift that turns a
+// value's offset from the window's low end into a bin number, then the bins that hold the two wanted ranks.
+constexpr int SEL_BINS_LOG2_MAX = 11;
+constexpr uint32_t SEL_SHIFT_MASK = 0x3fu, SEL_BIN_MASK = 0x1fffu, SEL_NO_BIN = SEL_BIN_MASK;   // "no samples"
+constexpr int SEL_B50_AT = 6, SEL_B95_AT = 19;
+__device__ __forceinline__ uint32_t sel_shift(uint32_t y) { return y & SEL_SHIFT_MASK; }
+__device__ __forceinline__ uint32_t sel_b50(uint32_t y) { return (y >> SEL_B50_AT) & SEL_BIN_MASK; }
+__device__ __forceinline__ uint32_t sel_b95(uint32_t y) { return (y >> SEL_B95_AT) & SEL_BIN_MASK; }
 
 // log2 of the number of bins the fast percentile path cuts an ID's value range into: about one bin
 // per WINDOW_SAMPLES_PER_BIN samples (the bin that holds a wanted rank is ranked directly afterwards), at least 2,
@@ -446,9 +464,9 @@ k_task_fused(const FusedArgs A) {
   int B = 31 - __builtin_clz(static_cast<uint32_t>(HIST_WORDS * 2) / (4 * D));
   B = B > 8 ? 8 : B;
   // the fast percentile path keeps one histogram per (ID, array) instead of four: its bins can be twice as fine
-  // (bin numbers must stay below 0xff, which marks "no samples")
-  int B1 = (static_cast<uint32_t>(HIST_WORDS * 2) >> (B + 1)) >= 2 * D ? B + 1 : B;
-  B1 = B1 > 7 ? 7 : B1;
+  // (as many bins as the 16-bit counters of 2 * D histograms leave room for, at most 2^SEL_BINS_LOG2_MAX)
+  int B1 = 31 - __builtin_clz(static_cast<uint32_t>(HIST_WORDS * 2) / (2 * D));
+  B1 = B1 > SEL_BINS_LOG2_MAX ? SEL_BINS_LOG2_MAX : B1;
 
   // ---- 2. rank the distinct IDs --------------------------------------------------------------
   {
@@ -481,6 +499,56 @@ k_task_fused(const FusedArgs A) {
 #pragma unroll
     for (int r = 0; r < KPT; ++r)
       if (r * NT + tid < m && gv[r] == NONE32) sm.last_rank = sl[r];
+  } else if (D <= static_cast<uint32_t>(PRIV_IDS)) {
+    // few IDs: lane-private accumulators, merged afterwards
+    const uint32_t np = D * PRIV_COPIES;
+    for (uint32_t q = tid; q < np; q += NT) {
+      sm.u.acc.p_esum[q] = 0; sm.u.acc.p_emin[q] = ~0u; sm.u.acc.p_emax[q] = 0;
+      sm.u.acc.p_gsum[q] = 0; sm.u.acc.p_gmin[q] = ~0u; sm.u.acc.p_gmax[q] = 0;
+      sm.u.acc.p_gcnt[q] = 0;
+    }
+    __syncthreads();
+    const uint32_t copy = lane_id() & (PRIV_COPIES - 1);
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+      const uint32_t i = r * NT + tid;
+      if (i < m) {
+        const uint32_t q = sl[r] * PRIV_COPIES + copy;
+        atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.p_esum[q]), static_cast<unsigned long long>(ev[r]));
+        atomicMin(&sm.u.acc.p_emin[q], ev[r]);
+        atomicMax(&sm.u.acc.p_emax[q], ev[r]);
+        if (gv[r] != NONE32) {
+          atomicAdd(&sm.u.acc.p_gcnt[q], 1u);
+          atomicAdd(reinterpret_cast<unsigned long long*>(&sm.u.acc.p_gsum[q]), static_cast<unsigned long long>(gv[r]));
+          atomicMin(&sm.u.acc.p_gmin[q], gv[r]);
+          atomicMax(&sm.u.acc.p_gmax[q], gv[r]);
+        }
+      }
+    }
+    __syncthreads();
+    // merge: PRIV_COPIES consecutive lanes hold the copies of one ID (trip count is the same for all lanes of a wave)
+    for (uint32_t q0 = 0; q0 < np; q0 += NT) {
+      const uint32_t q = q0 + tid;
+      const bool live = q < np;
+      uint64_t es = live ? sm.u.acc.p_esum[q] : 0, gs = live ? sm.u.acc.p_gsum[q] : 0;
+      uint32_t en = live ? sm.u.acc.p_emin[q] : ~0u, ex = live ? sm.u.acc.p_emax[q] : 0;
+      uint32_t gn = live ? sm.u.acc.p_gmin[q] : ~0u, gx = live ? sm.u.acc.p_gmax[q] : 0, gc = live ? sm.u.acc.p_gcnt[q] : 0;
+#pragma unroll
+      for (int mk = PRIV_COPIES / 2; mk >= 1; mk >>= 1) {
+        es += shfl_xor_u64(es, mk); gs += shfl_xor_u64(gs, mk);
+        const uint32_t en2 = __shfl_xor(en, mk, WAVE), ex2 = __shfl_xor(ex, mk, WAVE);
+        const uint32_t gn2 = __shfl_xor(gn, mk, WAVE), gx2 = __shfl_xor(gx, mk, WAVE);
+        en = en2 < en ? en2 : en; ex = ex2 > ex ? ex2 : ex;
+        gn = gn2 < gn ? gn2 : gn; gx = gx2 > gx ? gx2 : gx;
+        gc += __shfl_xor(gc, mk, WAVE);
+      }
+      if (live && (q & (PRIV_COPIES - 1)) == 0) {
+        const uint32_t j = q / PRIV_COPIES;
+        sm.u.acc.esum[j] = es; sm.u.acc.emin[j] = en; sm.u.acc.emax[j] = ex;
+        sm.u.acc.gsum[j] = gs; sm.u.acc.gmin[j] = gn; sm.u.acc.gmax[j] = gx;
+        sm.gcnt[j] = gc;
+      }
+    }
   } else {
     for (uint32_t j = tid; j < D; j += NT) {
       sm.u.acc.esum[j] = 0; sm.u.acc.emin[j] = ~0u; sm.u.acc.emax[j] = 0;
@@ -555,7 +623,7 @@ k_task_fused(const FusedArgs A) {
   // a short list and ranked directly.  If some bin is too crowded for that (many equal or
   // clustered samples), the general multi-pass radix selection below does the whole job instead.
   // Tables of earlier phases are dead by now and are reused:
-  uint2* sel = reinterpret_cast<uint2*>(sm.ht_key);            // [2][DMAX]: x = window low end, y = shift | bin50 << 8 | bin95 << 16
+  uint2* sel = reinterpret_cast<uint2*>(sm.ht_key);            // [2][DMAX]: x = window low end, y = shift | bin50 << 6 | bin95 << 19
   uint16_t* lcnt = reinterpret_cast<uint16_t*>(sm.ht_cnt);     // [2][2][DMAX]: list lengths (array, list A / B, ID)
   uint16_t* loff = reinterpret_cast<uint16_t*>(sm.memo_claim); // [2][2][DMAX]: list starts
   constexpr uint32_t LIST_MAX = 64;
@@ -594,7 +662,7 @@ k_task_fused(const FusedArgs A) {
       const uint32_t arr = (live && q >= D) ? 1u : 0u, j = live ? q - arr * D : 0u;
       const uint32_t k50 = sm.kth[2 * arr][j], k95 = sm.kth[2 * arr + 1][j];
       const uint32_t cnt_all = arr ? sm.gcnt[j] : sm.rcnt[j];
-      const uint32_t sh = live ? (sel[q].y & 0xffu) : 0u;
+      const uint32_t sh = live ? sel_shift(sel[q].y) : 0u;
       const uint32_t words = live ? (1u << window_bins_log2(cnt_all, B1)) >> 1 : 0u, wpl = (words + WG - 1) >> wg_log2;
       const uint32_t w_lo = gl * wpl < words ? gl * wpl : words, w_hi = w_lo + wpl < words ? w_lo + wpl : words;
       uint32_t mine = 0, incl = 0;
@@ -626,8 +694,8 @@ k_task_fused(const FusedArgs A) {
       }
       if (live && cnt_all == 0) {
         if (gl == 0) {
-          // no samples: both percentiles are 0, nothing to collect (bins 0xff never match a digit)
-          sel[q].y = sh | (0xffu << 8) | (0xffu << 16);
+          // no samples: both percentiles are 0, nothing to collect (SEL_NO_BIN never matches a bin number)
+          sel[q].y = sh | (SEL_NO_BIN << SEL_B50_AT) | (SEL_NO_BIN << SEL_B95_AT);
           lcnt[(2 * arr) * DMAX + j] = 0;
           lcnt[(2 * arr + 1) * DMAX + j] = 0;
         }
@@ -635,7 +703,7 @@ k_task_fused(const FusedArgs A) {
         // (bins one value wide, shift 0: the bin is the answer, nothing to collect)
         if (has50) {
           const uint32_t la = sh ? c50 : 0u;
-          atomicOr(&sel[q].y, bin50 << 8);
+          atomicOr(&sel[q].y, bin50 << SEL_B50_AT);
           lcnt[(2 * arr) * DMAX + j] = static_cast<uint16_t>(la);
           if (sh) sm.kth[2 * arr][j] = static_cast<uint16_t>(n50);
           if (la > LIST_MAX) atomicOr(&sm.fallback, 1u);
@@ -643,7 +711,7 @@ k_task_fused(const FusedArgs A) {
         if (has95) {
           // (the lower rank may lie in this bin too: then one list serves both)
           const uint32_t lb = (sh && !same_bin) ? c95 : 0u;
-          atomicOr(&sel[q].y, bin95 << 16);
+          atomicOr(&sel[q].y, bin95 << SEL_B95_AT);
           lcnt[(2 * arr + 1) * DMAX + j] = static_cast<uint16_t>(lb);
           if (sh) sm.kth[2 * arr + 1][j] = static_cast<uint16_t>(n95);
           if (lb > LIST_MAX) atomicOr(&sm.fallback, 1u);
@@ -682,17 +750,17 @@ k_task_fused(const FusedArgs A) {
           uint32_t j = sl[r];
           asm volatile("" : "+v"(j));
           const uint2 se = sel[j];
-          const uint32_t sh = se.y & 0xffu;
+          const uint32_t sh = sel_shift(se.y);
           if (sh) {
-            const uint32_t de = (ev[r] - se.x) >> sh, b50 = (se.y >> 8) & 0xffu, b95 = (se.y >> 16) & 0xffu;
+            const uint32_t de = (ev[r] - se.x) >> sh, b50 = sel_b50(se.y), b95 = sel_b95(se.y);
             if (de == b50) lists[loff[j] + atomicAdd(&cursor[4 * j], 1u)] = ev[r];
             else if (de == b95) lists[loff[DMAX + j] + atomicAdd(&cursor[4 * j + 1], 1u)] = ev[r];
           }
           if (gv[r] != NONE32) {
             const uint2 sg = sel[D + j];
-            const uint32_t shg = sg.y & 0xffu;
+            const uint32_t shg = sel_shift(sg.y);
             if (shg) {
-              const uint32_t dg = (gv[r] - sg.x) >> shg, b50 = (sg.y >> 8) & 0xffu, b95 = (sg.y >> 16) & 0xffu;
+              const uint32_t dg = (gv[r] - sg.x) >> shg, b50 = sel_b50(sg.y), b95 = sel_b95(sg.y);
               if (dg == b50) lists[loff[2 * DMAX + j] + atomicAdd(&cursor[4 * j + 2], 1u)] = gv[r];
               else if (dg == b95) lists[loff[3 * DMAX + j] + atomicAdd(&cursor[4 * j + 3], 1u)] = gv[r];
             }
@@ -707,12 +775,12 @@ k_task_fused(const FusedArgs A) {
       for (uint32_t q = tid / GS; q < P2; q += NT / GS) {
         const uint32_t arr = q >= D ? 1u : 0u, j = q - arr * D;
         const uint2 se = sel[q];
-        const uint32_t sh = se.y & 0xffu, b50 = (se.y >> 8) & 0xffu, b95 = (se.y >> 16) & 0xffu;
+        const uint32_t sh = sel_shift(se.y), b50 = sel_b50(se.y), b95 = sel_b95(se.y);
         uint64_t* row = staged_row(stage_a, stage_b, base, m, j);
-        if (b50 == 0xffu || sh == 0) {
+        if (b50 == SEL_NO_BIN || sh == 0) {
           if (gl == 0) {
-            row[arr ? 12 : 6] = b50 == 0xffu ? 0 : se.x + b50;
-            row[arr ? 13 : 7] = b50 == 0xffu ? 0 : se.x + b95;
+            row[arr ? 12 : 6] = b50 == SEL_NO_BIN ? 0 : se.x + b50;
+            row[arr ? 13 : 7] = b50 == SEL_NO_BIN ? 0 : se.x + b95;
           }
           continue;
         }
