@@ -99,7 +99,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg3", "cfg4"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--scenarios", type=int, default=None, help="cfg4 only: fewer scenarios (smoke runs)")
     ap.add_argument("--tasks", type=int, default=None, help="cfg1/cfg3 only: fewer tasks (smoke runs)")
     ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 1),
@@ -123,6 +123,10 @@ def main():
         cfg = traces.config(4, n_tasks=2 * args.scenarios if args.scenarios else None)
         sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 4096)
         name = "config 4: batched gap-fill"
+    elif args.workload == "cfg2":
+        cfg = traces.config(2, n_tasks=args.tasks)
+        sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 12)
+        name = "config 2: skewed IDs (profile only)"
     elif args.workload == "cfg3":
         cfg = traces.config(3, n_tasks=args.tasks)
         sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 48)
