@@ -173,6 +173,76 @@ def test_many_scenarios_with_predictions_beyond_32_bits():
     check_gapfill(prof, d_off, off, o_prof, hp, lp, 300, 0)
 
 
+def mixed_trace(seed, n_tasks, max_len=None, wide=True):
+    """Tasks of very different shapes side by side: every size class and its borders, from one ID to thousands,
+    smooth / constant / two-valued / heavy-tailed times, and a few times beyond 32 bits."""
+    rng = np.random.default_rng(seed)
+    len_choices = [0, 1, 2, 63, 64, 65, 500, 4095, 4096, 4097, 8191, 8192, 8193, 12000, 16383, 16384, 16385, 25000, 40000]
+    id_choices = [1, 2, 8, 15, 16, 17, 33, 100, 255, 256, 257, 511, 513, 3000]
+    if max_len is not None:
+        len_choices = [n for n in len_choices if n <= max_len]
+    lens = [int(rng.choice(len_choices)) for _ in range(n_tasks)]
+    total = sum(lens)
+    rec = np.zeros(total, dtype=traces.LAUNCH_DTYPE)
+    at = 0
+    for t, n in enumerate(lens):
+        if n == 0:
+            continue
+        k = int(rng.choice(id_choices))
+        kid = rng.integers(0, k, n)
+        style = int(rng.integers(0, 5 if wide else 4))
+        if style == 0:
+            ex = np.maximum(1, np.rint(rng.lognormal(np.log(20000), 0.8, n))).astype(np.int64)
+            gp = np.rint(rng.lognormal(np.log(8000), 1.0, n)).astype(np.int64)
+        elif style == 1:                                  # every sample of an ID identical
+            ex = 1000 + 7 * kid.astype(np.int64)
+            gp = 50 + (kid.astype(np.int64) % 3)
+        elif style == 2:                                  # two values, many ties
+            ex = np.where(rng.random(n) < 0.5, 10, 10_000_000).astype(np.int64)
+            gp = np.where(rng.random(n) < 0.9, 0, 123456).astype(np.int64)
+        elif style == 3:                                  # heavy tail around a tight cluster
+            ex = (5000 + rng.integers(0, 4, n) + np.where(rng.random(n) < 0.01, 1 << 30, 0)).astype(np.int64)
+            gp = rng.integers(0, 3, n).astype(np.int64)
+        else:                                             # beyond 32 bits now and then
+            ex = rng.integers(1, 100000, n).astype(np.int64) + np.where(rng.random(n) < 0.001, 1 << 33, 0)
+            gp = rng.integers(0, 100000, n).astype(np.int64) + np.where(rng.random(n) < 0.001, 1 << 34, 0)
+        sl = slice(at, at + n)
+        rec["name_id"][sl] = kid + 1000 * t
+        rec["grid"][sl, 0] = 1 + kid % 7
+        rec["grid"][sl, 1:] = 1
+        rec["block"][sl, 0] = 64
+        rec["block"][sl, 1:] = 1
+        start = np.cumsum(ex + gp) - (ex + gp)
+        rec["start_ns"][sl] = start
+        rec["end_ns"][sl] = start + ex
+        at += n
+    off = np.zeros(n_tasks + 1, dtype=np.uint64)
+    np.cumsum(lens, out=off[1:])
+    return rec, off, lens
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_mixed_task_shapes(seed):
+    rec, off, lens = mixed_trace(seed, 48)
+    print(f"seed {seed}: {rec.shape[0]} records, task lengths {lens[:16]} ...", flush=True)
+    prof, d_off, o_prof = check_profile(rec, off)
+    # every task against its successor, with the median and with the mean predictor
+    tasks = np.arange(len(lens), dtype=np.uint32)
+    hp, lp = tasks, np.roll(tasks, -1)
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 100, 0)
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 0, 2000, predictor=binding.FIKIT_PREDICT_MEAN)
+
+
+def test_mixed_task_shapes_many_scenarios():
+    """The same variety through the one-lane-per-scenario kernels: every ordered pair of 64 tasks."""
+    rec, off, lens = mixed_trace(21, 64, max_len=4097, wide=False)
+    print(f"{rec.shape[0]} records, task lengths {lens[:16]} ...", flush=True)
+    prof, d_off, o_prof = check_profile(rec, off)
+    hp, lp = all_pairs(range(len(lens)))
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 100, 0)
+    check_gapfill(prof, d_off, off, o_prof, hp, lp, 0, 2000, predictor=binding.FIKIT_PREDICT_MEAN)
+
+
 def test_all_distinct_ids_one_row_per_launch():
     n = 20000
     rec = np.zeros(n, dtype=traces.LAUNCH_DTYPE)

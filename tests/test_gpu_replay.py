@@ -10,7 +10,7 @@ import torch
 import oracle
 from paper_2311_10359_amd import binding, traces
 from parity_util import DEV, check_profile
-from test_gpu_parity import all_pairs, ragged_trace
+from test_gpu_parity import all_pairs, mixed_trace, ragged_trace
 from test_oracle_pins import replay_inputs
 
 pytestmark = pytest.mark.gpu
@@ -120,6 +120,15 @@ def test_replay_ragged_tasks_and_unaligned_outputs():
                          torch.empty(n_gaps + 1, dtype=torch.int64, device=DEV)[1:],
                          torch.empty(hp.size, dtype=torch.int64, device=DEV), torch.empty(hp.size, dtype=torch.int64, device=DEV))
     check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, 300, 0, out=out)
+
+
+def test_replay_mixed_task_shapes():
+    rec, off, lens = mixed_trace(22, 64, max_len=4097, wide=False)
+    prof, d_off, o_prof = check_profile(rec, off)
+    d_gap, gap = check_measure(rec, off)
+    hp, lp = all_pairs(range(len(lens)))
+    check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, 100, 0)
+    check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, 0, 2000, predictor=binding.FIKIT_PREDICT_MEAN)
 
 
 def test_replay_error_statuses():
