@@ -314,7 +314,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     if (int rc = scan_u32(hist, n_msd_tiles * 256, sums, nullptr, st)) return rc;
     tr.mark("plan");
     hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, &ctrl->n_class[0], static_cast<uint64_t>(4), 0u);   // the lists are reused for units
-    hipLaunchKernelGGL(k_msd_units, dim3(blocks_for(n_tasks, 64)), dim3(64), 0, st, d_task_offsets, n_tasks, is_long, mtiles, hist,
+    hipLaunchKernelGGL(k_msd_units, dim3(n_tasks), dim3(WAVE), 0, st, d_task_offsets, n_tasks, is_long, mtiles, hist,
                        ustart, ulen, utask, udcount, mflag, gflag, lists, static_cast<uint32_t>(n_units), ctrl);
     tr.mark("k_tile_scatter");
     hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets, n_tasks,

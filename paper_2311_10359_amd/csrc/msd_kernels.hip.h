@@ -89,16 +89,21 @@ k_hash_tiles(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ 
   H[static_cast<uint64_t>(tp) * 256 + static_cast<uint64_t>(threadIdx.x) * tiles_t + jl] = hist[threadIdx.x];
 }
 
-// One thread per long task: packs the task's ID buckets into units.  A task with a bucket of more
-// than FUSE_MAX launches keeps the general path (mflag 0); otherwise mflag 1 and gflag cleared.
-__global__ void k_msd_units(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ long_prefix,
-                            const uint32_t* __restrict__ tile_prefix, const uint32_t* __restrict__ Hs,
-                            uint32_t* __restrict__ ustart, uint32_t* __restrict__ ulen, uint32_t* __restrict__ utask,
-                            uint32_t* __restrict__ udcount, uint32_t* __restrict__ mflag, uint32_t* __restrict__ gflag,
-                            uint32_t* __restrict__ lists, uint32_t list_stride, Ctrl* ctrl) {
-  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+// One wave per task: packs a long task's ID buckets into units.  A task with a bucket of more than
+// FUSE_MAX launches keeps the general path (mflag 0); otherwise mflag 1 and gflag cleared.  The lanes
+// fetch the bucket boundaries together, one lane packs (a short sequential pass over at most 256
+// buckets in LDS), and the lanes together write the unused slots and the work lists.
+__global__ void __launch_bounds__(WAVE)
+k_msd_units(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ long_prefix,
+            const uint32_t* __restrict__ tile_prefix, const uint32_t* __restrict__ Hs,
+            uint32_t* __restrict__ ustart, uint32_t* __restrict__ ulen, uint32_t* __restrict__ utask,
+            uint32_t* __restrict__ udcount, uint32_t* __restrict__ mflag, uint32_t* __restrict__ gflag,
+            uint32_t* __restrict__ lists, uint32_t list_stride, Ctrl* ctrl) {
+  __shared__ uint32_t bstart[MSD_SLOTS + 1];   // where each bucket starts inside the task
+  __shared__ uint32_t n_used, all_fit;
+  const uint32_t t = blockIdx.x, lane = threadIdx.x;
   if (t >= n_tasks) return;
-  mflag[t] = 0;
+  if (lane == 0) mflag[t] = 0;
   if (long_prefix[t + 1] == long_prefix[t]) return;   // not a long task
   const uint32_t o = long_prefix[t];
   const uint64_t task_start = off[t], len = off[t + 1] - task_start;
@@ -106,41 +111,49 @@ __global__ void k_msd_units(const uint64_t* __restrict__ off, uint32_t n_tasks, 
   const uint32_t tp = tile_prefix[t], tiles_t = tile_prefix[t + 1] - tp;
   const uint64_t hbase = static_cast<uint64_t>(tp) * 256;
   const uint32_t h0 = Hs[hbase];
-  uint32_t u = o * MSD_SLOTS;
-  const uint32_t u_end = u + MSD_SLOTS;
-  bool ok = true;
-  uint32_t cur_start = 0, cur_len = 0, rel = 0;
-  for (uint32_t d = 0; d < nb; ++d) {
-    const uint32_t next = (d + 1 < nb) ? Hs[hbase + static_cast<uint64_t>(d + 1) * tiles_t] - h0 : static_cast<uint32_t>(len);
-    const uint32_t sz = next - rel;
-    if (sz > FUSE_MAX) ok = false;
-    if (cur_len > 0 && cur_len + sz > FUSE_MID_MAX) {
-      ustart[u] = static_cast<uint32_t>(task_start) + cur_start; ulen[u] = cur_len; utask[u] = static_cast<uint32_t>(t); udcount[u] = 0;
+  for (uint32_t d = lane; d <= nb; d += WAVE)
+    bstart[d] = d < nb ? Hs[hbase + static_cast<uint64_t>(d) * tiles_t] - h0 : static_cast<uint32_t>(len);
+  __syncthreads();
+  const uint32_t u0 = o * MSD_SLOTS;
+  if (lane == 0) {
+    uint32_t u = u0;
+    bool ok = true;
+    uint32_t cur_start = 0, cur_len = 0;
+    for (uint32_t d = 0; d < nb; ++d) {
+      const uint32_t rel = bstart[d], sz = bstart[d + 1] - rel;
+      if (sz > FUSE_MAX) ok = false;
+      if (cur_len > 0 && cur_len + sz > FUSE_MID_MAX) {
+        ustart[u] = static_cast<uint32_t>(task_start) + cur_start; ulen[u] = cur_len;
+        ++u;
+        cur_start = rel;
+        cur_len = 0;
+      }
+      cur_len += sz;
+    }
+    if (cur_len > 0) {
+      ustart[u] = static_cast<uint32_t>(task_start) + cur_start; ulen[u] = cur_len;
       ++u;
-      cur_start = rel;
-      cur_len = 0;
     }
-    cur_len += sz;
-    rel = next;
+    n_used = u - u0;
+    all_fit = ok ? 1u : 0u;
+    if (ok) {
+      mflag[t] = 1;
+      gflag[t] = 0;
+      atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), ~0ull);   // one general task fewer
+    }
   }
-  if (cur_len > 0) {
-    ustart[u] = static_cast<uint32_t>(task_start) + cur_start; ulen[u] = cur_len; utask[u] = static_cast<uint32_t>(t); udcount[u] = 0;
-    ++u;
-  }
-  for (; u < u_end; ++u) { ustart[u] = 0; ulen[u] = 0; utask[u] = static_cast<uint32_t>(t); udcount[u] = 0; }
-  if (ok) {
-    mflag[t] = 1;
-    gflag[t] = 0;
-    atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), ~0ull);   // one general task fewer
+  __syncthreads();   // (also makes lane 0's unit entries visible to the other lanes)
+  const uint32_t used = all_fit ? n_used : 0;
+  for (uint32_t k = lane; k < MSD_SLOTS; k += WAVE) {
+    const uint32_t u = u0 + k;
+    utask[u] = t;
+    udcount[u] = 0;
+    if (k >= used) { ustart[u] = 0; ulen[u] = 0; continue; }
     // work lists of units by size class (see k_classify)
-    for (u = o * MSD_SLOTS; u < u_end; ++u) {
-      const uint32_t l = ulen[u];
-      if (l == 0) continue;
-      const uint32_t c = l <= FUSE_SMALL_MAX ? 0u : (l <= FUSE_MID_MAX ? 1u : 2u);
-      lists[static_cast<uint64_t>(c) * list_stride + atomicAdd(&ctrl->n_class[c], 1u)] = u;
-    }
-  } else {
-    for (u = o * MSD_SLOTS; u < u_end; ++u) ulen[u] = 0;
+    const uint32_t l = ulen[u];
+    if (l == 0) continue;
+    const uint32_t c = l <= FUSE_SMALL_MAX ? 0u : (l <= FUSE_MID_MAX ? 1u : 2u);
+    lists[static_cast<uint64_t>(c) * list_stride + atomicAdd(&ctrl->n_class[c], 1u)] = u;
   }
 }
 
