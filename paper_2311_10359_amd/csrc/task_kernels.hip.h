@@ -464,8 +464,9 @@ k_task_fused(const FusedArgs A) {
   int B = 31 - __builtin_clz(static_cast<uint32_t>(HIST_WORDS * 2) / (4 * D));
   B = B > 8 ? 8 : B;
   // the fast percentile path keeps one histogram per (ID, array) instead of four: its bins can be twice as fine
-  // (as many bins as the 16-bit counters of 2 * D histograms leave room for, at most 2^SEL_BINS_LOG2_MAX)
-  int B1 = 31 - __builtin_clz(static_cast<uint32_t>(HIST_WORDS * 2) / (2 * D));
+  // (as many bins as the 16-bit counters of 2 * D histograms leave room for, at most 2^SEL_BINS_LOG2_MAX; a row of
+  // the histogram array holds one word, two bins, of every histogram and is 2 * D words long made odd)
+  int B1 = 32 - __builtin_clz(static_cast<uint32_t>(HIST_WORDS) / ((2 * D) | 1u));
   B1 = B1 > SEL_BINS_LOG2_MAX ? SEL_BINS_LOG2_MAX : B1;
 
   // ---- 2. rank the distinct IDs --------------------------------------------------------------
@@ -629,6 +630,7 @@ k_task_fused(const FusedArgs A) {
   constexpr uint32_t LIST_MAX = 64;
   const uint32_t bins = 1u << B;
   const uint32_t P2 = 2 * D;   // (ID, array) pairs
+  const uint32_t PS = P2 | 1u;  // row stride of the histogram array: odd, so that rows start on different LDS banks
   for (uint32_t i = tid; i < HIST_WORDS; i += NT) sm.u.hist[i] = 0;
   if (tid == 0) sm.fallback = 0;
   __syncthreads();
@@ -640,21 +642,22 @@ k_task_fused(const FusedArgs A) {
       asm volatile("" : "+v"(j));
       const uint2 se = sel[j];
       const uint32_t de = (ev[r] - se.x) >> se.y;
-      atomicAdd(&sm.u.hist[__umul24(de >> 1, P2) + j], (de & 1u) ? 0x10000u : 1u);
+      atomicAdd(&sm.u.hist[__umul24(de >> 1, PS) + j], (de & 1u) ? 0x10000u : 1u);
       if (gv[r] != NONE32) {
         const uint2 sg = sel[D + j];
         const uint32_t dg = (gv[r] - sg.x) >> sg.y;
-        atomicAdd(&sm.u.hist[__umul24(dg >> 1, P2) + D + j], (dg & 1u) ? 0x10000u : 1u);
+        atomicAdd(&sm.u.hist[__umul24(dg >> 1, PS) + D + j], (dg & 1u) ? 0x10000u : 1u);
       }
     }
   }
   __syncthreads();
   {
-    // 1, 2, 4 or 8 lanes per (ID, array), as many as there are threads for: each sums its slice of the
+    // 1, 2, 4 ... 64 lanes per (ID, array), as many as there are threads for: each sums its slice of the
     // pair's bins, a prefix sum over the slices tells which lane's slice holds each wanted rank, and
-    // that lane finds the bin.  (Groups of lanes are aligned inside the rows of 16 lanes.)
+    // that lane finds the bin.
     const uint32_t per = static_cast<uint32_t>(NT) / P2;
-    const uint32_t wg_log2 = per >= 8 ? 3u : (per >= 4 ? 2u : (per >= 2 ? 1u : 0u)), WG = 1u << wg_log2;
+    const uint32_t per_log2 = 31u - __builtin_clz(per | 1u);
+    const uint32_t wg_log2 = per_log2 > 6u ? 6u : per_log2, WG = 1u << wg_log2;
     const uint32_t gl = tid & (WG - 1);
     for (uint32_t q0 = 0; q0 < P2; q0 += NT >> wg_log2) {   // (trip count is the same for all lanes of a wave)
       const uint32_t q = q0 + (tid >> wg_log2);
@@ -663,26 +666,26 @@ k_task_fused(const FusedArgs A) {
       const uint32_t k50 = sm.kth[2 * arr][j], k95 = sm.kth[2 * arr + 1][j];
       const uint32_t cnt_all = arr ? sm.gcnt[j] : sm.rcnt[j];
       const uint32_t sh = live ? sel_shift(sel[q].y) : 0u;
-      const uint32_t words = live ? (1u << window_bins_log2(cnt_all, B1)) >> 1 : 0u, wpl = (words + WG - 1) >> wg_log2;
+      const uint32_t words = live ? (1u << window_bins_log2(cnt_all, B1)) >> 1 : 0u, wpl = ((words + WG - 1) >> wg_log2) | 1u;   // (odd: the lanes' slices start on different banks)
       const uint32_t w_lo = gl * wpl < words ? gl * wpl : words, w_hi = w_lo + wpl < words ? w_lo + wpl : words;
       uint32_t mine = 0, incl = 0;
       if (WG > 1) {
         for (uint32_t w = w_lo; w < w_hi; ++w) {
-          const uint32_t pair = sm.u.hist[w * P2 + q];
+          const uint32_t pair = sm.u.hist[w * PS + q];
           mine += (pair & 0xffffu) + (pair >> 16);
         }
-        uint32_t up;
-        incl = mine;
-        up = dpp_or_zero<0x111, 0xf>(incl); incl += gl >= 1 ? up : 0u;
-        if (WG > 2) { up = dpp_or_zero<0x112, 0xf>(incl); incl += gl >= 2 ? up : 0u; }
-        if (WG > 4) { up = dpp_or_zero<0x114, 0xf>(incl); incl += gl >= 4 ? up : 0u; }
+        // prefix over the group's lanes: a prefix over the wave, minus what precedes the group
+        const uint32_t wave_incl = wave_incl_scan_u32(mine);
+        const uint32_t first = lane_id() - gl;
+        const uint32_t before_group = __shfl(wave_incl, first > 0 ? static_cast<int>(first) - 1 : 0, WAVE);
+        incl = wave_incl - (first > 0 ? before_group : 0u);
       }
       // bins of this lane's slice that hold the wanted ranks (if any): bin number, rank inside it, its count
       uint32_t cum = incl - mine, bin50 = 0, n50 = 0, c50 = 0, bin95 = 0, n95 = 0, c95 = 0;
       bool has50 = false, has95 = false, same_bin = false;
       for (uint32_t w = w_lo; w < w_hi; ++w) {
-        const uint32_t pair = sm.u.hist[w * P2 + q];
-        sm.u.hist[w * P2 + q] = 0;
+        const uint32_t pair = sm.u.hist[w * PS + q];
+        sm.u.hist[w * PS + q] = 0;
 #pragma unroll
         for (uint32_t h = 0; h < 2; ++h) {
           const uint32_t c = h ? pair >> 16 : pair & 0xffffu;
