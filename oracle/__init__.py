@@ -64,6 +64,9 @@ def _load():
         lib.oracle_replay.restype = ctypes.c_int
         lib.oracle_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, i64, i64, ctypes.c_int, vp, vp, vp,
                                       vp, vp, ctypes.c_int]
+        lib.oracle_prio_fill.restype = ctypes.c_int
+        lib.oracle_prio_fill.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, vp, u64, i64, i64, ctypes.c_int, vp, vp, vp,
+                                         vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -177,3 +180,45 @@ def replay(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_row
     if st != OK:
         raise OracleError(st)
     return fill_count, filled_ns, delay, placed
+
+
+def prio_fill(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_row_offsets: np.ndarray,
+              hp_task: np.ndarray, lp_offsets: np.ndarray, lp_task: np.ndarray, lp_prio: np.ndarray, margin_ns: int,
+              min_gap_ns: int, gap_offsets: np.ndarray, predictor: int = 0, want_issue: bool = False):
+    """Several low-priority tasks per scenario (entries lp_offsets[s]..lp_offsets[s+1] of lp_task / lp_prio).
+    -> (fill_count, filled_ns, lp_placed[entries], lp_placed_ns[entries][, issue_entry, issue_offsets])."""
+    ids = np.ascontiguousarray(ids, dtype=np.uint64)
+    task_offsets = np.ascontiguousarray(task_offsets, dtype=np.uint64)
+    rows = np.ascontiguousarray(rows)
+    assert rows.dtype.itemsize == 128
+    tro = np.ascontiguousarray(task_row_offsets, dtype=np.uint64)
+    hp = np.ascontiguousarray(hp_task, dtype=np.uint32)
+    lo = np.ascontiguousarray(lp_offsets, dtype=np.uint64)
+    lt = np.ascontiguousarray(lp_task, dtype=np.uint32)
+    lq = np.ascontiguousarray(lp_prio, dtype=np.uint32)
+    go = np.ascontiguousarray(gap_offsets, dtype=np.uint64)
+    s = hp.shape[0]
+    assert lo.shape[0] == s + 1 and lt.shape[0] == lq.shape[0]
+    n_gaps = int(go[-1]) if s else 0
+    n_entries = lt.shape[0]
+    fill_count = np.zeros(n_gaps, dtype=np.uint32)
+    filled_ns = np.zeros(n_gaps, dtype=np.int64)
+    placed = np.zeros(n_entries, dtype=np.uint64)
+    placed_ns = np.zeros(n_entries, dtype=np.int64)
+    issue = issue_off = None
+    if want_issue:
+        lens = (task_offsets[1:] - task_offsets[:-1])[lt.astype(np.int64)] if n_entries else np.zeros(0, np.uint64)
+        per_scen = np.zeros(s, dtype=np.uint64)
+        for k in range(s):
+            per_scen[k] = lens[int(lo[k]):int(lo[k + 1])].sum()
+        issue_off = np.zeros(s + 1, dtype=np.uint64)
+        np.cumsum(per_scen, out=issue_off[1:])
+        issue = np.full(int(issue_off[-1]), 0xffffffff, dtype=np.uint32)
+    st = _load().oracle_prio_fill(_p(ids), _p(task_offsets), task_offsets.shape[0] - 1, _p(rows), _p(tro), _p(hp), _p(lo),
+                                  _p(lt), _p(lq), s, margin_ns, min_gap_ns, predictor, _p(go), _p(fill_count),
+                                  _p(filled_ns), _p(placed), _p(placed_ns), _p(issue_off), _p(issue))
+    if st != OK:
+        raise OracleError(st)
+    if want_issue:
+        return fill_count, filled_ns, placed, placed_ns, issue, issue_off
+    return fill_count, filled_ns, placed, placed_ns

@@ -33,6 +33,11 @@
 //                       actual gap delays the high-priority task (overhead 1); with feedback the
 //                       controller stops issuing once the next high-priority request has
 //                       arrived, and only the kernel already issued can run over (overhead 2).
+//   oracle_prio_fill  - Algorithm 1 with the full Algorithm 2 (BestPrioFit): several low-priority
+//                       tasks wait in the priority queues Q1..Q9, each with one request at a time
+//                       (its next kernel); per gap the procedure keeps taking, from the highest
+//                       priority level that has a request that fits, the request that fits best
+//                       (the longest), until nothing fits.
 //
 // All quantities are integers (nanoseconds, counts); nothing is floating point.
 
@@ -380,6 +385,111 @@ int oracle_replay(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n_
     }
     hp_delay_ns[s] = delay;
     lp_placed[s] = p;
+  }
+  return OK;
+}
+
+
+// Gap filling with several low-priority tasks (Algorithm 1 calling Algorithm 2, BestPrioFit).
+//
+// Scenario s: high-priority task hp_task[s] holds the GPU; its low-priority tasks are the entries
+// lp_offsets[s] .. lp_offsets[s+1] of lp_task / lp_prio (priority level 1..9, 1 the highest after the
+// high-priority task's own level 0).  Every low-priority task has one waiting request at a time, its
+// next kernel; when that is issued, the task's following kernel is enqueued.  For every predicted gap
+// that is not skipped (as in oracle_gapfill), with r = gap - margin left:
+//   scan the levels from 1 to 9; at the first level that has a waiting request whose predicted
+//   duration is <= r, take the one with the longest duration among those (the one closest to r);
+//   among equally long ones the one that was enqueued first (the initial requests count as enqueued
+//   in the order of the scenario's list); issue it, r -= duration, and scan again from level 1;
+//   the gap is done when no level has a request that fits.
+// Outputs: per gap the number of kernels issued and their total predicted duration; per
+// low-priority entry the number of its kernels issued into gaps and their total predicted duration;
+// optionally (issue_offsets[S+1], issue_entry) the entry index (0-based inside the scenario) of every
+// issued kernel in issue order.
+int oracle_prio_fill(const uint64_t* ids, const uint64_t* task_offsets, uint32_t n_tasks, const void* rows_v,
+                     const uint64_t* task_row_offsets, const uint32_t* hp_task, const uint64_t* lp_offsets,
+                     const uint32_t* lp_task, const uint32_t* lp_prio, uint64_t n_scenarios, int64_t margin_ns,
+                     int64_t min_gap_ns, int predictor, const uint64_t* gap_offsets, uint32_t* fill_count,
+                     int64_t* filled_ns, uint64_t* lp_placed, int64_t* lp_placed_ns,
+                     const uint64_t* issue_offsets, uint32_t* issue_entry) {
+  const Row* rows = static_cast<const Row*>(rows_v);
+  if (!task_offsets || !task_row_offsets) return INVALID_ARG;
+  if (n_scenarios && (!hp_task || !lp_offsets || !gap_offsets)) return INVALID_ARG;
+  if (margin_ns < 0 || min_gap_ns < 0 || predictor < 0 || predictor > 1) return INVALID_ARG;
+  if (n_scenarios && lp_offsets[0] != 0) return INVALID_ARG;
+
+  for (uint64_t s = 0; s < n_scenarios; ++s) {
+    const uint32_t hp = hp_task[s];
+    if (hp >= n_tasks || lp_offsets[s + 1] < lp_offsets[s]) return INVALID_ARG;
+    const uint64_t e0 = lp_offsets[s], K = lp_offsets[s + 1] - e0;
+    std::map<uint64_t, const Row*> hp_rows;
+    for (uint64_t r = task_row_offsets[hp]; r < task_row_offsets[hp + 1]; ++r) hp_rows[rows[r].kernel_id] = &rows[r];
+
+    // the waiting queue of every low-priority task: predicted durations of its kernels, in launch order
+    std::vector<std::vector<int64_t>> D(K);
+    std::vector<uint64_t> next(K, 0);    // next kernel of task k to issue
+    std::vector<uint64_t> stamp(K);      // when the waiting request of task k was enqueued
+    for (uint64_t k = 0; k < K; ++k) {
+      const uint32_t lp = lp_task[e0 + k];
+      if (lp >= n_tasks || lp_prio[e0 + k] < 1 || lp_prio[e0 + k] > 9) return INVALID_ARG;
+      std::map<uint64_t, const Row*> lp_rows;
+      for (uint64_t r = task_row_offsets[lp]; r < task_row_offsets[lp + 1]; ++r) lp_rows[rows[r].kernel_id] = &rows[r];
+      const uint64_t l0 = task_offsets[lp], L = task_offsets[lp + 1] - l0;
+      D[k].resize(L);
+      for (uint64_t j = 0; j < L; ++j) {
+        auto it = lp_rows.find(ids[l0 + j]);
+        if (it == lp_rows.end()) return UNKNOWN_ID;
+        D[k][j] = predicted(it->second->exec, predictor);
+      }
+      stamp[k] = k;
+      lp_placed[e0 + k] = 0;
+      lp_placed_ns[e0 + k] = 0;
+    }
+    uint64_t clock = K;   // enqueue stamps handed out so far
+    uint64_t issued = 0;
+
+    const uint64_t h0 = task_offsets[hp], H = task_offsets[hp + 1] - h0;
+    const uint64_t g0 = gap_offsets[s];
+    for (uint64_t i = 0; i < H; ++i) {
+      auto it = hp_rows.find(ids[h0 + i]);
+      if (it == hp_rows.end()) return UNKNOWN_ID;
+      if (i + 1 == H) break;  // no gap after the last launch
+      const int64_t G = predicted(it->second->gap, predictor);
+      uint32_t c = 0;
+      int64_t f = 0;
+      if (G >= min_gap_ns && G >= margin_ns) {
+        int64_t r = G - margin_ns;
+        for (;;) {
+          // BestPrioFit: the highest level with a request that fits; there the longest; then the oldest
+          bool found = false;
+          uint64_t best = 0;
+          for (uint32_t level = 1; level <= 9 && !found; ++level) {
+            for (uint64_t k = 0; k < K; ++k) {
+              if (lp_prio[e0 + k] != level || next[k] >= D[k].size()) continue;
+              const int64_t d = D[k][next[k]];
+              if (d > r) continue;
+              if (!found || d > D[best][next[best]] || (d == D[best][next[best]] && stamp[k] < stamp[best])) {
+                found = true;
+                best = k;
+              }
+            }
+          }
+          if (!found) break;
+          const int64_t d = D[best][next[best]];
+          r -= d;
+          f += d;
+          ++c;
+          ++next[best];
+          stamp[best] = clock++;   // the task's following kernel is enqueued now
+          lp_placed[e0 + best] += 1;
+          lp_placed_ns[e0 + best] += d;
+          if (issue_entry) issue_entry[issue_offsets[s] + issued] = static_cast<uint32_t>(best);
+          ++issued;
+        }
+      }
+      fill_count[g0 + i] = c;
+      filled_ns[g0 + i] = f;
+    }
   }
   return OK;
 }

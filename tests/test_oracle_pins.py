@@ -8,6 +8,9 @@ P4  brute-force enumeration of every first-in-first-out schedule on tiny traces.
 P5  special cases that reduce to library routines (numpy.sort, numpy.unique) or closed forms.
 P6  per-launch measurement and the replay against actual idle times: hand-worked example
     (tests/golden/p6_replay_hand_worked.json), ties to the pinned gap fill, closed form by prefix sums.
+P7  several low-priority tasks in priority queues (BestPrioFit): hand-worked cases after the paper's own example
+    (tests/golden/p7_prio_fill_hand_worked.json), the one-task case against the pinned gap fill, and every
+    decision of the issue log checked against the rule written as a sort key.
 """
 import itertools
 import json
@@ -611,6 +614,116 @@ def test_p6_replay_ties(cfg):
                 if c:
                     assert int(fn4[int(go[s]) + g]) - D[p + c - 1] < int(gap[h0 + g])
                 p += c
+
+
+# ---------------------------------------------------------------- P7
+def prio_inputs(hp_launches, hp_gap, lp):
+    """Rows and IDs for one high-priority task (one kernel, predicted idle time hp_gap) and the given low-priority
+    tasks (one kernel ID per distinct duration of a task)."""
+    ids, off, rows, tro = [1] * hp_launches, [0, hp_launches], [], [0]
+    rows.append((1, 0, 7, hp_gap))
+    tro.append(1)
+    for t, task in enumerate(lp, start=1):
+        durs = sorted(set(task["durations"]))
+        for d in durs:
+            rows.append((1000 * t + durs.index(d), t, d, 1))
+        ids += [1000 * t + durs.index(d) for d in task["durations"]]
+        off.append(len(ids))
+        tro.append(len(rows))
+    r = np.zeros(len(rows), dtype=oracle.ROW_DTYPE)
+    for k, (kid, task, e, g) in enumerate(rows):
+        r[k]["kernel_id"], r[k]["task"] = kid, task
+        r[k]["exec"]["p50"], r[k]["gap"]["p50"] = e, g
+    lp_task = np.arange(1, len(lp) + 1, dtype=np.uint32)
+    lp_prio = np.array([task["prio"] for task in lp], dtype=np.uint32)
+    return (np.array(ids, dtype=np.uint64), np.array(off, dtype=np.uint64), r, np.array(tro, dtype=np.uint64),
+            np.array([0], dtype=np.uint32), np.array([0, len(lp)], dtype=np.uint64), lp_task, lp_prio)
+
+
+@pytest.mark.parametrize("case", ["abc", "equal_priority", "longest_fit"])
+def test_p7_prio_fill_hand_worked(golden_dir, case):
+    with open(os.path.join(golden_dir, "p7_prio_fill_hand_worked.json")) as f:
+        golden = json.load(f)
+    exp = golden["cases"][case]
+    ids, off, rows, tro, hp, lo, lt, lq = prio_inputs(golden["hp_launches"], golden["hp_gap"], exp["lp"])
+    go = traces.gap_offsets(off, hp)
+    fc, fn, placed, placed_ns, issue, ioff = oracle.prio_fill(ids, off, rows, tro, hp, lo, lt, lq, 0, 0, go, want_issue=True)
+    assert fc.tolist() == exp["fill_count"] and fn.tolist() == exp["filled_ns"]
+    assert placed.tolist() == exp["lp_placed"] and placed_ns.tolist() == exp["lp_placed_ns"]
+    assert issue[: int(placed.sum())].tolist() == exp["issue_entry"]
+
+
+def random_prio_scenarios(cfg, rng, n_scen, max_lp=4):
+    hp = rng.integers(0, cfg.n_tasks, n_scen).astype(np.uint32)
+    k = rng.integers(0, max_lp + 1, n_scen)
+    lo = np.zeros(n_scen + 1, dtype=np.uint64)
+    np.cumsum(k, out=lo[1:])
+    lt = rng.integers(0, cfg.n_tasks, int(lo[-1])).astype(np.uint32)
+    lq = rng.integers(1, 10, int(lo[-1])).astype(np.uint32)
+    lq[rng.random(lq.shape[0]) < 0.5] = 4      # plenty of equal priorities
+    return hp, lo, lt, lq
+
+
+@pytest.mark.parametrize("cfg", small_configs(), ids=lambda c: c.name)
+def test_p7_prio_fill_ties_and_rule(cfg):
+    rec, off = traces.build(cfg)
+    ids, rows, tro = oracle.profile(rec, off)
+    rng = np.random.default_rng(77)
+    # one low-priority task: the gap fill itself, whatever the level
+    hp, lp = traces.scenarios(cfg)
+    if hp.size:
+        go = traces.gap_offsets(off, hp)
+        ref = oracle.gapfill(ids, off, rows, tro, hp, lp, cfg.margin_ns, 0, go)
+        lo = np.arange(hp.size + 1, dtype=np.uint64)
+        got = oracle.prio_fill(ids, off, rows, tro, hp, lo, lp, rng.integers(1, 10, hp.size).astype(np.uint32),
+                               cfg.margin_ns, 0, go)
+        assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1]) and np.array_equal(got[2], ref[3])
+    # several: replay the issue log and check every decision against the rule written as a sort key
+    hp, lo, lt, lq = random_prio_scenarios(cfg, rng, 12)
+    go = traces.gap_offsets(off, hp)
+    margin, min_gap = cfg.margin_ns, 3000
+    fc, fn, placed, placed_ns, issue, ioff = oracle.prio_fill(ids, off, rows, tro, hp, lo, lt, lq, margin, min_gap, go,
+                                                             want_issue=True)
+    for s in range(hp.size):
+        e0, K = int(lo[s]), int(lo[s + 1] - lo[s])
+        h0, H = int(off[hp[s]]), int(off[hp[s] + 1] - off[hp[s]])
+        lut_g = {int(r["kernel_id"]): int(r["gap"]["p50"]) for r in rows[int(tro[hp[s]]):int(tro[hp[s] + 1])]}
+        D = []
+        for k in range(K):
+            t = int(lt[e0 + k])
+            lut_e = {int(r["kernel_id"]): int(r["exec"]["p50"]) for r in rows[int(tro[t]):int(tro[t + 1])]}
+            D.append([lut_e[int(i)] for i in ids[int(off[t]):int(off[t + 1])]])
+        nxt, stamp, clock, at = [0] * K, list(range(K)), K, int(ioff[s])
+        count = [0] * K
+        for g in range(max(H - 1, 0)):
+            G = lut_g[int(ids[h0 + g])]
+            c = f = 0
+            if G >= min_gap and G >= margin:
+                r = G - margin
+                while True:
+                    cand = sorted((int(lq[e0 + k]), -D[k][nxt[k]], stamp[k], k) for k in range(K)
+                                  if nxt[k] < len(D[k]) and D[k][nxt[k]] <= r)
+                    if not cand:
+                        break
+                    k = cand[0][3]
+                    assert int(issue[at]) == k, (s, g)
+                    at += 1
+                    r -= D[k][nxt[k]]
+                    f += D[k][nxt[k]]
+                    c += 1
+                    nxt[k] += 1
+                    count[k] += 1
+                    stamp[k] = clock
+                    clock += 1
+            assert int(fc[int(go[s]) + g]) == c and int(fn[int(go[s]) + g]) == f, (s, g)
+        assert [int(x) for x in placed[e0:e0 + K]] == count
+        assert at - int(ioff[s]) == sum(count)
+    # argument errors
+    for bad_prio in (0, 10):
+        with pytest.raises(oracle.OracleError) as e:
+            oracle.prio_fill(ids, off, rows, tro, hp[:1], np.array([0, 1], dtype=np.uint64), np.array([0], dtype=np.uint32),
+                             np.array([bad_prio], dtype=np.uint32), 0, 0, traces.gap_offsets(off, hp[:1]))
+        assert e.value.status == oracle.INVALID_ARG
 
 
 def test_oracle_error_statuses():
