@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--replay", action="store_true",
                     help="after the timed steps, also time fikit_measure and fikit_gapfill_replay (reported beside "
                          "the metric, not part of it)")
+    ap.add_argument("--prio", type=int, default=0, metavar="K",
+                    help="after the timed steps, also time fikit_prio_fill with K low-priority tasks per scenario "
+                         "(reported beside the metric, not part of it)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware counter runs)")
     args = ap.parse_args()
@@ -285,6 +288,36 @@ def main():
         log(f"[bench] replay: {json.dumps(replay)}")
         del d_exec, d_gap
 
+    # ---- several low-priority tasks per scenario in priority queues (beside the metric) ----------
+    prio = None
+    if args.prio > 0 and n_scen:
+        _, p_lo, p_lt, p_lq = traces.prio_scenarios(cfg, args.prio)
+        d_plo, d_plt, d_plq = binding.to_device_u64(p_lo, dev), binding.to_device_u32(p_lt, dev), binding.to_device_u32(p_lq, dev)
+        pf_out = binding.PrioFill(gf_out.fill_count, gf_out.filled_ns, torch.empty(p_lt.size, dtype=torch.int64, device=dev),
+                                  torch.empty(p_lt.size, dtype=torch.int64, device=dev))
+
+        def prio_call():
+            binding.fikit_prio_fill(ids, d_off, prof.rows, tro, d_hp, d_plo, d_plt, d_plq, d_go, margin_ns=cfg.margin_ns,
+                                    min_gap_ns=cfg.min_gap_ns, n_gaps=n_gaps, n_ids=n, out=pf_out, workspace_buf=ws)
+
+        prio_call()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        binding.fikit_trace_enable(True)
+        ev[0].record()
+        for _ in range(args.steps):
+            prio_call()
+        ev[1].record()
+        torch.cuda.synchronize()
+        rt = binding.fikit_trace_read()
+        binding.fikit_trace_enable(False)
+        ms = ev[0].elapsed_time(ev[1]) / args.steps
+        prio = {"lp_tasks_per_scenario": args.prio, "ms": round(ms, 3), "scenarios_per_s": round(n_scen / (ms * 1e-3), 1),
+                "kernels_issued_per_s": round(float(pf_out.lp_placed.sum()) / (ms * 1e-3), 1),
+                "mean_kernels_per_gap": round(float(pf_out.fill_count.double().mean()), 4),
+                "kernel_ms": {k: round(v[0] / args.steps, 3) for k, v in rt.items() if k.startswith("k_")}}
+        log(f"[bench] prio_fill: {json.dumps(prio)}")
+        del d_plo, d_plt, d_plq, pf_out
+
     # ---- roofline of the dominant kernel ------------------------------------------------------
     lens = np.array([cfg.launches(t) for t in range(cfg.n_tasks)], dtype=np.int64)
     n_small = int(lens[lens <= 4096].sum())
@@ -362,6 +395,8 @@ def main():
     }
     if replay:
         out["replay"] = replay
+    if prio:
+        out["prio_fill"] = prio
     # whole calls against the HBM peak: counter-measured bytes of every kernel of the call / the call's time
     calls = stored_call_traffic(name)
     if calls:

@@ -87,7 +87,9 @@ typedef enum fikit_status {
   FIKIT_BAD_RECORD = -4,          /* some record has end_ns < start_ns                          */
   FIKIT_UNKNOWN_ID = -5,          /* a scenario launch whose ID is absent from its task's rows  */
   FIKIT_HIP_ERROR = -6,           /* the HIP runtime reported an error                          */
-  FIKIT_UNSUPPORTED = -7          /* fikit_gapfill_replay: a predicted time of 2^32 - 1 ns or more */
+  FIKIT_UNSUPPORTED = -7          /* fikit_gapfill_replay, fikit_prio_fill: a predicted time of
+                                     2^32 - 1 ns or more; fikit_prio_fill: a scenario beyond its
+                                     stated limits                                                */
 } fikit_status;
 
 /* Bytes of device workspace fikit_profile needs for these sizes (0 on size overflow). */
@@ -229,6 +231,50 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
                          uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_hp_delay_ns,
                          uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes,
                          void* hip_stream);
+
+/* Most low-priority tasks one scenario of fikit_prio_fill may hold. */
+#define FIKIT_PRIO_MAX_LP 64
+
+/* Bytes of device workspace fikit_prio_fill needs for these sizes (0 on size overflow). */
+size_t fikit_prio_fill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios);
+
+/*
+ * Gap filling with several low-priority tasks per scenario: Algorithm 1 calling the whole of
+ * Algorithm 2 (BestPrioFit) over the priority queues Q1..Q9 (Q0 is the high-priority task that
+ * holds the GPU).
+ *
+ *   d_lp_offsets [n_scenarios+1] uint64, first 0, non-decreasing: scenario s owns the entries
+ *                d_lp_offsets[s] .. d_lp_offsets[s+1]-1 of d_lp_task / d_lp_prio, at most
+ *                FIKIT_PRIO_MAX_LP of them (else FIKIT_UNSUPPORTED); their launches together must
+ *                number fewer than 2^32 - 64 (else FIKIT_UNSUPPORTED).
+ *   d_lp_task    per entry, a low-priority task of the scenario (a task may appear in several
+ *                entries and scenarios; every entry is a separate run of it).
+ *   d_lp_prio    per entry, its priority level, 1 (highest) .. 9 (else FIKIT_INVALID_ARG).
+ *   d_fill_count, d_filled_ns  per gap (laid out by d_gap_offsets as in fikit_gapfill): kernels
+ *                issued into it and the sum of their predicted durations.
+ *   d_lp_placed, d_lp_placed_ns  per entry: how many of its kernels were issued into gaps, and
+ *                the sum of their predicted durations.
+ *   all other arguments as in fikit_gapfill.
+ *
+ * Every low-priority task has one waiting request at a time, its next kernel; when that is issued
+ * its following kernel is enqueued.  In every gap that is not skipped (the rule of fikit_gapfill),
+ * with r = gap - margin_ns left: the levels are scanned from 1 to 9; at the first level that holds
+ * a request whose predicted duration is at most r, the longest such request is taken (among equally
+ * long ones the one enqueued first; the initial requests count as enqueued in list order), issued,
+ * r is reduced by its duration and the scan starts again at level 1; the gap is done when no level
+ * holds a request that fits.  With one entry per scenario the per-gap results are fikit_gapfill's.
+ *
+ * Predicted times must be below 2^32 - 1 ns, else FIKIT_UNSUPPORTED.
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNKNOWN_ID, UNSUPPORTED, HIP_ERROR.
+ */
+int fikit_prio_fill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks,
+                    const fikit_row* d_rows, const uint64_t* d_task_row_offsets,
+                    const uint32_t* d_hp_task, const uint64_t* d_lp_offsets,
+                    const uint32_t* d_lp_task, const uint32_t* d_lp_prio, uint64_t n_scenarios,
+                    const fikit_gapfill_params* h_params, const uint64_t* d_gap_offsets,
+                    uint32_t* d_fill_count, int64_t* d_filled_ns, uint64_t* d_lp_placed,
+                    int64_t* d_lp_placed_ns, void* d_workspace, size_t workspace_bytes,
+                    void* hip_stream);
 
 const char* fikit_status_string(int status);
 int fikit_version(void);

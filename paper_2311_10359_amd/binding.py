@@ -27,7 +27,7 @@ FIKIT_PREDICT_P50, FIKIT_PREDICT_MEAN = 0, 1
 
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
            "fikit_gapfill", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
-           "fikit_gapfill_replay", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
+           "fikit_gapfill_replay", "fikit_prio_fill_workspace_bytes", "fikit_prio_fill", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
 
 # Layout of a profile row as seen from numpy (128 bytes; see fikit_row in fikit.h).
 STATS_DTYPE = np.dtype([("count", "<u8"), ("sum", "<u8"), ("min", "<i8"), ("max", "<i8"),
@@ -86,6 +86,11 @@ def load() -> ctypes.CDLL:
         lib.fikit_measure.argtypes = [vp, u64, vp, u32, vp, vp, vp, sz, vp]
         lib.fikit_replay_workspace_bytes.restype = sz
         lib.fikit_replay_workspace_bytes.argtypes = [u64, u32, u64]
+        lib.fikit_prio_fill_workspace_bytes.restype = sz
+        lib.fikit_prio_fill_workspace_bytes.argtypes = [u64, u32, u64]
+        lib.fikit_prio_fill.restype = ctypes.c_int
+        lib.fikit_prio_fill.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, vp, u64, ctypes.POINTER(_GapfillParams), vp,
+                                        vp, vp, vp, vp, vp, sz, vp]
         lib.fikit_gapfill_replay.restype = ctypes.c_int
         lib.fikit_gapfill_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, ctypes.POINTER(_ReplayParams), vp,
                                              vp, vp, vp, vp, vp, sz, vp]
@@ -303,6 +308,58 @@ def fikit_gapfill_replay(ids: torch.Tensor, task_offsets: torch.Tensor, rows: to
                                       _stream_handle(stream))
     if st != FIKIT_OK:
         raise FikitError(st, "fikit_gapfill_replay")
+    return out
+
+
+class PrioFill(NamedTuple):
+    fill_count: torch.Tensor     # int32 view of uint32 [n_gaps]
+    filled_ns: torch.Tensor      # int64 [n_gaps]
+    lp_placed: torch.Tensor      # int64 view of uint64 [n_entries]
+    lp_placed_ns: torch.Tensor   # int64 [n_entries]
+
+
+FIKIT_PRIO_MAX_LP = 64
+
+
+def fikit_prio_fill_workspace_bytes(n_ids: int, n_tasks: int, n_scenarios: int) -> int:
+    return int(load().fikit_prio_fill_workspace_bytes(n_ids, n_tasks, n_scenarios))
+
+
+def fikit_prio_fill(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Tensor, task_row_offsets: torch.Tensor,
+                    hp_task: torch.Tensor, lp_offsets: torch.Tensor, lp_task: torch.Tensor, lp_prio: torch.Tensor,
+                    gap_offsets: torch.Tensor, *, margin_ns: int, min_gap_ns: int, predictor: int = FIKIT_PREDICT_P50,
+                    n_gaps: Optional[int] = None, n_ids: Optional[int] = None, out: Optional[PrioFill] = None,
+                    workspace_buf: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> PrioFill:
+    """hp_task: int32 [S]; lp_offsets: int64 [S+1]; lp_task, lp_prio: int32 [n_entries]; gap_offsets: int64 [S+1]."""
+    lib = load()
+    dev = task_offsets.device
+    n_tasks = task_offsets.numel() - 1
+    s = hp_task.numel()
+    n_entries = lp_task.numel()
+    assert hp_task.dtype == torch.int32 and lp_task.dtype == torch.int32 and lp_prio.dtype == torch.int32
+    assert lp_prio.numel() == n_entries
+    assert lp_offsets.dtype == torch.int64 and lp_offsets.numel() == s + 1
+    assert gap_offsets.dtype == torch.int64 and gap_offsets.numel() == s + 1
+    for t in (ids, task_offsets, rows, task_row_offsets, hp_task, lp_offsets, lp_task, lp_prio, gap_offsets):
+        assert t.is_contiguous() and t.device == dev
+    if n_gaps is None:
+        n_gaps = int(gap_offsets[-1].item()) if s else 0
+    if n_ids is None:
+        n_ids = ids.numel()
+    if out is None:
+        out = PrioFill(torch.empty(n_gaps, dtype=torch.int32, device=dev), torch.empty(n_gaps, dtype=torch.int64, device=dev),
+                       torch.empty(n_entries, dtype=torch.int64, device=dev),
+                       torch.empty(n_entries, dtype=torch.int64, device=dev))
+    if workspace_buf is None:
+        workspace_buf = workspace(fikit_prio_fill_workspace_bytes(n_ids, n_tasks, s), dev)
+    params = _GapfillParams(margin_ns, min_gap_ns, predictor, 0)
+    with torch.cuda.device(dev):
+        st = lib.fikit_prio_fill(_ptr(ids), _ptr(task_offsets), n_tasks, _ptr(rows), _ptr(task_row_offsets), _ptr(hp_task),
+                                 _ptr(lp_offsets), _ptr(lp_task), _ptr(lp_prio), s, ctypes.byref(params), _ptr(gap_offsets),
+                                 _ptr(out.fill_count), _ptr(out.filled_ns), _ptr(out.lp_placed), _ptr(out.lp_placed_ns),
+                                 _ptr(workspace_buf), workspace_buf.numel(), _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_prio_fill")
     return out
 
 

@@ -22,6 +22,8 @@ enum : uint32_t {
   ERR_TASK_INDEX = 1u << 3,  // scenario names a task >= n_tasks
   ERR_GAP_OFFSETS = 1u << 4, // scenario gap offsets do not match the trace lengths
   ERR_ACTUAL_GAP = 1u << 5,  // replay: negative actual idle time after a launch that has a gap
+  ERR_LP_LIST = 1u << 6,     // priority queues: list offsets not monotone, or a level outside 1..9
+  ERR_LP_LIMIT = 1u << 7,    // priority queues: more low-priority tasks or launches in a scenario than supported
 };
 
 // Control block at the start of the workspace; cleared by k_clear_ctrl at the start of a call.
@@ -33,7 +35,8 @@ struct Ctrl {
   uint64_t n_general;     // tasks that take the general sort-based path
   uint64_t n_long;        // tasks too long for the one-workgroup path
   uint64_t n_heads;       // rows found by the general path
-  uint32_t n_class[4];    // length of the work lists (small, mid, medium tasks or units; spare)
+  uint32_t n_class[4];    // length of the work lists (small, mid, medium tasks or units); [3]: priority queues, the
+                          // largest number of low-priority tasks of a scenario
 };
 static_assert(sizeof(Ctrl) == 64, "control block is 64 bytes");
 

@@ -11,6 +11,7 @@
 #include "stats_kernels.hip.h"
 #include "task_kernels.hip.h"
 #include "msd_kernels.hip.h"
+#include "prio_kernels.hip.h"
 
 namespace {
 
@@ -145,15 +146,29 @@ struct Tracer {
 };
 
 int status_from_bits(uint32_t bits) {
-  if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS | ERR_ACTUAL_GAP)) return FIKIT_INVALID_ARG;
+  if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS | ERR_ACTUAL_GAP | ERR_LP_LIST)) return FIKIT_INVALID_ARG;
   if (bits & ERR_BAD_RECORD) return FIKIT_BAD_RECORD;
   if (bits & ERR_UNKNOWN_ID) return FIKIT_UNKNOWN_ID;
+  if (bits & ERR_LP_LIMIT) return FIKIT_UNSUPPORTED;
   return FIKIT_OK;
 }
 
 int read_ctrl(const Ctrl* d_ctrl, Ctrl* h, hipStream_t st) {
   FIKIT_HIP(hipMemcpyAsync(h, d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
   FIKIT_HIP(hipStreamSynchronize(st));
+  return FIKIT_OK;
+}
+
+template <int W>
+int launch_prio_walk(hipStream_t st, const uint64_t* off, const uint32_t* hp_task, const uint64_t* lp_off,
+                     const uint32_t* lp_task, const uint32_t* lp_prio, uint64_t n_scen, const uint64_t* gap_off,
+                     const uint32_t* lp_e, const uint2* hp_eg, int64_t margin, int64_t min_gap, uint32_t* fill_count,
+                     int64_t* filled_ns, uint64_t* placed, int64_t* placed_ns, uint32_t vec_ok, const Ctrl* ctrl) {
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_pf_walk<W>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                static_cast<int>(sizeof(PrioWalkSmem))));
+  hipLaunchKernelGGL(k_pf_walk<W>, dim3(blocks_for(n_scen * W, LW_THREADS)), dim3(LW_THREADS), sizeof(PrioWalkSmem), st, off,
+                     hp_task, lp_off, lp_task, lp_prio, n_scen, gap_off, lp_e, hp_eg, margin, min_gap, fill_count, filled_ns,
+                     placed, placed_ns, vec_ok, ctrl);
   return FIKIT_OK;
 }
 
@@ -642,6 +657,102 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
   Ctrl h{};
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   if (int rc = status_from_bits(h.status)) return rc;
+  // (the walk has not run in this case: its outputs are undefined)
+  return h.wide ? FIKIT_UNSUPPORTED : FIKIT_OK;
+}
+
+size_t fikit_prio_fill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios) {
+  (void)n_scenarios;
+  if (n_ids >= MAX_ELEMS) return 0;
+  Carver c;
+  c.take(256);
+  c.take(static_cast<uint64_t>(n_tasks) * 4);
+  c.take(static_cast<uint64_t>(n_tasks) * 4 * 2);
+  c.take(static_cast<uint64_t>(n_tasks) * 8);
+  c.take(n_ids * 4 + GF_PAD);
+  c.take(n_ids * 8 + GF_PAD);
+  return static_cast<size_t>(c.at);
+}
+
+int fikit_prio_fill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks, const fikit_row* d_rows,
+                    const uint64_t* d_task_row_offsets, const uint32_t* d_hp_task, const uint64_t* d_lp_offsets,
+                    const uint32_t* d_lp_task, const uint32_t* d_lp_prio, uint64_t n_scenarios,
+                    const fikit_gapfill_params* h_params, const uint64_t* d_gap_offsets, uint32_t* d_fill_count,
+                    int64_t* d_filled_ns, uint64_t* d_lp_placed, int64_t* d_lp_placed_ns, void* d_workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  if (!h_params || h_params->margin_ns < 0 || h_params->min_gap_ns < 0 || h_params->reserved != 0 ||
+      h_params->predictor < FIKIT_PREDICT_P50 || h_params->predictor > FIKIT_PREDICT_MEAN)
+    return FIKIT_INVALID_ARG;
+  if (!d_task_offsets || !d_task_row_offsets || !d_workspace) return FIKIT_INVALID_ARG;
+  if (n_scenarios >= MAX_ELEMS / FIKIT_PRIO_MAX_LP) return FIKIT_INVALID_ARG;
+  if (n_scenarios > 0 && (!d_hp_task || !d_lp_offsets || !d_gap_offsets || n_tasks == 0)) return FIKIT_INVALID_ARG;
+  if (!aligned(d_ids, 8) || !aligned(d_task_offsets, 8) || !aligned(d_rows, 16) || !aligned(d_task_row_offsets, 8) ||
+      !aligned(d_hp_task, 4) || !aligned(d_lp_offsets, 8) || !aligned(d_lp_task, 4) || !aligned(d_lp_prio, 4) ||
+      !aligned(d_gap_offsets, 8) || !aligned(d_fill_count, 4) || !aligned(d_filled_ns, 8) || !aligned(d_lp_placed, 8) ||
+      !aligned(d_lp_placed_ns, 8) || !aligned(d_workspace, 256))
+    return FIKIT_INVALID_ARG;
+  if (n_scenarios == 0) return FIKIT_OK;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint64_t n_ids = 0, n_gaps = 0, n_entries = 0;
+  FIKIT_HIP(hipMemcpyAsync(&n_ids, d_task_offsets + n_tasks, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipMemcpyAsync(&n_gaps, d_gap_offsets + n_scenarios, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipMemcpyAsync(&n_entries, d_lp_offsets + n_scenarios, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipStreamSynchronize(st));
+  if (n_ids >= MAX_ELEMS || n_gaps >= MAX_ELEMS || n_entries >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_ids > 0 && (!d_ids || !d_rows)) return FIKIT_INVALID_ARG;
+  if (n_gaps > 0 && (!d_fill_count || !d_filled_ns)) return FIKIT_INVALID_ARG;
+  if (n_entries > 0 && (!d_lp_task || !d_lp_prio || !d_lp_placed || !d_lp_placed_ns)) return FIKIT_INVALID_ARG;
+  if (workspace_bytes < fikit_prio_fill_workspace_bytes(n_ids, n_tasks, n_scenarios)) return FIKIT_WORKSPACE_TOO_SMALL;
+
+  unsigned char* ws = static_cast<unsigned char*>(d_workspace);
+  Carver c;
+  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
+  uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
+  uint32_t* glists = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4 * 2));
+  uint64_t* lp_total = reinterpret_cast<uint64_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 8));
+  uint32_t* lp_e = reinterpret_cast<uint32_t*>(ws + c.take(n_ids * 4 + GF_PAD));
+  uint2* hp_eg = reinterpret_cast<uint2*>(ws + c.take(n_ids * 8 + GF_PAD));
+
+  Tracer tr(st);
+  tr.mark("pf_setup");
+  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+  hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, role, static_cast<uint64_t>(n_tasks), 0u);
+  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_ids, ctrl);
+  hipLaunchKernelGGL(k_pf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
+                     d_lp_offsets, d_lp_task, d_lp_prio, n_scenarios, n_entries, d_gap_offsets, role, ctrl);
+  hipLaunchKernelGGL(k_gf_lists, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, role, 8192u, glists,
+                     ctrl);
+  FIKIT_HIP(hipGetLastError());
+  tr.mark("host_sync");
+  Ctrl h{};
+  if (int rc = read_ctrl(ctrl, &h, st)) return rc;   // the widest scenario decides how many lanes share one
+  if (int rc = status_from_bits(h.status)) return rc;
+  tr.mark("k_gf_predict32");
+  hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                     d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total,
+                     static_cast<uint32_t>(h_params->predictor), ctrl);
+  const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
+  const uint32_t widest = h.n_class[3];
+  tr.mark("k_pf_walk");
+  int rc = FIKIT_OK;
+#define FIKIT_PF_WALK(W)                                                                                                   \
+  rc = launch_prio_walk<W>(st, d_task_offsets, d_hp_task, d_lp_offsets, d_lp_task, d_lp_prio, n_scenarios, d_gap_offsets, \
+                           lp_e, hp_eg, h_params->margin_ns, h_params->min_gap_ns, d_fill_count, d_filled_ns, d_lp_placed, \
+                           d_lp_placed_ns, vec_ok, ctrl)
+  if (widest <= 1) FIKIT_PF_WALK(1);
+  else if (widest <= 2) FIKIT_PF_WALK(2);
+  else if (widest <= 4) FIKIT_PF_WALK(4);
+  else if (widest <= 8) FIKIT_PF_WALK(8);
+  else if (widest <= 16) FIKIT_PF_WALK(16);
+  else if (widest <= 32) FIKIT_PF_WALK(32);
+  else FIKIT_PF_WALK(64);
+#undef FIKIT_PF_WALK
+  if (rc) return rc;
+  FIKIT_HIP(hipGetLastError());
+  tr.mark("host_sync");
+  if (int rc2 = read_ctrl(ctrl, &h, st)) return rc2;
+  if (int rc2 = status_from_bits(h.status)) return rc2;
   // (the walk has not run in this case: its outputs are undefined)
   return h.wide ? FIKIT_UNSUPPORTED : FIKIT_OK;
 }

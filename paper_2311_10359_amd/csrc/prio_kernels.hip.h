@@ -1,0 +1,309 @@
+// Gap filling with several low-priority tasks per scenario: Algorithm 1 calling the whole of
+// Algorithm 2 (BestPrioFit) over the priority queues Q1..Q9.
+#pragma once
+
+#include "common.hip.h"
+#include "gapfill_kernels.hip.h"
+
+namespace fikit {
+
+constexpr uint32_t PF_MAX_LP = FIKIT_PRIO_MAX_LP;   // low-priority tasks of one scenario (one lane each, one wave at most)
+
+// Checks the scenario arguments, records in role[t] how each task is used and leaves the largest
+// number of low-priority tasks of a scenario in ctrl->n_class[3].
+__global__ void k_pf_scenarios(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ hp_task,
+                               const uint64_t* __restrict__ lp_off, const uint32_t* __restrict__ lp_task,
+                               const uint32_t* __restrict__ lp_prio, uint64_t n_scen, uint64_t n_entries,
+                               const uint64_t* __restrict__ gap_off, uint32_t* __restrict__ role, Ctrl* ctrl) {
+  if (ctrl->status & ERR_OFFSETS) return;
+  const uint64_t s = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  uint32_t k_here = 0;
+  if (s < n_scen) {
+    const uint32_t hp = hp_task[s];
+    const uint64_t e0 = lp_off[s], e1 = lp_off[s + 1];
+    if (hp >= n_tasks) {
+      atomicOr(&ctrl->status, ERR_TASK_INDEX);
+    } else if (e1 < e0 || e1 > n_entries || (s == 0 && e0 != 0)) {
+      atomicOr(&ctrl->status, ERR_LP_LIST);
+    } else if (e1 - e0 > PF_MAX_LP) {
+      atomicOr(&ctrl->status, ERR_LP_LIMIT);
+    } else {
+      const uint64_t H = off[hp + 1] - off[hp];
+      const uint64_t want = H > 0 ? H - 1 : 0;
+      if (gap_off[s + 1] < gap_off[s] || gap_off[s + 1] - gap_off[s] != want || (s == 0 && gap_off[0] != 0))
+        atomicOr(&ctrl->status, ERR_GAP_OFFSETS);
+      atomicOr(&role[hp], ROLE_HP);
+      k_here = static_cast<uint32_t>(e1 - e0);
+      uint64_t launches = 0;
+      for (uint64_t e = e0; e < e1; ++e) {
+        const uint32_t lp = lp_task[e], q = lp_prio[e];
+        if (lp >= n_tasks) { atomicOr(&ctrl->status, ERR_TASK_INDEX); continue; }
+        if (q < 1 || q > 9) atomicOr(&ctrl->status, ERR_LP_LIST);
+        launches += off[lp + 1] - off[lp];
+        atomicOr(&role[lp], ROLE_LP);
+      }
+      // (the age of a waiting request is counted in 32 bits)
+      if (launches >= (1ull << 32) - PF_MAX_LP) atomicOr(&ctrl->status, ERR_LP_LIMIT);
+    }
+  }
+  const uint32_t k_wave = wave_max_u32(k_here);
+  if (lane_id() == 0 && k_wave) atomicMax(&ctrl->n_class[3], k_wave);
+}
+
+struct PrioWalkSmem {   // [entry][lane], as in LaneWalkSmem; the idle times and the results of a scenario
+                        // live in the column of its first lane
+  uint32_t lp[LW_LP_CAP][LW_THREADS];
+  uint32_t hp_g[LW_HP_CAP][LW_THREADS];
+  uint32_t out_c[LW_OUT_CAP][LW_THREADS];
+  uint32_t out_f[LW_OUT_CAP][LW_THREADS];
+};
+
+template <int W>
+__device__ __forceinline__ uint64_t group_min_u64(uint64_t v) {
+#pragma unroll
+  for (int m = W >> 1; m >= 1; m >>= 1) { const uint64_t o = shfl_xor_u64(v, m); v = o < v ? o : v; }
+  return v;
+}
+template <int W>
+__device__ __forceinline__ uint32_t group_max_u32(uint32_t v) {
+#pragma unroll
+  for (int m = W >> 1; m >= 1; m >>= 1) { const uint32_t o = __shfl_xor(v, m, WAVE); v = o > v ? o : v; }
+  return v;
+}
+
+__device__ __forceinline__ void pw_store_scalar(const PrioWalkSmem& sm, uint32_t col, uint32_t first, uint32_t count,
+                                                uint32_t* __restrict__ fill_count, int64_t* __restrict__ filled_ns) {
+  for (uint32_t k = 0; k < count; ++k) {
+    const uint32_t at = first + k;
+    fill_count[at] = sm.out_c[at & (LW_OUT_CAP - 1)][col];
+    filled_ns[at] = static_cast<int64_t>(sm.out_f[at & (LW_OUT_CAP - 1)][col]);
+  }
+}
+
+// W adjacent lanes (a power of two, W <= 64) step through one scenario together.  Every lane owns one
+// low-priority task: a ring of its next predicted durations, the position of its waiting request and
+// when that request was enqueued.  The first lane of the group also owns the ring of predicted idle
+// times of the high-priority trace and writes the per-gap results; what describes the open gap (time
+// left, kernels issued, time filled) is kept identically in all lanes of the group.
+// One BestPrioFit decision: every lane whose request fits offers the key (level, -duration); the
+// group's smallest key is the highest level that has a fitting request and there the longest one; among
+// lanes that offered it the request that has waited longest wins, is issued, and the lane's next
+// request is enqueued.  With W == 1 this is the first-in-first-out walk of one queue.
+template <int W>
+__global__ void __launch_bounds__(LW_THREADS)
+k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task, const uint64_t* __restrict__ lp_off,
+          const uint32_t* __restrict__ lp_task, const uint32_t* __restrict__ lp_prio, uint64_t n_scen,
+          const uint64_t* __restrict__ gap_off, const uint32_t* __restrict__ lp_e, const uint2* __restrict__ hp_eg,
+          int64_t margin, int64_t min_gap, uint32_t* __restrict__ fill_count, int64_t* __restrict__ filled_ns,
+          uint64_t* __restrict__ placed_out, int64_t* __restrict__ placed_ns_out, uint32_t vec_ok, const Ctrl* ctrl) {
+  static_assert(W >= 1 && W <= WAVE && (W & (W - 1)) == 0, "group width");
+  extern __shared__ __align__(16) unsigned char pw_raw[];
+  PrioWalkSmem& sm = *reinterpret_cast<PrioWalkSmem*>(pw_raw);
+  if (ctrl->status || ctrl->wide) return;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t member = tid & (W - 1);
+  const uint32_t col = tid - member;                       // column of the group's shared rings
+  const uint64_t s = (static_cast<uint64_t>(blockIdx.x) * LW_THREADS + tid) / W;
+  const bool valid = s < n_scen;
+  const bool lead = valid && member == 0;
+  const uint32_t gshift = lane_id() & ~static_cast<uint32_t>(W - 1);
+  const uint64_t gmask = W == WAVE ? ~0ull : ((1ull << (W & 63)) - 1ull) << gshift;
+
+  // positions are global element numbers (all below 2^32)
+  uint32_t h0 = 0, hp_end = 0, l0 = 0, lp_end = 0, g_first = 0, n_gaps = 0, prio = 0;
+  uint64_t entry = 0;
+  bool has_entry = false;
+  if (valid) {
+    const uint32_t hp = hp_task[s];
+    h0 = static_cast<uint32_t>(off[hp]); hp_end = static_cast<uint32_t>(off[hp + 1]);
+    g_first = static_cast<uint32_t>(gap_off[s]);
+    n_gaps = hp_end > h0 ? hp_end - h0 - 1 : 0;
+    const uint64_t e0 = lp_off[s], K = lp_off[s + 1] - e0;
+    if (member < K) {
+      entry = e0 + member;
+      const uint32_t lp = lp_task[entry];
+      l0 = static_cast<uint32_t>(off[lp]); lp_end = static_cast<uint32_t>(off[lp + 1]);
+      prio = lp_prio[entry];
+      has_entry = true;
+    }
+  }
+  uint32_t hp_pos = h0, lp_pos = l0;
+  uint32_t hp_landed = h0 & ~(LW_HP_CHUNK - 1), lp_landed = l0 & ~(LW_LP_CHUNK - 1);   // rings hold entries below these
+  uint32_t hp_req = 0, lp_req = 0;
+  bool hp_fly = false, lp_fly = false;
+  uint4 hr[4], lr[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) hr[k] = lr[k] = make_uint4(0, 0, 0, 0);
+
+  uint32_t g = g_first;              // global number of the next gap to report
+  uint32_t flushed = g_first;        // results below this are in memory
+  const uint32_t g_end = g_first + n_gaps;
+  uint32_t c = 0, f = 0, rem = 0;
+  uint32_t clock = W;                // enqueue stamps handed out so far (only their order matters: the initial
+  uint32_t stamp = member;           // requests are enqueued in list order, before everything else)
+  uint64_t placed_ns = 0;
+  const int64_t floor64 = min_gap > margin ? min_gap : margin;
+  const uint32_t gap_floor = floor64 >= static_cast<int64_t>(WIDE32) ? WIDE32 : static_cast<uint32_t>(floor64);
+  const uint32_t margin32 = margin >= static_cast<int64_t>(WIDE32) ? WIDE32 : static_cast<uint32_t>(margin);
+  bool in_gap = false;
+  bool pending = false;               // a gap has closed and its result (c, f) is not staged yet
+  // nothing to step through: no scenario, or no low-priority kernel at all (every gap then gets zeros)
+  const bool no_kernels = (ballot(lp_end == l0) & gmask) == gmask;
+  bool finished = !valid || no_kernels;
+
+  for (;;) {
+    // ---- once per period: park what was read, read on, write complete groups of results ----
+    if (hp_fly) {
+      if (lead) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t at = (hp_req + 2 * k) & (LW_HP_CAP - 1);
+          sm.hp_g[at][tid] = hr[k].y;
+          sm.hp_g[at + 1][tid] = hr[k].w;
+        }
+      }
+      hp_landed = hp_req + LW_HP_CHUNK;
+      hp_fly = false;
+    }
+    if (lp_fly) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t at = (lp_req + 4 * k) & (LW_LP_CAP - 1);
+        sm.lp[at][tid] = lr[k].x; sm.lp[at + 1][tid] = lr[k].y; sm.lp[at + 2][tid] = lr[k].z; sm.lp[at + 3][tid] = lr[k].w;
+      }
+      lp_landed = lp_req + LW_LP_CHUNK;
+      lp_fly = false;
+    }
+    if (!finished && hp_landed < hp_end && static_cast<int32_t>(hp_landed - hp_pos) <= static_cast<int32_t>(LW_HP_CAP - LW_HP_CHUNK)) {
+      if (lead) {
+        const uint4* src = reinterpret_cast<const uint4*>(hp_eg + hp_landed);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) hr[k] = src[k];
+      }
+      hp_req = hp_landed;
+      hp_fly = true;
+    }
+    if (!finished && lp_landed < lp_end && static_cast<int32_t>(lp_landed - lp_pos) <= static_cast<int32_t>(LW_LP_CAP - LW_LP_CHUNK)) {
+      const uint4* src = reinterpret_cast<const uint4*>(lp_e + lp_landed);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) lr[k] = src[k];
+      lp_req = lp_landed;
+      lp_fly = true;
+    }
+    if (flushed < g && (flushed & (LW_OUT_CHUNK - 1))) {   // (first results of a scenario, up to a multiple of 8)
+      const uint32_t to8 = LW_OUT_CHUNK - (flushed & (LW_OUT_CHUNK - 1));
+      const uint32_t cnt = g - flushed < to8 ? g - flushed : to8;
+      if (lead) pw_store_scalar(sm, tid, flushed, cnt, fill_count, filled_ns);
+      flushed += cnt;
+    }
+    while (flushed + LW_OUT_CHUNK <= g) {
+      if (lead) {
+        if (vec_ok) {
+          const uint32_t at = flushed & (LW_OUT_CAP - 1);
+          uint32_t cc[LW_OUT_CHUNK], ff[LW_OUT_CHUNK];
+#pragma unroll
+          for (uint32_t k = 0; k < LW_OUT_CHUNK; ++k) { cc[k] = sm.out_c[at + k][tid]; ff[k] = sm.out_f[at + k][tid]; }
+          uint4* oc = reinterpret_cast<uint4*>(fill_count + flushed);
+          oc[0] = make_uint4(cc[0], cc[1], cc[2], cc[3]);
+          oc[1] = make_uint4(cc[4], cc[5], cc[6], cc[7]);
+          uint4* of = reinterpret_cast<uint4*>(filled_ns + flushed);
+#pragma unroll
+          for (uint32_t k = 0; k < 4; ++k) of[k] = make_uint4(ff[2 * k], 0u, ff[2 * k + 1], 0u);
+        } else {
+          pw_store_scalar(sm, tid, flushed, LW_OUT_CHUNK, fill_count, filled_ns);
+        }
+      }
+      flushed += LW_OUT_CHUNK;
+    }
+    if (__all(finished)) break;
+
+    // ---- one period, without branches: LW_OPENS times { stage the result of the gap that closed, take
+    // the next high-priority launch and open its gap; LW_TRIES decisions }.  A group whose rings lack an
+    // entry it needs idles in that sub-step. ----
+#pragma unroll
+    for (uint32_t o = 0; o < LW_OPENS; ++o) {
+      {
+        // (a staging slot that is written early is simply written again)
+        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
+        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
+        g += pending ? 1u : 0u;
+        pending = false;
+        const uint32_t G = sm.hp_g[hp_pos & (LW_HP_CAP - 1)][col];
+        // between gaps: the next high-priority launch runs, then its gap opens (the last launch has none)
+        const bool idle = !finished && !in_gap;
+        const bool at_end = idle && hp_pos == hp_end;
+        const bool take = idle && !at_end && hp_pos < hp_landed;
+        hp_pos += take ? 1u : 0u;
+        const bool last = take && hp_pos == hp_end;
+        const bool gap = take && !last;
+        const bool usable = gap && G >= gap_floor;
+        const bool skip = gap && !usable;
+        // a skipped gap reports zeros
+        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = 0u;
+        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = 0u;
+        g += skip ? 1u : 0u;
+        in_gap = in_gap || usable;
+        rem = usable ? G - margin32 : rem;
+        c = usable ? 0u : c;
+        f = usable ? 0u : f;
+        finished = finished || at_end || last;
+      }
+#pragma unroll
+      for (uint32_t k = 0; k < LW_TRIES; ++k) {
+        const bool exhausted = lp_pos == lp_end;                 // (also: a lane without a task)
+        const bool ready = exhausted || lp_pos < lp_landed;      // the waiting request, if any, is known
+        const bool all_ready = (ballot(ready) & gmask) == gmask;
+        const bool tryq = in_gap && all_ready;
+        const uint32_t d = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid];
+        const bool fits = tryq && !exhausted && d <= rem;
+        const uint64_t key = fits ? (static_cast<uint64_t>(prio) << 32) | (0xffffffffu - d) : ~0ull;
+        const uint64_t best = group_min_u64<W>(key);
+        const bool any = best != ~0ull;
+        const bool tie = fits && key == best;
+        const uint32_t age = tie ? clock - stamp : 0u;           // >= 1 for a waiting request
+        const uint32_t oldest = group_max_u32<W>(age);           // (all lanes take part in the exchange)
+        const bool win = tie && age == oldest;
+        const uint32_t dd = any ? 0xffffffffu - static_cast<uint32_t>(best) : 0u;
+        rem -= dd; f += dd;
+        c += any ? 1u : 0u;
+        lp_pos += win ? 1u : 0u;
+        placed_ns += win ? dd : 0u;
+        stamp = win ? clock : stamp;                             // the task's following kernel is enqueued now
+        clock += any ? 1u : 0u;
+        const bool all_issued = (ballot(lp_pos == lp_end) & gmask) == gmask;
+        const bool emptied = any && all_issued;                  // every queue has been issued
+        const bool close = (tryq && !any) || emptied;
+        pending = pending || close;
+        finished = finished || emptied;
+        in_gap = in_gap && !close;
+      }
+    }
+  }
+
+  if (!valid) return;
+  if (pending) {
+    sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
+    sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
+    ++g;
+  }
+  if (has_entry) {
+    placed_out[entry] = lp_pos - l0;
+    placed_ns_out[entry] = static_cast<int64_t>(placed_ns);
+  }
+  if (!lead) return;
+  // what is still staged, then zeros for the gaps after the queues ran empty
+  pw_store_scalar(sm, tid, flushed, g - flushed, fill_count, filled_ns);
+  uint32_t z = g;
+  while (z < g_end && (z & (LW_OUT_CHUNK - 1))) { fill_count[z] = 0; filled_ns[z] = 0; ++z; }
+  if (vec_ok) {
+    for (; z + LW_OUT_CHUNK <= g_end; z += LW_OUT_CHUNK) {
+      uint4* oc = reinterpret_cast<uint4*>(fill_count + z);
+      oc[0] = oc[1] = make_uint4(0, 0, 0, 0);
+      uint4* of = reinterpret_cast<uint4*>(filled_ns + z);
+      of[0] = of[1] = of[2] = of[3] = make_uint4(0, 0, 0, 0);
+    }
+  }
+  for (; z < g_end; ++z) { fill_count[z] = 0; filled_ns[z] = 0; }
+}
+
+}  // namespace fikit

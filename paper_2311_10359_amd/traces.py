@@ -355,6 +355,22 @@ def scenarios(cfg: TraceConfig) -> Tuple[np.ndarray, np.ndarray]:
     return np.zeros(0, dtype=np.uint32), np.zeros(0, dtype=np.uint32)
 
 
+def prio_scenarios(cfg: TraceConfig, k: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """The scenarios of `scenarios(cfg)` with k low-priority tasks each instead of one: scenario s keeps its own and
+    borrows those of the next k-1 scenarios (cyclically).  Priority levels 1..9 follow a fixed pattern in which
+    neighbouring entries often share a level.  -> (hp_task[S], lp_offsets[S+1], lp_task[S*k], lp_prio[S*k])."""
+    hp, lp = scenarios(cfg)
+    n = hp.shape[0]
+    if n == 0 or k == 0:
+        return hp, np.zeros(n + 1, dtype=np.uint64), np.zeros(0, dtype=np.uint32), np.zeros(0, dtype=np.uint32)
+    s = np.arange(n, dtype=np.int64)[:, None]
+    j = np.arange(k, dtype=np.int64)[None, :]
+    lp_task = lp[(s + j) % n].astype(np.uint32).reshape(-1)
+    lp_prio = (1 + ((s // 3 + 2 * (j // 2)) % 9)).astype(np.uint32).reshape(-1)
+    lp_offsets = (np.arange(n + 1, dtype=np.uint64) * np.uint64(k)).astype(np.uint64)
+    return hp, lp_offsets, lp_task, lp_prio
+
+
 def gap_offsets(offsets: np.ndarray, hp_task: np.ndarray) -> np.ndarray:
     """Where each scenario's per-gap outputs start: a scenario whose high-priority trace has H
     launches owns max(H - 1, 0) consecutive output slots (one per idle gap between launches)."""

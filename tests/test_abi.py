@@ -72,6 +72,15 @@ def test_host_side_argument_checks_need_no_gpu():
     r = binding._ReplayParams(0, -1, 0, 0)
     assert lib.fikit_gapfill_replay(fake, fake, 1, fake, fake, fake, fake, fake, 1, ctypes.byref(r), fake, fake, fake, fake,
                                     fake, fake, 1 << 20, null) == -1
+    p = binding._GapfillParams(0, 0, 0, 0)
+    assert lib.fikit_prio_fill(fake, fake, 1, fake, fake, fake, null, fake, fake, 1, ctypes.byref(p), fake, fake, fake, fake,
+                               fake, fake, 1 << 20, null) == -1
+    assert lib.fikit_prio_fill(fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, None, fake, fake, fake, fake,
+                               fake, fake, 1 << 20, null) == -1
+    p = binding._GapfillParams(0, 0, 0, 1)   # reserved must be 0
+    assert lib.fikit_prio_fill(fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, ctypes.byref(p), fake, fake, fake, fake,
+                               fake, fake, 1 << 20, null) == -1
+    assert lib.fikit_prio_fill_workspace_bytes(1 << 33, 1, 1) == 0
     assert lib.fikit_measure(fake, 10, null, 1, fake, fake, fake, 256, null) == -1
     assert lib.fikit_measure(fake, 10, fake, 1, fake, fake, fake, 16, null) == -2
     assert lib.fikit_measure_workspace_bytes() == 256
