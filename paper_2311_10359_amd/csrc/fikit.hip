@@ -165,8 +165,8 @@ int launch_prio_walk(hipStream_t st, const uint64_t* off, const uint32_t* hp_tas
                      const uint32_t* lp_e, const uint2* hp_eg, int64_t margin, int64_t min_gap, uint32_t* fill_count,
                      int64_t* filled_ns, uint64_t* placed, int64_t* placed_ns, uint32_t vec_ok, const Ctrl* ctrl) {
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_pf_walk<W>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(sizeof(PrioWalkSmem))));
-  hipLaunchKernelGGL(k_pf_walk<W>, dim3(blocks_for(n_scen * W, LW_THREADS)), dim3(LW_THREADS), sizeof(PrioWalkSmem), st, off,
+                                static_cast<int>(sizeof(PrioWalkSmem<W>))));
+  hipLaunchKernelGGL(k_pf_walk<W>, dim3(blocks_for(n_scen * W, PW_THREADS)), dim3(PW_THREADS), sizeof(PrioWalkSmem<W>), st, off,
                      hp_task, lp_off, lp_task, lp_prio, n_scen, gap_off, lp_e, hp_eg, margin, min_gap, fill_count, filled_ns,
                      placed, placed_ns, vec_ok, ctrl);
   return FIKIT_OK;

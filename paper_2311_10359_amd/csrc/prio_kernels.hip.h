@@ -50,33 +50,54 @@ __global__ void k_pf_scenarios(const uint64_t* __restrict__ off, uint32_t n_task
   if (lane_id() == 0 && k_wave) atomicMax(&ctrl->n_class[3], k_wave);
 }
 
-struct PrioWalkSmem {   // [entry][lane], as in LaneWalkSmem; the idle times and the results of a scenario
-                        // live in the column of its first lane
-  uint32_t lp[LW_LP_CAP][LW_THREADS];
-  uint32_t hp_g[LW_HP_CAP][LW_THREADS];
-  uint32_t out_c[LW_OUT_CAP][LW_THREADS];
-  uint32_t out_f[LW_OUT_CAP][LW_THREADS];
+constexpr int PW_THREADS = 128;
+constexpr uint32_t PW_OPENS = 4, PW_TRIES = 6;   // per period: gaps opened, and decisions per gap opened
+constexpr uint32_t PW_OUT_CAP = 16;              // staged results: at most 7 left over + 2 per gap opened in a period
+
+template <int W>
+struct PrioWalkSmem {   // [entry][column]: a lane's durations in its own column; the idle times and the results of a
+                        // scenario in the column of its group
+  uint32_t lp[LW_LP_CAP][PW_THREADS];
+  uint32_t hp_g[LW_HP_CAP][PW_THREADS / W];
+  uint32_t out_c[PW_OUT_CAP][PW_THREADS / W];
+  uint32_t out_f[PW_OUT_CAP][PW_THREADS / W];
+};
+
+// Largest value among the W adjacent lanes of a group, in all of them.  Inside a row of 16 lanes the
+// values move by data-parallel-primitive swaps (pairs, quads) and mirrors (8, 16 lanes: once all lanes of
+// each half hold the half's result, mirroring exchanges the halves); every lane has a source lane in
+// these patterns.  All 64 lanes must call.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ uint32_t max_u32(uint32_t a, uint32_t b) { return a > b ? a : b; }
+template <int W>
+__device__ __forceinline__ uint32_t group_max_u32(uint32_t v) {
+  if (W >= 2) v = max_u32(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]
+  if (W >= 4) v = max_u32(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]
+  if (W >= 8) v = max_u32(v, dpp_move<0x141>(v));   // row_half_mirror
+  if (W >= 16) v = max_u32(v, dpp_move<0x140>(v));  // row_mirror
+  if (W >= 32) v = max_u32(v, static_cast<uint32_t>(__shfl_xor(v, 16, WAVE)));
+  if (W >= 64) v = max_u32(v, static_cast<uint32_t>(__shfl_xor(v, 32, WAVE)));
+  return v;
+}
+
+// What a lane offers to a decision (the largest offer of the group decides what happens):
+enum : uint32_t {
+  OFFER_NONE = 0,    // the lane has no request left
+  OFFER_NO_FIT = 1,  // its request is longer than what is left of the gap
+  // 15 - level (6 .. 14): its request fits
+  OFFER_WAIT = 15,   // its request is not known yet (still being read): nothing is decided in this step
 };
 
 template <int W>
-__device__ __forceinline__ uint64_t group_min_u64(uint64_t v) {
-#pragma unroll
-  for (int m = W >> 1; m >= 1; m >>= 1) { const uint64_t o = shfl_xor_u64(v, m); v = o < v ? o : v; }
-  return v;
-}
-template <int W>
-__device__ __forceinline__ uint32_t group_max_u32(uint32_t v) {
-#pragma unroll
-  for (int m = W >> 1; m >= 1; m >>= 1) { const uint32_t o = __shfl_xor(v, m, WAVE); v = o > v ? o : v; }
-  return v;
-}
-
-__device__ __forceinline__ void pw_store_scalar(const PrioWalkSmem& sm, uint32_t col, uint32_t first, uint32_t count,
+__device__ __forceinline__ void pw_store_scalar(const PrioWalkSmem<W>& sm, uint32_t col, uint32_t first, uint32_t count,
                                                 uint32_t* __restrict__ fill_count, int64_t* __restrict__ filled_ns) {
   for (uint32_t k = 0; k < count; ++k) {
     const uint32_t at = first + k;
-    fill_count[at] = sm.out_c[at & (LW_OUT_CAP - 1)][col];
-    filled_ns[at] = static_cast<int64_t>(sm.out_f[at & (LW_OUT_CAP - 1)][col]);
+    fill_count[at] = sm.out_c[at & (PW_OUT_CAP - 1)][col];
+    filled_ns[at] = static_cast<int64_t>(sm.out_f[at & (PW_OUT_CAP - 1)][col]);
   }
 }
 
@@ -85,12 +106,12 @@ __device__ __forceinline__ void pw_store_scalar(const PrioWalkSmem& sm, uint32_t
 // when that request was enqueued.  The first lane of the group also owns the ring of predicted idle
 // times of the high-priority trace and writes the per-gap results; what describes the open gap (time
 // left, kernels issued, time filled) is kept identically in all lanes of the group.
-// One BestPrioFit decision: every lane whose request fits offers the key (level, -duration); the
-// group's smallest key is the highest level that has a fitting request and there the longest one; among
-// lanes that offered it the request that has waited longest wins, is issued, and the lane's next
-// request is enqueued.  With W == 1 this is the first-in-first-out walk of one queue.
+// One BestPrioFit decision, three reductions over the group: the highest level among the lanes whose
+// request fits (and whether any request is still unknown, does not fit, or is left at all); the longest
+// duration among those lanes; the longest wait among the lanes that offer it.  That lane's request is
+// issued and its next request enqueued.  With W == 1 this is the first-in-first-out walk of one queue.
 template <int W>
-__global__ void __launch_bounds__(LW_THREADS)
+__global__ void __launch_bounds__(PW_THREADS)
 k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task, const uint64_t* __restrict__ lp_off,
           const uint32_t* __restrict__ lp_task, const uint32_t* __restrict__ lp_prio, uint64_t n_scen,
           const uint64_t* __restrict__ gap_off, const uint32_t* __restrict__ lp_e, const uint2* __restrict__ hp_eg,
@@ -98,12 +119,12 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
           uint64_t* __restrict__ placed_out, int64_t* __restrict__ placed_ns_out, uint32_t vec_ok, const Ctrl* ctrl) {
   static_assert(W >= 1 && W <= WAVE && (W & (W - 1)) == 0, "group width");
   extern __shared__ __align__(16) unsigned char pw_raw[];
-  PrioWalkSmem& sm = *reinterpret_cast<PrioWalkSmem*>(pw_raw);
+  PrioWalkSmem<W>& sm = *reinterpret_cast<PrioWalkSmem<W>*>(pw_raw);
   if (ctrl->status || ctrl->wide) return;
   const uint32_t tid = threadIdx.x;
   const uint32_t member = tid & (W - 1);
-  const uint32_t col = tid - member;                       // column of the group's shared rings
-  const uint64_t s = (static_cast<uint64_t>(blockIdx.x) * LW_THREADS + tid) / W;
+  const uint32_t col = tid / W;                            // column of the group's shared rings
+  const uint64_t s = (static_cast<uint64_t>(blockIdx.x) * PW_THREADS + tid) / W;
   const bool valid = s < n_scen;
   const bool lead = valid && member == 0;
   const uint32_t gshift = lane_id() & ~static_cast<uint32_t>(W - 1);
@@ -139,6 +160,7 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
   uint32_t flushed = g_first;        // results below this are in memory
   const uint32_t g_end = g_first + n_gaps;
   uint32_t c = 0, f = 0, rem = 0;
+  const uint32_t offer_fit = 15u - prio;
   uint32_t clock = W;                // enqueue stamps handed out so far (only their order matters: the initial
   uint32_t stamp = member;           // requests are enqueued in list order, before everything else)
   uint64_t placed_ns = 0;
@@ -158,8 +180,8 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const uint32_t at = (hp_req + 2 * k) & (LW_HP_CAP - 1);
-          sm.hp_g[at][tid] = hr[k].y;
-          sm.hp_g[at + 1][tid] = hr[k].w;
+          sm.hp_g[at][col] = hr[k].y;
+          sm.hp_g[at + 1][col] = hr[k].w;
         }
       }
       hp_landed = hp_req + LW_HP_CHUNK;
@@ -193,16 +215,16 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
     if (flushed < g && (flushed & (LW_OUT_CHUNK - 1))) {   // (first results of a scenario, up to a multiple of 8)
       const uint32_t to8 = LW_OUT_CHUNK - (flushed & (LW_OUT_CHUNK - 1));
       const uint32_t cnt = g - flushed < to8 ? g - flushed : to8;
-      if (lead) pw_store_scalar(sm, tid, flushed, cnt, fill_count, filled_ns);
+      if (lead) pw_store_scalar<W>(sm, col, flushed, cnt, fill_count, filled_ns);
       flushed += cnt;
     }
     while (flushed + LW_OUT_CHUNK <= g) {
       if (lead) {
         if (vec_ok) {
-          const uint32_t at = flushed & (LW_OUT_CAP - 1);
+          const uint32_t at = flushed & (PW_OUT_CAP - 1);
           uint32_t cc[LW_OUT_CHUNK], ff[LW_OUT_CHUNK];
 #pragma unroll
-          for (uint32_t k = 0; k < LW_OUT_CHUNK; ++k) { cc[k] = sm.out_c[at + k][tid]; ff[k] = sm.out_f[at + k][tid]; }
+          for (uint32_t k = 0; k < LW_OUT_CHUNK; ++k) { cc[k] = sm.out_c[at + k][col]; ff[k] = sm.out_f[at + k][col]; }
           uint4* oc = reinterpret_cast<uint4*>(fill_count + flushed);
           oc[0] = make_uint4(cc[0], cc[1], cc[2], cc[3]);
           oc[1] = make_uint4(cc[4], cc[5], cc[6], cc[7]);
@@ -210,22 +232,22 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
 #pragma unroll
           for (uint32_t k = 0; k < 4; ++k) of[k] = make_uint4(ff[2 * k], 0u, ff[2 * k + 1], 0u);
         } else {
-          pw_store_scalar(sm, tid, flushed, LW_OUT_CHUNK, fill_count, filled_ns);
+          pw_store_scalar<W>(sm, col, flushed, LW_OUT_CHUNK, fill_count, filled_ns);
         }
       }
       flushed += LW_OUT_CHUNK;
     }
     if (__all(finished)) break;
 
-    // ---- one period, without branches: LW_OPENS times { stage the result of the gap that closed, take
-    // the next high-priority launch and open its gap; LW_TRIES decisions }.  A group whose rings lack an
+    // ---- one period, without branches: PW_OPENS times { stage the result of the gap that closed, take
+    // the next high-priority launch and open its gap; PW_TRIES decisions }.  A group whose rings lack an
     // entry it needs idles in that sub-step. ----
 #pragma unroll
-    for (uint32_t o = 0; o < LW_OPENS; ++o) {
+    for (uint32_t o = 0; o < PW_OPENS; ++o) {
       {
-        // (a staging slot that is written early is simply written again)
-        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
-        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
+        // (a staging slot that is written early is simply written again; all lanes of a group write the same)
+        sm.out_c[g & (PW_OUT_CAP - 1)][col] = c;
+        sm.out_f[g & (PW_OUT_CAP - 1)][col] = f;
         g += pending ? 1u : 0u;
         pending = false;
         const uint32_t G = sm.hp_g[hp_pos & (LW_HP_CAP - 1)][col];
@@ -239,8 +261,8 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
         const bool usable = gap && G >= gap_floor;
         const bool skip = gap && !usable;
         // a skipped gap reports zeros
-        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = 0u;
-        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = 0u;
+        sm.out_c[g & (PW_OUT_CAP - 1)][col] = 0u;
+        sm.out_f[g & (PW_OUT_CAP - 1)][col] = 0u;
         g += skip ? 1u : 0u;
         in_gap = in_gap || usable;
         rem = usable ? G - margin32 : rem;
@@ -249,32 +271,32 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
         finished = finished || at_end || last;
       }
 #pragma unroll
-      for (uint32_t k = 0; k < LW_TRIES; ++k) {
-        const bool exhausted = lp_pos == lp_end;                 // (also: a lane without a task)
-        const bool ready = exhausted || lp_pos < lp_landed;      // the waiting request, if any, is known
-        const bool all_ready = (ballot(ready) & gmask) == gmask;
-        const bool tryq = in_gap && all_ready;
+      for (uint32_t k = 0; k < PW_TRIES; ++k) {
         const uint32_t d = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid];
-        const bool fits = tryq && !exhausted && d <= rem;
-        const uint64_t key = fits ? (static_cast<uint64_t>(prio) << 32) | (0xffffffffu - d) : ~0ull;
-        const uint64_t best = group_min_u64<W>(key);
-        const bool any = best != ~0ull;
-        const bool tie = fits && key == best;
-        const uint32_t age = tie ? clock - stamp : 0u;           // >= 1 for a waiting request
-        const uint32_t oldest = group_max_u32<W>(age);           // (all lanes take part in the exchange)
+        const uint32_t offer = lp_pos == lp_end ? OFFER_NONE                    // (also: a lane without a task)
+                               : lp_pos >= lp_landed ? OFFER_WAIT
+                               : d <= rem ? offer_fit : OFFER_NO_FIT;
+        const uint32_t top = group_max_u32<W>(offer);                           // (all lanes take part)
+        const uint32_t best = in_gap ? top : OFFER_WAIT;
+        const bool any = best - 6u <= 8u;                                       // some request fits: best = 15 - its level
+        const bool at_level = any && offer == best;
+        const uint32_t longest = group_max_u32<W>(at_level ? d + 1u : 0u);      // (durations are below 2^32 - 1)
+        const bool tie = at_level && d + 1u == longest;
+        const uint32_t age = tie ? clock - stamp : 0u;                          // >= 1 for a waiting request
+        const uint32_t oldest = group_max_u32<W>(age);
         const bool win = tie && age == oldest;
-        const uint32_t dd = any ? 0xffffffffu - static_cast<uint32_t>(best) : 0u;
+        const uint32_t dd = any ? longest - 1u : 0u;
         rem -= dd; f += dd;
         c += any ? 1u : 0u;
         lp_pos += win ? 1u : 0u;
         placed_ns += win ? dd : 0u;
         stamp = win ? clock : stamp;                             // the task's following kernel is enqueued now
         clock += any ? 1u : 0u;
-        const bool all_issued = (ballot(lp_pos == lp_end) & gmask) == gmask;
-        const bool emptied = any && all_issued;                  // every queue has been issued
-        const bool close = (tryq && !any) || emptied;
+        // nothing fits: the gap is done; no request left anywhere (seen one decision after the last issue):
+        // so is the scenario
+        const bool close = best <= OFFER_NO_FIT;
         pending = pending || close;
-        finished = finished || emptied;
+        finished = finished || best == OFFER_NONE;
         in_gap = in_gap && !close;
       }
     }
@@ -282,8 +304,8 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
 
   if (!valid) return;
   if (pending) {
-    sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
-    sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
+    sm.out_c[g & (PW_OUT_CAP - 1)][col] = c;
+    sm.out_f[g & (PW_OUT_CAP - 1)][col] = f;
     ++g;
   }
   if (has_entry) {
@@ -292,7 +314,7 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
   }
   if (!lead) return;
   // what is still staged, then zeros for the gaps after the queues ran empty
-  pw_store_scalar(sm, tid, flushed, g - flushed, fill_count, filled_ns);
+  pw_store_scalar<W>(sm, col, flushed, g - flushed, fill_count, filled_ns);
   uint32_t z = g;
   while (z < g_end && (z & (LW_OUT_CHUNK - 1))) { fill_count[z] = 0; filled_ns[z] = 0; ++z; }
   if (vec_ok) {
