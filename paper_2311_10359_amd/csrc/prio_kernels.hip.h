@@ -50,8 +50,18 @@ __global__ void k_pf_scenarios(const uint64_t* __restrict__ off, uint32_t n_task
   if (lane_id() == 0 && k_wave) atomicMax(&ctrl->n_class[3], k_wave);
 }
 
-constexpr int PW_THREADS = 128;
-constexpr uint32_t PW_OPENS = 4, PW_TRIES = 6;   // per period: gaps opened, and decisions per gap opened
+#ifndef FIKIT_PW_THREADS
+#define FIKIT_PW_THREADS 128
+#endif
+#ifndef FIKIT_PW_OPENS
+#define FIKIT_PW_OPENS 3
+#endif
+#ifndef FIKIT_PW_TRIES
+#define FIKIT_PW_TRIES 6
+#endif
+constexpr int PW_THREADS = FIKIT_PW_THREADS;
+constexpr uint32_t PW_OPENS = FIKIT_PW_OPENS, PW_TRIES = FIKIT_PW_TRIES;   // per period: gaps opened, and decisions per gap opened
+static_assert(2 * PW_OPENS + 7 < 16, "the staged results of a period fit the ring");
 constexpr uint32_t PW_OUT_CAP = 16;              // staged results: at most 7 left over + 2 per gap opened in a period
 
 template <int W>

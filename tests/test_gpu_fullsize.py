@@ -193,3 +193,32 @@ def test_config4_batched_gapfill_full_size():
         say(f"  replay, feedback={feedback}: mean delay of the high-priority task {float(rep.hp_delay_ns.double().mean()) / 1e6:.3f} ms; "
             f"sampled scenarios match the oracle")
         del rep
+    del d_gap, got
+    # three low-priority tasks per scenario in priority queues (the configuration bench.py --prio 3 times)
+    k = 3
+    _, p_lo, p_lt, p_lq = traces.prio_scenarios(cfg, k)
+    t0 = time.time()
+    pf = binding.fikit_prio_fill(prof.ids, d_off, prof.rows, prof.task_row_offsets, d_hp, binding.to_device_u64(p_lo, DEV),
+                                 binding.to_device_u32(p_lt, DEV), binding.to_device_u32(p_lq, DEV), d_go,
+                                 margin_ns=cfg.margin_ns, min_gap_ns=cfg.min_gap_ns)
+    say(f"  fikit_prio_fill: {hp.size} scenarios with {k} low-priority tasks each in {time.time() - t0:.2f}s")
+    # properties at full size: what the gaps of a scenario took is what its tasks placed
+    assert torch.equal(pf.fill_count.view(-1, 4095).to(torch.int64).sum(dim=1), pf.lp_placed.view(-1, k).sum(dim=1))
+    assert torch.equal(pf.filled_ns.view(-1, 4095).sum(dim=1), pf.lp_placed_ns.view(-1, k).sum(dim=1))
+    assert bool((pf.lp_placed <= 16384).all()) and bool((pf.filled_ns >= 0).all())
+    for s in scen:
+        tasks = [2 * s] + [int(t) for t in p_lt[k * s:k * s + k]]
+        recs = [traces.task_records(cfg, t) for t in tasks]
+        loc_off = np.zeros(len(recs) + 1, dtype=np.uint64)
+        np.cumsum([r.shape[0] for r in recs], out=loc_off[1:])
+        o_ids, o_rows, o_tro = oracle.profile(np.concatenate(recs), loc_off)
+        one = np.array([0], dtype=np.uint32)
+        exp = oracle.prio_fill(o_ids, loc_off, o_rows, o_tro, one, np.array([0, k], dtype=np.uint64),
+                               np.arange(1, k + 1, dtype=np.uint32), p_lq[k * s:k * s + k], cfg.margin_ns, cfg.min_gap_ns,
+                               traces.gap_offsets(loc_off, one))
+        g0, g1 = int(go[s]), int(go[s + 1])
+        assert np.array_equal(binding.u32_to_numpy(pf.fill_count[g0:g1]), exp[0]), f"scenario {s}"
+        assert np.array_equal(pf.filled_ns[g0:g1].cpu().numpy(), exp[1]), f"scenario {s}"
+        assert np.array_equal(binding.u64_to_numpy(pf.lp_placed[k * s:k * s + k]), exp[2]), f"scenario {s}"
+        assert np.array_equal(pf.lp_placed_ns[k * s:k * s + k].cpu().numpy(), exp[3]), f"scenario {s}"
+    say(f"  priority queues: sampled scenarios {scen} match the oracle")
