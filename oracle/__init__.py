@@ -64,6 +64,8 @@ def _load():
         lib.oracle_replay.restype = ctypes.c_int
         lib.oracle_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, i64, i64, ctypes.c_int, vp, vp, vp,
                                       vp, vp, ctypes.c_int]
+        lib.oracle_pairing_best.restype = ctypes.c_int
+        lib.oracle_pairing_best.argtypes = [vp, vp, u64, u32, vp, vp, vp, vp, vp, vp, vp]
         lib.oracle_prio_fill.restype = ctypes.c_int
         lib.oracle_prio_fill.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, vp, u64, i64, i64, ctypes.c_int, vp, vp, vp,
                                          vp, vp, vp, vp]
@@ -222,3 +224,25 @@ def prio_fill(ids: np.ndarray, task_offsets: np.ndarray, rows: np.ndarray, task_
     if want_issue:
         return fill_count, filled_ns, placed, placed_ns, issue, issue_off
     return fill_count, filled_ns, placed, placed_ns
+
+
+def pairing_best(hp_task: np.ndarray, lp_task: np.ndarray, n_tasks: int, gap_offsets: np.ndarray, filled_ns: np.ndarray,
+                 lp_completion_ns: np.ndarray):
+    """-> (scenario_filled_ns[S], best_scenario[n_tasks], best_lp[n_tasks], best_filled_ns[n_tasks])."""
+    hp = np.ascontiguousarray(hp_task, dtype=np.uint32)
+    lp = np.ascontiguousarray(lp_task, dtype=np.uint32)
+    go = np.ascontiguousarray(gap_offsets, dtype=np.uint64)
+    fn = np.ascontiguousarray(filled_ns, dtype=np.int64)
+    comp = np.ascontiguousarray(lp_completion_ns, dtype=np.int64)
+    s = hp.shape[0]
+    assert lp.shape[0] == s and go.shape[0] == s + 1 and comp.shape[0] == s
+    assert s == 0 or fn.shape[0] >= int(go[-1])
+    total = np.zeros(s, dtype=np.int64)
+    best_s = np.zeros(n_tasks, dtype=np.uint64)
+    best_lp = np.zeros(n_tasks, dtype=np.uint32)
+    best_f = np.zeros(n_tasks, dtype=np.int64)
+    st = _load().oracle_pairing_best(_p(hp), _p(lp), s, n_tasks, _p(go), _p(fn), _p(comp), _p(total), _p(best_s),
+                                     _p(best_lp), _p(best_f))
+    if st != OK:
+        raise OracleError(st)
+    return total, best_s, best_lp, best_f

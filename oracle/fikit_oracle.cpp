@@ -38,6 +38,11 @@
 //                       (its next kernel); per gap the procedure keeps taking, from the highest
 //                       priority level that has a request that fits, the request that fits best
 //                       (the longest), until nothing fits.
+//   oracle_pairing_best - the question of the paper's discussion section ("What Tasks are Suitable
+//                       for Sharing a GPU": measure combinations of tasks beforehand, then find for
+//                       a task its best matching partner in those measurements): over evaluated
+//                       (high-priority, low-priority) combinations, per high-priority task the
+//                       partner whose kernels fill the most of its idle time.
 //
 // All quantities are integers (nanoseconds, counts); nothing is floating point.
 
@@ -489,6 +494,50 @@ int oracle_prio_fill(const uint64_t* ids, const uint64_t* task_offsets, uint32_t
       }
       fill_count[g0 + i] = c;
       filled_ns[g0 + i] = f;
+    }
+  }
+  return OK;
+}
+
+
+// The best partner of every high-priority task among evaluated combinations.
+//
+// Scenario s pairs hp_task[s] with lp_task[s]; its gap fill left filled_ns for its gaps
+// gap_offsets[s] .. gap_offsets[s+1]-1 and the completion time lp_completion_ns[s] of the partner.
+// scenario_filled_ns[s] = the idle time of the high-priority task that the partner's kernels fill = the
+// sum of the scenario's filled_ns (the high-priority task's idle time is the same in all its scenarios,
+// so the largest filled time is also the largest filled fraction).  For every task t that is the
+// high-priority task of at least one scenario: the scenario with the largest filled time; among equal
+// ones the one whose partner completes earliest; among those the first in scenario order.  Outputs per
+// task: that scenario, its partner and its filled time; a task that heads no scenario gets
+// best_scenario = 2^64 - 1, best_lp = 2^32 - 1, best_filled_ns = 0.
+int oracle_pairing_best(const uint32_t* hp_task, const uint32_t* lp_task, uint64_t n_scenarios, uint32_t n_tasks,
+                        const uint64_t* gap_offsets, const int64_t* filled_ns, const int64_t* lp_completion_ns,
+                        int64_t* scenario_filled_ns, uint64_t* best_scenario, uint32_t* best_lp,
+                        int64_t* best_filled_ns) {
+  if (n_scenarios && (!hp_task || !lp_task || !gap_offsets || !lp_completion_ns || !scenario_filled_ns)) return INVALID_ARG;
+  if (n_tasks && (!best_scenario || !best_lp || !best_filled_ns)) return INVALID_ARG;
+  for (uint32_t t = 0; t < n_tasks; ++t) {
+    best_scenario[t] = ~0ull;
+    best_lp[t] = ~0u;
+    best_filled_ns[t] = 0;
+  }
+  if (n_scenarios && gap_offsets[0] != 0) return INVALID_ARG;
+  for (uint64_t s = 0; s < n_scenarios; ++s) {
+    if (hp_task[s] >= n_tasks || lp_task[s] >= n_tasks || gap_offsets[s + 1] < gap_offsets[s]) return INVALID_ARG;
+    int64_t total = 0;
+    for (uint64_t g = gap_offsets[s]; g < gap_offsets[s + 1]; ++g) total += filled_ns[g];
+    scenario_filled_ns[s] = total;
+  }
+  for (uint64_t s = 0; s < n_scenarios; ++s) {
+    const uint32_t t = hp_task[s];
+    const uint64_t b = best_scenario[t];
+    const bool better = b == ~0ull || scenario_filled_ns[s] > scenario_filled_ns[b] ||
+                        (scenario_filled_ns[s] == scenario_filled_ns[b] && lp_completion_ns[s] < lp_completion_ns[b]);
+    if (better) {
+      best_scenario[t] = s;
+      best_lp[t] = lp_task[s];
+      best_filled_ns[t] = scenario_filled_ns[s];
     }
   }
   return OK;

@@ -11,6 +11,8 @@ P6  per-launch measurement and the replay against actual idle times: hand-worked
 P7  several low-priority tasks in priority queues (BestPrioFit): hand-worked cases after the paper's own example
     (tests/golden/p7_prio_fill_hand_worked.json), the one-task case against the pinned gap fill, and every
     decision of the issue log checked against the rule written as a sort key.
+P8  best partner per high-priority task: a hand-worked case (tests/golden/p8_pairing_hand_worked.json), numpy's
+    lexsort on random inputs, and the gap fill of a grid of combinations searched by a plain Python loop.
 """
 import itertools
 import json
@@ -724,6 +726,95 @@ def test_p7_prio_fill_ties_and_rule(cfg):
             oracle.prio_fill(ids, off, rows, tro, hp[:1], np.array([0, 1], dtype=np.uint64), np.array([0], dtype=np.uint32),
                              np.array([bad_prio], dtype=np.uint32), 0, 0, traces.gap_offsets(off, hp[:1]))
         assert e.value.status == oracle.INVALID_ARG
+
+
+# ---------------------------------------------------------------- P8
+NO_SCENARIO, NO_TASK = np.uint64(2**64 - 1), np.uint32(2**32 - 1)
+
+
+def pairing_golden(golden):
+    sc = golden["scenarios"]
+    hp = np.array([x["hp"] for x in sc], dtype=np.uint32)
+    lp = np.array([x["lp"] for x in sc], dtype=np.uint32)
+    go = np.zeros(len(sc) + 1, dtype=np.uint64)
+    np.cumsum([len(x["filled_ns"]) for x in sc], out=go[1:])
+    fn = np.array([v for x in sc for v in x["filled_ns"]], dtype=np.int64)
+    comp = np.array([x["lp_completion_ns"] for x in sc], dtype=np.int64)
+    exp = (np.array(golden["scenario_filled_ns"], dtype=np.int64),
+           np.array([NO_SCENARIO if v < 0 else v for v in golden["best_scenario"]], dtype=np.uint64),
+           np.array([NO_TASK if v < 0 else v for v in golden["best_lp"]], dtype=np.uint32),
+           np.array(golden["best_filled_ns"], dtype=np.int64))
+    return hp, lp, golden["n_tasks"], go, fn, comp, exp
+
+
+def test_p8_pairing_hand_worked(golden_dir):
+    with open(os.path.join(golden_dir, "p8_pairing_hand_worked.json")) as f:
+        golden = json.load(f)
+    hp, lp, n_tasks, go, fn, comp, exp = pairing_golden(golden)
+    got = oracle.pairing_best(hp, lp, n_tasks, go, fn, comp)
+    for a, b in zip(got, exp):
+        assert np.array_equal(a, b)
+
+
+def pairing_by_lexsort(hp, lp, n_tasks, go, fn, comp):
+    total = np.array([fn[int(go[s]):int(go[s + 1])].sum() for s in range(hp.size)], dtype=np.int64)
+    best_s = np.full(n_tasks, NO_SCENARIO, dtype=np.uint64)
+    best_lp = np.full(n_tasks, NO_TASK, dtype=np.uint32)
+    best_f = np.zeros(n_tasks, dtype=np.int64)
+    order = np.lexsort((np.arange(hp.size), comp, -total, hp))      # last key first: task, most filled, earliest done, first
+    first = np.ones(hp.size, dtype=bool)
+    first[1:] = hp[order][1:] != hp[order][:-1]
+    for s in order[first]:
+        best_s[hp[s]], best_lp[hp[s]], best_f[hp[s]] = s, lp[s], total[s]
+    return total, best_s, best_lp, best_f
+
+
+def random_pairing(rng, n_tasks, n_scen, max_gaps, values):
+    hp = rng.integers(0, n_tasks, n_scen).astype(np.uint32)
+    lp = rng.integers(0, n_tasks, n_scen).astype(np.uint32)
+    go = np.zeros(n_scen + 1, dtype=np.uint64)
+    np.cumsum(rng.integers(0, max_gaps + 1, n_scen), out=go[1:])
+    fn = rng.integers(0, values, int(go[-1])).astype(np.int64)
+    comp = rng.integers(0, 4, n_scen).astype(np.int64)            # many ties
+    return hp, lp, go, fn, comp
+
+
+def test_p8_pairing_against_lexsort():
+    rng = np.random.default_rng(8)
+    for n_tasks, n_scen, max_gaps, values in ((1, 1, 0, 1), (7, 200, 3, 2), (50, 40, 9, 1000), (9, 3000, 2, 3), (300, 5000, 40, 10**12)):
+        hp, lp, go, fn, comp = random_pairing(rng, n_tasks, n_scen, max_gaps, values)
+        got = oracle.pairing_best(hp, lp, n_tasks, go, fn, comp)
+        for a, b in zip(got, pairing_by_lexsort(hp, lp, n_tasks, go, fn, comp)):
+            assert np.array_equal(a, b)
+    got = oracle.pairing_best(np.zeros(0, np.uint32), np.zeros(0, np.uint32), 3, np.zeros(1, np.uint64), np.zeros(0, np.int64),
+                              np.zeros(0, np.int64))
+    assert got[0].size == 0 and (got[1] == NO_SCENARIO).all() and (got[2] == NO_TASK).all() and (got[3] == 0).all()
+    with pytest.raises(oracle.OracleError):
+        oracle.pairing_best(np.array([3], np.uint32), np.array([0], np.uint32), 3, np.zeros(2, np.uint64), np.zeros(0, np.int64),
+                            np.zeros(1, np.int64))
+
+
+def test_p8_pairing_of_a_grid_of_gap_fills():
+    cfg = traces.config(1, n_tasks=8, launches=3000)          # 4 x 4 combinations
+    rec, off = traces.build(cfg)
+    ids, rows, tro = oracle.profile(rec, off)
+    hp, lp = traces.scenarios(cfg)
+    assert hp.size == 16
+    go = traces.gap_offsets(off, hp)
+    fc, fn, comp, placed = oracle.gapfill(ids, off, rows, tro, hp, lp, cfg.margin_ns, cfg.min_gap_ns, go)
+    total, best_s, best_lp, best_f = oracle.pairing_best(hp, lp, cfg.n_tasks, go, fn, comp)
+    for t in range(cfg.n_tasks):
+        mine = [s for s in range(hp.size) if hp[s] == t]
+        if not mine:
+            assert best_s[t] == NO_SCENARIO and best_lp[t] == NO_TASK and best_f[t] == 0
+            continue
+        sums = {s: sum(int(v) for v in fn[int(go[s]):int(go[s + 1])]) for s in mine}
+        top = max(sums.values())
+        cands = [s for s in mine if sums[s] == top]
+        soonest = min(int(comp[s]) for s in cands)
+        pick = min(s for s in cands if int(comp[s]) == soonest)
+        assert int(best_s[t]) == pick and int(best_lp[t]) == int(lp[pick]) and int(best_f[t]) == top
+        assert all(int(total[s]) == sums[s] for s in mine)
 
 
 def test_oracle_error_statuses():
