@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--prio", type=int, default=0, metavar="K",
                     help="after the timed steps, also time fikit_prio_fill with K low-priority tasks per scenario "
                          "(reported beside the metric, not part of it)")
+    ap.add_argument("--pairing", action="store_true",
+                    help="after the timed steps, also time fikit_pairing_best over the gap fill's results (reported "
+                         "beside the metric, not part of it)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware counter runs)")
     args = ap.parse_args()
@@ -288,6 +291,38 @@ def main():
         log(f"[bench] replay: {json.dumps(replay)}")
         del d_exec, d_gap
 
+    # ---- best partner per high-priority task over the gap fill's results (beside the metric) -----
+    pairing = None
+    if args.pairing and n_scen:
+        step()                                     # (the replay leg may have overwritten the gap fill's results)
+        pr_out = binding.Pairing(torch.empty(n_scen, dtype=torch.int64, device=dev),
+                                 torch.empty(cfg.n_tasks, dtype=torch.int64, device=dev),
+                                 torch.empty(cfg.n_tasks, dtype=torch.int32, device=dev),
+                                 torch.empty(cfg.n_tasks, dtype=torch.int64, device=dev))
+
+        def pairing_call():
+            binding.fikit_pairing_best(d_hp, d_lp, cfg.n_tasks, d_go, gf_out.filled_ns, gf_out.lp_completion_ns, out=pr_out,
+                                       workspace_buf=ws)
+
+        pairing_call()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        binding.fikit_trace_enable(True)
+        ev[0].record()
+        for _ in range(args.steps):
+            pairing_call()
+        ev[1].record()
+        torch.cuda.synchronize()
+        rt = binding.fikit_trace_read()
+        binding.fikit_trace_enable(False)
+        ms = ev[0].elapsed_time(ev[1]) / args.steps
+        sum_ms = rt["k_pair_sum"][0] / args.steps
+        pairing = {"ms": round(ms, 3), "scenarios_per_s": round(n_scen / (ms * 1e-3), 1),
+                   "k_pair_sum_ms": round(sum_ms, 3), "k_pair_sum_algorithmic_GB/s": round(n_gaps * 8 / (sum_ms * 1e-3) / 1e9, 1),
+                   "tasks_with_a_partner": int((pr_out.best_lp >= 0).sum()),
+                   "mean_best_filled_ms": round(float(pr_out.best_filled_ns[pr_out.best_lp >= 0].double().mean()) / 1e6, 3)}
+        log(f"[bench] pairing: {json.dumps(pairing)}")
+        del pr_out
+
     # ---- several low-priority tasks per scenario in priority queues (beside the metric) ----------
     prio = None
     if args.prio > 0 and n_scen:
@@ -397,6 +432,8 @@ def main():
         out["replay"] = replay
     if prio:
         out["prio_fill"] = prio
+    if pairing:
+        out["pairing"] = pairing
     # whole calls against the HBM peak: counter-measured bytes of every kernel of the call / the call's time
     calls = stored_call_traffic(name)
     if calls:

@@ -276,6 +276,36 @@ int fikit_prio_fill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint3
                     int64_t* d_lp_placed_ns, void* d_workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/* Bytes of device workspace fikit_pairing_best needs (0 on size overflow). */
+size_t fikit_pairing_workspace_bytes(uint32_t n_tasks);
+
+/*
+ * Which low-priority partner suits each high-priority task best, among combinations that have been
+ * evaluated with fikit_gapfill (the paper's discussion section, "What Tasks are Suitable for Sharing a
+ * GPU": measure combinations beforehand, then look a task's best matching partner up).
+ *
+ *   d_hp_task, d_lp_task [n_scenarios]  the combinations (any number per task, in any order).
+ *   d_gap_offsets, d_filled_ns, d_lp_completion_ns   fikit_gapfill's layout and outputs for them.
+ *   d_scenario_filled_ns [n_scenarios] receives the idle time of the high-priority task that the
+ *                      partner's kernels fill: the sum of the scenario's d_filled_ns (modulo 2^64).
+ *   d_best_scenario, d_best_lp, d_best_filled_ns [n_tasks]  per task t that is the high-priority task of
+ *                      at least one scenario: the scenario with the largest filled time (= the largest
+ *                      filled fraction, the task's idle time being the same in all its scenarios); among
+ *                      equal ones the one whose partner completes earliest; among those the first in
+ *                      scenario order; its partner; its filled time.  Other tasks get 2^64 - 1,
+ *                      2^32 - 1 and 0.
+ *   d_workspace        256-byte aligned, at least fikit_pairing_workspace_bytes(n_tasks) bytes.
+ *
+ * Buffers are the caller's; the call synchronises the stream.
+ * Errors: INVALID_ARG (also: task index out of range, gap offsets not monotone),
+ * WORKSPACE_TOO_SMALL, HIP_ERROR.
+ */
+int fikit_pairing_best(const uint32_t* d_hp_task, const uint32_t* d_lp_task, uint64_t n_scenarios,
+                       uint32_t n_tasks, const uint64_t* d_gap_offsets, const int64_t* d_filled_ns,
+                       const int64_t* d_lp_completion_ns, int64_t* d_scenario_filled_ns,
+                       uint64_t* d_best_scenario, uint32_t* d_best_lp, int64_t* d_best_filled_ns,
+                       void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 const char* fikit_status_string(int status);
 int fikit_version(void);
 

@@ -27,7 +27,8 @@ FIKIT_PREDICT_P50, FIKIT_PREDICT_MEAN = 0, 1
 
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
            "fikit_gapfill", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
-           "fikit_gapfill_replay", "fikit_prio_fill_workspace_bytes", "fikit_prio_fill", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
+           "fikit_gapfill_replay", "fikit_prio_fill_workspace_bytes", "fikit_prio_fill", "fikit_pairing_workspace_bytes",
+           "fikit_pairing_best", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
 
 # Layout of a profile row as seen from numpy (128 bytes; see fikit_row in fikit.h).
 STATS_DTYPE = np.dtype([("count", "<u8"), ("sum", "<u8"), ("min", "<i8"), ("max", "<i8"),
@@ -91,6 +92,10 @@ def load() -> ctypes.CDLL:
         lib.fikit_prio_fill.restype = ctypes.c_int
         lib.fikit_prio_fill.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, vp, u64, ctypes.POINTER(_GapfillParams), vp,
                                         vp, vp, vp, vp, vp, sz, vp]
+        lib.fikit_pairing_workspace_bytes.restype = sz
+        lib.fikit_pairing_workspace_bytes.argtypes = [u32]
+        lib.fikit_pairing_best.restype = ctypes.c_int
+        lib.fikit_pairing_best.argtypes = [vp, vp, u64, u32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.fikit_gapfill_replay.restype = ctypes.c_int
         lib.fikit_gapfill_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, ctypes.POINTER(_ReplayParams), vp,
                                              vp, vp, vp, vp, vp, sz, vp]
@@ -360,6 +365,44 @@ def fikit_prio_fill(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.T
                                  _ptr(workspace_buf), workspace_buf.numel(), _stream_handle(stream))
     if st != FIKIT_OK:
         raise FikitError(st, "fikit_prio_fill")
+    return out
+
+
+class Pairing(NamedTuple):
+    scenario_filled_ns: torch.Tensor  # int64 [S]
+    best_scenario: torch.Tensor       # int64 view of uint64 [n_tasks] (-1 = the task heads no scenario)
+    best_lp: torch.Tensor             # int32 view of uint32 [n_tasks] (-1 = none)
+    best_filled_ns: torch.Tensor      # int64 [n_tasks]
+
+
+def fikit_pairing_workspace_bytes(n_tasks: int) -> int:
+    return int(load().fikit_pairing_workspace_bytes(n_tasks))
+
+
+def fikit_pairing_best(hp_task: torch.Tensor, lp_task: torch.Tensor, n_tasks: int, gap_offsets: torch.Tensor,
+                       filled_ns: torch.Tensor, lp_completion_ns: torch.Tensor, *, out: Optional[Pairing] = None,
+                       workspace_buf: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> Pairing:
+    """hp_task, lp_task: int32 [S]; gap_offsets: int64 [S+1]; filled_ns: int64 [n_gaps]; lp_completion_ns: int64 [S]."""
+    lib = load()
+    dev = hp_task.device
+    s = hp_task.numel()
+    assert hp_task.dtype == torch.int32 and lp_task.dtype == torch.int32 and lp_task.numel() == s
+    assert gap_offsets.dtype == torch.int64 and gap_offsets.numel() == s + 1
+    assert filled_ns.dtype == torch.int64 and lp_completion_ns.dtype == torch.int64 and lp_completion_ns.numel() == s
+    for t in (hp_task, lp_task, gap_offsets, filled_ns, lp_completion_ns):
+        assert t.is_contiguous() and t.device == dev
+    if out is None:
+        out = Pairing(torch.empty(s, dtype=torch.int64, device=dev), torch.empty(n_tasks, dtype=torch.int64, device=dev),
+                      torch.empty(n_tasks, dtype=torch.int32, device=dev), torch.empty(n_tasks, dtype=torch.int64, device=dev))
+    if workspace_buf is None:
+        workspace_buf = workspace(fikit_pairing_workspace_bytes(n_tasks), dev)
+    with torch.cuda.device(dev):
+        st = lib.fikit_pairing_best(_ptr(hp_task), _ptr(lp_task), s, n_tasks, _ptr(gap_offsets), _ptr(filled_ns),
+                                    _ptr(lp_completion_ns), _ptr(out.scenario_filled_ns), _ptr(out.best_scenario),
+                                    _ptr(out.best_lp), _ptr(out.best_filled_ns), _ptr(workspace_buf), workspace_buf.numel(),
+                                    _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_pairing_best")
     return out
 
 

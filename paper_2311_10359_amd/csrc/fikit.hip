@@ -12,6 +12,7 @@
 #include "task_kernels.hip.h"
 #include "msd_kernels.hip.h"
 #include "prio_kernels.hip.h"
+#include "pairing_kernels.hip.h"
 
 namespace {
 
@@ -755,6 +756,66 @@ int fikit_prio_fill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint3
   if (int rc2 = status_from_bits(h.status)) return rc2;
   // (the walk has not run in this case: its outputs are undefined)
   return h.wide ? FIKIT_UNSUPPORTED : FIKIT_OK;
+}
+
+size_t fikit_pairing_workspace_bytes(uint32_t n_tasks) {
+  Carver c;
+  c.take(256);
+  c.take(static_cast<uint64_t>(n_tasks) * 8);
+  return static_cast<size_t>(c.at);
+}
+
+int fikit_pairing_best(const uint32_t* d_hp_task, const uint32_t* d_lp_task, uint64_t n_scenarios, uint32_t n_tasks,
+                       const uint64_t* d_gap_offsets, const int64_t* d_filled_ns, const int64_t* d_lp_completion_ns,
+                       int64_t* d_scenario_filled_ns, uint64_t* d_best_scenario, uint32_t* d_best_lp,
+                       int64_t* d_best_filled_ns, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!d_workspace || n_scenarios >= (1ull << 31)) return FIKIT_INVALID_ARG;   // (one workgroup per scenario)
+  if (n_tasks > 0 && (!d_best_scenario || !d_best_lp || !d_best_filled_ns)) return FIKIT_INVALID_ARG;
+  if (n_scenarios > 0 &&
+      (!d_hp_task || !d_lp_task || !d_gap_offsets || !d_lp_completion_ns || !d_scenario_filled_ns || n_tasks == 0))
+    return FIKIT_INVALID_ARG;
+  if (!aligned(d_hp_task, 4) || !aligned(d_lp_task, 4) || !aligned(d_gap_offsets, 8) || !aligned(d_filled_ns, 8) ||
+      !aligned(d_lp_completion_ns, 8) || !aligned(d_scenario_filled_ns, 8) || !aligned(d_best_scenario, 8) ||
+      !aligned(d_best_lp, 4) || !aligned(d_best_filled_ns, 8) || !aligned(d_workspace, 256))
+    return FIKIT_INVALID_ARG;
+  if (workspace_bytes < fikit_pairing_workspace_bytes(n_tasks)) return FIKIT_WORKSPACE_TOO_SMALL;
+  if (n_tasks == 0) return FIKIT_OK;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint64_t n_gaps = 0;
+  if (n_scenarios > 0) {
+    FIKIT_HIP(hipMemcpyAsync(&n_gaps, d_gap_offsets + n_scenarios, 8, hipMemcpyDeviceToHost, st));
+    FIKIT_HIP(hipStreamSynchronize(st));
+    if (n_gaps >= MAX_ELEMS || (n_gaps > 0 && !d_filled_ns)) return FIKIT_INVALID_ARG;
+  }
+  unsigned char* ws = static_cast<unsigned char*>(d_workspace);
+  Carver c;
+  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
+  long long* soonest = reinterpret_cast<long long*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 8));
+  long long* top_filled = reinterpret_cast<long long*>(d_best_filled_ns);
+  unsigned long long* best_scenario = reinterpret_cast<unsigned long long*>(d_best_scenario);
+
+  Tracer tr(st);
+  tr.mark("pair_setup");
+  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+  hipLaunchKernelGGL(k_pair_init, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, n_tasks, top_filled, soonest, best_scenario);
+  if (n_scenarios > 0) {
+    tr.mark("k_pair_sum");
+    hipLaunchKernelGGL(k_pair_sum, dim3(static_cast<uint32_t>(n_scenarios)), dim3(PAIR_THREADS), 0, st, d_hp_task, d_lp_task,
+                       n_scenarios, n_tasks, d_gap_offsets, n_gaps, d_filled_ns, d_scenario_filled_ns, top_filled, ctrl);
+    tr.mark("k_pair_pick");
+    hipLaunchKernelGGL(k_pair_soonest, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_hp_task, n_scenarios,
+                       d_scenario_filled_ns, d_lp_completion_ns, top_filled, soonest, ctrl);
+    hipLaunchKernelGGL(k_pair_first, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_hp_task, n_scenarios,
+                       d_scenario_filled_ns, d_lp_completion_ns, top_filled, soonest, best_scenario, ctrl);
+  }
+  hipLaunchKernelGGL(k_pair_finish, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, n_tasks, d_lp_task, best_scenario,
+                     d_best_lp, top_filled, ctrl);
+  FIKIT_HIP(hipGetLastError());
+  tr.mark("host_sync");
+  Ctrl h{};
+  if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+  return status_from_bits(h.status);
 }
 
 }  // extern "C"

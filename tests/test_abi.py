@@ -81,6 +81,11 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.fikit_prio_fill(fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, ctypes.byref(p), fake, fake, fake, fake,
                                fake, fake, 1 << 20, null) == -1
     assert lib.fikit_prio_fill_workspace_bytes(1 << 33, 1, 1) == 0
+    assert lib.fikit_pairing_best(fake, fake, 1, 1, fake, fake, null, fake, fake, fake, fake, fake, 1 << 20, null) == -1
+    assert lib.fikit_pairing_best(fake, fake, 1, 1, fake, fake, fake, fake, odd, fake, fake, fake, 1 << 20, null) == -1
+    assert lib.fikit_pairing_best(fake, fake, 1, 1, fake, fake, fake, fake, fake, fake, fake, fake, 16, null) == -2
+    assert lib.fikit_pairing_best(fake, fake, 1 << 31, 1, fake, fake, fake, fake, fake, fake, fake, fake, 1 << 20, null) == -1
+    assert lib.fikit_pairing_workspace_bytes(1000) >= 8000
     assert lib.fikit_measure(fake, 10, null, 1, fake, fake, fake, 256, null) == -1
     assert lib.fikit_measure(fake, 10, fake, 1, fake, fake, fake, 16, null) == -2
     assert lib.fikit_measure_workspace_bytes() == 256
