@@ -20,12 +20,17 @@
  *                    long as its predicted duration does not exceed what is left of the gap
  *                    (Algorithm 2 with a single waiting request is first-in-first-out).
  *
+ * Beside these two: fikit_measure (the per-launch measurements themselves), fikit_gapfill_replay (the
+ * fill replayed against the idle times that occurred, without and with real-time feedback),
+ * fikit_prio_fill (several low-priority tasks per scenario in the priority queues of Algorithm 2) and
+ * fikit_pairing_best (the best partner of every high-priority task among evaluated combinations).
+ *
  * Conventions
  *   - d_* arguments are device pointers, h_* are host pointers.  The caller owns every buffer,
  *     including the workspace; the library allocates no device memory and keeps no state
  *     between calls.  Inputs are left untouched.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default
- *     stream).  Both calls synchronise that stream before they return, so outputs and the
+ *     stream).  Every call synchronises that stream before it returns, so outputs and the
  *     returned status are final on return.
  *   - Return value: FIKIT_OK or a negative fikit_status.  Nothing aborts or throws.  After an
  *     error the contents of the output buffers are unspecified.
