@@ -175,3 +175,21 @@ def test_prio_wide_predictions_are_refused():
                                 binding.to_device_u32(np.ones(hp.size, np.uint32), DEV),
                                 binding.to_device_u64(traces.gap_offsets(off, hp), DEV), margin_ns=0, min_gap_ns=0)
     assert e.value.status == binding.FIKIT_UNSUPPORTED
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_prio_seeded_sweep(seed):
+    """Random task shapes, list lengths around the group-width borders, margins and thresholds."""
+    rng = np.random.default_rng(1000 + seed)
+    rec, off, _ = mixed_trace(300 + seed, 20, 4097, wide=False)
+    prof, d_off, o_prof = check_profile(rec, off)
+    for _ in range(3):
+        k_max = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17, 32, 33, 64]))
+        n_scen = int(rng.integers(1, 400)) if k_max <= 9 else int(rng.integers(1, 40))
+        hp, lo, lt, lq = prio_lists(rng, off.size - 1, n_scen, k_max, same_level=float(rng.choice([0.0, 0.5, 1.0])))
+        margin = int(rng.choice([0, 1, 500, 10**6]))
+        min_gap = int(rng.choice([0, 3, 10**4, 10**9]))
+        predictor = int(rng.integers(0, 2))
+        print(f"seed {seed}: up to {k_max} tasks, {n_scen} scenarios, margin {margin}, min gap {min_gap}, predictor {predictor}",
+              flush=True)
+        check_prio(prof, d_off, off, o_prof, hp, lo, lt, lq, margin, min_gap, predictor=predictor)
