@@ -433,9 +433,21 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     tr.mark("k_stats_small");
     hipLaunchKernelGGL(k_stats_small, dim3(blocks_for(n_heads, 4)), dim3(256), 0, st, seg_start, n_heads, d_task_offsets,
                        n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out);
+    // rows with long segments: by work list (the staging areas e1 / g1 are free once the rows are gathered)
+    tr.mark("k_stats_lists");
+    uint32_t* rlist = reinterpret_cast<uint32_t*>(e1);
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, &ctrl->n_class[0], static_cast<uint64_t>(2), 0u);
+    hipLaunchKernelGGL(k_stats_lists, dim3(blocks_for(n_heads, 256)), dim3(256), 0, st, seg_start, n_heads, d_task_offsets,
+                       n_tasks, rlist, ctrl);
     tr.mark("k_stats_big");
-    hipLaunchKernelGGL(k_stats_big, dim3(static_cast<uint32_t>(n_heads)), dim3(BIG_THREADS), 0, st, seg_start, n_heads,
-                       d_task_offsets, n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out);
+    const uint32_t big_grid = static_cast<uint32_t>(n_heads < 4096 ? n_heads : 4096);
+    const uint32_t huge_grid = static_cast<uint32_t>(n_heads < 512 ? n_heads : 512);
+    hipLaunchKernelGGL(k_stats_big<BIG_THREADS>, dim3(big_grid), dim3(BIG_THREADS), 0, st, seg_start, n_heads, d_task_offsets,
+                       n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out, rlist, &ctrl->n_class[0], 0u);
+    tr.mark("k_stats_huge");
+    hipLaunchKernelGGL(k_stats_big<HUGE_THREADS>, dim3(huge_grid), dim3(HUGE_THREADS), 0, st, seg_start, n_heads,
+                       d_task_offsets, n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out, rlist, &ctrl->n_class[1],
+                       1u);
   }
   FIKIT_HIP(hipGetLastError());
   FIKIT_HIP(hipStreamSynchronize(st));
