@@ -29,7 +29,8 @@ enum : uint32_t {
 // Control block at the start of the workspace; cleared by k_clear_ctrl at the start of a call.
 struct Ctrl {
   uint32_t status;        // ERR_* bits
-  uint32_t wide;          // gap fill: a prediction did not fit 32 bits, the 64-bit kernels take over
+  uint32_t wide;          // gap fill: a prediction did not fit 32 bits, the 64-bit kernels take over;
+                          // profile: the short sort left some task's keys out of order
   uint64_t n_big_tiles;   // tiles of the tasks sorted by the multi-pass path
   uint64_t n_rows;        // number of (task, ID) rows
   uint64_t n_general;     // tasks that take the general sort-based path

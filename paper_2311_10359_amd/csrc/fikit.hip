@@ -376,11 +376,14 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     hipLaunchKernelGGL(k_leaf_sort, dim3(xcd_grid(n_tasks)), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, gflag, ids,
                        k2, e0, g0, ctrl);
     FIKIT_HIP(hipGetLastError());
-    if (n_big_tiles > 0) {
-      const uint64_t* kin = ids;
+    // Eight stable passes over the eight key bytes sort any keys.  Kernel IDs are hashes: a task's distinct IDs
+    // almost always differ in their upper four bytes already, so four passes over those are tried first; the
+    // head search below also notices keys that are still out of order, and then all eight passes are run on
+    // what the four left (any order of the (key, values) triples is a valid start).
+    auto sort_passes = [&](const uint64_t* kin, int64_t* ein, int64_t* gin, int first_byte) -> int {
       uint64_t* kout = k1;
-      int64_t *ein = e0, *eout = e1, *gin = g0, *gout = g1;
-      for (int pass = 0; pass < 8; ++pass) {
+      int64_t *eout = (ein == e0) ? e1 : e0, *gout = (gin == g0) ? g1 : g0;
+      for (int pass = first_byte; pass < 8; ++pass) {
         const int shift = 8 * pass;
         tr.mark("k_tile_hist");
         hipLaunchKernelGGL(k_tile_hist, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(256), 0, st, d_task_offsets, n_tasks,
@@ -396,13 +399,25 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
         int64_t* t = ein; ein = eout; eout = t;
         t = gin; gin = gout; gout = t;
       }
+      return FIKIT_OK;   // (an even number of passes: keys end in k2, values in the arrays they started in)
+    };
+    auto find_heads = [&]() -> int {
+      tr.mark("heads");
+      hipLaunchKernelGGL(k_head_bits, dim3(blocks_for(n, 256)), dim3(256), 0, st, k2, n, d_task_offsets, n_tasks, gflag, bits, ctrl);
+      hipLaunchKernelGGL(k_popcount_words, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, L.n_words, word_prefix);
+      if (int rc = scan_u32(word_prefix, L.n_words, sums, &ctrl->n_heads, st)) return rc;
+      tr.mark("host_sync");
+      return read_ctrl(ctrl, &h, st);
+    };
+    if (n_big_tiles > 0)
+      if (int rc = sort_passes(ids, e0, g0, 4)) return rc;
+    if (int rc = find_heads()) return rc;
+    if (h.wide) {
+      hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, &ctrl->wide, static_cast<uint64_t>(1), 0u);
+      if (int rc = sort_passes(k2, e0, g0, 0)) return rc;
+      if (int rc = find_heads()) return rc;
+      if (h.wide) return FIKIT_HIP_ERROR;   // cannot happen: eight passes sort
     }
-    tr.mark("heads");
-    hipLaunchKernelGGL(k_head_bits, dim3(blocks_for(n, 256)), dim3(256), 0, st, k2, n, d_task_offsets, n_tasks, gflag, bits);
-    hipLaunchKernelGGL(k_popcount_words, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, L.n_words, word_prefix);
-    if (int rc = scan_u32(word_prefix, L.n_words, sums, &ctrl->n_heads, st)) return rc;
-    tr.mark("host_sync");
-    if (int rc = read_ctrl(ctrl, &h, st)) return rc;
     n_heads = h.n_heads;
     tr.mark("heads");
     hipLaunchKernelGGL(k_general_row_counts, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, gflag,

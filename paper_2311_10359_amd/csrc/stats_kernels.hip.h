@@ -11,10 +11,11 @@ namespace fikit {
 // ------------------------------------------------------------------ segment heads
 // One bit per sorted position: set where a new (task, ID) group of a general-path task begins
 // (positions of other tasks give 0).  A wave produces one 64-bit word with a ballot of "I start a
-// task, or my key differs from my left neighbour's".
+// task, or my key differs from my left neighbour's".  A key below its left neighbour's inside a task
+// means the task is not sorted (yet): ctrl->wide is raised.
 __global__ void __launch_bounds__(256)
 k_head_bits(const uint64_t* __restrict__ key, uint64_t n, const uint64_t* __restrict__ off, uint32_t n_tasks,
-            const uint32_t* __restrict__ gflag, uint64_t* __restrict__ bits) {
+            const uint32_t* __restrict__ gflag, uint64_t* __restrict__ bits, Ctrl* ctrl) {
   const uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
   const uint64_t first = i - lane_id();  // the wave's first position (same in every lane)
   bool head = false;
@@ -22,7 +23,10 @@ k_head_bits(const uint64_t* __restrict__ key, uint64_t n, const uint64_t* __rest
     uint32_t t = task_of(off, n_tasks, first);
     if (i < n) {
       while (off[t + 1] <= i) ++t;      // step over task boundaries inside the wave's window
-      if (gflag[t]) head = (i == off[t]) || (key[i] != key[i - 1]);
+      if (gflag[t]) {
+        head = (i == off[t]) || (key[i] != key[i - 1]);
+        if (i != off[t] && key[i] < key[i - 1]) atomicOr(&ctrl->wide, 1u);
+      }
     }
   }
   const uint64_t word = ballot(head);

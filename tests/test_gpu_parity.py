@@ -327,3 +327,53 @@ def test_error_statuses():
     with pytest.raises(binding.FikitError) as e:
         binding.fikit_gapfill(prof.ids, d_off, prof.rows, prof.task_row_offsets, *args, margin_ns=-1, min_gap_ns=0)
     assert e.value.status == binding.FIKIT_INVALID_ARG
+
+
+def fnv1a64_rows(rows32):
+    """Kernel IDs of records given as an [N, 32] byte array (the published FNV-1a-64 recurrence, vectorised)."""
+    h = np.full(rows32.shape[0], 0xcbf29ce484222325, dtype=np.uint64)
+    prime = np.uint64(0x100000001b3)
+    with np.errstate(over="ignore"):
+        for k in range(32):
+            h = (h ^ rows32[:, k].astype(np.uint64)) * prime
+    return h
+
+
+def test_general_path_ids_that_share_their_upper_half():
+    """The sort of the general path first orders the upper four bytes of the IDs only; IDs that agree there and
+    arrive in the wrong order must be noticed and sorted in full."""
+    rng = np.random.default_rng(3)
+    cand = np.zeros(400000, dtype=traces.LAUNCH_DTYPE)
+    cand["name_id"] = rng.integers(0, 2**32, cand.shape[0], dtype=np.uint64).astype(np.uint32)
+    cand["grid"] = rng.integers(1, 2**20, (cand.shape[0], 3))
+    cand["block"] = rng.integers(1, 1025, (cand.shape[0], 3))
+    ids = fnv1a64_rows(cand.view(np.uint8).reshape(-1, 64)[:, :32])
+    assert int(ids[0]) == oracle.kernel_id(cand[:1].tobytes()[:32])
+    order = np.argsort(ids >> np.uint64(32), kind="stable")
+    hi = (ids >> np.uint64(32))[order]
+    twin = np.nonzero((hi[1:] == hi[:-1]) & (ids[order][1:] != ids[order][:-1]))[0]
+    assert twin.size > 0, "no two candidates share the upper half of their ID"
+    a, b = int(order[twin[0]]), int(order[twin[0] + 1])
+    big, small = (a, b) if ids[a] > ids[b] else (b, a)
+    n = 40000
+    # one ID with 30,000 launches (no unit holds it: the whole task takes the general path), the twins in
+    # between, the one with the larger ID first, and a few hundred other IDs
+    pick = rng.integers(1000, 1300, n)
+    pick[rng.random(n) < 0.75] = 7
+    pick[100:200:2] = big
+    pick[101:200:2] = small
+    rec = np.zeros(n + 50, dtype=traces.LAUNCH_DTYPE)
+    rec[:n] = cand[pick]
+    rec[n:] = cand[5]                                       # a second, short task
+    ex = rng.integers(1, 50000, n + 50)
+    gp = rng.integers(0, 30000, n + 50)
+    start = np.cumsum(ex + gp) - (ex + gp)
+    rec["start_ns"], rec["end_ns"] = start, start + ex
+    binding.fikit_trace_enable(True)
+    try:
+        check_profile(rec, np.array([0, n, n + 50], dtype=np.uint64))
+        passes = binding.fikit_trace_read()["k_tile_scatter"][1]
+    finally:
+        binding.fikit_trace_enable(False)
+    # (one more pass belongs to the partition by the top ID bits that was tried first)
+    assert passes in (12, 13), f"{passes} scatter passes: the four-pass sort was not followed by the full one"
