@@ -282,6 +282,8 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   auto mid_u = k_task_fused<512, 16, 256, 7168, 4, true, 4>;
   auto medium_u = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, true, 4, FUSE_M_ESTATS>;
   constexpr size_t mid_lds = sizeof(FusedSmem<512, 256, 7168>);
+  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tile_scatter), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                static_cast<int>(sizeof(TileSmem))));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
   constexpr size_t small_lds = sizeof(FusedSmem<FUSE_S_THREADS, 256, 7168>),
@@ -333,7 +335,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     hipLaunchKernelGGL(k_msd_units, dim3(n_tasks), dim3(WAVE), 0, st, d_task_offsets, n_tasks, is_long, mtiles, hist,
                        ustart, ulen, utask, udcount, mflag, gflag, lists, static_cast<uint32_t>(n_units), ctrl);
     tr.mark("k_tile_scatter");
-    hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets, n_tasks,
+    hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(TILE_THREADS), sizeof(TileSmem), st, d_task_offsets, n_tasks,
                        mtiles, hist, 0, mflag, FUSE_SMALL_MAX, ids, k1, e0, e1, g0, g1);
     FusedArgs ua = fa;
     ua.ustart = ustart; ua.ulen = ulen; ua.utask = utask; ua.skey = k1; ua.mflag = mflag; ua.dcount = udcount;
@@ -391,7 +393,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
         tr.mark("scan_tile_hist");
         if (int rc = scan_u32(hist, n_big_tiles * 256, sums, nullptr, st)) return rc;
         tr.mark("k_tile_scatter");
-        hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), 0, st, d_task_offsets,
+        hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), sizeof(TileSmem), st, d_task_offsets,
                            n_tasks, tiles, hist, shift, static_cast<const uint32_t*>(nullptr), 0u, kin, kout, ein, eout, gin, gout);
         FIKIT_HIP(hipGetLastError());
         kin = kout;

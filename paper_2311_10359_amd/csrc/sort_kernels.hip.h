@@ -68,8 +68,14 @@ constexpr int LEAF_THREADS = 1024;
 constexpr int LEAF_WAVES = LEAF_THREADS / WAVE;
 constexpr int LEAF_KPT = LEAF / LEAF_THREADS;
 
-constexpr uint32_t TILE = 4096;        // records per tile of the multi-pass path
-constexpr int TILE_THREADS = 512;
+#ifndef FIKIT_TILE
+#define FIKIT_TILE 8192
+#endif
+#ifndef FIKIT_TILE_THREADS
+#define FIKIT_TILE_THREADS 512
+#endif
+constexpr uint32_t TILE = FIKIT_TILE;  // records per tile of the multi-pass path
+constexpr int TILE_THREADS = FIKIT_TILE_THREADS;
 constexpr int TILE_WAVES = TILE_THREADS / WAVE;
 constexpr int TILE_KPT = TILE / TILE_THREADS;
 
@@ -273,7 +279,8 @@ k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_
                const uint64_t* __restrict__ key_in, uint64_t* __restrict__ key_out,
                const int64_t* __restrict__ exec_in, int64_t* __restrict__ exec_out,
                const int64_t* __restrict__ gap_in, int64_t* __restrict__ gap_out) {
-  __shared__ TileSmem sm;
+  extern __shared__ __align__(16) unsigned char tile_raw[];
+  TileSmem& sm = *reinterpret_cast<TileSmem*>(tile_raw);
   const uint32_t j = blockIdx.x;
   const uint32_t t = task_of_tile(tile_prefix, n_tasks, j);
   const uint32_t tp = tile_prefix[t];
