@@ -564,7 +564,7 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
                      d_task_row_offsets, role, glists, pe, pg, open, only_if_wide, static_cast<uint32_t>(h_params->predictor), ctrl);
 #ifndef FIKIT_WALK_GW
 #define FIKIT_WALK_GW 64
-#define FIKIT_WALK_WINDOW false
+#define FIKIT_WALK_WINDOW true
 #endif
   constexpr int GW = FIKIT_WALK_GW;
   tr.mark("k_gf_walk");

@@ -240,9 +240,14 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
     win1 = GW + gl < L ? pe[l0 + GW + gl] : INT64_MAX;
   }
 
+  // The predicted gaps of the next round are read while this round is worked on; without the window the prefix
+  // sum at the head of the queue is read again only when the head has moved.
+  int64_t next_g = gl < n_gaps ? pg[h0 + gl] : 0;
+  int64_t head_pe = (!WINDOW && L > 0) ? pe[l0] : INT64_MAX;
   for (uint64_t i0 = 0; i0 < n_gaps; i0 += GW) {
     const uint64_t mine = i0 + gl;
-    const int64_t my_g = mine < n_gaps ? pg[h0 + mine] : 0;
+    const int64_t my_g = next_g;
+    next_g = mine + GW < n_gaps ? pg[h0 + mine + GW] : 0;
     uint32_t my_c = 0;
     int64_t my_f = 0;
     const uint32_t steps = static_cast<uint32_t>(n_gaps - i0 < GW ? n_gaps - i0 : GW);
@@ -250,7 +255,10 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
     while (k < steps) {
       // Gaps that the head of the queue does not fit into take nothing and change nothing: every lane tests
       // its own gap against the head, and the group goes straight to the first gap that takes something.
-      const int64_t head = p < L ? pe[l0 + p] - consumed : INT64_MAX;
+      // (with the window the prefix sum at the head comes from the lane that holds entry p: wb <= p < wb + GW)
+      const int64_t head_abs = WINDOW ? static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(win0), gbase + static_cast<uint32_t>(p - wb)))
+                                      : head_pe;
+      const int64_t head = p < L ? head_abs - consumed : INT64_MAX;
       const bool takes = gl >= k && gl < steps && my_g >= min_gap && my_g >= margin && head <= my_g - margin;
       const uint64_t tb = (ballot(takes) >> gbase) & gmask;
       if (tb == 0) break;
@@ -289,6 +297,7 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
         f = last_fit - consumed;
         consumed = last_fit;
         p += c;
+        if (!WINDOW && c > 0) head_pe = p < L ? pe[l0 + p] : INT64_MAX;
         if (p == L && c > 0 && !done) {
           completion = open[h0 + i0 + k] + f;
           done = true;
