@@ -163,8 +163,23 @@ def test_config4_batched_gapfill_full_size():
         assert np.array_equal(got.filled_ns[g0:g1].cpu().numpy(), exp[1]), f"scenario {s}"
         assert int(got.lp_completion_ns[s]) == int(exp[2][0]) and int(got.lp_placed[s]) == int(exp[3][0])
     say(f"  sampled scenarios {scen} match the oracle")
-    # replay against the actual idle times, without and with real-time feedback
     d_hp, d_lp, d_go = binding.to_device_u32(hp, DEV), binding.to_device_u32(lp, DEV), binding.to_device_u64(go, DEV)
+    # best partner per high-priority task over these results: every task heads exactly one scenario here, so the
+    # search must return that scenario, and the per-scenario sums must be the row sums of the filled times
+    pair = binding.fikit_pairing_best(d_hp, d_lp, cfg.n_tasks, d_go, got.filled_ns, got.lp_completion_ns)
+    torch.cuda.synchronize()
+    assert torch.equal(pair.scenario_filled_ns, got.filled_ns.view(-1, 4095).sum(dim=1))
+    heads = torch.from_numpy(hp.astype(np.int64)).to(DEV)
+    assert torch.equal(pair.best_scenario[heads], torch.arange(hp.size, device=DEV))
+    assert torch.equal(pair.best_lp[heads].to(torch.int64), torch.from_numpy(lp.astype(np.int64)).to(DEV))
+    assert torch.equal(pair.best_filled_ns[heads], pair.scenario_filled_ns)
+    others = torch.ones(cfg.n_tasks, dtype=torch.bool, device=DEV)
+    others[heads] = False
+    assert bool((pair.best_scenario[others] == -1).all()) and bool((pair.best_lp[others] == -1).all())
+    assert bool((pair.best_filled_ns[others] == 0).all())
+    say("  fikit_pairing_best: sums and picks consistent at full size")
+    del pair
+    # replay against the actual idle times, without and with real-time feedback
     hp_gap = d_gap.view(-1, 4096 + 16384)[:, :4095]          # actual idle time of every gap, scenario by scenario
     for feedback in (False, True):
         t0 = time.time()
