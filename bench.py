@@ -127,7 +127,7 @@ def main():
 
     if args.workload == "cfg4":
         cfg = traces.config(4, n_tasks=2 * args.scenarios if args.scenarios else None)
-        sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 4096)
+        sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 16384)   # about 12 s of oracle time
         name = "config 4: batched gap-fill"
     elif args.workload == "cfg2":
         cfg = traces.config(2, n_tasks=args.tasks)
