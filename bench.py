@@ -42,7 +42,7 @@ GAPFILL_KERNELS = ("k_gf_predict", "k_gf_walk", "k_gf_predict32", "k_gf_walk_lan
 
 
 def source_hash():
-    """Hash of the library sources, to tell whether stored counter readings still describe this build."""
+    """Hash of the library sources, to tell whether stored counter readings still describe the library as it stands."""
     import hashlib
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2311_10359_amd", "csrc")
