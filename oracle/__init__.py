@@ -64,6 +64,8 @@ def _load():
         lib.oracle_replay.restype = ctypes.c_int
         lib.oracle_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, i64, i64, ctypes.c_int, vp, vp, vp,
                                       vp, vp, ctypes.c_int]
+        lib.oracle_profile_merge.restype = ctypes.c_int
+        lib.oracle_profile_merge.argtypes = [vp, vp, vp, vp, u32, vp, u64, vp, vp]
         lib.oracle_pairing_best.restype = ctypes.c_int
         lib.oracle_pairing_best.argtypes = [vp, vp, u64, u32, vp, vp, vp, vp, vp, vp, vp]
         lib.oracle_prio_fill.restype = ctypes.c_int
@@ -246,3 +248,25 @@ def pairing_best(hp_task: np.ndarray, lp_task: np.ndarray, n_tasks: int, gap_off
     if st != OK:
         raise OracleError(st)
     return total, best_s, best_lp, best_f
+
+
+def profile_merge(a_rows: np.ndarray, a_offsets: np.ndarray, b_rows: np.ndarray, b_offsets: np.ndarray,
+                  row_capacity: Optional[int] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """-> (rows[n_rows], task_row_offsets[n_tasks + 1]) of the merged profile."""
+    a_rows = np.ascontiguousarray(a_rows)
+    b_rows = np.ascontiguousarray(b_rows)
+    assert a_rows.dtype.itemsize == 128 and b_rows.dtype.itemsize == 128
+    ao = np.ascontiguousarray(a_offsets, dtype=np.uint64)
+    bo = np.ascontiguousarray(b_offsets, dtype=np.uint64)
+    assert ao.shape == bo.shape
+    n_tasks = ao.shape[0] - 1
+    cap = a_rows.shape[0] + b_rows.shape[0] if row_capacity is None else row_capacity
+    out = np.zeros(cap, dtype=a_rows.dtype)
+    oo = np.zeros(n_tasks + 1, dtype=np.uint64)
+    n = ctypes.c_uint64(0)
+    st = _load().oracle_profile_merge(_p(a_rows), _p(ao), _p(b_rows), _p(bo), n_tasks, _p(out), cap, _p(oo), ctypes.byref(n))
+    if st != OK:
+        err = OracleError(st)
+        err.n_rows = n.value
+        raise err
+    return out[: n.value].copy(), oo

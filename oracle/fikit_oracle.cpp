@@ -43,6 +43,10 @@
 //                       a task its best matching partner in those measurements): over evaluated
 //                       (high-priority, low-priority) combinations, per high-priority task the
 //                       partner whose kernels fill the most of its idle time.
+//   oracle_profile_merge - the statistics of the measurement phase accumulated over runs (Section 3.2: the
+//                       sums of SK_j and SG_j run over the T measured runs of a task, and a run of N
+//                       kernels contributes N - 1 idle times): the profile of further runs is merged
+//                       into the profile of the runs so far.
 //
 // All quantities are integers (nanoseconds, counts); nothing is floating point.
 
@@ -541,6 +545,77 @@ int oracle_pairing_best(const uint32_t* hp_task, const uint32_t* lp_task, uint64
     }
   }
   return OK;
+}
+
+
+// Merging the profiles of two sets of runs of the same tasks (Section 3.2: SK_j and SG_j are sums over
+// all T runs of a task divided by the number of samples; a run of N kernels has N - 1 idle times, so
+// profiling every run on its own and merging keeps the idle time between two runs out of the samples).
+//
+// a and b hold rows of the same n_tasks tasks (task t: rows a_offsets[t] .. a_offsets[t+1]-1, ordered by
+// ID as an unsigned number; likewise b).  Output: per task the union of the IDs, in the same order.  An ID
+// in one input only: its row, unchanged.  An ID in both: count and sum add up (sum modulo 2^64), min and
+// max combine; these are exactly the values a profile of all samples would have, and so is the mean.
+// The percentiles of the union cannot be known from two rows: p50 and p95 are taken, for the execution
+// times and for the idle times separately, from the input that has more samples (from a if equal).
+int oracle_profile_merge(const void* a_rows_v, const uint64_t* a_offsets, const void* b_rows_v, const uint64_t* b_offsets,
+                         uint32_t n_tasks, void* rows_out_v, uint64_t row_capacity, uint64_t* offsets_out,
+                         uint64_t* n_rows_out) {
+  const Row* a = static_cast<const Row*>(a_rows_v);
+  const Row* b = static_cast<const Row*>(b_rows_v);
+  Row* out = static_cast<Row*>(rows_out_v);
+  if (!a_offsets || !b_offsets || !offsets_out || !n_rows_out) return INVALID_ARG;
+  if (a_offsets[0] != 0 || b_offsets[0] != 0) return INVALID_ARG;
+  auto merge_stats = [](const Stats& x, const Stats& y) {
+    if (x.count == 0) return y;
+    if (y.count == 0) return x;
+    Stats m;
+    m.count = x.count + y.count;
+    m.sum = x.sum + y.sum;
+    m.min = std::min(x.min, y.min);
+    m.max = std::max(x.max, y.max);
+    const Stats& larger = y.count > x.count ? y : x;
+    m.p50 = larger.p50;
+    m.p95 = larger.p95;
+    return m;
+  };
+  uint64_t n = 0;
+  for (uint32_t t = 0; t < n_tasks; ++t) {
+    if (a_offsets[t + 1] < a_offsets[t] || b_offsets[t + 1] < b_offsets[t]) return INVALID_ARG;
+    offsets_out[t] = n;
+    std::map<uint64_t, Row> rows;   // ordered by ID
+    for (uint64_t r = a_offsets[t]; r < a_offsets[t + 1]; ++r) {
+      if (a[r].task != t) return INVALID_ARG;
+      if (r > a_offsets[t] && a[r].kernel_id <= a[r - 1].kernel_id) return INVALID_ARG;
+      rows[a[r].kernel_id] = a[r];
+    }
+    for (uint64_t r = b_offsets[t]; r < b_offsets[t + 1]; ++r) {
+      if (b[r].task != t) return INVALID_ARG;
+      if (r > b_offsets[t] && b[r].kernel_id <= b[r - 1].kernel_id) return INVALID_ARG;
+      auto it = rows.find(b[r].kernel_id);
+      if (it == rows.end()) {
+        rows[b[r].kernel_id] = b[r];
+      } else {
+        it->second.exec = merge_stats(it->second.exec, b[r].exec);
+        it->second.gap = merge_stats(it->second.gap, b[r].gap);
+      }
+    }
+    for (const auto& kv : rows) {
+      if (n < row_capacity) {
+        Row row;
+        std::memset(&row, 0, sizeof(row));
+        row.kernel_id = kv.first;
+        row.task = t;
+        row.exec = kv.second.exec;
+        row.gap = kv.second.gap;
+        out[n] = row;
+      }
+      ++n;
+    }
+  }
+  offsets_out[n_tasks] = n;
+  *n_rows_out = n;
+  return n > row_capacity ? ROW_CAPACITY : OK;
 }
 
 

@@ -13,6 +13,9 @@ P7  several low-priority tasks in priority queues (BestPrioFit): hand-worked cas
     decision of the issue log checked against the rule written as a sort key.
 P8  best partner per high-priority task: a hand-worked case (tests/golden/p8_pairing_hand_worked.json), numpy's
     lexsort on random inputs, and the gap fill of a grid of combinations searched by a plain Python loop.
+P9  profiles merged over runs: a hand-worked case (tests/golden/p9_merge_hand_worked.json), and the merge of the
+    profiles of a task's runs against the profile of the whole trace with the idle times between runs taken out
+    (count, sum, min, max; numpy on the pinned per-launch measurements), identity and symmetry.
 """
 import itertools
 import json
@@ -815,6 +818,111 @@ def test_p8_pairing_of_a_grid_of_gap_fills():
         pick = min(s for s in cands if int(comp[s]) == soonest)
         assert int(best_s[t]) == pick and int(best_lp[t]) == int(lp[pick]) and int(best_f[t]) == top
         assert all(int(total[s]) == sums[s] for s in mine)
+
+
+# ---------------------------------------------------------------- P9
+STAT_FIELDS = ("count", "sum", "min", "max", "p50", "p95")
+
+
+def rows_from_json(items):
+    rows = np.zeros(len(items), dtype=oracle.ROW_DTYPE)
+    for r, it in zip(rows, items):
+        r["kernel_id"], r["task"] = it["id"], it["task"]
+        for blk in ("exec", "gap"):
+            for f, v in zip(STAT_FIELDS, it[blk]):
+                r[blk][f] = v
+    return rows
+
+
+def offsets_of(rows, n_tasks):
+    off = np.zeros(n_tasks + 1, dtype=np.uint64)
+    np.cumsum(np.bincount(rows["task"].astype(np.int64), minlength=n_tasks), out=off[1:])
+    return off
+
+
+def test_p9_merge_hand_worked(golden_dir):
+    with open(os.path.join(golden_dir, "p9_merge_hand_worked.json")) as f:
+        golden = json.load(f)
+    n_tasks = golden["n_tasks"]
+    a, b, exp = rows_from_json(golden["a"]), rows_from_json(golden["b"]), rows_from_json(golden["merged"])
+    got, off = oracle.profile_merge(a, offsets_of(a, n_tasks), b, offsets_of(b, n_tasks))
+    assert got.tobytes() == exp.tobytes()
+    assert np.array_equal(off, offsets_of(exp, n_tasks))
+
+
+def split_runs(rec, off, cut):
+    """Every task's trace cut at fraction `cut` into two runs: (records, offsets) of the first and of the second."""
+    first, second, o1, o2 = [], [], [0], [0]
+    for t in range(off.size - 1):
+        a, b = int(off[t]), int(off[t + 1])
+        c = a + int((b - a) * cut)
+        first.append(rec[a:c])
+        second.append(rec[c:b])
+        o1.append(o1[-1] + c - a)
+        o2.append(o2[-1] + b - c)
+    return (np.concatenate(first), np.array(o1, dtype=np.uint64)), (np.concatenate(second), np.array(o2, dtype=np.uint64))
+
+
+@pytest.mark.parametrize("cfg", small_configs(), ids=lambda c: c.name)
+def test_p9_merge_of_runs_is_the_profile_without_the_idle_time_between_runs(cfg):
+    rec, off = traces.build(cfg)
+    (r1, o1), (r2, o2) = split_runs(rec, off, 0.37)
+    _, rows1, tro1 = oracle.profile(r1, o1)
+    _, rows2, tro2 = oracle.profile(r2, o2)
+    merged, mtro = oracle.profile_merge(rows1, tro1, rows2, tro2)
+    ids, whole, wtro = oracle.profile(rec, off)
+    # same IDs in the same order, same execution-time statistics but for the percentiles
+    assert np.array_equal(mtro, wtro)
+    assert np.array_equal(merged["kernel_id"], whole["kernel_id"]) and np.array_equal(merged["task"], whole["task"])
+    for f in ("count", "sum", "min", "max"):
+        assert np.array_equal(merged["exec"][f], whole["exec"][f]), f
+    # idle times: those of the whole trace except the one that follows the last launch of a task's first run
+    ex, gp = oracle.measure(rec, off)
+    gp = gp.copy()
+    for t in range(off.size - 1):
+        if o1[t + 1] > o1[t] and o2[t + 1] > o2[t]:
+            gp[int(off[t]) + int(o1[t + 1] - o1[t]) - 1] = -1
+    for t in range(off.size - 1):
+        a, b = int(off[t]), int(off[t + 1])
+        for r in range(int(mtro[t]), int(mtro[t + 1])):
+            g = gp[a:b][(ids[a:b] == merged["kernel_id"][r]) & (gp[a:b] >= 0)]
+            row = merged["gap"][r]
+            assert int(row["count"]) == g.size
+            if g.size:
+                assert int(row["sum"]) == int(g.sum()) and int(row["min"]) == int(g.min()) and int(row["max"]) == int(g.max())
+                assert int(row["min"]) <= int(row["p50"]) <= int(row["p95"]) <= int(row["max"])
+            else:
+                assert all(int(row[f]) == 0 for f in STAT_FIELDS)
+    # identity and symmetry
+    empty = np.zeros(0, dtype=oracle.ROW_DTYPE)
+    zero = np.zeros(off.size, dtype=np.uint64)
+    same, same_off = oracle.profile_merge(rows1, tro1, empty, zero)
+    assert same.tobytes() == rows1.tobytes() and np.array_equal(same_off, tro1)
+    same, _ = oracle.profile_merge(empty, zero, rows1, tro1)
+    assert same.tobytes() == rows1.tobytes()
+    other, other_off = oracle.profile_merge(rows2, tro2, rows1, tro1)
+    assert np.array_equal(other_off, mtro)
+    for blk in ("exec", "gap"):
+        for f in ("count", "sum", "min", "max"):
+            assert np.array_equal(other[blk][f], merged[blk][f])
+        # the percentiles are those of the input with more samples
+        for r in range(merged.shape[0]):
+            t, kid = int(merged["task"][r]), merged["kernel_id"][r]
+            src = [x for x in (rows1[int(tro1[t]):int(tro1[t + 1])], rows2[int(tro2[t]):int(tro2[t + 1])])]
+            cands = [x[x["kernel_id"] == kid] for x in src]
+            cands = [c[0][blk] for c in cands if c.size and int(c[0][blk]["count"]) > 0]
+            if cands:
+                best = max(cands, key=lambda c: int(c["count"]))      # (max keeps the first of equals)
+                assert int(merged[blk]["p50"][r]) == int(best["p50"]) and int(merged[blk]["p95"][r]) == int(best["p95"])
+    # capacity and argument errors
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.profile_merge(rows1, tro1, rows2, tro2, row_capacity=max(merged.shape[0] - 1, 0))
+    assert e.value.status == oracle.ROW_CAPACITY and e.value.n_rows == merged.shape[0]
+    if rows1.shape[0] > 1:
+        bad = rows1.copy()
+        bad["task"][0] = 99
+        with pytest.raises(oracle.OracleError):
+            oracle.profile_merge(bad, tro1, rows2, tro2)
 
 
 def test_oracle_error_statuses():
