@@ -22,8 +22,9 @@
  *
  * Beside these two: fikit_measure (the per-launch measurements themselves), fikit_gapfill_replay (the
  * fill replayed against the idle times that occurred, without and with real-time feedback),
- * fikit_prio_fill (several low-priority tasks per scenario in the priority queues of Algorithm 2) and
- * fikit_pairing_best (the best partner of every high-priority task among evaluated combinations).
+ * fikit_prio_fill (several low-priority tasks per scenario in the priority queues of Algorithm 2),
+ * fikit_pairing_best (the best partner of every high-priority task among evaluated combinations) and
+ * fikit_profile_merge (the profile of further runs merged into the profile so far).
  *
  * Conventions
  *   - d_* arguments are device pointers, h_* are host pointers.  The caller owns every buffer,
@@ -310,6 +311,36 @@ int fikit_pairing_best(const uint32_t* d_hp_task, const uint32_t* d_lp_task, uin
                        const int64_t* d_lp_completion_ns, int64_t* d_scenario_filled_ns,
                        uint64_t* d_best_scenario, uint32_t* d_best_lp, int64_t* d_best_filled_ns,
                        void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device workspace fikit_profile_merge needs (0 on size overflow). */
+size_t fikit_profile_merge_workspace_bytes(uint32_t n_tasks);
+
+/*
+ * Merges the profile of further runs of the same tasks into the profile of the runs so far (Section
+ * 3.2: the statistics run over all T measured runs of a task, and a run of N kernels contributes N - 1
+ * idle times; profiling every run on its own and merging keeps the idle time between runs out).
+ *
+ *   d_rows_a, d_task_row_offsets_a   a profile as fikit_profile writes it: task t owns rows
+ *                      d_task_row_offsets_a[t] .. [t+1]-1, ordered by kernel_id as an unsigned number,
+ *                      each with task == t (else FIKIT_INVALID_ARG).
+ *   d_rows_b, d_task_row_offsets_b   another profile of the same n_tasks tasks.
+ *   d_rows_out         [row_capacity] receives, per task, one row per ID of either input, in the same
+ *                      order.  An ID of one input only: its row.  An ID of both: count and sum add up
+ *                      (sum modulo 2^64), min and max combine: exactly the values a profile of all
+ *                      samples together would hold, and so is the mean (FIKIT_PREDICT_MEAN).  The
+ *                      percentiles of the union cannot be known from two rows: p50 and p95 are taken,
+ *                      for exec and for gap separately, from the input whose block has more samples
+ *                      (from a if equal).
+ *   d_task_row_offsets_out [n_tasks+1], h_n_rows   as in fikit_profile (also on FIKIT_ROW_CAPACITY).
+ *   d_workspace        256-byte aligned, at least fikit_profile_merge_workspace_bytes(n_tasks) bytes.
+ *
+ * The output must not overlap the inputs.  Buffers are the caller's; the call synchronises the stream.
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, ROW_CAPACITY, HIP_ERROR.
+ */
+int fikit_profile_merge(const fikit_row* d_rows_a, const uint64_t* d_task_row_offsets_a,
+                        const fikit_row* d_rows_b, const uint64_t* d_task_row_offsets_b, uint32_t n_tasks,
+                        fikit_row* d_rows_out, uint64_t row_capacity, uint64_t* d_task_row_offsets_out,
+                        uint64_t* h_n_rows, void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 const char* fikit_status_string(int status);
 int fikit_version(void);

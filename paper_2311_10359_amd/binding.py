@@ -28,7 +28,7 @@ FIKIT_PREDICT_P50, FIKIT_PREDICT_MEAN = 0, 1
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
            "fikit_gapfill", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
            "fikit_gapfill_replay", "fikit_prio_fill_workspace_bytes", "fikit_prio_fill", "fikit_pairing_workspace_bytes",
-           "fikit_pairing_best", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
+           "fikit_pairing_best", "fikit_profile_merge_workspace_bytes", "fikit_profile_merge", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
 
 # Layout of a profile row as seen from numpy (128 bytes; see fikit_row in fikit.h).
 STATS_DTYPE = np.dtype([("count", "<u8"), ("sum", "<u8"), ("min", "<i8"), ("max", "<i8"),
@@ -96,6 +96,10 @@ def load() -> ctypes.CDLL:
         lib.fikit_pairing_workspace_bytes.argtypes = [u32]
         lib.fikit_pairing_best.restype = ctypes.c_int
         lib.fikit_pairing_best.argtypes = [vp, vp, u64, u32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.fikit_profile_merge_workspace_bytes.restype = sz
+        lib.fikit_profile_merge_workspace_bytes.argtypes = [u32]
+        lib.fikit_profile_merge.restype = ctypes.c_int
+        lib.fikit_profile_merge.argtypes = [vp, vp, vp, vp, u32, vp, u64, vp, ctypes.POINTER(ctypes.c_uint64), vp, sz, vp]
         lib.fikit_gapfill_replay.restype = ctypes.c_int
         lib.fikit_gapfill_replay.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp, u64, ctypes.POINTER(_ReplayParams), vp,
                                              vp, vp, vp, vp, vp, sz, vp]
@@ -404,6 +408,47 @@ def fikit_pairing_best(hp_task: torch.Tensor, lp_task: torch.Tensor, n_tasks: in
     if st != FIKIT_OK:
         raise FikitError(st, "fikit_pairing_best")
     return out
+
+
+class MergedProfile(NamedTuple):
+    rows: torch.Tensor              # uint8 [n_rows, 128]
+    task_row_offsets: torch.Tensor  # int64 [n_tasks + 1]
+    n_rows: int
+
+
+def fikit_profile_merge_workspace_bytes(n_tasks: int) -> int:
+    return int(load().fikit_profile_merge_workspace_bytes(n_tasks))
+
+
+def fikit_profile_merge(rows_a: torch.Tensor, task_row_offsets_a: torch.Tensor, rows_b: torch.Tensor,
+                        task_row_offsets_b: torch.Tensor, *, row_capacity: Optional[int] = None,
+                        rows_out: Optional[torch.Tensor] = None, task_row_offsets_out: Optional[torch.Tensor] = None,
+                        workspace_buf: Optional[torch.Tensor] = None,
+                        stream: Optional[torch.cuda.Stream] = None) -> MergedProfile:
+    """rows_*: uint8 [n, 128] (fikit_profile's rows); task_row_offsets_*: int64 [n_tasks + 1]."""
+    lib = load()
+    dev = task_row_offsets_a.device
+    n_tasks = task_row_offsets_a.numel() - 1
+    assert task_row_offsets_b.numel() == n_tasks + 1
+    assert task_row_offsets_a.dtype == torch.int64 and task_row_offsets_b.dtype == torch.int64
+    for t in (rows_a, rows_b):
+        assert t.dtype == torch.uint8 and t.is_contiguous() and t.device == dev and t.numel() % ROW_BYTES == 0
+    if row_capacity is None:
+        row_capacity = rows_out.shape[0] if rows_out is not None else (rows_a.numel() + rows_b.numel()) // ROW_BYTES
+    if rows_out is None:
+        rows_out = torch.empty((row_capacity, ROW_BYTES), dtype=torch.uint8, device=dev)
+    if task_row_offsets_out is None:
+        task_row_offsets_out = torch.empty(n_tasks + 1, dtype=torch.int64, device=dev)
+    if workspace_buf is None:
+        workspace_buf = workspace(fikit_profile_merge_workspace_bytes(n_tasks), dev)
+    n_rows = ctypes.c_uint64(0)
+    with torch.cuda.device(dev):
+        st = lib.fikit_profile_merge(_ptr(rows_a), _ptr(task_row_offsets_a), _ptr(rows_b), _ptr(task_row_offsets_b), n_tasks,
+                                     _ptr(rows_out), row_capacity, _ptr(task_row_offsets_out), ctypes.byref(n_rows),
+                                     _ptr(workspace_buf), workspace_buf.numel(), _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_profile_merge", n_rows=n_rows.value)
+    return MergedProfile(rows_out[: n_rows.value], task_row_offsets_out, n_rows.value)
 
 
 # ---- helpers to move host arrays in and out (marshalling only) ---------------------------------

@@ -13,6 +13,7 @@
 #include "msd_kernels.hip.h"
 #include "prio_kernels.hip.h"
 #include "pairing_kernels.hip.h"
+#include "merge_kernels.hip.h"
 
 namespace {
 
@@ -147,7 +148,7 @@ struct Tracer {
 };
 
 int status_from_bits(uint32_t bits) {
-  if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS | ERR_ACTUAL_GAP | ERR_LP_LIST)) return FIKIT_INVALID_ARG;
+  if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS | ERR_ACTUAL_GAP | ERR_LP_LIST | ERR_ROWS)) return FIKIT_INVALID_ARG;
   if (bits & ERR_BAD_RECORD) return FIKIT_BAD_RECORD;
   if (bits & ERR_UNKNOWN_ID) return FIKIT_UNKNOWN_ID;
   if (bits & ERR_LP_LIMIT) return FIKIT_UNSUPPORTED;
@@ -845,6 +846,68 @@ int fikit_pairing_best(const uint32_t* d_hp_task, const uint32_t* d_lp_task, uin
   Ctrl h{};
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
   return status_from_bits(h.status);
+}
+
+size_t fikit_profile_merge_workspace_bytes(uint32_t n_tasks) {
+  Carver c;
+  c.take(256);
+  c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
+  c.take(((static_cast<uint64_t>(n_tasks) + 1) / SCAN_TILE + 2) * 4);
+  return static_cast<size_t>(c.at);
+}
+
+int fikit_profile_merge(const fikit_row* d_rows_a, const uint64_t* d_task_row_offsets_a, const fikit_row* d_rows_b,
+                        const uint64_t* d_task_row_offsets_b, uint32_t n_tasks, fikit_row* d_rows_out, uint64_t row_capacity,
+                        uint64_t* d_task_row_offsets_out, uint64_t* h_n_rows, void* d_workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  if (h_n_rows) *h_n_rows = 0;
+  if (!h_n_rows || !d_task_row_offsets_a || !d_task_row_offsets_b || !d_task_row_offsets_out || !d_workspace || n_tasks == 0)
+    return FIKIT_INVALID_ARG;
+  if (row_capacity > 0 && !d_rows_out) return FIKIT_INVALID_ARG;
+  if (!aligned(d_rows_a, 16) || !aligned(d_rows_b, 16) || !aligned(d_rows_out, 16) || !aligned(d_task_row_offsets_a, 8) ||
+      !aligned(d_task_row_offsets_b, 8) || !aligned(d_task_row_offsets_out, 8) || !aligned(d_workspace, 256))
+    return FIKIT_INVALID_ARG;
+  if (workspace_bytes < fikit_profile_merge_workspace_bytes(n_tasks)) return FIKIT_WORKSPACE_TOO_SMALL;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint64_t na = 0, nb = 0;
+  FIKIT_HIP(hipMemcpyAsync(&na, d_task_row_offsets_a + n_tasks, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipMemcpyAsync(&nb, d_task_row_offsets_b + n_tasks, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipStreamSynchronize(st));
+  if (na >= MAX_ELEMS || nb >= MAX_ELEMS || na + nb >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if ((na > 0 && !d_rows_a) || (nb > 0 && !d_rows_b)) return FIKIT_INVALID_ARG;
+
+  unsigned char* ws = static_cast<unsigned char*>(d_workspace);
+  Carver c;
+  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
+  uint32_t* dcount = reinterpret_cast<uint32_t*>(ws + c.take((static_cast<uint64_t>(n_tasks) + 1) * 4));
+  uint32_t* sums = reinterpret_cast<uint32_t*>(ws + c.take(((static_cast<uint64_t>(n_tasks) + 1) / SCAN_TILE + 2) * 4));
+
+  Tracer tr(st);
+  tr.mark("merge_count");
+  const uint32_t grid = n_tasks < 65536u ? n_tasks : 65536u;
+  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_row_offsets_a, n_tasks, na, ctrl);
+  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_row_offsets_b, n_tasks, nb, ctrl);
+  hipLaunchKernelGGL(k_merge<0>, dim3(grid), dim3(MERGE_THREADS), 0, st, d_rows_a, d_task_row_offsets_a, d_rows_b,
+                     d_task_row_offsets_b, n_tasks, dcount, static_cast<const uint64_t*>(nullptr),
+                     static_cast<fikit_row*>(nullptr), ctrl);
+  if (int rc = scan_u32(dcount, static_cast<uint64_t>(n_tasks) + 1, sums, &ctrl->n_rows, st)) return rc;
+  hipLaunchKernelGGL(k_widen_offsets, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st, dcount,
+                     static_cast<uint64_t>(n_tasks) + 1, d_task_row_offsets_out);
+  FIKIT_HIP(hipGetLastError());
+  tr.mark("host_sync");
+  Ctrl h{};
+  if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+  if (int rc = status_from_bits(h.status)) return rc;
+  *h_n_rows = h.n_rows;
+  if (h.n_rows > row_capacity) return FIKIT_ROW_CAPACITY;
+  tr.mark("k_merge_rows");
+  hipLaunchKernelGGL(k_merge<1>, dim3(grid), dim3(MERGE_THREADS), 0, st, d_rows_a, d_task_row_offsets_a, d_rows_b,
+                     d_task_row_offsets_b, n_tasks, dcount, d_task_row_offsets_out, d_rows_out, ctrl);
+  FIKIT_HIP(hipGetLastError());
+  FIKIT_HIP(hipStreamSynchronize(st));
+  return FIKIT_OK;
 }
 
 }  // extern "C"

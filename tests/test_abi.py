@@ -86,6 +86,11 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.fikit_pairing_best(fake, fake, 1, 1, fake, fake, fake, fake, fake, fake, fake, fake, 16, null) == -2
     assert lib.fikit_pairing_best(fake, fake, 1 << 31, 1, fake, fake, fake, fake, fake, fake, fake, fake, 1 << 20, null) == -1
     assert lib.fikit_pairing_workspace_bytes(1000) >= 8000
+    assert lib.fikit_profile_merge(fake, fake, fake, fake, 1, fake, 10, fake, None, fake, 1 << 20, null) == -1
+    assert lib.fikit_profile_merge(fake, null, fake, fake, 1, fake, 10, fake, ctypes.byref(n_rows), fake, 1 << 20, null) == -1
+    assert lib.fikit_profile_merge(fake, fake, fake, fake, 1, fake, 10, fake, ctypes.byref(n_rows), fake, 16, null) == -2
+    assert lib.fikit_profile_merge(fake, fake, fake, fake, 0, fake, 10, fake, ctypes.byref(n_rows), fake, 1 << 20, null) == -1
+    assert lib.fikit_profile_merge_workspace_bytes(1000) >= 4004
     assert lib.fikit_measure(fake, 10, null, 1, fake, fake, fake, 256, null) == -1
     assert lib.fikit_measure(fake, 10, fake, 1, fake, fake, fake, 16, null) == -2
     assert lib.fikit_measure_workspace_bytes() == 256
