@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--pairing", action="store_true",
                     help="after the timed steps, also time fikit_pairing_best over the gap fill's results (reported "
                          "beside the metric, not part of it)")
+    ap.add_argument("--merge", action="store_true",
+                    help="after the timed steps, also time fikit_profile_merge of the profile with itself (reported "
+                         "beside the metric, not part of it)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware counter runs)")
     args = ap.parse_args()
@@ -323,6 +326,35 @@ def main():
         log(f"[bench] pairing: {json.dumps(pairing)}")
         del pr_out
 
+    # ---- the profile merged with a second profile of the same tasks (beside the metric) ----------
+    merge = None
+    if args.merge:
+        n_rows = prof.n_rows
+        m_rows = torch.empty((n_rows, 128), dtype=torch.uint8, device=dev)
+        m_tro = torch.empty(cfg.n_tasks + 1, dtype=torch.int64, device=dev)
+
+        def merge_call():
+            return binding.fikit_profile_merge(prof.rows, tro, prof.rows, tro, row_capacity=n_rows, rows_out=m_rows,
+                                               task_row_offsets_out=m_tro, workspace_buf=ws)
+
+        merged = merge_call()
+        assert merged.n_rows == n_rows
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        binding.fikit_trace_enable(True)
+        ev[0].record()
+        for _ in range(args.steps):
+            merge_call()
+        ev[1].record()
+        torch.cuda.synchronize()
+        rt = binding.fikit_trace_read()
+        binding.fikit_trace_enable(False)
+        ms = ev[0].elapsed_time(ev[1]) / args.steps
+        merge = {"rows_in": 2 * n_rows, "rows_out": n_rows, "ms": round(ms, 3), "rows_out_per_s": round(n_rows / (ms * 1e-3), 1),
+                 "algorithmic_GB/s": round(3 * n_rows * 128 / (ms * 1e-3) / 1e9, 1),
+                 "kernel_ms": {k: round(v[0] / args.steps, 3) for k, v in rt.items() if k.startswith(("k_", "merge"))}}
+        log(f"[bench] profile_merge: {json.dumps(merge)}")
+        del m_rows, m_tro
+
     # ---- several low-priority tasks per scenario in priority queues (beside the metric) ----------
     prio = None
     if args.prio > 0 and n_scen:
@@ -434,6 +466,8 @@ def main():
         out["prio_fill"] = prio
     if pairing:
         out["pairing"] = pairing
+    if merge:
+        out["profile_merge"] = merge
     # whole calls against the HBM peak: counter-measured bytes of every kernel of the call / the call's time
     calls = stored_call_traffic(name)
     if calls:

@@ -127,6 +127,16 @@ def test_config4_batched_gapfill_full_size():
     check_global_properties(prof, off, cfg.n_tasks)
     scen = [0, 1, 777, 32768, 65534, 65535]
     check_sampled_tasks(cfg, prof, off, [t for s in scen for t in (2 * s, 2 * s + 1)])
+    # the profile merged with itself: same IDs, counts and sums doubled (modulo 2^64), everything else as it was
+    twice = binding.fikit_profile_merge(prof.rows, prof.task_row_offsets, prof.rows, prof.task_row_offsets)
+    torch.cuda.synchronize()
+    assert twice.n_rows == prof.n_rows and torch.equal(twice.task_row_offsets, prof.task_row_offsets)
+    r1, r2 = prof.rows.view(torch.int64).reshape(-1, 16), twice.rows.view(torch.int64).reshape(-1, 16)
+    doubled = [2, 3, 8, 9]                                   # exec.count, exec.sum, gap.count, gap.sum
+    same = [f for f in range(16) if f not in doubled]
+    assert torch.equal(r2[:, same], r1[:, same]) and torch.equal(r2[:, doubled], r1[:, doubled] * 2)
+    say("  fikit_profile_merge of the profile with itself: consistent at full size")
+    del twice, r1, r2
     # per-launch measurement at full size (the actual idle times are the replay's input further down)
     d_exec, d_gap = binding.fikit_measure(d_rec, d_off)
     for s in scen[:3]:
