@@ -14,7 +14,10 @@ struct MergeSmem {
   uint64_t ida[MERGE_IDS];
   uint64_t idb[MERGE_IDS];
   uint32_t aux[8];
+  uint32_t partner[MERGE_THREADS];   // per row of the round: its row in the other table, or MERGE_NONE
+  uint32_t place[MERGE_THREADS];     // where it goes in the task's output, or MERGE_NONE: nowhere
 };
+constexpr uint32_t MERGE_NONE = 0xffffffffu;
 
 // Number of rows of `rows[0..n)` (ordered by ID) whose ID is below `id`; *found: one of them equals it.
 // `ids` is the LDS copy of the IDs, or null.
@@ -30,19 +33,36 @@ __device__ __forceinline__ uint32_t ids_below(const fikit_row* __restrict__ rows
   return lo;
 }
 
-__device__ __forceinline__ fikit_stats merge_stats(const fikit_stats& x, const fikit_stats& y) {
-  if (x.count == 0) return y;
-  if (y.count == 0) return x;
-  fikit_stats m;
-  m.count = x.count + y.count;
-  m.sum = x.sum + y.sum;
-  m.min = x.min < y.min ? x.min : y.min;
-  m.max = x.max > y.max ? x.max : y.max;
-  // the percentiles of the union are not known: those of the input with more samples stand in
-  const bool from_y = y.count > x.count;
-  m.p50 = from_y ? y.p50 : x.p50;
-  m.p95 = from_y ? y.p95 : x.p95;
-  return m;
+// One 8-byte field of a merged row.  f: the field's number in the row (0 ID, 1 task, 2..7 the execution
+// times' count, sum, min, max, p50, p95, 8..13 the same of the idle times, 14..15 reserved); x, y: the field
+// in the two rows; cx, cy: the sample counts of the field's block in the two rows.
+__device__ __forceinline__ uint64_t merge_field(uint32_t f, uint64_t x, uint64_t y, uint64_t cx, uint64_t cy) {
+  if (f < 2 || f >= 14) return x;
+  if (cx == 0) return y;
+  if (cy == 0) return x;
+  const uint32_t kind = (f - 2) % 6;
+  const int64_t sx = static_cast<int64_t>(x), sy = static_cast<int64_t>(y);
+  if (kind <= 1) return x + y;                                            // count, sum (modulo 2^64)
+  if (kind == 2) return static_cast<uint64_t>(sx < sy ? sx : sy);         // min
+  if (kind == 3) return static_cast<uint64_t>(sx > sy ? sx : sy);         // max
+  return cy > cx ? y : x;   // the percentiles of the union are not known: those of the input with more samples stand in
+}
+
+// Writes the planned rows of a round (sm.place / sm.partner, `rows` of them, taken from src[first ..]): sixteen
+// lanes per row, one 8-byte field each, so that a wave reads and writes whole rows side by side.
+__device__ __forceinline__ void merge_write_round(const MergeSmem& sm, const fikit_row* __restrict__ src, uint32_t first,
+                                                  uint32_t rows, const fikit_row* __restrict__ other, fikit_row* __restrict__ out) {
+  const uint32_t tid = threadIdx.x, f = tid & 15u;
+  const int row_lane0 = static_cast<int>(lane_id() - f);
+  for (uint32_t r = tid >> 4; r < rows; r += MERGE_THREADS / 16) {      // (the sixteen lanes of a row stay together)
+    const uint32_t place = sm.place[r], partner = sm.partner[r];
+    const uint64_t x = reinterpret_cast<const uint64_t*>(src + first + r)[f];
+    const uint64_t y = partner != MERGE_NONE ? reinterpret_cast<const uint64_t*>(other + partner)[f] : 0;
+    const int count_lane = row_lane0 + (f < 8 ? 2 : 8);
+    const uint64_t cx = shfl_u64(x, count_lane), cy = shfl_u64(y, count_lane);
+    const uint64_t v = partner != MERGE_NONE ? merge_field(f, x, y, cx, cy) : x;
+    if (place != MERGE_NONE) reinterpret_cast<uint64_t*>(out + place)[f] = v;
+  }
 }
 
 // MODE 0: checks both inputs of a task (task field, IDs strictly ascending) and counts the rows of the
@@ -89,14 +109,12 @@ k_merge(const fikit_row* __restrict__ a, const uint64_t* __restrict__ a_off, con
       }
       uint32_t total;
       const uint32_t before = block_excl_scan_256(found ? 1u : 0u, sm.aux, total);
-      if (MODE == 1 && i < na) {
-        fikit_row row = ra[i];
-        if (found) {
-          const fikit_row other = rb[below];
-          row.exec = merge_stats(row.exec, other.exec);
-          row.gap = merge_stats(row.gap, other.gap);
-        }
-        out[row_off[t] + i + below - (carry + before)] = row;
+      if (MODE == 1) {
+        sm.partner[tid] = found ? below : MERGE_NONE;
+        sm.place[tid] = i < na ? i + below - (carry + before) : MERGE_NONE;
+        __syncthreads();
+        merge_write_round(sm, ra, i0, na - i0 < MERGE_THREADS ? na - i0 : MERGE_THREADS, rb, out + row_off[t]);
+        __syncthreads();
       }
       carry += total;
     }
@@ -114,7 +132,11 @@ k_merge(const fikit_row* __restrict__ a, const uint64_t* __restrict__ a_off, con
       if (MODE == 1) {
         uint32_t total;
         const uint32_t before = block_excl_scan_256(found ? 1u : 0u, sm.aux, total);
-        if (k < nb && !found) out[row_off[t] + k + below - (carry + before)] = rb[k];
+        sm.partner[tid] = MERGE_NONE;
+        sm.place[tid] = (k < nb && !found) ? k + below - (carry + before) : MERGE_NONE;    // (matched rows went out with a's)
+        __syncthreads();
+        merge_write_round(sm, rb, k0, nb - k0 < MERGE_THREADS ? nb - k0 : MERGE_THREADS, ra, out + row_off[t]);
+        __syncthreads();
         carry += total;
       }
     }
