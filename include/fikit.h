@@ -93,9 +93,11 @@ typedef enum fikit_status {
   FIKIT_BAD_RECORD = -4,          /* some record has end_ns < start_ns                          */
   FIKIT_UNKNOWN_ID = -5,          /* a scenario launch whose ID is absent from its task's rows  */
   FIKIT_HIP_ERROR = -6,           /* the HIP runtime reported an error                          */
-  FIKIT_UNSUPPORTED = -7          /* fikit_gapfill_replay, fikit_prio_fill: a predicted time of
+  FIKIT_UNSUPPORTED = -7,         /* fikit_gapfill_replay, fikit_prio_fill: a predicted time of
                                      2^32 - 1 ns or more; fikit_prio_fill: a scenario beyond its
                                      stated limits                                                */
+  FIKIT_TOO_LARGE = -8            /* fikit_gapfill_static: more launches or tasks than its built-in
+                                     scratch buffer holds                                          */
 } fikit_status;
 
 /* Bytes of device workspace fikit_profile needs for these sizes (0 on size overflow). */
@@ -173,6 +175,38 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
                   uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_lp_completion_ns,
                   uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes,
                   void* hip_stream);
+
+/* Largest inputs of fikit_gapfill_static. */
+#define FIKIT_STATIC_MAX_IDS (1u << 20)   /* launches of all tasks together */
+#define FIKIT_STATIC_MAX_TASKS 16384u
+
+/*
+ * fikit_gapfill for callers that cannot allocate device memory or wait for the device: code that is being
+ * captured into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  It computes what
+ * fikit_gapfill computes, with these differences:
+ *
+ *   - no workspace argument: the library's own scratch buffer is used, a device array of about 24 MiB that is
+ *     part of the library's code object (every GPU the library is used on holds one for the life of the
+ *     process).  Inputs beyond FIKIT_STATIC_MAX_IDS launches or FIKIT_STATIC_MAX_TASKS tasks are refused with
+ *     FIKIT_TOO_LARGE before anything is enqueued.
+ *   - n_ids (= d_task_offsets[n_tasks]) and n_gaps (= d_gap_offsets[n_scenarios]) are passed by the caller
+ *     instead of being read back; a mismatch is reported as FIKIT_INVALID_ARG through d_status.
+ *   - the call only enqueues work on hip_stream and returns; it does not synchronise.  d_status (device,
+ *     int32) receives the fikit_status of the data-dependent checks (FIKIT_OK, FIKIT_INVALID_ARG,
+ *     FIKIT_UNKNOWN_ID) once the stream has run that far; outputs are valid only if it is FIKIT_OK.  The
+ *     return value covers what the host can see: INVALID_ARG, TOO_LARGE, HIP_ERROR.
+ *   - it calls no hipMalloc / hipFree, records no events and creates nothing; the first call on a device
+ *     looks up that device's scratch address and sets one kernel attribute.
+ *
+ * All calls on one GPU share that GPU's scratch buffer: calls that may overlap in time (different streams,
+ * different threads) race and must be serialised by the caller.  Calls on one stream are safe back to back.
+ */
+int fikit_gapfill_static(const uint64_t* d_ids, uint64_t n_ids, const uint64_t* d_task_offsets, uint32_t n_tasks,
+                         const fikit_row* d_rows, const uint64_t* d_task_row_offsets,
+                         const uint32_t* d_hp_task, const uint32_t* d_lp_task, uint64_t n_scenarios,
+                         const fikit_gapfill_params* h_params, const uint64_t* d_gap_offsets, uint64_t n_gaps,
+                         uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_lp_completion_ns,
+                         uint64_t* d_lp_placed, int32_t* d_status, void* hip_stream);
 
 /* Bytes of device workspace fikit_measure needs. */
 size_t fikit_measure_workspace_bytes(void);

@@ -23,10 +23,13 @@ FIKIT_BAD_RECORD = -4
 FIKIT_UNKNOWN_ID = -5
 FIKIT_HIP_ERROR = -6
 FIKIT_UNSUPPORTED = -7
+FIKIT_TOO_LARGE = -8
+FIKIT_STATIC_MAX_IDS = 1 << 20
+FIKIT_STATIC_MAX_TASKS = 16384
 FIKIT_PREDICT_P50, FIKIT_PREDICT_MEAN = 0, 1
 
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
-           "fikit_gapfill", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
+           "fikit_gapfill", "fikit_gapfill_static", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
            "fikit_gapfill_replay", "fikit_prio_fill_workspace_bytes", "fikit_prio_fill", "fikit_pairing_workspace_bytes",
            "fikit_pairing_best", "fikit_profile_merge_workspace_bytes", "fikit_profile_merge", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
 
@@ -81,6 +84,9 @@ def load() -> ctypes.CDLL:
         lib.fikit_gapfill.restype = ctypes.c_int
         lib.fikit_gapfill.argtypes = [vp, vp, u32, vp, vp, vp, vp, u64, ctypes.POINTER(_GapfillParams), vp,
                                       vp, vp, vp, vp, vp, sz, vp]
+        lib.fikit_gapfill_static.restype = ctypes.c_int
+        lib.fikit_gapfill_static.argtypes = [vp, u64, vp, u32, vp, vp, vp, vp, u64, ctypes.POINTER(_GapfillParams), vp, u64,
+                                             vp, vp, vp, vp, vp, vp]
         lib.fikit_measure_workspace_bytes.restype = sz
         lib.fikit_measure_workspace_bytes.argtypes = []
         lib.fikit_measure.restype = ctypes.c_int
@@ -242,6 +248,27 @@ def fikit_gapfill(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Ten
     if st != FIKIT_OK:
         raise FikitError(st, "fikit_gapfill")
     return out
+
+
+def fikit_gapfill_static(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Tensor, task_row_offsets: torch.Tensor,
+                         hp_task: torch.Tensor, lp_task: torch.Tensor, gap_offsets: torch.Tensor, *, n_ids: int, n_gaps: int,
+                         margin_ns: int, min_gap_ns: int, out: GapFill, status_out: torch.Tensor,
+                         predictor: int = FIKIT_PREDICT_P50, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """fikit_gapfill on the library's built-in scratch buffer.  Every buffer, including the outputs and the int32
+    status word, is the caller's; nothing is allocated, nothing is waited for: read status_out after synchronising."""
+    lib = load()
+    dev = task_offsets.device
+    n_tasks = task_offsets.numel() - 1
+    s = hp_task.numel()
+    assert status_out.dtype == torch.int32 and status_out.numel() >= 1 and status_out.device == dev
+    params = _GapfillParams(margin_ns, min_gap_ns, predictor, 0)
+    with torch.cuda.device(dev):
+        st = lib.fikit_gapfill_static(_ptr(ids), n_ids, _ptr(task_offsets), n_tasks, _ptr(rows), _ptr(task_row_offsets),
+                                      _ptr(hp_task), _ptr(lp_task), s, ctypes.byref(params), _ptr(gap_offsets), n_gaps,
+                                      _ptr(out.fill_count), _ptr(out.filled_ns), _ptr(out.lp_completion_ns),
+                                      _ptr(out.lp_placed), _ptr(status_out), _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_gapfill_static")
 
 
 def fikit_measure_workspace_bytes() -> int:

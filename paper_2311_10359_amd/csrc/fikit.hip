@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "common.hip.h"
 #include "gapfill_kernels.hip.h"
 #include "profile_kernels.hip.h"
@@ -20,6 +22,7 @@ namespace {
 using namespace fikit;
 
 constexpr uint64_t MAX_ELEMS = (1ull << 32) - (1ull << 24);
+constexpr int WALK_GW = 64;   // lanes that share a scenario in the few-scenario walk
 
 #define FIKIT_HIP(expr)                           \
   do {                                            \
@@ -119,7 +122,7 @@ struct Tracer {
   const char* name[TRACE_MAX_MARKS];
   int n = 0;
   bool on;
-  explicit Tracer(hipStream_t s) : st(s), on(g_trace_on) {}
+  explicit Tracer(hipStream_t s, bool allowed = true) : st(s), on(allowed && g_trace_on) {}
   void mark(const char* what) {
     if (!on || n >= TRACE_MAX_MARKS) return;
     if (hipEventCreate(&ev[n]) != hipSuccess) { on = false; return; }
@@ -203,7 +206,8 @@ const char* fikit_status_string(int status) {
     case FIKIT_BAD_RECORD: return "record with end_ns < start_ns";
     case FIKIT_UNKNOWN_ID: return "launch ID missing from its task's profile";
     case FIKIT_HIP_ERROR: return "HIP runtime error";
-    case FIKIT_UNSUPPORTED: return "a predicted time of 2^32 - 1 ns or more (replay)";
+    case FIKIT_UNSUPPORTED: return "beyond a stated limit of this call (a predicted time of 2^32 - 1 ns or more, or too many low-priority tasks in a scenario)";
+    case FIKIT_TOO_LARGE: return "input larger than the built-in scratch buffer of fikit_gapfill_static";
     default: return "unknown status";
   }
 }
@@ -477,18 +481,88 @@ constexpr uint64_t GF_PAD = 256;
 // One lane per scenario pays off once there are about as many scenarios as the GPU has lanes to run at a time.
 constexpr uint64_t GF_LANES_MIN_SCENARIOS = 4096;
 
+}  // extern "C"
+
+namespace {
+
+constexpr uint64_t ws_align(uint64_t v) { return (v + 255) / 256 * 256; }
+
+// Workspace of the gap fill: control block, task roles, two work lists, queue totals, three per-launch arrays.
+constexpr uint64_t gapfill_ws_bytes(uint64_t n_ids, uint64_t n_tasks) {
+  return 256 + ws_align(n_tasks * 4) + ws_align(n_tasks * 4 * 2) + ws_align(n_tasks * 8) + 2 * ws_align(n_ids * 8 + GF_PAD) +
+         ws_align(n_ids * 8);
+}
+
+bool gapfill_params_ok(const fikit_gapfill_params* p) {
+  return p && p->margin_ns >= 0 && p->min_gap_ns >= 0 && p->reserved == 0 && p->predictor >= FIKIT_PREDICT_P50 &&
+         p->predictor <= FIKIT_PREDICT_MEAN;
+}
+
+// Enqueues every kernel of the gap fill on `st`; `ws` holds gapfill_ws_bytes(n_ids, n_tasks) bytes whose first 64
+// are the control block.  Nothing is read back and nothing is allocated here.
+int gapfill_enqueue(hipStream_t st, Tracer& tr, const uint64_t* d_ids, uint64_t n_ids, const uint64_t* d_task_offsets,
+                    uint32_t n_tasks, const fikit_row* d_rows, const uint64_t* d_task_row_offsets, const uint32_t* d_hp_task,
+                    const uint32_t* d_lp_task, uint64_t n_scenarios, const fikit_gapfill_params* h_params,
+                    const uint64_t* d_gap_offsets, uint64_t n_gaps, uint32_t* d_fill_count, int64_t* d_filled_ns,
+                    int64_t* d_lp_completion_ns, uint64_t* d_lp_placed, unsigned char* ws, bool set_attributes) {
+  Carver c;
+  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
+  uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
+  uint32_t* glists = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4 * 2));
+  uint64_t* lp_total = reinterpret_cast<uint64_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 8));
+  int64_t* pe = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
+  int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
+  int64_t* open = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
+  // the 32-bit arrays of the one-lane-per-scenario kernels share the space of the 64-bit ones
+  uint32_t* lp_e = reinterpret_cast<uint32_t*>(pe);
+  uint2* hp_eg = reinterpret_cast<uint2*>(pg);
+
+  tr.mark("gf_setup");
+  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+  hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, role, static_cast<uint64_t>(n_tasks), 0u);
+  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_ids, ctrl);
+  hipLaunchKernelGGL(k_gf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
+                     d_lp_task, n_scenarios, d_gap_offsets, n_gaps, role, ctrl);
+  tr.mark("gf_lists");
+  hipLaunchKernelGGL(k_gf_lists, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, role, 8192u, glists,
+                     ctrl);
+  // Many scenarios: one lane per scenario on 32-bit predictions; the 64-bit kernels then only run if a
+  // prediction did not fit (they check Ctrl::wide).  Few scenarios: the 64-bit kernels, a group of lanes each.
+  const bool lanes = n_scenarios >= GF_LANES_MIN_SCENARIOS && n_gaps < MAX_ELEMS;
+  if (lanes) {
+    tr.mark("k_gf_predict32");
+    hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                       d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total, static_cast<uint32_t>(h_params->predictor), ctrl);
+    tr.mark("k_gf_walk_lanes");
+    if (set_attributes)
+      FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes<LW_PLAN>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(LaneWalkSmem))));
+    const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
+    hipLaunchKernelGGL(k_gf_walk_lanes<LW_PLAN>, dim3(blocks_for(n_scenarios, LW_THREADS)), dim3(LW_THREADS), sizeof(LaneWalkSmem), st,
+                       d_task_offsets, d_hp_task, d_lp_task, n_scenarios, d_gap_offsets, lp_e, hp_eg, lp_total,
+                       h_params->margin_ns, h_params->min_gap_ns, d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed,
+                       vec_ok, ctrl);
+  }
+  const uint32_t only_if_wide = lanes ? 1u : 0u;
+  tr.mark("k_gf_predict");
+  hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                     d_task_row_offsets, role, glists, pe, pg, open, only_if_wide, static_cast<uint32_t>(h_params->predictor), ctrl);
+  tr.mark("k_gf_walk");
+  hipLaunchKernelGGL((k_gf_walk<WALK_GW, true>), dim3(blocks_for(n_scenarios, 256 / WALK_GW)), dim3(256), 0, st, d_task_offsets, d_hp_task,
+                     d_lp_task, n_scenarios, d_gap_offsets, pe, pg, open, h_params->margin_ns, h_params->min_gap_ns,
+                     d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed, only_if_wide, ctrl);
+  FIKIT_HIP(hipGetLastError());
+  return FIKIT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 size_t fikit_gapfill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios) {
   (void)n_scenarios;
   if (n_ids >= MAX_ELEMS) return 0;
-  Carver c;
-  c.take(256);
-  c.take(static_cast<uint64_t>(n_tasks) * 4);
-  c.take(static_cast<uint64_t>(n_tasks) * 4 * 2);
-  c.take(static_cast<uint64_t>(n_tasks) * 8);
-  c.take(n_ids * 8 + GF_PAD);
-  c.take(n_ids * 8 + GF_PAD);
-  c.take(n_ids * 8);
-  return static_cast<size_t>(c.at);
+  return static_cast<size_t>(gapfill_ws_bytes(n_ids, n_tasks));
 }
 
 int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks, const fikit_row* d_rows,
@@ -496,9 +570,7 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
                   uint64_t n_scenarios, const fikit_gapfill_params* h_params, const uint64_t* d_gap_offsets,
                   uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_lp_completion_ns, uint64_t* d_lp_placed,
                   void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!h_params || h_params->margin_ns < 0 || h_params->min_gap_ns < 0 || h_params->reserved != 0 ||
-      h_params->predictor < FIKIT_PREDICT_P50 || h_params->predictor > FIKIT_PREDICT_MEAN)
-    return FIKIT_INVALID_ARG;
+  if (!gapfill_params_ok(h_params)) return FIKIT_INVALID_ARG;
   if (!d_task_offsets || !d_task_row_offsets || !d_workspace) return FIKIT_INVALID_ARG;
   if (n_scenarios >= MAX_ELEMS) return FIKIT_INVALID_ARG;
   if (n_scenarios > 0 && (!d_hp_task || !d_lp_task || !d_gap_offsets || !d_lp_completion_ns || !d_lp_placed || n_tasks == 0))
@@ -521,62 +593,96 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   if (workspace_bytes < fikit_gapfill_workspace_bytes(n_ids, n_tasks, n_scenarios)) return FIKIT_WORKSPACE_TOO_SMALL;
 
   unsigned char* ws = static_cast<unsigned char*>(d_workspace);
-  Carver c;
-  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
-  uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
-  uint32_t* glists = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4 * 2));
-  uint64_t* lp_total = reinterpret_cast<uint64_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 8));
-  int64_t* pe = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
-  int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
-  int64_t* open = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8));
-  // the 32-bit arrays of the one-lane-per-scenario kernels share the space of the 64-bit ones
-  uint32_t* lp_e = reinterpret_cast<uint32_t*>(pe);
-  uint2* hp_eg = reinterpret_cast<uint2*>(pg);
-
   Tracer tr(st);
-  tr.mark("gf_setup");
-  hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
-  hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, role, static_cast<uint64_t>(n_tasks), 0u);
-  hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_ids, ctrl);
-  hipLaunchKernelGGL(k_gf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
-                     d_lp_task, n_scenarios, d_gap_offsets, role, ctrl);
-  tr.mark("gf_lists");
-  hipLaunchKernelGGL(k_gf_lists, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, role, 8192u, glists,
-                     ctrl);
-  // Many scenarios: one lane per scenario on 32-bit predictions; the 64-bit kernels then only run if a
-  // prediction did not fit (they check Ctrl::wide).  Few scenarios: the 64-bit kernels, a group of lanes each.
-  const bool lanes = n_scenarios >= GF_LANES_MIN_SCENARIOS && n_gaps < MAX_ELEMS;
-  if (lanes) {
-    tr.mark("k_gf_predict32");
-    hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                       d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total, static_cast<uint32_t>(h_params->predictor), ctrl);
-    tr.mark("k_gf_walk_lanes");
-    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes<LW_PLAN>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(LaneWalkSmem))));
-    const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
-    hipLaunchKernelGGL(k_gf_walk_lanes<LW_PLAN>, dim3(blocks_for(n_scenarios, LW_THREADS)), dim3(LW_THREADS), sizeof(LaneWalkSmem), st,
-                       d_task_offsets, d_hp_task, d_lp_task, n_scenarios, d_gap_offsets, lp_e, hp_eg, lp_total,
-                       h_params->margin_ns, h_params->min_gap_ns, d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed,
-                       vec_ok, ctrl);
-  }
-  const uint32_t only_if_wide = lanes ? 1u : 0u;
-  tr.mark("k_gf_predict");
-  hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                     d_task_row_offsets, role, glists, pe, pg, open, only_if_wide, static_cast<uint32_t>(h_params->predictor), ctrl);
-#ifndef FIKIT_WALK_GW
-#define FIKIT_WALK_GW 64
-#define FIKIT_WALK_WINDOW true
-#endif
-  constexpr int GW = FIKIT_WALK_GW;
-  tr.mark("k_gf_walk");
-  hipLaunchKernelGGL((k_gf_walk<GW, FIKIT_WALK_WINDOW>), dim3(blocks_for(n_scenarios, 256 / GW)), dim3(256), 0, st, d_task_offsets, d_hp_task,
-                     d_lp_task, n_scenarios, d_gap_offsets, pe, pg, open, h_params->margin_ns, h_params->min_gap_ns,
-                     d_fill_count, d_filled_ns, d_lp_completion_ns, d_lp_placed, only_if_wide, ctrl);
-  FIKIT_HIP(hipGetLastError());
+  if (int rc = gapfill_enqueue(st, tr, d_ids, n_ids, d_task_offsets, n_tasks, d_rows, d_task_row_offsets, d_hp_task, d_lp_task,
+                               n_scenarios, h_params, d_gap_offsets, n_gaps, d_fill_count, d_filled_ns, d_lp_completion_ns,
+                               d_lp_placed, ws, true))
+    return rc;
   tr.mark("host_sync");
   Ctrl h{};
-  if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+  if (int rc = read_ctrl(reinterpret_cast<const Ctrl*>(ws), &h, st)) return rc;
   return status_from_bits(h.status);
+}
+
+}  // extern "C"
+
+namespace {
+
+// ---- fikit_gapfill_static: the gap fill for callers that cannot allocate --------------------------------------
+// Its workspace is a device array that is part of the library's code object.  Every GPU the library runs on holds
+// its own copy at its own address; that address is looked up once per device, with the device current.
+constexpr uint64_t STATIC_SCRATCH_BYTES = gapfill_ws_bytes(FIKIT_STATIC_MAX_IDS, FIKIT_STATIC_MAX_TASKS);
+static_assert(STATIC_SCRATCH_BYTES <= (32ull << 20), "the built-in scratch buffer is meant to stay modest");
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex g_static_mutex;
+unsigned char* g_static_scratch[STATIC_MAX_DEVICES] = {};
+
+// Address of the current device's scratch array (set-up on the first call on that device).
+int static_scratch_of_current_device(unsigned char** out) {
+  int dev = -1;
+  FIKIT_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return FIKIT_HIP_ERROR;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_scratch[dev]) {
+    unsigned char* ptr = nullptr;
+    FIKIT_HIP(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+    if (!ptr) return FIKIT_HIP_ERROR;
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes<LW_PLAN>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(LaneWalkSmem))));
+    g_static_scratch[dev] = ptr;
+  }
+  *out = g_static_scratch[dev];
+  return FIKIT_OK;
+}
+
+// The status a finished call would return, from the error bits its kernels left.
+__global__ void k_publish_status(const Ctrl* ctrl, int32_t* status_out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const uint32_t bits = ctrl->status;
+  int32_t st = FIKIT_OK;
+  if (bits & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) st = FIKIT_INVALID_ARG;
+  else if (bits & ERR_UNKNOWN_ID) st = FIKIT_UNKNOWN_ID;
+  *status_out = st;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fikit_gapfill_static(const uint64_t* d_ids, uint64_t n_ids, const uint64_t* d_task_offsets, uint32_t n_tasks,
+                         const fikit_row* d_rows, const uint64_t* d_task_row_offsets, const uint32_t* d_hp_task,
+                         const uint32_t* d_lp_task, uint64_t n_scenarios, const fikit_gapfill_params* h_params,
+                         const uint64_t* d_gap_offsets, uint64_t n_gaps, uint32_t* d_fill_count, int64_t* d_filled_ns,
+                         int64_t* d_lp_completion_ns, uint64_t* d_lp_placed, int32_t* d_status, void* hip_stream) {
+  if (!gapfill_params_ok(h_params)) return FIKIT_INVALID_ARG;
+  if (!d_task_offsets || !d_task_row_offsets || !d_status || !aligned(d_status, 4)) return FIKIT_INVALID_ARG;
+  if (n_scenarios >= MAX_ELEMS || n_gaps >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_ids > FIKIT_STATIC_MAX_IDS || n_tasks > FIKIT_STATIC_MAX_TASKS) return FIKIT_TOO_LARGE;
+  if (n_tasks == 0) return FIKIT_INVALID_ARG;
+  if (n_scenarios > 0 && (!d_hp_task || !d_lp_task || !d_gap_offsets || !d_lp_completion_ns || !d_lp_placed))
+    return FIKIT_INVALID_ARG;
+  if (n_ids > 0 && (!d_ids || !d_rows)) return FIKIT_INVALID_ARG;
+  if (n_gaps > 0 && (!d_fill_count || !d_filled_ns)) return FIKIT_INVALID_ARG;
+  if (!aligned(d_ids, 8) || !aligned(d_task_offsets, 8) || !aligned(d_rows, 16) || !aligned(d_task_row_offsets, 8) ||
+      !aligned(d_hp_task, 4) || !aligned(d_lp_task, 4) || !aligned(d_gap_offsets, 8) || !aligned(d_fill_count, 4) ||
+      !aligned(d_filled_ns, 8) || !aligned(d_lp_completion_ns, 8) || !aligned(d_lp_placed, 8))
+    return FIKIT_INVALID_ARG;
+  unsigned char* ws = nullptr;
+  if (int rc = static_scratch_of_current_device(&ws)) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  Tracer tr(st, false);   // (recording events would allocate)
+  if (n_scenarios == 0) {
+    hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, reinterpret_cast<Ctrl*>(ws));
+  } else if (int rc = gapfill_enqueue(st, tr, d_ids, n_ids, d_task_offsets, n_tasks, d_rows, d_task_row_offsets, d_hp_task,
+                                      d_lp_task, n_scenarios, h_params, d_gap_offsets, n_gaps, d_fill_count, d_filled_ns,
+                                      d_lp_completion_ns, d_lp_placed, ws, false)) {
+    return rc;
+  }
+  hipLaunchKernelGGL(k_publish_status, dim3(1), dim3(64), 0, st, reinterpret_cast<const Ctrl*>(ws), d_status);
+  FIKIT_HIP(hipGetLastError());
+  return FIKIT_OK;
 }
 
 size_t fikit_measure_workspace_bytes(void) { return 256; }
@@ -658,7 +764,7 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
   hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, role, static_cast<uint64_t>(n_tasks), 0u);
   hipLaunchKernelGGL(k_validate_offsets, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, n_ids, ctrl);
   hipLaunchKernelGGL(k_gf_scenarios, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, d_hp_task,
-                     d_lp_task, n_scenarios, d_gap_offsets, role, ctrl);
+                     d_lp_task, n_scenarios, d_gap_offsets, n_gaps, role, ctrl);
   tr.mark("gf_lists");
   hipLaunchKernelGGL(k_gf_lists, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, role, 8192u, glists,
                      ctrl);

@@ -14,13 +14,15 @@ namespace fikit {
 
 constexpr uint32_t ROLE_HP = 1u, ROLE_LP = 2u;
 
-// Checks scenario arguments and records in role[t] how each task is used.
+// Checks scenario arguments (n_gaps: the number of per-gap output slots the host sized its buffers for) and
+// records in role[t] how each task is used.
 __global__ void k_gf_scenarios(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ hp_task,
                                const uint32_t* __restrict__ lp_task, uint64_t n_scen,
-                               const uint64_t* __restrict__ gap_off, uint32_t* __restrict__ role, Ctrl* ctrl) {
+                               const uint64_t* __restrict__ gap_off, uint64_t n_gaps, uint32_t* __restrict__ role, Ctrl* ctrl) {
   if (ctrl->status & ERR_OFFSETS) return;
   const uint64_t s = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (s >= n_scen) return;
+  if (s + 1 == n_scen && gap_off[n_scen] != n_gaps) atomicOr(&ctrl->status, ERR_GAP_OFFSETS);
   const uint32_t hp = hp_task[s], lp = lp_task[s];
   if (hp >= n_tasks || lp >= n_tasks) { atomicOr(&ctrl->status, ERR_TASK_INDEX); return; }
   const uint64_t H = off[hp + 1] - off[hp];

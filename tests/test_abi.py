@@ -28,7 +28,7 @@ def test_host_only_entry_points():
     lib = binding.load()
     assert lib.fikit_version() >= 1
     assert binding.status_string(0) == "ok"
-    for st in range(-6, 0):
+    for st in range(-8, 0):
         assert binding.status_string(st) not in ("ok", "unknown status")
     assert binding.status_string(-99) == "unknown status"
     # workspace queries are pure host arithmetic: monotone in the sizes, 0 beyond the size limit
@@ -91,6 +91,16 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.fikit_profile_merge(fake, fake, fake, fake, 1, fake, 10, fake, ctypes.byref(n_rows), fake, 16, null) == -2
     assert lib.fikit_profile_merge(fake, fake, fake, fake, 0, fake, 10, fake, ctypes.byref(n_rows), fake, 1 << 20, null) == -1
     assert lib.fikit_profile_merge_workspace_bytes(1000) >= 4004
+    # the variant on the built-in scratch buffer refuses what does not fit it, before any HIP call
+    p = binding._GapfillParams(500, 0, 0, 0)
+    assert lib.fikit_gapfill_static(fake, binding.FIKIT_STATIC_MAX_IDS + 1, fake, 2, fake, fake, fake, fake, 1, ctypes.byref(p),
+                                    fake, 1, fake, fake, fake, fake, fake, null) == binding.FIKIT_TOO_LARGE
+    assert lib.fikit_gapfill_static(fake, 100, fake, binding.FIKIT_STATIC_MAX_TASKS + 1, fake, fake, fake, fake, 1,
+                                    ctypes.byref(p), fake, 1, fake, fake, fake, fake, fake, null) == binding.FIKIT_TOO_LARGE
+    assert lib.fikit_gapfill_static(fake, 100, fake, 2, fake, fake, fake, fake, 1, ctypes.byref(p), fake, 1, fake, fake, fake,
+                                    fake, null, null) == -1     # no status word
+    assert lib.fikit_gapfill_static(fake, 100, fake, 2, fake, fake, fake, fake, 1, None, fake, 1, fake, fake, fake,
+                                    fake, fake, null) == -1
     assert lib.fikit_measure(fake, 10, null, 1, fake, fake, fake, 256, null) == -1
     assert lib.fikit_measure(fake, 10, fake, 1, fake, fake, fake, 16, null) == -2
     assert lib.fikit_measure_workspace_bytes() == 256
