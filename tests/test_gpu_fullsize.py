@@ -1,8 +1,10 @@
 """The five workloads at their full sizes, in the launch configuration bench.py times.
 
-The oracle cannot redo a billion records in seconds, so it recomputes a sample of tasks and
-scenarios one by one (every task's records can be regenerated alone from its seed); the rest
-is covered by properties that hold at any size."""
+fikit_profile and fikit_gapfill are compared with the oracle whole: every Kernel ID, every row, every
+gap and every scenario (worker processes regenerate the workload piece by piece from its seeds and run
+the single-threaded oracle on each piece, see whole_workload.py).  The calls that build on them (replay,
+priority queues, pairing, merge, measurement) are checked at full size on sampled scenarios recomputed
+one by one, plus properties that hold at any size."""
 import time
 
 import numpy as np
@@ -12,6 +14,7 @@ import torch
 import oracle
 from paper_2311_10359_amd import binding, traces
 from parity_util import DEV
+from whole_workload import compare_whole_workload
 
 pytestmark = pytest.mark.gpu
 
@@ -63,21 +66,6 @@ def check_global_properties(prof, off, n_tasks):
     assert torch.equal(task, expect_task)
 
 
-def check_sampled_tasks(cfg, prof, off, tasks):
-    tro = binding.u64_to_numpy(prof.task_row_offsets)
-    for t in tasks:
-        rec = traces.task_records(cfg, t)
-        o_ids, o_rows, _ = oracle.profile(rec, np.array([0, rec.shape[0]], dtype=np.uint64))
-        lo, hi = int(off[t]), int(off[t + 1])
-        assert np.array_equal(binding.u64_to_numpy(prof.ids[lo:hi]), o_ids), f"task {t}: IDs differ"
-        got = binding.rows_to_numpy(prof.rows[int(tro[t]):int(tro[t + 1])])
-        o_rows = o_rows.copy()
-        o_rows["task"] = t
-        assert got.shape == o_rows.shape, f"task {t}: {got.shape[0]} rows, oracle {o_rows.shape[0]}"
-        assert got.tobytes() == o_rows.tobytes(), f"task {t}: rows differ"
-    say(f"  sampled tasks {list(tasks)} match the oracle")
-
-
 def profile_full(cfg):
     d_rec, off = upload(cfg)
     d_off = binding.to_device_u64(off, DEV)
@@ -111,13 +99,14 @@ def test_config1_medium_full_oracle():
     assert np.array_equal(binding.u64_to_numpy(got.lp_placed), exp[3])
 
 
-@pytest.mark.parametrize("index,sample", [(2, (0, 37, 63)), (3, (0, 101, 255))])
-def test_profile_only_workloads_full_size(index, sample):
+@pytest.mark.parametrize("index", [2, 3])
+def test_profile_only_workloads_full_size(index):
     cfg = traces.config(index)
-    say(f"config {index} ({cfg.name}), {cfg.n_records} records")
+    say(f"config {index} ({cfg.name}), {cfg.n_records} records, whole workload against the oracle")
     prof, off, d_off, d_rec = profile_full(cfg)
+    del d_rec
     check_global_properties(prof, off, cfg.n_tasks)
-    check_sampled_tasks(cfg, prof, off, sample)
+    compare_whole_workload(cfg, off, {"ids": prof.ids, "rows": prof.rows, "task_row_offsets": prof.task_row_offsets}, say=say)
 
 
 def test_config4_batched_gapfill_full_size():
@@ -126,7 +115,6 @@ def test_config4_batched_gapfill_full_size():
     prof, off, d_off, d_rec = profile_full(cfg)
     check_global_properties(prof, off, cfg.n_tasks)
     scen = [0, 1, 777, 32768, 65534, 65535]
-    check_sampled_tasks(cfg, prof, off, [t for s in scen for t in (2 * s, 2 * s + 1)])
     # the profile merged with itself: same IDs, counts and sums doubled (modulo 2^64), everything else as it was
     twice = binding.fikit_profile_merge(prof.rows, prof.task_row_offsets, prof.rows, prof.task_row_offsets)
     torch.cuda.synchronize()
@@ -160,20 +148,12 @@ def test_config4_batched_gapfill_full_size():
     assert torch.equal(fc.sum(dim=1), placed)
     assert bool((placed <= 16384).all()) and bool((got.filled_ns >= 0).all())
     assert bool((got.lp_completion_ns > 0).all())
-    # sampled scenarios one by one
-    for s in scen:
-        recs = [traces.task_records(cfg, 2 * s), traces.task_records(cfg, 2 * s + 1)]
-        loc_off = np.array([0, recs[0].shape[0], recs[0].shape[0] + recs[1].shape[0]], dtype=np.uint64)
-        o_ids, o_rows, o_tro = oracle.profile(np.concatenate(recs), loc_off)
-        one = np.array([0], dtype=np.uint32)
-        exp = oracle.gapfill(o_ids, loc_off, o_rows, o_tro, one, one + 1, cfg.margin_ns, cfg.min_gap_ns,
-                             traces.gap_offsets(loc_off, one))
-        g0, g1 = int(go[s]), int(go[s + 1])
-        assert np.array_equal(binding.u32_to_numpy(got.fill_count[g0:g1]), exp[0]), f"scenario {s}"
-        assert np.array_equal(got.filled_ns[g0:g1].cpu().numpy(), exp[1]), f"scenario {s}"
-        assert int(got.lp_completion_ns[s]) == int(exp[2][0]) and int(got.lp_placed[s]) == int(exp[3][0])
-    say(f"  sampled scenarios {scen} match the oracle")
+    # the whole workload against the oracle: every task's IDs and rows, every scenario's outputs
     d_hp, d_lp, d_go = binding.to_device_u32(hp, DEV), binding.to_device_u32(lp, DEV), binding.to_device_u64(go, DEV)
+    whole = compare_whole_workload(cfg, off, {"ids": prof.ids, "rows": prof.rows, "task_row_offsets": prof.task_row_offsets,
+                                              "gap_offsets": d_go, "fill_count": got.fill_count, "filled_ns": got.filled_ns,
+                                              "lp_completion_ns": got.lp_completion_ns, "lp_placed": got.lp_placed}, say=say)
+    assert whole["equal_scenarios"] == hp.size
     # best partner per high-priority task over these results: every task heads exactly one scenario here, so the
     # search must return that scenario, and the per-scenario sums must be the row sums of the filled times
     pair = binding.fikit_pairing_best(d_hp, d_lp, cfg.n_tasks, d_go, got.filled_ns, got.lp_completion_ns)
