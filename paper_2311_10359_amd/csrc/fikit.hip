@@ -51,8 +51,8 @@ struct Carver {
 
 struct ProfileLayout {
   uint64_t ctrl, k0, k1, k2, e0, e1, g0, g1, tiles, hist, sums, bits, word_prefix, gflag, dcount, total;
-  uint64_t is_long, mtiles, mflag, units, lists;   // long-task partition path; work lists
-  uint64_t max_tiles, n_words, max_units;
+  uint64_t is_long, mtiles, mflag, wflag, units, lists;   // long-task partition path; work lists
+  uint64_t max_tiles, max_ptiles, n_words, max_units;
 };
 
 ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
@@ -64,14 +64,21 @@ ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
   L.max_tiles = n / TILE + big_tasks;
   L.ctrl = c.take(256);
   L.k0 = c.take(n * 8);
-  L.k1 = c.take(n * 8 + 8);  // after the sort: segment starts
-  L.k2 = c.take(n * 8);
+  L.k1 = c.take(n * 8);      // long tasks: tile-ordered IDs; general path: keys (sorted in the end)
+  L.k2 = c.take(n * 8 + 8);  // long tasks: tile-ordered values; general path: second key buffer, then segment starts
   L.e0 = c.take(n * 8);
   L.e1 = c.take(n * 8);      // also: first half of the staged rows of one-workgroup tasks
   L.g0 = c.take(n * 8);
   L.g1 = c.take(n * 8);      // also: second half of the staged rows
   L.tiles = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
-  L.hist = c.take(L.max_tiles * 256 * 4);
+  uint64_t long_tasks = n / (static_cast<uint64_t>(FUSE_MAX) + 1);
+  if (long_tasks > n_tasks) long_tasks = n_tasks;
+  L.max_ptiles = n / PT_TILE + long_tasks;
+  {
+    // tile histograms of the sort passes; before them the bucket boundaries of the long tasks' tiles live here
+    const uint64_t a = L.max_tiles * 256 * 4, b = L.max_ptiles * PT_ROWS * 2;
+    L.hist = c.take(a > b ? a : b);
+  }
   uint64_t longest = L.max_tiles * 256;
   if (longest < static_cast<uint64_t>(n_tasks) + 1) longest = static_cast<uint64_t>(n_tasks) + 1;
   if (longest < L.n_words) longest = L.n_words;
@@ -83,10 +90,9 @@ ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
   L.is_long = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
   L.mtiles = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
   L.mflag = c.take(static_cast<uint64_t>(n_tasks) * 4);
-  uint64_t long_tasks = n / (static_cast<uint64_t>(FUSE_MAX) + 1);
-  if (long_tasks > n_tasks) long_tasks = n_tasks;
+  L.wflag = c.take(static_cast<uint64_t>(n_tasks) * 4);
   L.max_units = long_tasks * MSD_SLOTS;
-  L.units = c.take(L.max_units * 4 * 5);   // start, length, task, row count, first row
+  L.units = c.take(L.max_units * 4 * 6);   // start, length, task, row count, first row, buckets
   {
     const uint64_t longest_list = L.max_units > n_tasks ? L.max_units : n_tasks;
     L.lists = c.take(longest_list * 4 * 3);
@@ -265,7 +271,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   uint32_t* dcount = reinterpret_cast<uint32_t*>(ws + L.dcount);
   uint64_t* bits = reinterpret_cast<uint64_t*>(ws + L.bits);
   uint32_t* word_prefix = reinterpret_cast<uint32_t*>(ws + L.word_prefix);
-  uint32_t* seg_start = reinterpret_cast<uint32_t*>(k1);
+  uint32_t* seg_start = reinterpret_cast<uint32_t*>(k2);
 
   // Short tasks with few distinct IDs: one workgroup each, records read once, rows staged.
   tr.mark("plan");
@@ -280,6 +286,10 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   uint32_t* utask = ulen + L.max_units;
   uint32_t* udcount = utask + L.max_units;
   uint32_t* urow = udcount + L.max_units;
+  uint32_t* ubuckets = urow + L.max_units;
+  uint32_t* wflag = reinterpret_cast<uint32_t*>(ws + L.wflag);
+  uint16_t* bound = reinterpret_cast<uint16_t*>(hist);
+  uint2* part_kg = reinterpret_cast<uint2*>(k2);
   auto small = k_task_fused<FUSE_S_THREADS, FUSE_SMALL_MAX / FUSE_S_THREADS, 256, 7168, FUSE_S_LB, false, FUSE_S_WPE>;
   auto medium = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, false, 4, FUSE_M_ESTATS>;
   auto mid = k_task_fused<512, 16, 256, 7168, 2, false, 4>;
@@ -287,8 +297,6 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   auto mid_u = k_task_fused<512, 16, 256, 7168, 4, true, 4>;
   auto medium_u = k_task_fused<FUSE_M_THREADS, FUSE_MAX / FUSE_M_THREADS, FUSE_M_DMAX, FUSE_M_HIST, 2, true, 4, FUSE_M_ESTATS>;
   constexpr size_t mid_lds = sizeof(FusedSmem<512, 256, 7168>);
-  FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tile_scatter), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(sizeof(TileSmem))));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mid_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(mid_lds)));
   constexpr size_t small_lds = sizeof(FusedSmem<FUSE_S_THREADS, 256, 7168>),
@@ -298,7 +306,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(small_lds)));
   FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(medium_u), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(medium_lds)));
   FusedArgs fa{};
-  fa.rec = d_records; fa.off = d_task_offsets; fa.ids = ids; fa.e0 = e0; fa.g0 = g0;
+  fa.rec = d_records; fa.off = d_task_offsets; fa.ids = ids; fa.e0 = e0; fa.g0 = g0; fa.key0 = k1;
   fa.stage_a = e1; fa.stage_b = g1; fa.dcount = dcount; fa.gflag = gflag; fa.ctrl = ctrl;
   {
     tr.mark("k_task_fused_small");
@@ -317,33 +325,31 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   if (int rc = status_from_bits(h.status)) return rc;
   uint64_t n_units = 0;
   if (h.n_long > 0) {
-    // Long tasks: Kernel ID and per-launch values into memory, one partition pass by the top ID bits,
-    // then the one-workgroup kernel on units of buckets.
+    // Long tasks: one pass over the records orders every tile by the top ID bits (IDs out in launch order on
+    // the way), then the one-workgroup kernel on units of buckets, which gathers its launches from the tiles.
     n_units = h.n_long * MSD_SLOTS;
     if (n_units > L.max_units) return FIKIT_HIP_ERROR;   // cannot happen: a long task has more than FUSE_MAX launches
     tr.mark("plan");
     hipLaunchKernelGGL(k_plan_msd, dim3(blocks_for(static_cast<uint64_t>(n_tasks) + 1, 256)), dim3(256), 0, st, d_task_offsets,
-                       n_tasks, gflag, is_long, mtiles);
+                       n_tasks, gflag, is_long, mtiles, wflag);
     if (int rc = scan_u32(is_long, static_cast<uint64_t>(n_tasks) + 1, sums, nullptr, st)) return rc;
     if (int rc = scan_u32(mtiles, static_cast<uint64_t>(n_tasks) + 1, sums, &ctrl->n_big_tiles, st)) return rc;
     tr.mark("host_sync");
     if (int rc = read_ctrl(ctrl, &h, st)) return rc;
     const uint64_t n_msd_tiles = h.n_big_tiles;
-    if (n_msd_tiles == 0 || n_msd_tiles > L.max_tiles) return FIKIT_HIP_ERROR;
-    tr.mark("k_hash_tiles");
-    hipLaunchKernelGGL(k_hash_tiles, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(256), 0, st, d_records, d_task_offsets, n_tasks,
-                       mtiles, ids, e0, g0, hist, ctrl);
-    tr.mark("scan_tile_hist");
-    if (int rc = scan_u32(hist, n_msd_tiles * 256, sums, nullptr, st)) return rc;
-    tr.mark("plan");
+    if (n_msd_tiles == 0 || n_msd_tiles > L.max_ptiles) return FIKIT_HIP_ERROR;
+    tr.mark("k_tile_partition");
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tile_partition), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  static_cast<int>(sizeof(PartSmem))));
+    hipLaunchKernelGGL(k_tile_partition, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(PT_THREADS), sizeof(PartSmem), st, d_records,
+                       d_task_offsets, n_tasks, mtiles, ids, k1, part_kg, bound, wflag, ctrl);
+    tr.mark("k_msd_units");
     hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, &ctrl->n_class[0], static_cast<uint64_t>(4), 0u);   // the lists are reused for units
-    hipLaunchKernelGGL(k_msd_units, dim3(n_tasks), dim3(WAVE), 0, st, d_task_offsets, n_tasks, is_long, mtiles, hist,
-                       ustart, ulen, utask, udcount, mflag, gflag, lists, static_cast<uint32_t>(n_units), ctrl);
-    tr.mark("k_tile_scatter");
-    hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(TILE_THREADS), sizeof(TileSmem), st, d_task_offsets, n_tasks,
-                       mtiles, hist, 0, mflag, FUSE_SMALL_MAX, ids, k1, e0, e1, g0, g1);
+    hipLaunchKernelGGL(k_msd_units, dim3(n_tasks), dim3(MSD_SLOTS), 0, st, d_task_offsets, n_tasks, is_long, mtiles, bound, wflag,
+                       ustart, ulen, utask, udcount, ubuckets, mflag, gflag, lists, static_cast<uint32_t>(n_units), ctrl);
     FusedArgs ua = fa;
-    ua.ustart = ustart; ua.ulen = ulen; ua.utask = utask; ua.skey = k1; ua.mflag = mflag; ua.dcount = udcount;
+    ua.ustart = ustart; ua.ulen = ulen; ua.utask = utask; ua.ubuckets = ubuckets; ua.tile_prefix = mtiles; ua.bound = bound;
+    ua.tile_len = PT_TILE; ua.part_id = k1; ua.part_kg = part_kg; ua.mflag = mflag; ua.dcount = udcount;
     tr.mark("k_unit_fused_small");
     ua.list = lists; ua.count = &ctrl->n_class[0]; ua.max_len = FUSE_SMALL_MAX;
     hipLaunchKernelGGL(small_u, dim3(static_cast<uint32_t>(n_units)), dim3(FUSE_S_THREADS), small_lds, st, ua);
@@ -359,6 +365,11 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     tr.mark("host_sync");
     if (int rc = read_ctrl(ctrl, &h, st)) return rc;
     if (int rc = status_from_bits(h.status)) return rc;
+    if (h.n_general > 0) {
+      tr.mark("k_long_general_values");
+      hipLaunchKernelGGL(k_long_general_values, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(256), 0, st, d_records, d_task_offsets,
+                         n_tasks, mtiles, gflag, wflag, ids, k1, part_kg, e0, g0);
+    }
   }
   const bool any_general = h.n_general > 0;
   uint64_t n_heads = 0;
@@ -376,20 +387,22 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     const uint64_t n_big_tiles = h.n_big_tiles;
     if (n_big_tiles > L.max_tiles) return FIKIT_HIP_ERROR;  // cannot happen for valid offsets
 
-    // sorted keys end in k2, payload in e0 / g0
+    // keys start in k1 (in whatever order each task's triples were handed over) and end there sorted, payload in e0 / g0
     FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_leaf_sort), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   static_cast<int>(sizeof(LeafSmem))));
     tr.mark("k_leaf_sort");
-    hipLaunchKernelGGL(k_leaf_sort, dim3(xcd_grid(n_tasks)), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, gflag, ids,
-                       k2, e0, g0, ctrl);
+    hipLaunchKernelGGL(k_leaf_sort, dim3(xcd_grid(n_tasks)), dim3(LEAF_THREADS), sizeof(LeafSmem), st, d_task_offsets, n_tasks, gflag, k1,
+                       k1, e0, g0, ctrl);
     FIKIT_HIP(hipGetLastError());
     // Eight stable passes over the eight key bytes sort any keys.  Kernel IDs are hashes: a task's distinct IDs
     // almost always differ in their upper four bytes already, so four passes over those are tried first; the
     // head search below also notices keys that are still out of order, and then all eight passes are run on
     // what the four left (any order of the (key, values) triples is a valid start).
-    auto sort_passes = [&](const uint64_t* kin, int64_t* ein, int64_t* gin, int first_byte) -> int {
-      uint64_t* kout = k1;
-      int64_t *eout = (ein == e0) ? e1 : e0, *gout = (gin == g0) ? g1 : g0;
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tile_scatter), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  static_cast<int>(sizeof(TileSmem))));
+    auto sort_passes = [&](int first_byte) -> int {
+      uint64_t *kin = k1, *kout = k2;
+      int64_t *ein = e0, *eout = e1, *gin = g0, *gout = g1;
       for (int pass = first_byte; pass < 8; ++pass) {
         const int shift = 8 * pass;
         tr.mark("k_tile_hist");
@@ -399,29 +412,28 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
         if (int rc = scan_u32(hist, n_big_tiles * 256, sums, nullptr, st)) return rc;
         tr.mark("k_tile_scatter");
         hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), sizeof(TileSmem), st, d_task_offsets,
-                           n_tasks, tiles, hist, shift, static_cast<const uint32_t*>(nullptr), 0u, kin, kout, ein, eout, gin, gout);
+                           n_tasks, tiles, hist, shift, kin, kout, ein, eout, gin, gout);
         FIKIT_HIP(hipGetLastError());
-        kin = kout;
-        kout = (kout == k1) ? k2 : k1;
+        uint64_t* tk = kin; kin = kout; kout = tk;
         int64_t* t = ein; ein = eout; eout = t;
         t = gin; gin = gout; gout = t;
       }
-      return FIKIT_OK;   // (an even number of passes: keys end in k2, values in the arrays they started in)
+      return FIKIT_OK;   // (an even number of passes: keys and values end in the arrays they started in)
     };
     auto find_heads = [&]() -> int {
       tr.mark("heads");
-      hipLaunchKernelGGL(k_head_bits, dim3(blocks_for(n, 256)), dim3(256), 0, st, k2, n, d_task_offsets, n_tasks, gflag, bits, ctrl);
+      hipLaunchKernelGGL(k_head_bits, dim3(blocks_for(n, 256)), dim3(256), 0, st, k1, n, d_task_offsets, n_tasks, gflag, bits, ctrl);
       hipLaunchKernelGGL(k_popcount_words, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, L.n_words, word_prefix);
       if (int rc = scan_u32(word_prefix, L.n_words, sums, &ctrl->n_heads, st)) return rc;
       tr.mark("host_sync");
       return read_ctrl(ctrl, &h, st);
     };
     if (n_big_tiles > 0)
-      if (int rc = sort_passes(ids, e0, g0, 4)) return rc;
+      if (int rc = sort_passes(4)) return rc;
     if (int rc = find_heads()) return rc;
     if (h.wide) {
       hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, &ctrl->wide, static_cast<uint64_t>(1), 0u);
-      if (int rc = sort_passes(k2, e0, g0, 0)) return rc;
+      if (int rc = sort_passes(0)) return rc;
       if (int rc = find_heads()) return rc;
       if (h.wide) return FIKIT_HIP_ERROR;   // cannot happen: eight passes sort
     }
@@ -454,7 +466,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
                        seg_start);
     tr.mark("k_stats_small");
     hipLaunchKernelGGL(k_stats_small, dim3(blocks_for(n_heads, 4)), dim3(256), 0, st, seg_start, n_heads, d_task_offsets,
-                       n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out);
+                       n_tasks, k1, e0, g0, bits, word_prefix, n, dcount, d_rows_out);
     // rows with long segments: by work list (the staging areas e1 / g1 are free once the rows are gathered)
     tr.mark("k_stats_lists");
     uint32_t* rlist = reinterpret_cast<uint32_t*>(e1);
@@ -465,10 +477,10 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     const uint32_t big_grid = static_cast<uint32_t>(n_heads < 4096 ? n_heads : 4096);
     const uint32_t huge_grid = static_cast<uint32_t>(n_heads < 512 ? n_heads : 512);
     hipLaunchKernelGGL(k_stats_big<BIG_THREADS>, dim3(big_grid), dim3(BIG_THREADS), 0, st, seg_start, n_heads, d_task_offsets,
-                       n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out, rlist, &ctrl->n_class[0], 0u);
+                       n_tasks, k1, e0, g0, bits, word_prefix, n, dcount, d_rows_out, rlist, &ctrl->n_class[0], 0u);
     tr.mark("k_stats_huge");
     hipLaunchKernelGGL(k_stats_big<HUGE_THREADS>, dim3(huge_grid), dim3(HUGE_THREADS), 0, st, seg_start, n_heads,
-                       d_task_offsets, n_tasks, k2, e0, g0, bits, word_prefix, n, dcount, d_rows_out, rlist, &ctrl->n_class[1],
+                       d_task_offsets, n_tasks, k1, e0, g0, bits, word_prefix, n, dcount, d_rows_out, rlist, &ctrl->n_class[1],
                        1u);
   }
   FIKIT_HIP(hipGetLastError());

@@ -68,14 +68,8 @@ constexpr int LEAF_THREADS = 1024;
 constexpr int LEAF_WAVES = LEAF_THREADS / WAVE;
 constexpr int LEAF_KPT = LEAF / LEAF_THREADS;
 
-#ifndef FIKIT_TILE
-#define FIKIT_TILE 8192
-#endif
-#ifndef FIKIT_TILE_THREADS
-#define FIKIT_TILE_THREADS 512
-#endif
-constexpr uint32_t TILE = FIKIT_TILE;  // records per tile of the multi-pass path
-constexpr int TILE_THREADS = FIKIT_TILE_THREADS;
+constexpr uint32_t TILE = 8192;  // records per tile of the multi-pass path
+constexpr int TILE_THREADS = 512;
 constexpr int TILE_WAVES = TILE_THREADS / WAVE;
 constexpr int TILE_KPT = TILE / TILE_THREADS;
 
@@ -156,8 +150,8 @@ __device__ __forceinline__ void tile_digit_offsets(uint32_t (*cnt)[256], uint32_
 
 // ------------------------------------------------------------------ LDS sort of a short task
 // One workgroup per task of 1..LEAF records.  Sorts (key, local index) by eight 8-bit passes in
-// LDS, then writes the sorted keys and gathers the payload in the sorted order (in place:
-// every payload value is in a register before the first one is overwritten).
+// LDS, then writes the sorted keys and gathers the payload in the sorted order (in place, keys too if
+// key_in == key_out: every key is in LDS and every payload value in a register before the first one is overwritten).
 struct LeafSmem {
   uint64_t key[LEAF];
   uint32_t cnt[LEAF_WAVES][256];
@@ -166,8 +160,8 @@ struct LeafSmem {
 };
 
 __global__ void __launch_bounds__(LEAF_THREADS)
-k_leaf_sort(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ gflag, const uint64_t* __restrict__ ids,
-            uint64_t* __restrict__ key_out, int64_t* __restrict__ exec_io, int64_t* __restrict__ gap_io,
+k_leaf_sort(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ gflag, const uint64_t* key_in,
+            uint64_t* key_out, int64_t* __restrict__ exec_io, int64_t* __restrict__ gap_io,
             const Ctrl* ctrl) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   LeafSmem& sm = *reinterpret_cast<LeafSmem*>(smem_raw);
@@ -180,7 +174,7 @@ k_leaf_sort(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* 
   const uint32_t m = static_cast<uint32_t>(len64);
   const uint32_t tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
 
-  for (uint32_t i = tid; i < m; i += LEAF_THREADS) { sm.key[i] = ids[base + i]; sm.idx[i] = static_cast<uint16_t>(i); }
+  for (uint32_t i = tid; i < m; i += LEAF_THREADS) { sm.key[i] = key_in[base + i]; sm.idx[i] = static_cast<uint16_t>(i); }
   // every wave owns `rounds` consecutive groups of 64 positions
   const uint32_t rounds = (m + LEAF_THREADS - 1) / LEAF_THREADS;
   const uint32_t wave_base = w * rounds * WAVE;
@@ -275,8 +269,7 @@ struct TileSmem {
 // Stable scatter of one tile by the current digit.  Hs is H after the exclusive scan.
 __global__ void __launch_bounds__(TILE_THREADS)
 k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix,
-               const uint32_t* __restrict__ Hs, int shift, const uint32_t* __restrict__ only_if, uint32_t top_bits_per,
-               const uint64_t* __restrict__ key_in, uint64_t* __restrict__ key_out,
+               const uint32_t* __restrict__ Hs, int shift, const uint64_t* __restrict__ key_in, uint64_t* __restrict__ key_out,
                const int64_t* __restrict__ exec_in, int64_t* __restrict__ exec_out,
                const int64_t* __restrict__ gap_in, int64_t* __restrict__ gap_out) {
   extern __shared__ __align__(16) unsigned char tile_raw[];
@@ -291,15 +284,6 @@ k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_
   const uint64_t end = off[t + 1];
   const uint32_t m = static_cast<uint32_t>(end - start < TILE ? end - start : TILE);
   const uint32_t tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  if (only_if && !only_if[t]) return;   // partition pass: the task was left to the general path
-  if (top_bits_per) {
-    // partition pass: the digit is the task's top ID bits (about one bucket per top_bits_per launches)
-    const uint64_t want = (end - task_start + top_bits_per - 1) / top_bits_per;
-    uint32_t b = 1;
-    while ((1ull << b) < want && b < 8) ++b;
-    shift = 64 - static_cast<int>(b);
-  }
-
   for (uint32_t d = lane; d < 256; d += WAVE) sm.cnt[w][d] = 0;
   __builtin_amdgcn_wave_barrier();
 

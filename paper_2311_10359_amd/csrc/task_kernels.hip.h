@@ -31,25 +31,10 @@ constexpr uint64_t HT_EMPTY = ~0ull;
 constexpr uint32_t FUSE_SMALL_MAX = 4096;    // tasks up to this many launches: 512-thread workgroup, 8 launches per thread
 constexpr uint32_t FUSE_MID_MAX = 8192;      // up to this many: 512-thread workgroup, 16 launches per thread
 constexpr uint32_t FUSE_MAX = 16384;         // tasks up to this many launches: one larger workgroup
-#ifndef FUSE_M_THREADS_V
-#define FUSE_M_THREADS_V 1024
-#define FUSE_M_DMAX_V 512
-#define FUSE_M_HIST_V 16384
-#endif
-#ifndef FUSE_S_THREADS_V
-#define FUSE_S_THREADS_V 512
-#define FUSE_S_WPE_V 6
-#endif
-#ifndef FUSE_S_LB_V
-#define FUSE_S_LB_V 1
-#endif
-constexpr int FUSE_S_LB = FUSE_S_LB_V;
-#ifndef FUSE_M_ESTATS_V
-#define FUSE_M_ESTATS_V true
-#endif
-constexpr bool FUSE_M_ESTATS = FUSE_M_ESTATS_V;
-constexpr int FUSE_S_THREADS = FUSE_S_THREADS_V, FUSE_S_WPE = FUSE_S_WPE_V;
-constexpr int FUSE_M_THREADS = FUSE_M_THREADS_V, FUSE_M_DMAX = FUSE_M_DMAX_V, FUSE_M_HIST = FUSE_M_HIST_V;
+constexpr int FUSE_S_THREADS = 512, FUSE_S_WPE = 6, FUSE_S_LB = 1;            // shape for tasks up to FUSE_SMALL_MAX
+constexpr int FUSE_M_THREADS = 1024, FUSE_M_DMAX = 512, FUSE_M_HIST = 16384;  // shape for tasks up to FUSE_MAX
+constexpr bool FUSE_M_ESTATS = true;
+constexpr uint32_t UNIT_RUNS_MAX = 1024;     // most tiles a long task may have for its units to be gathered (one run per tile)
 
 template <int NT>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* aux, uint32_t& total) {
@@ -155,10 +140,7 @@ __device__ __forceinline__ uint32_t sel_b95(uint32_t y) { return (y >> SEL_B95_A
 // log2 of the number of bins the fast percentile path cuts an ID's value range into: about one bin
 // per WINDOW_SAMPLES_PER_BIN samples (the bin that holds a wanted rank is ranked directly afterwards), at least 2,
 // at most 2^max_log2.
-#ifndef WINDOW_SAMPLES_PER_BIN_V
-#define WINDOW_SAMPLES_PER_BIN_V 1
-#endif
-constexpr uint32_t WINDOW_SAMPLES_PER_BIN = WINDOW_SAMPLES_PER_BIN_V;
+constexpr uint32_t WINDOW_SAMPLES_PER_BIN = 1;
 __device__ __forceinline__ uint32_t window_bins_log2(uint32_t count, uint32_t max_log2) {
   const uint32_t want = count / WINDOW_SAMPLES_PER_BIN;
   const uint32_t lg = want <= 2 ? 1u : 32u - __builtin_clz(want - 1);
@@ -192,11 +174,17 @@ struct FusedArgs {
   uint64_t* ids;               // receives the IDs in launch order
   int64_t* e0;                 // per-launch values handed to the general path when a task does not fit
   int64_t* g0;
-  // units: groups of ID buckets of a long task, already in (ID, exec, gap) arrays
-  const uint32_t* ustart;
+  uint64_t* key0;              // ... with their IDs, in the same order
+  // units: groups of consecutive ID buckets of a long task, whose launches lie bucket-ordered inside every tile
+  const uint32_t* ustart;      // where the unit would start if the task were in bucket order: names its staging slice
   const uint32_t* ulen;
   const uint32_t* utask;
-  const uint64_t* skey;
+  const uint32_t* ubuckets;    // first bucket | (bucket after the last) << 16
+  const uint32_t* tile_prefix; // first tile of every task
+  const uint16_t* bound;       // bucket boundaries of the tiles (layout: see k_tile_partition)
+  uint32_t tile_len;           // launches per tile
+  const uint64_t* part_id;     // tile-ordered IDs
+  const uint2* part_kg;        // tile-ordered (execution time, idle time or NONE32)
   uint32_t* mflag;             // cleared when a unit sends its task to the general path
   // both
   int64_t* stage_a;            // rows are staged in the task's / unit's own slice of these two arrays
@@ -272,22 +260,50 @@ k_task_fused(const FusedArgs A) {
 #pragma unroll
   for (int r = 0; r < KPT; ++r) { ev[r] = 0; gv[r] = NONE32; sl[r] = 0; }
   if (UNITS) {
-    // values come from the partitioned arrays; IDs go straight into the ID table
+    // The unit's launches lie in one run per tile of its task: between the boundaries of its first bucket and of
+    // the bucket after its last.  Run table in LDS (the space of the identity memo, which units do not use):
+    // where each run starts in the tile-ordered arrays, and how many of the unit's launches precede it.
+    uint32_t* run_at = reinterpret_cast<uint32_t*>(&sm.u.memo);
+    uint32_t* run_before = run_at + UNIT_RUNS_MAX;          // [tiles + 1]
+    const uint32_t ub = A.ubuckets[unit], d0 = ub & 0xffffu, d1 = ub >> 16;
+    const uint32_t tp = A.tile_prefix[t], tiles_t = A.tile_prefix[t + 1] - tp;
+    const uint64_t task_start = A.off[t];
+    const uint16_t* b_lo = A.bound + static_cast<uint64_t>(tp) * (256 + 1) + static_cast<uint64_t>(d0) * tiles_t;
+    const uint16_t* b_hi = A.bound + static_cast<uint64_t>(tp) * (256 + 1) + static_cast<uint64_t>(d1) * tiles_t;
+    uint32_t carry = 0;
+    for (uint32_t j0 = 0; j0 < tiles_t; j0 += NT) {   // (trip count is the same for every thread)
+      const uint32_t j = j0 + tid;
+      uint32_t lo = 0, c = 0;
+      if (j < tiles_t) { lo = b_lo[j]; c = static_cast<uint32_t>(b_hi[j]) - lo; }
+      uint32_t total;
+      const uint32_t ex = block_excl_scan<NT>(c, sm.aux, total);
+      if (j < tiles_t) {
+        run_at[j] = static_cast<uint32_t>(task_start) + j * A.tile_len + lo;
+        run_before[j] = carry + ex;
+      }
+      carry += total;
+    }
+    if (tid == 0) run_before[tiles_t] = carry;
+    __syncthreads();
+    if (carry != m) {   // (cannot happen: the unit's length is the sum of these runs)
+      if (tid == 0) atomicOr(&ctrl->status, ERR_OFFSETS);
+      return;
+    }
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
       const uint32_t i = r * NT + tid;
       if (i < m) {
-        const uint64_t id = A.skey[base + i];
-        const uint64_t e64 = static_cast<uint64_t>(stage_a[base + i]);
-        const int64_t g64 = stage_b[base + i];
-        wide |= (e64 >= NONE32);
-        ev[r] = static_cast<uint32_t>(e64);
+        // runs are of similar length: start at the proportional guess, then step to the run that holds launch i
+        uint32_t j = static_cast<uint32_t>((static_cast<uint64_t>(i) * tiles_t) / m);
+        while (run_before[j] > i) --j;
+        while (run_before[j + 1] <= i) ++j;
+        const uint32_t at = run_at[j] + (i - run_before[j]);
+        const uint64_t id = A.part_id[at];
+        const uint2 kg = A.part_kg[at];
+        ev[r] = kg.x;
+        gv[r] = kg.y;
         my_maxe = ev[r] > my_maxe ? ev[r] : my_maxe;
-        if (g64 != GAP_NONE) {
-          wide |= (static_cast<uint64_t>(g64) >= NONE32);
-          gv[r] = static_cast<uint32_t>(g64);
-          my_maxg = gv[r] > my_maxg ? gv[r] : my_maxg;
-        }
+        if (gv[r] != NONE32) my_maxg = gv[r] > my_maxg ? gv[r] : my_maxg;
         uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (HT - 1);
         bool placed = false;
         if (id != HT_EMPTY) {
@@ -440,7 +456,7 @@ k_task_fused(const FusedArgs A) {
   const uint32_t D = sm.ndist;
   if (sm.fallback || D > DMAX || D > 2 * (m >> 4)) {
     if (UNITS) {
-      // the whole task goes to the general path (its per-launch values are still in e0 / g0)
+      // the whole task goes to the general path (k_long_general_values hands its per-launch values over)
       if (tid == 0 && atomicExch(&A.mflag[t], 0u) == 1u) {
         gflag[t] = 1;
         atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), 1ull);
@@ -448,6 +464,7 @@ k_task_fused(const FusedArgs A) {
       return;
     }
     // general path: hand over the per-launch values (recomputed at full width)
+    // (every thread reads back the IDs it wrote itself)
     for (uint32_t i = tid; i < m; i += NT) {
       const fikit_launch* q = rec + base + i;
       const int64_t end = q->end_ns;
@@ -455,6 +472,7 @@ k_task_fused(const FusedArgs A) {
       int64_t g = GAP_NONE;
       if (i + 1 < m) { g = q[1].start_ns - end; g = g < 0 ? 0 : g; }
       g0[base + i] = g;
+      A.key0[base + i] = ids[base + i];
     }
     if (tid == 0) { gflag[t] = 1; atomicAdd(reinterpret_cast<unsigned long long*>(&ctrl->n_general), 1ull); }
     return;
