@@ -14,7 +14,9 @@
 //   oracle_profile    - the measurement phase's statistical output (Section 3.2, "Data
 //                       acquisition and statistical output during the measurement phase"): the
 //                       set of unique IDs S_UID of each task, and per ID the execution times
-//                       K and the idle times G that follow a kernel of that ID.  The paper
+//                       K and the idle times G that follow a kernel of that ID, over all measured
+//                       runs of the task (a launch record names its run; a run of N kernels has
+//                       N - 1 idle times, none between one run and the next).  The paper
 //                       prints the means SK_j and SG_j; this oracle emits count and sum (so the
 //                       mean is sum/count) and, beyond the paper, min, max and nearest-rank p50
 //                       and p95 of the same samples.
@@ -66,7 +68,8 @@ struct Launch {
   uint32_t shmem;
   int64_t start_ns;
   int64_t end_ns;
-  uint8_t reserved[16];
+  uint32_t run;  // which of the task's measured runs the launch belongs to (not part of the identity)
+  uint8_t reserved[12];
 };
 static_assert(sizeof(Launch) == 64, "launch record is 64 bytes");
 
@@ -139,7 +142,7 @@ int64_t predicted(const Stats& s, int predictor) {
 
 struct Samples {
   std::vector<int64_t> exec;  // K: execution time of every launch with this ID
-  std::vector<int64_t> gap;   // G: idle time after every launch with this ID (not the last of the task)
+  std::vector<int64_t> gap;   // G: idle time after every launch with this ID (not the last of a run)
 };
 
 bool offsets_ok(const uint64_t* off, uint32_t n_tasks, uint64_t n) {
@@ -181,7 +184,9 @@ int oracle_profile(const void* records_v, uint64_t n_records, const uint64_t* ta
       const int64_t k = rec[i].end_ns - rec[i].start_ns;  // execution time K
       Samples& s = by_id[id];
       s.exec.push_back(k);
-      if (i + 1 < hi) {  // idle time G: from this kernel's end to the next kernel's start
+      // idle time G: from this kernel's end to the next kernel's start; a run of N kernels has N - 1 of them
+      // (Section 3.2), so the last kernel of a run has none even if another run of the task follows
+      if (i + 1 < hi && rec[i + 1].run == rec[i].run) {
         int64_t g = rec[i + 1].start_ns - rec[i].end_ns;
         if (g < 0) g = 0;  // overlapping kernels leave no idle time
         s.gap.push_back(g);
@@ -314,7 +319,7 @@ int oracle_measure(const void* records_v, uint64_t n_records, const uint64_t* ta
       if (rec[i].end_ns < rec[i].start_ns) return BAD_RECORD;
       exec_ns[i] = rec[i].end_ns - rec[i].start_ns;
       int64_t g = -1;
-      if (i + 1 < hi) {
+      if (i + 1 < hi && rec[i + 1].run == rec[i].run) {  // (no idle time after the last kernel of a run)
         g = rec[i + 1].start_ns - rec[i].end_ns;
         if (g < 0) g = 0;
       }

@@ -35,7 +35,8 @@ LAUNCH_DTYPE = np.dtype(
         ("shmem", "<u4"),
         ("start_ns", "<i8"),
         ("end_ns", "<i8"),
-        ("reserved", "u1", (16,)),
+        ("run", "<u4"),
+        ("reserved", "u1", (12,)),
     ]
 )
 assert LAUNCH_DTYPE.itemsize == 64
@@ -70,6 +71,7 @@ class TraceConfig:
     scenario_kind: str = "none"  # "pair01" | "grid" | "adjacent" | "none"
     margin_ns: int = 500
     min_gap_ns: int = 0
+    runs: int = 1  # measured runs per task: the trace is cut into this many runs of (almost) equal length
     overrides: tuple = ()  # the keyword overrides config() was called with (to rebuild it elsewhere)
 
     @property
@@ -82,7 +84,7 @@ def _const(v):
 
 
 def config(index: int, *, n_tasks: Optional[int] = None, launches: Optional[int] = None,
-           hp_launches: Optional[int] = None, lp_launches: Optional[int] = None) -> TraceConfig:
+           hp_launches: Optional[int] = None, lp_launches: Optional[int] = None, runs: Optional[int] = None) -> TraceConfig:
     """The five workloads.  Keyword overrides shrink a workload while keeping its structure
     (same distributions, same ID pattern) so that it can be checked on a CPU in seconds."""
     ln = math.log
@@ -127,8 +129,8 @@ def config(index: int, *, n_tasks: Optional[int] = None, launches: Optional[int]
     else:
         raise ValueError(f"no workload {index}")
     ov = tuple((k, v) for k, v in (("n_tasks", n_tasks), ("launches", launches), ("hp_launches", hp_launches),
-                                   ("lp_launches", lp_launches)) if v is not None)
-    return replace(cfg, overrides=ov)
+                                   ("lp_launches", lp_launches), ("runs", runs)) if v is not None)
+    return replace(cfg, overrides=ov, runs=runs or 1)
 
 
 def _rng(cfg: TraceConfig, task: int, stream: int) -> np.random.Generator:
@@ -238,6 +240,9 @@ def task_records(cfg: TraceConfig, task: int, out: Optional[np.ndarray] = None) 
     quads = rec.view("<i8").reshape(n, 8)
     quads[:, 4] = start
     np.add(start, exec_ns, out=quads[:, 5])
+    if cfg.runs > 1:
+        # launch i belongs to run floor(i * runs / n); the time between two runs stays in the timestamps
+        words[:, 12] = (np.arange(n, dtype=np.int64) * cfg.runs // n).astype(np.uint32)
     return rec
 
 

@@ -925,6 +925,67 @@ def test_p9_merge_of_runs_is_the_profile_without_the_idle_time_between_runs(cfg)
             oracle.profile_merge(bad, tro1, rows2, tro2)
 
 
+# ---------------------------------------------------------------- P10: several measured runs in one trace
+@pytest.mark.parametrize("case", ["two_runs_of_six", "three_runs_of_four", "run_numbers_need_not_be_consecutive_or_ascending"])
+def test_p10_runs_hand_worked(p1, golden_dir, case):
+    g1, rec, off = p1
+    with open(os.path.join(golden_dir, "p10_runs_hand_worked.json")) as f:
+        g = json.load(f)["cases"][case]
+    hp = rec[:12].copy()
+    hp["run"] = g["run_of_launch"]
+    _, rows, _ = oracle.profile(hp, np.array([0, 12], dtype=np.uint64))
+    assert len(rows) == 3
+    for r, name in zip(rows, g1["rows_in_order"][:3]):
+        assert stats_tuple(r["exec"]) == g1["rows"][name]["exec"]      # execution times do not depend on the runs
+        assert stats_tuple(r["gap"]) == g["gap"][name], name
+    if "SG_C" in g:
+        c = rows[2]
+        assert Fraction(int(c["gap"]["sum"]), int(c["gap"]["count"])) == g["SG_C"]
+    _, gp = oracle.measure(hp, np.array([0, 12], dtype=np.uint64))
+    ends = [i for i in range(12) if i == 11 or g["run_of_launch"][i + 1] != g["run_of_launch"][i]]
+    assert [i for i in range(12) if gp[i] < 0] == ends
+
+
+@pytest.mark.parametrize("cfg", small_configs(), ids=lambda c: c.name)
+@pytest.mark.parametrize("runs", [2, 5])
+def test_p10_runs_in_one_trace_against_numpy_and_against_the_merge_of_separate_profiles(cfg, runs):
+    cfg = traces.config(cfg.index, runs=runs, **dict(cfg.overrides))
+    rec, off = traces.build(cfg)
+    assert int(rec["run"].max()) == runs - 1
+    ids, rows, tro = oracle.profile(rec, off)
+    plain = rec.copy()
+    plain["run"] = 0
+    ids0, rows0, tro0 = oracle.profile(plain, off)
+    # the run number is no part of the identity, and execution times do not depend on it
+    assert np.array_equal(ids, ids0) and np.array_equal(tro, tro0)
+    assert np.array_equal(rows["kernel_id"], rows0["kernel_id"]) and rows["exec"].tobytes() == rows0["exec"].tobytes()
+    n_runs = sum(len(np.unique(rec["run"][int(off[t]):int(off[t + 1])])) for t in range(cfg.n_tasks))
+    assert int(rows["gap"]["count"].sum()) == rec.shape[0] - n_runs          # N - 1 idle times per run
+    # every field, percentiles included, from plain numpy on the samples that the definition keeps
+    for t in range(cfg.n_tasks):
+        lo, hi = int(off[t]), int(off[t + 1])
+        same_run = rec["run"][lo + 1:hi] == rec["run"][lo:hi - 1]
+        gap = np.maximum(0, rec["start_ns"][lo + 1:hi] - rec["end_ns"][lo:hi - 1])
+        r = rows[int(tro[t]):int(tro[t + 1])]
+        pick = np.random.default_rng(t).choice(len(r), size=min(len(r), 16), replace=False)
+        for k in pick:
+            mine = ids[lo:hi - 1] == r["kernel_id"][k]
+            assert stats_tuple(r[k]["gap"]) == numpy_stats(gap[mine & same_run])
+    # the runs profiled one by one and merged: the same counts, sums, minima and maxima
+    merged, mtro = None, None
+    for q in range(runs):
+        keep = rec["run"] == q
+        sub = plain[keep]
+        sub_off = np.zeros(cfg.n_tasks + 1, dtype=np.uint64)
+        np.cumsum([int(keep[int(off[t]):int(off[t + 1])].sum()) for t in range(cfg.n_tasks)], out=sub_off[1:])
+        _, rq, tq = oracle.profile(sub, sub_off)
+        merged, mtro = (rq, tq) if merged is None else oracle.profile_merge(merged, mtro, rq, tq)
+    assert np.array_equal(mtro, tro) and np.array_equal(merged["kernel_id"], rows["kernel_id"])
+    for blk in ("exec", "gap"):
+        for f in ("count", "sum", "min", "max"):
+            assert np.array_equal(merged[blk][f], rows[blk][f]), (blk, f)
+
+
 def test_oracle_error_statuses():
     rec = make_records([(1, (1, 1, 1), (1, 1, 1), 0, 10, 5)])
     with pytest.raises(oracle.OracleError) as e:
