@@ -51,8 +51,10 @@ extern "C" {
 #endif
 
 /* One intercepted kernel launch.  64 bytes, little endian, 16-byte aligned.
- * Bytes 0..31 are the identity of the kernel (what the Kernel ID is made of); bytes 48..63
- * are ignored. */
+ * Bytes 0..31 are the identity of the kernel (what the Kernel ID is made of); `run` says which
+ * of the task's measured runs the launch belongs to (Section 3.2: a task is measured over T runs;
+ * a run's launches are consecutive; any numbers will do, only a change from one launch to the
+ * next matters); bytes 52..63 are ignored. */
 typedef struct fikit_launch {
   uint32_t name_id;      /*  0  interned kernel function name          */
   uint32_t grid[3];      /*  4  grid dimensions x, y, z                */
@@ -60,7 +62,8 @@ typedef struct fikit_launch {
   uint32_t shmem;        /* 28  dynamic shared-memory bytes            */
   int64_t start_ns;      /* 32  device time at which the kernel began  */
   int64_t end_ns;        /* 40  device time at which the kernel ended  */
-  uint8_t reserved[16];  /* 48  ignored                                */
+  uint32_t run;          /* 48  measured run the launch belongs to     */
+  uint8_t reserved[12];  /* 52  ignored                                */
 } fikit_launch;
 
 /* Statistics of one sample set.  count == 0 implies every other field is 0. */
@@ -114,7 +117,10 @@ size_t fikit_profile_workspace_bytes(uint64_t n_records, uint32_t n_tasks);
  *   d_rows_out         [row_capacity] receives the rows, ordered by task, then by kernel_id as
  *                      an unsigned number.  Execution time of a launch = end_ns - start_ns; the
  *                      idle time after a launch = max(0, next start_ns - end_ns), where "next"
- *                      is the following launch of the same task; a task's last launch has none.
+ *                      is the following launch of the same task and run; the last launch of a run
+ *                      has none (a run of N launches gives N - 1 idle times, Section 3.2), so the
+ *                      rows of a trace that holds several runs are exactly the statistics over all
+ *                      of them, percentiles included.
  *   d_task_row_offsets [n_tasks+1] receives, per task, where its rows start (last = row count).
  *   h_n_rows           host; receives the number of rows (also on FIKIT_ROW_CAPACITY).
  *   d_workspace        256-byte aligned, at least fikit_profile_workspace_bytes(...) bytes.
@@ -218,7 +224,7 @@ size_t fikit_measure_workspace_bytes(void);
  *   d_records, d_task_offsets, n_tasks   as in fikit_profile.
  *   d_exec_ns   [n_records] receives end_ns - start_ns of every launch.
  *   d_gap_ns    [n_records] receives the idle time after the launch, max(0, start_ns of the
- *               task's next launch - end_ns), or -1 for the last launch of a task.
+ *               task's next launch - end_ns), or -1 for the last launch of a run or task.
  *   d_workspace 256-byte aligned, at least fikit_measure_workspace_bytes() bytes.
  *
  * Buffers are the caller's; the call synchronises the stream.  Errors: INVALID_ARG,
@@ -245,8 +251,9 @@ size_t fikit_replay_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n
  * issued kernels run back to back from the start of the gap for their predicted duration.
  *
  *   d_actual_gap_ns  [n_ids] idle time that followed every launch (fikit_measure's d_gap_ns);
- *                    only high-priority launches that have a gap are looked at, and theirs must be
- *                    >= 0 (else INVALID_ARG).
+ *                    only high-priority launches but the trace's last are looked at, and theirs
+ *                    must be >= 0 (else INVALID_ARG: a high-priority trace that holds several
+ *                    measured runs has no idle time at the run ends and cannot be replayed).
  *   h_params         host pointer.  feedback == 0: every kernel that fits the predicted gap is
  *                    issued (the paper's profile-only controller).  feedback != 0: before each
  *                    issue the controller checks whether the next high-priority request has

@@ -73,6 +73,12 @@ __device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int d) {
   return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
+// Lane i receives lane i + 1's value; lane 63 keeps its own.  A data-parallel-primitive move over the whole wave
+// (no LDS traffic); call it with all 64 lanes active.
+__device__ __forceinline__ uint32_t from_next_lane(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), 0x130, 0xf, 0xf, false));   // wave_shl:1
+}
+
 // Wave-wide reductions over all 64 lanes (result in every lane).
 __device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v) {
 #pragma unroll

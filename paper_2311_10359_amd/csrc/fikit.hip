@@ -51,7 +51,7 @@ struct Carver {
 
 struct ProfileLayout {
   uint64_t ctrl, k0, k1, k2, e0, e1, g0, g1, tiles, hist, sums, bits, word_prefix, gflag, dcount, total;
-  uint64_t is_long, mtiles, mflag, wflag, units, lists;   // long-task partition path; work lists
+  uint64_t is_long, mtiles, mflag, wflag, bsize, units, lists;   // long-task partition path; work lists
   uint64_t max_tiles, max_ptiles, n_words, max_units;
 };
 
@@ -91,6 +91,7 @@ ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
   L.mtiles = c.take((static_cast<uint64_t>(n_tasks) + 1) * 4);
   L.mflag = c.take(static_cast<uint64_t>(n_tasks) * 4);
   L.wflag = c.take(static_cast<uint64_t>(n_tasks) * 4);
+  L.bsize = c.take(long_tasks * MSD_SLOTS * 4);   // bucket sizes of the long tasks
   L.max_units = long_tasks * MSD_SLOTS;
   L.units = c.take(L.max_units * 4 * 6);   // start, length, task, row count, first row, buckets
   {
@@ -339,13 +340,15 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     const uint64_t n_msd_tiles = h.n_big_tiles;
     if (n_msd_tiles == 0 || n_msd_tiles > L.max_ptiles) return FIKIT_HIP_ERROR;
     tr.mark("k_tile_partition");
+    uint32_t* bucket_size = reinterpret_cast<uint32_t*>(ws + L.bsize);
+    hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(h.n_long * MSD_SLOTS, 256)), dim3(256), 0, st, bucket_size, h.n_long * MSD_SLOTS, 0u);
     FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tile_partition), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   static_cast<int>(sizeof(PartSmem))));
     hipLaunchKernelGGL(k_tile_partition, dim3(static_cast<uint32_t>(n_msd_tiles)), dim3(PT_THREADS), sizeof(PartSmem), st, d_records,
-                       d_task_offsets, n_tasks, mtiles, ids, k1, part_kg, bound, wflag, ctrl);
+                       d_task_offsets, n_tasks, mtiles, is_long, ids, k1, part_kg, bound, bucket_size, wflag, ctrl);
     tr.mark("k_msd_units");
     hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, &ctrl->n_class[0], static_cast<uint64_t>(4), 0u);   // the lists are reused for units
-    hipLaunchKernelGGL(k_msd_units, dim3(n_tasks), dim3(MSD_SLOTS), 0, st, d_task_offsets, n_tasks, is_long, mtiles, bound, wflag,
+    hipLaunchKernelGGL(k_msd_units, dim3(n_tasks), dim3(MSD_SLOTS), 0, st, d_task_offsets, n_tasks, is_long, mtiles, bucket_size, wflag,
                        ustart, ulen, utask, udcount, ubuckets, mflag, gflag, lists, static_cast<uint32_t>(n_units), ctrl);
     FusedArgs ua = fa;
     ua.ustart = ustart; ua.ulen = ulen; ua.utask = utask; ua.ubuckets = ubuckets; ua.tile_prefix = mtiles; ua.bound = bound;

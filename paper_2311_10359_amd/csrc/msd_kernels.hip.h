@@ -77,8 +77,7 @@ __device__ __forceinline__ uint32_t wave_rank_bits(uint32_t digit, bool valid, u
 }
 
 struct PartSmem {
-  uint64_t id[PT_TILE];
-  uint2 kg[PT_TILE];
+  uint64_t stage[PT_TILE];   // the tile's IDs in bucket order, then its values
   uint32_t cnt[PT_WAVES][256];
   uint32_t aux[8];
 };
@@ -90,8 +89,9 @@ struct PartSmem {
 // to the general path.
 __global__ void __launch_bounds__(PT_THREADS)
 k_tile_partition(const fikit_launch* __restrict__ rec, const uint64_t* __restrict__ off, uint32_t n_tasks,
-                 const uint32_t* __restrict__ tile_prefix, uint64_t* __restrict__ ids, uint64_t* __restrict__ part_id,
-                 uint2* __restrict__ part_kg, uint16_t* __restrict__ bound, uint32_t* __restrict__ wflag, Ctrl* ctrl) {
+                 const uint32_t* __restrict__ tile_prefix, const uint32_t* __restrict__ long_prefix,
+                 uint64_t* __restrict__ ids, uint64_t* __restrict__ part_id, uint2* __restrict__ part_kg,
+                 uint16_t* __restrict__ bound, uint32_t* __restrict__ bucket_size, uint32_t* __restrict__ wflag, Ctrl* ctrl) {
   extern __shared__ __align__(16) unsigned char part_raw[];
   PartSmem& sm = *reinterpret_cast<PartSmem*>(part_raw);
   const uint32_t j = blockIdx.x;
@@ -116,22 +116,28 @@ k_tile_partition(const fikit_launch* __restrict__ rec, const uint64_t* __restric
   for (int r0 = 0; r0 < PT_KPT; r0 += PT_LB) {
     uint4 qa[PT_LB], qb[PT_LB], qc[PT_LB];
     int64_t qn[PT_LB];
+    uint32_t qrun[PT_LB], qnrun[PT_LB];
 #pragma unroll
     for (int u = 0; u < PT_LB; ++u) {
       const uint32_t pos = wave_base + (r0 + u) * WAVE + lane;
       qa[u] = qb[u] = qc[u] = make_uint4(0, 0, 0, 0);
       qn[u] = 0;
+      qrun[u] = 0; qnrun[u] = 1;
       if (pos < m) {
         const uint64_t i = start + pos;
         const uint4* p = reinterpret_cast<const uint4*>(rec + i);
         qa[u] = p[0]; qb[u] = p[1]; qc[u] = p[2];
-        if (i + 1 < task_end) qn[u] = rec[i + 1].start_ns;
+        qrun[u] = rec[i].run;
+        // the next launch is the next lane's; only the wave's last lane has to read it
+        if (lane == WAVE - 1 && i + 1 < task_end) { qn[u] = rec[i + 1].start_ns; qnrun[u] = rec[i + 1].run; }
       }
     }
 #pragma unroll
     for (int u = 0; u < PT_LB; ++u) {
       const int r = r0 + u;
       const uint32_t pos = wave_base + r * WAVE + lane;
+      const uint32_t nx_lo = from_next_lane(qc[u].x), nx_hi = from_next_lane(qc[u].y), nx_run = from_next_lane(qrun[u]);
+      if (lane != WAVE - 1) { qn[u] = static_cast<int64_t>((static_cast<uint64_t>(nx_hi) << 32) | nx_lo); qnrun[u] = nx_run; }
       idr[r] = 0;
       kgr[r] = make_uint2(0, 0);
       if (pos < m) {
@@ -145,7 +151,7 @@ k_tile_partition(const fikit_launch* __restrict__ rec, const uint64_t* __restric
         const uint64_t e64 = static_cast<uint64_t>(en - st);
         wide |= (e64 >= NONE32);
         uint32_t g32 = NONE32;
-        if (i + 1 < task_end) {
+        if (i + 1 < task_end && qnrun[u] == qrun[u]) {   // an idle time follows: same task, same run
           const int64_t g = qn[u] - en;
           const uint64_t g64 = static_cast<uint64_t>(g < 0 ? 0 : g);
           wide |= (g64 >= NONE32);
@@ -167,23 +173,41 @@ k_tile_partition(const fikit_launch* __restrict__ rec, const uint64_t* __restric
     rk[r] = wave_rank_bits(static_cast<uint32_t>(idr[r] >> shift), pos < m, sm.cnt[w], bits);
   }
   tile_digit_offsets<PT_WAVES>(sm.cnt, sm.aux, nullptr);
-  // where each bucket starts inside the tile (buckets the task does not have start at the tile's end)
-  if (tid < 256) bound[static_cast<uint64_t>(tp) * PT_ROWS + static_cast<uint64_t>(tid) * tiles_t + jl] = static_cast<uint16_t>(sm.cnt[0][tid]);
+  // where each bucket starts inside the tile (buckets the task does not have start at the tile's end), and the
+  // tile's share of the task's bucket sizes (integer adds: the totals do not depend on the order of the tiles)
+  if (tid < 256) {
+    const uint32_t first = sm.cnt[0][tid], next = tid < 255 ? sm.cnt[0][tid + 1] : m;
+    bound[static_cast<uint64_t>(tp) * PT_ROWS + static_cast<uint64_t>(tid) * tiles_t + jl] = static_cast<uint16_t>(first);
+    if (next > first) atomicAdd(&bucket_size[static_cast<uint64_t>(long_prefix[t]) * MSD_SLOTS + tid], next - first);
+  }
   if (tid == 256) bound[static_cast<uint64_t>(tp) * PT_ROWS + static_cast<uint64_t>(MSD_SLOTS) * tiles_t + jl] = static_cast<uint16_t>(m);
+  uint32_t at[PT_KPT];
 #pragma unroll
   for (int r = 0; r < PT_KPT; ++r) {
     const uint32_t pos = wave_base + r * WAVE + lane;
-    if (pos < m) {
-      const uint32_t at = sm.cnt[w][static_cast<uint32_t>(idr[r] >> shift)] + rk[r];
-      sm.id[at] = idr[r];
-      sm.kg[at] = kgr[r];
-    }
+    at[r] = sm.cnt[w][static_cast<uint32_t>(idr[r] >> shift)] + rk[r];
+    if (pos < m) sm.stage[at[r]] = idr[r];
   }
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < PT_KPT; ++r) {
     const uint32_t i = tid + r * PT_THREADS;
-    if (i < m) { part_id[start + i] = sm.id[i]; part_kg[start + i] = sm.kg[i]; }
+    if (i < m) part_id[start + i] = sm.stage[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < PT_KPT; ++r) {
+    const uint32_t pos = wave_base + r * WAVE + lane;
+    if (pos < m) sm.stage[at[r]] = (static_cast<uint64_t>(kgr[r].y) << 32) | kgr[r].x;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < PT_KPT; ++r) {
+    const uint32_t i = tid + r * PT_THREADS;
+    if (i < m) {
+      const uint64_t v = sm.stage[i];
+      part_kg[start + i] = make_uint2(static_cast<uint32_t>(v), static_cast<uint32_t>(v >> 32));
+    }
   }
 }
 
@@ -191,10 +215,10 @@ k_tile_partition(const fikit_launch* __restrict__ rec, const uint64_t* __restric
 // FUSE_MAX launches, or with an execution or idle time that does not fit 32 bits, keeps the general path
 // (mflag 0); otherwise mflag 1 and gflag cleared.  Thread d sums bucket d over the task's tiles, one thread
 // packs (a short sequential pass over at most 256 buckets in LDS), and all threads together write the unit
-// slots and the work lists.
+// slots and the work lists.  bucket_size: the task's bucket sizes as the tiles added them up.
 __global__ void __launch_bounds__(MSD_SLOTS)
 k_msd_units(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ long_prefix,
-            const uint32_t* __restrict__ tile_prefix, const uint16_t* __restrict__ bound, const uint32_t* __restrict__ wflag,
+            const uint32_t* __restrict__ tile_prefix, const uint32_t* __restrict__ bucket_size, const uint32_t* __restrict__ wflag,
             uint32_t* __restrict__ ustart, uint32_t* __restrict__ ulen, uint32_t* __restrict__ utask,
             uint32_t* __restrict__ udcount, uint32_t* __restrict__ ubuckets, uint32_t* __restrict__ mflag,
             uint32_t* __restrict__ gflag, uint32_t* __restrict__ lists, uint32_t list_stride, Ctrl* ctrl) {
@@ -209,12 +233,8 @@ k_msd_units(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* 
   const uint32_t o = long_prefix[t];
   const uint64_t task_start = off[t], len = off[t + 1] - task_start;
   const uint32_t nb = 1u << msd_bits(len);
-  const uint32_t tp = tile_prefix[t], tiles_t = tile_prefix[t + 1] - tp;
-  const uint16_t* lo = bound + static_cast<uint64_t>(tp) * PT_ROWS + static_cast<uint64_t>(d) * tiles_t;
-  const uint16_t* hi = lo + tiles_t;
-  uint32_t size = 0;
-  if (d < nb)
-    for (uint32_t j = 0; j < tiles_t; ++j) size += static_cast<uint32_t>(hi[j]) - static_cast<uint32_t>(lo[j]);
+  const uint32_t tiles_t = tile_prefix[t + 1] - tile_prefix[t];
+  const uint32_t size = d < nb ? bucket_size[static_cast<uint64_t>(o) * MSD_SLOTS + d] : 0u;
   uint32_t total;
   const uint32_t before = block_excl_scan_256(size, aux, total);
   bstart[d] = before;
@@ -250,14 +270,24 @@ k_msd_units(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* 
   const uint32_t u = o * MSD_SLOTS + d;
   utask[u] = t;
   udcount[u] = 0;
-  if (d >= used) { ustart[u] = 0; ulen[u] = 0; ubuckets[u] = 0; return; }
-  const uint32_t l = ul[d];
-  ustart[u] = static_cast<uint32_t>(task_start) + us[d];
+  const bool live = d < used;
+  const uint32_t l = live ? ul[d] : 0u;
+  ustart[u] = live ? static_cast<uint32_t>(task_start) + us[d] : 0u;
   ulen[u] = l;
-  ubuckets[u] = ub[d];
-  // work lists of units by size class (see k_classify)
-  const uint32_t c = l <= FUSE_SMALL_MAX ? 0u : (l <= FUSE_MID_MAX ? 1u : 2u);
-  lists[static_cast<uint64_t>(c) * list_stride + atomicAdd(&ctrl->n_class[c], 1u)] = u;
+  ubuckets[u] = live ? ub[d] : 0u;
+  // work lists of units by size class (see k_classify): one reservation per task and class (a counter that every
+  // unit bumped on its own would serialise the whole launch on one address)
+  const uint32_t c = !live ? 3u : (l <= FUSE_SMALL_MAX ? 0u : (l <= FUSE_MID_MAX ? 1u : 2u));
+  __syncthreads();   // (aux is reused)
+  for (uint32_t k = 0; k < 3; ++k) {
+    uint32_t total;
+    const uint32_t at = block_excl_scan_256(c == k ? 1u : 0u, aux, total);
+    __shared__ uint32_t list_base;
+    if (d == 0) list_base = total ? atomicAdd(&ctrl->n_class[k], total) : 0u;
+    __syncthreads();
+    if (c == k) lists[static_cast<uint64_t>(k) * list_stride + list_base + at] = u;
+    __syncthreads();
+  }
 }
 
 // Long tasks that the general path has to take after all (a bucket too large for a workgroup, too many
@@ -282,7 +312,7 @@ k_long_general_values(const fikit_launch* __restrict__ rec, const uint64_t* __re
     if (from_records) {
       const int64_t en = rec[i].end_ns;
       int64_t gap = GAP_NONE;
-      if (i + 1 < task_end) { gap = rec[i + 1].start_ns - en; gap = gap < 0 ? 0 : gap; }
+      if (i + 1 < task_end && rec[i + 1].run == rec[i].run) { gap = rec[i + 1].start_ns - en; gap = gap < 0 ? 0 : gap; }
       key[i] = ids[i];
       e0[i] = en - rec[i].start_ns;
       g0[i] = gap;

@@ -75,11 +75,11 @@ k_measure(const fikit_launch* __restrict__ rec, uint64_t n, int64_t* __restrict_
   if (end < start) atomicOr(&ctrl->status, ERR_BAD_RECORD);
   exec_ns[i] = end - start;
   int64_t g = GAP_NONE;
-  if (i + 1 < n) { g = rec[i + 1].start_ns - end; g = g < 0 ? 0 : g; }
+  if (i + 1 < n && rec[i + 1].run == rec[i].run) { g = rec[i + 1].start_ns - end; g = g < 0 ? 0 : g; }   // (same run)
   gap_ns[i] = g;
 }
 
-// The last launch of every task has no idle time after it.
+// The last launch of every task has no idle time after it (whatever run the next task's first launch names).
 __global__ void k_measure_task_ends(const uint64_t* __restrict__ off, uint32_t n_tasks, int64_t* __restrict__ gap_ns,
                                     const Ctrl* ctrl) {
   if (ctrl->status & ERR_OFFSETS) return;

@@ -102,8 +102,7 @@ struct FusedSmem {
   uint32_t maxe, maxg;
   uint32_t ndist;
   uint32_t fallback;
-  uint32_t last_rank;        // rank of the ID whose launch has no idle time after it (the task's last), or NONE32
-  struct { uint64_t esum[HE], gsum[HE]; uint32_t emin[HE], emax[HE], gmin[HE], gmax[HE]; } early;   // by slot
+  struct { uint64_t esum[HE], gsum[HE]; uint32_t emin[HE], emax[HE], gmin[HE], gmax[HE], nogap[HE]; } early;   // by slot
   uint16_t rslot[ESTATS ? DMAX : 1];   // rank -> slot
 };
 
@@ -204,6 +203,8 @@ __device__ __forceinline__ void early_stats(Smem& sm, uint32_t s, uint32_t e, ui
     atomicAdd(reinterpret_cast<unsigned long long*>(&sm.early.gsum[s]), static_cast<unsigned long long>(g));
     atomicMin(&sm.early.gmin[s], g);
     atomicMax(&sm.early.gmax[s], g);
+  } else {
+    atomicAdd(&sm.early.nogap[s], 1u);   // (the last launch of a run)
   }
 }
 
@@ -246,10 +247,10 @@ k_task_fused(const FusedArgs A) {
     sm.ht_key[i] = HT_EMPTY; sm.ht_cnt[i] = 0; sm.memo_claim[i] = 0; sm.u.memo.ready[i] = 0;
     if (ESTATS) {
       sm.early.esum[i] = 0; sm.early.emin[i] = ~0u; sm.early.emax[i] = 0;
-      sm.early.gsum[i] = 0; sm.early.gmin[i] = ~0u; sm.early.gmax[i] = 0;
+      sm.early.gsum[i] = 0; sm.early.gmin[i] = ~0u; sm.early.gmax[i] = 0; sm.early.nogap[i] = 0;
     }
   }
-  if (tid == 0) { sm.ndist = 0; sm.fallback = 0; sm.maxe = 0; sm.maxg = 0; sm.last_rank = NONE32; }
+  if (tid == 0) { sm.ndist = 0; sm.fallback = 0; sm.maxe = 0; sm.maxg = 0; }
   __syncthreads();
 
   // ---- 1. read, identify, measure ------------------------------------------------------------
@@ -257,6 +258,7 @@ k_task_fused(const FusedArgs A) {
   uint32_t sl[KPT];            // ID-table slot, later the rank of the launch's ID
   uint32_t my_maxe = 0, my_maxg = 0;
   bool bad = false, wide = false;
+  const uint32_t lane = lane_id();
 #pragma unroll
   for (int r = 0; r < KPT; ++r) { ev[r] = 0; gv[r] = NONE32; sl[r] = 0; }
   if (UNITS) {
@@ -289,19 +291,38 @@ k_task_fused(const FusedArgs A) {
       if (tid == 0) atomicOr(&ctrl->status, ERR_OFFSETS);
       return;
     }
+    // all of a thread's launches are located first and then read together, so that their loads are in flight at once
+    const uint64_t tiles_per_launch = (static_cast<uint64_t>(tiles_t) << 32) / m;   // tiles / m in 32.32 fixed point
+    uint32_t at[KPT];
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+      const uint32_t i = r * NT + tid;
+      at[r] = 0;
+      if (i < m) {
+        // runs are of similar length: start at the proportional guess, then step to the run that holds launch i
+        uint32_t j = static_cast<uint32_t>((static_cast<uint64_t>(i) * tiles_per_launch) >> 32);
+        j = j < tiles_t ? j : tiles_t - 1;
+        while (run_before[j] > i) --j;
+        while (run_before[j + 1] <= i) ++j;
+        at[r] = run_at[j] + (i - run_before[j]);
+      }
+    }
+    uint64_t idq[KPT];
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+      idq[r] = 0;
+      if (r * NT + tid < m) {
+        idq[r] = A.part_id[at[r]];
+        const uint2 kg = A.part_kg[at[r]];
+        ev[r] = kg.x;
+        gv[r] = kg.y;
+      }
+    }
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
       const uint32_t i = r * NT + tid;
       if (i < m) {
-        // runs are of similar length: start at the proportional guess, then step to the run that holds launch i
-        uint32_t j = static_cast<uint32_t>((static_cast<uint64_t>(i) * tiles_t) / m);
-        while (run_before[j] > i) --j;
-        while (run_before[j + 1] <= i) ++j;
-        const uint32_t at = run_at[j] + (i - run_before[j]);
-        const uint64_t id = A.part_id[at];
-        const uint2 kg = A.part_kg[at];
-        ev[r] = kg.x;
-        gv[r] = kg.y;
+        const uint64_t id = idq[r];
         my_maxe = ev[r] > my_maxe ? ev[r] : my_maxe;
         if (gv[r] != NONE32) my_maxg = gv[r] > my_maxg ? gv[r] : my_maxg;
         uint32_t h = (static_cast<uint32_t>(id >> 32) ^ static_cast<uint32_t>(id)) & (HT - 1);
@@ -331,25 +352,31 @@ k_task_fused(const FusedArgs A) {
     if (static_cast<uint32_t>(r0) * NT < m) {
       uint4 qa[LB], qb[LB], qc[LB];
       int64_t qn[LB];
+      uint32_t qrun[LB], qnrun[LB];
 #pragma unroll
       for (int u = 0; u < LB; ++u) {
         const uint32_t i = (r0 + u) * NT + tid;
         qa[u] = qb[u] = qc[u] = make_uint4(0, 0, 0, 0);
         qn[u] = 0;
+        qrun[u] = 0; qnrun[u] = 1;
         if (i < m) {
           const uint4* p = reinterpret_cast<const uint4*>(rec + base + i);
           qa[u] = p[0]; qb[u] = p[1]; qc[u] = p[2];
-          if (i + 1 < m) qn[u] = rec[base + i + 1].start_ns;
+          qrun[u] = rec[base + i].run;
+          // the next launch is the next lane's; only the wave's last lane has to read it
+          if (lane == WAVE - 1 && i + 1 < m) { qn[u] = rec[base + i + 1].start_ns; qnrun[u] = rec[base + i + 1].run; }
         }
       }
 #pragma unroll
       for (int u = 0; u < LB; ++u) {
         const int r = r0 + u;
         const uint32_t i = r * NT + tid;
+        const uint32_t nx_lo = from_next_lane(qc[u].x), nx_hi = from_next_lane(qc[u].y), nx_run = from_next_lane(qrun[u]);
         if (i < m) {
           const uint4 a = qa[u], b = qb[u], c = qc[u];
-          const int64_t next_start = qn[u];
-          const bool has_next = (i + 1 < m);
+          const int64_t next_start = lane == WAVE - 1 ? qn[u] : static_cast<int64_t>((static_cast<uint64_t>(nx_hi) << 32) | nx_lo);
+          const uint32_t next_run = lane == WAVE - 1 ? qnrun[u] : nx_run;
+          const bool has_next = (i + 1 < m) && next_run == qrun[u];   // an idle time follows: same task, same run
           const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
           const int64_t start = static_cast<int64_t>((static_cast<uint64_t>(c.y) << 32) | c.x);
           const int64_t end = static_cast<int64_t>((static_cast<uint64_t>(c.w) << 32) | c.z);
@@ -470,7 +497,7 @@ k_task_fused(const FusedArgs A) {
       const int64_t end = q->end_ns;
       e0[base + i] = end - q->start_ns;
       int64_t g = GAP_NONE;
-      if (i + 1 < m) { g = q[1].start_ns - end; g = g < 0 ? 0 : g; }
+      if (i + 1 < m && q[1].run == q->run) { g = q[1].start_ns - end; g = g < 0 ? 0 : g; }
       g0[base + i] = g;
       A.key0[base + i] = ids[base + i];
     }
@@ -514,10 +541,7 @@ k_task_fused(const FusedArgs A) {
 
   // ---- 3. count / sum / min / max per ID ------------------------------------------------------
   if (ESTATS) {
-    // (gathered while reading; what is left is the number of idle times: every launch but the task's last has one)
-#pragma unroll
-    for (int r = 0; r < KPT; ++r)
-      if (r * NT + tid < m && gv[r] == NONE32) sm.last_rank = sl[r];
+    // (gathered while reading, and so was the number of launches without an idle time)
   } else if (D <= static_cast<uint32_t>(PRIV_IDS)) {
     // few IDs: lane-private accumulators, merged afterwards
     const uint32_t np = D * PRIV_COPIES;
@@ -600,7 +624,7 @@ k_task_fused(const FusedArgs A) {
     uint64_t esum, gsum;
     if (ESTATS) {
       const uint32_t s = sm.rslot[j];
-      gc = ec - (sm.last_rank == j ? 1u : 0u);
+      gc = ec - sm.early.nogap[s];
       sm.gcnt[j] = gc;
       esum = sm.early.esum[s]; emin = sm.early.emin[s]; emax = sm.early.emax[s];
       gsum = sm.early.gsum[s]; gmin = sm.early.gmin[s]; gmax = sm.early.gmax[s];
