@@ -96,9 +96,8 @@ typedef enum fikit_status {
   FIKIT_BAD_RECORD = -4,          /* some record has end_ns < start_ns                          */
   FIKIT_UNKNOWN_ID = -5,          /* a scenario launch whose ID is absent from its task's rows  */
   FIKIT_HIP_ERROR = -6,           /* the HIP runtime reported an error                          */
-  FIKIT_UNSUPPORTED = -7,         /* fikit_gapfill_replay, fikit_prio_fill: a predicted time of
-                                     2^32 - 1 ns or more; fikit_prio_fill: a scenario beyond its
-                                     stated limits                                                */
+  FIKIT_UNSUPPORTED = -7,         /* fikit_prio_fill: a scenario whose list entries and launches
+                                     together number 2^32 or more                                 */
   FIKIT_TOO_LARGE = -8            /* fikit_gapfill_static: more launches or tasks than its built-in
                                      scratch buffer holds                                          */
 } fikit_status;
@@ -267,8 +266,8 @@ size_t fikit_replay_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n
  *   d_lp_placed      [n_scenarios] number of low-priority kernels issued into gaps.
  *   all other arguments as in fikit_gapfill.
  *
- * Predicted times must be below 2^32 - 1 ns (about 4.29 s), else FIKIT_UNSUPPORTED.
- * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNKNOWN_ID, UNSUPPORTED, HIP_ERROR.
+ * Predictions of 2^32 - 1 ns (about 4.29 s) or more are handled by slower 64-bit kernels.
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNKNOWN_ID, HIP_ERROR.
  */
 int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks,
                          const fikit_row* d_rows, const uint64_t* d_task_row_offsets,
@@ -279,7 +278,7 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
                          uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes,
                          void* hip_stream);
 
-/* Most low-priority tasks one scenario of fikit_prio_fill may hold. */
+/* Most low-priority tasks of a scenario that fikit_prio_fill's fast kernels take (a scenario may hold more). */
 #define FIKIT_PRIO_MAX_LP 64
 
 /* Bytes of device workspace fikit_prio_fill needs for these sizes (0 on size overflow). */
@@ -291,9 +290,9 @@ size_t fikit_prio_fill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_
  * holds the GPU).
  *
  *   d_lp_offsets [n_scenarios+1] uint64, first 0, non-decreasing: scenario s owns the entries
- *                d_lp_offsets[s] .. d_lp_offsets[s+1]-1 of d_lp_task / d_lp_prio, at most
- *                FIKIT_PRIO_MAX_LP of them (else FIKIT_UNSUPPORTED); their launches together must
- *                number fewer than 2^32 - 64 (else FIKIT_UNSUPPORTED).
+ *                d_lp_offsets[s] .. d_lp_offsets[s+1]-1 of d_lp_task / d_lp_prio; the entries of a
+ *                scenario and their launches together must number fewer than 2^32 (else
+ *                FIKIT_UNSUPPORTED).
  *   d_lp_task    per entry, a low-priority task of the scenario (a task may appear in several
  *                entries and scenarios; every entry is a separate run of it).
  *   d_lp_prio    per entry, its priority level, 1 (highest) .. 9 (else FIKIT_INVALID_ARG).
@@ -311,7 +310,8 @@ size_t fikit_prio_fill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_
  * r is reduced by its duration and the scan starts again at level 1; the gap is done when no level
  * holds a request that fits.  With one entry per scenario the per-gap results are fikit_gapfill's.
  *
- * Predicted times must be below 2^32 - 1 ns, else FIKIT_UNSUPPORTED.
+ * If some scenario holds more than FIKIT_PRIO_MAX_LP low-priority tasks, or a prediction is 2^32 - 1 ns or more,
+ * slower kernels do the call (one lane per scenario, every decision looks at all its waiting requests).
  * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNKNOWN_ID, UNSUPPORTED, HIP_ERROR.
  */
 int fikit_prio_fill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_t n_tasks,

@@ -213,7 +213,7 @@ const char* fikit_status_string(int status) {
     case FIKIT_BAD_RECORD: return "record with end_ns < start_ns";
     case FIKIT_UNKNOWN_ID: return "launch ID missing from its task's profile";
     case FIKIT_HIP_ERROR: return "HIP runtime error";
-    case FIKIT_UNSUPPORTED: return "beyond a stated limit of this call (a predicted time of 2^32 - 1 ns or more, or too many low-priority tasks in a scenario)";
+    case FIKIT_UNSUPPORTED: return "beyond a stated limit of this call (list entries and launches of a scenario number 2^32 or more)";
     case FIKIT_TOO_LARGE: return "input larger than the built-in scratch buffer of fikit_gapfill_static";
     default: return "unknown status";
   }
@@ -765,13 +765,15 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
   if (workspace_bytes < fikit_replay_workspace_bytes(n_ids, n_tasks, n_scenarios)) return FIKIT_WORKSPACE_TOO_SMALL;
 
   unsigned char* ws = static_cast<unsigned char*>(d_workspace);
-  Carver c;   // (same layout as fikit_gapfill; only the 32-bit arrays are used)
+  Carver c;   // (same layout as fikit_gapfill: the 32-bit arrays share the space of the 64-bit ones)
   Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
   uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
   uint32_t* glists = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4 * 2));
   uint64_t* lp_total = reinterpret_cast<uint64_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 8));
-  uint32_t* lp_e = reinterpret_cast<uint32_t*>(ws + c.take(n_ids * 8 + GF_PAD));
-  uint2* hp_eg = reinterpret_cast<uint2*>(ws + c.take(n_ids * 8 + GF_PAD));
+  int64_t* pe = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
+  int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
+  uint32_t* lp_e = reinterpret_cast<uint32_t*>(pe);
+  uint2* hp_eg = reinterpret_cast<uint2*>(pg);
 
   Tracer tr(st);
   tr.mark("gf_setup");
@@ -804,13 +806,19 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
                        n_scenarios, d_gap_offsets, lp_e, hp_eg, lp_total, h_params->margin_ns, h_params->min_gap_ns,
                        d_fill_count, d_filled_ns, d_hp_delay_ns, d_lp_placed, vec_ok, ctrl);
   }
+  // a prediction that did not fit 32 bits (Ctrl::wide): the walk above has not run; the 64-bit kernels do the call
+  tr.mark("k_gf_replay_wide");
+  hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                     d_task_row_offsets, role, glists, pe, pg, static_cast<int64_t*>(nullptr), 1u,
+                     static_cast<uint32_t>(h_params->predictor), ctrl);
+  hipLaunchKernelGGL(k_gf_replay_wide, dim3(blocks_for(n_scenarios, 256)), dim3(256), 0, st, d_task_offsets, d_hp_task, d_lp_task,
+                     n_scenarios, d_gap_offsets, pe, pg, d_actual_gap_ns, h_params->margin_ns, h_params->min_gap_ns,
+                     h_params->feedback ? 1u : 0u, d_fill_count, d_filled_ns, d_hp_delay_ns, d_lp_placed, ctrl);
   FIKIT_HIP(hipGetLastError());
   tr.mark("host_sync");
   Ctrl h{};
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;
-  if (int rc = status_from_bits(h.status)) return rc;
-  // (the walk has not run in this case: its outputs are undefined)
-  return h.wide ? FIKIT_UNSUPPORTED : FIKIT_OK;
+  return status_from_bits(h.status);
 }
 
 size_t fikit_prio_fill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_t n_scenarios) {
@@ -821,7 +829,7 @@ size_t fikit_prio_fill_workspace_bytes(uint64_t n_ids, uint32_t n_tasks, uint64_
   c.take(static_cast<uint64_t>(n_tasks) * 4);
   c.take(static_cast<uint64_t>(n_tasks) * 4 * 2);
   c.take(static_cast<uint64_t>(n_tasks) * 8);
-  c.take(n_ids * 4 + GF_PAD);
+  c.take(n_ids * 8 + GF_PAD);
   c.take(n_ids * 8 + GF_PAD);
   return static_cast<size_t>(c.at);
 }
@@ -863,8 +871,10 @@ int fikit_prio_fill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint3
   uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
   uint32_t* glists = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4 * 2));
   uint64_t* lp_total = reinterpret_cast<uint64_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 8));
-  uint32_t* lp_e = reinterpret_cast<uint32_t*>(ws + c.take(n_ids * 4 + GF_PAD));
-  uint2* hp_eg = reinterpret_cast<uint2*>(ws + c.take(n_ids * 8 + GF_PAD));
+  int64_t* pe = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));   // the 32-bit arrays share the space of the 64-bit ones
+  int64_t* pg = reinterpret_cast<int64_t*>(ws + c.take(n_ids * 8 + GF_PAD));
+  uint32_t* lp_e = reinterpret_cast<uint32_t*>(pe);
+  uint2* hp_eg = reinterpret_cast<uint2*>(pg);
 
   Tracer tr(st);
   tr.mark("pf_setup");
@@ -880,33 +890,44 @@ int fikit_prio_fill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint3
   Ctrl h{};
   if (int rc = read_ctrl(ctrl, &h, st)) return rc;   // the widest scenario decides how many lanes share one
   if (int rc = status_from_bits(h.status)) return rc;
-  tr.mark("k_gf_predict32");
-  hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                     d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total,
-                     static_cast<uint32_t>(h_params->predictor), ctrl);
-  const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
   const uint32_t widest = h.n_class[3];
-  tr.mark("k_pf_walk");
-  int rc = FIKIT_OK;
+  // Up to 64 low-priority tasks per scenario: a group of lanes per scenario on 32-bit predictions; the 64-bit
+  // kernels then only run if a prediction did not fit (they check Ctrl::wide).  More tasks: the 64-bit kernels.
+  const bool groups = widest <= PF_MAX_LP;
+  if (groups) {
+    tr.mark("k_gf_predict32");
+    hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                       d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total,
+                       static_cast<uint32_t>(h_params->predictor), ctrl);
+    const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
+    tr.mark("k_pf_walk");
+    int rc = FIKIT_OK;
 #define FIKIT_PF_WALK(W)                                                                                                   \
   rc = launch_prio_walk<W>(st, d_task_offsets, d_hp_task, d_lp_offsets, d_lp_task, d_lp_prio, n_scenarios, d_gap_offsets, \
                            lp_e, hp_eg, h_params->margin_ns, h_params->min_gap_ns, d_fill_count, d_filled_ns, d_lp_placed, \
                            d_lp_placed_ns, vec_ok, ctrl)
-  if (widest <= 1) FIKIT_PF_WALK(1);
-  else if (widest <= 2) FIKIT_PF_WALK(2);
-  else if (widest <= 4) FIKIT_PF_WALK(4);
-  else if (widest <= 8) FIKIT_PF_WALK(8);
-  else if (widest <= 16) FIKIT_PF_WALK(16);
-  else if (widest <= 32) FIKIT_PF_WALK(32);
-  else FIKIT_PF_WALK(64);
+    if (widest <= 1) FIKIT_PF_WALK(1);
+    else if (widest <= 2) FIKIT_PF_WALK(2);
+    else if (widest <= 4) FIKIT_PF_WALK(4);
+    else if (widest <= 8) FIKIT_PF_WALK(8);
+    else if (widest <= 16) FIKIT_PF_WALK(16);
+    else if (widest <= 32) FIKIT_PF_WALK(32);
+    else FIKIT_PF_WALK(64);
 #undef FIKIT_PF_WALK
-  if (rc) return rc;
+    if (rc) return rc;
+  }
+  const uint32_t only_if_wide = groups ? 1u : 0u;
+  tr.mark("k_pf_walk_wide");
+  hipLaunchKernelGGL(k_gf_predict, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
+                     d_task_row_offsets, role, glists, pe, pg, static_cast<int64_t*>(nullptr), only_if_wide,
+                     static_cast<uint32_t>(h_params->predictor), ctrl);
+  hipLaunchKernelGGL(k_pf_walk_wide, dim3(blocks_for(n_scenarios, 64)), dim3(64), 0, st, d_task_offsets, d_hp_task, d_lp_offsets,
+                     d_lp_task, d_lp_prio, n_scenarios, d_gap_offsets, pe, pg, h_params->margin_ns, h_params->min_gap_ns,
+                     d_fill_count, d_filled_ns, d_lp_placed, d_lp_placed_ns, only_if_wide, ctrl);
   FIKIT_HIP(hipGetLastError());
   tr.mark("host_sync");
   if (int rc2 = read_ctrl(ctrl, &h, st)) return rc2;
-  if (int rc2 = status_from_bits(h.status)) return rc2;
-  // (the walk has not run in this case: its outputs are undefined)
-  return h.wide ? FIKIT_UNSUPPORTED : FIKIT_OK;
+  return status_from_bits(h.status);
 }
 
 size_t fikit_pairing_workspace_bytes(uint32_t n_tasks) {

@@ -94,7 +94,7 @@ __device__ __forceinline__ bool predict_one(uint64_t id, bool in_lds, const Pred
 //   as low-priority queue:   pe[i]   = sum of predicted execution times of launches 0..i
 //   as high-priority trace:  pg[i]   = predicted idle time after launch i
 //                            open[i] = predicted time at which launch i ends (its gap opens):
-//                                      sum_{k<=i} E_k + sum_{k<i} G_k
+//                                      sum_{k<=i} E_k + sum_{k<i} G_k   (not written if open is null)
 // Prefix sums run thread -> wave -> workgroup, with a running carry from chunk to chunk.
 __global__ void __launch_bounds__(PRED_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8)))
 k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
@@ -183,16 +183,16 @@ k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off,
         if (rl & ROLE_LP) *reinterpret_cast<ulonglong2*>(pe + base + i0) = make_ulonglong2(pe0, pe1);
         if (rl & ROLE_HP) {
           *reinterpret_cast<ulonglong2*>(pg + base + i0) = make_ulonglong2(static_cast<uint64_t>(g[2 * k]), static_cast<uint64_t>(g[2 * k + 1]));
-          *reinterpret_cast<ulonglong2*>(open + base + i0) = make_ulonglong2(op0, op1);
+          if (open) *reinterpret_cast<ulonglong2*>(open + base + i0) = make_ulonglong2(op0, op1);
         }
       } else {
         if (i0 < len) {
           if (rl & ROLE_LP) pe[base + i0] = static_cast<int64_t>(pe0);
-          if (rl & ROLE_HP) { pg[base + i0] = g[2 * k]; open[base + i0] = static_cast<int64_t>(op0); }
+          if (rl & ROLE_HP) { pg[base + i0] = g[2 * k]; if (open) open[base + i0] = static_cast<int64_t>(op0); }
         }
         if (i0 + 1 < len) {
           if (rl & ROLE_LP) pe[base + i0 + 1] = static_cast<int64_t>(pe1);
-          if (rl & ROLE_HP) { pg[base + i0 + 1] = g[2 * k + 1]; open[base + i0 + 1] = static_cast<int64_t>(op1); }
+          if (rl & ROLE_HP) { pg[base + i0 + 1] = g[2 * k + 1]; if (open) open[base + i0 + 1] = static_cast<int64_t>(op1); }
         }
       }
     }
@@ -430,6 +430,48 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
   if (unknown) atomicOr(&ctrl->status, ERR_UNKNOWN_ID);
   if (bad_actual) atomicOr(&ctrl->status, ERR_ACTUAL_GAP);
   if (wide) atomicOr(&ctrl->wide, 1u);
+}
+
+// The replay for predictions that do not fit 32 bits (Ctrl::wide): one lane per scenario steps through
+// its gaps literally, on the 64-bit arrays of k_gf_predict (a low-priority kernel's predicted duration is the
+// difference of two prefix sums).  Rare and slow on purpose; results are those of the 32-bit kernels.
+__global__ void __launch_bounds__(256)
+k_gf_replay_wide(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task, const uint32_t* __restrict__ lp_task,
+                 uint64_t n_scen, const uint64_t* __restrict__ gap_off, const int64_t* __restrict__ pe,
+                 const int64_t* __restrict__ pg, const int64_t* __restrict__ actual, int64_t margin, int64_t min_gap,
+                 uint32_t feedback, uint32_t* __restrict__ fill_count, int64_t* __restrict__ filled_ns,
+                 int64_t* __restrict__ delay_out, uint64_t* __restrict__ placed_out, Ctrl* ctrl) {
+  if ((ctrl->status & ~ERR_ACTUAL_GAP) || !ctrl->wide) return;   // (the one bit this kernel itself may set)
+  const uint64_t s = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (s >= n_scen) return;
+  const uint32_t hp = hp_task[s], lp = lp_task[s];
+  const uint64_t h0 = off[hp], H = off[hp + 1] - h0;
+  const uint64_t l0 = off[lp], L = off[lp + 1] - l0;
+  const uint64_t g0 = gap_off[s];
+  uint64_t p = 0;
+  int64_t consumed = 0, delay = 0;
+  bool bad_actual = false;
+  for (uint64_t i = 0; i + 1 < H; ++i) {
+    const int64_t G = pg[h0 + i], a = actual[h0 + i];
+    bad_actual |= a < 0;
+    uint32_t c = 0;
+    int64_t f = 0;
+    if (G >= min_gap && G >= margin) {
+      int64_t rem = G - margin;
+      while (p < L) {
+        const int64_t d = pe[l0 + p] - consumed;
+        if (d > rem || (feedback && f >= a)) break;
+        rem -= d; f += d; consumed += d;
+        ++p; ++c;
+      }
+      if (f > a) delay += f - a;
+    }
+    fill_count[g0 + i] = c;
+    filled_ns[g0 + i] = f;
+  }
+  if (bad_actual) atomicOr(&ctrl->status, ERR_ACTUAL_GAP);
+  delay_out[s] = delay;
+  placed_out[s] = p;
 }
 
 constexpr int LW_THREADS = 256;

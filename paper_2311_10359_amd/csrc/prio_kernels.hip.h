@@ -25,8 +25,6 @@ __global__ void k_pf_scenarios(const uint64_t* __restrict__ off, uint32_t n_task
       atomicOr(&ctrl->status, ERR_TASK_INDEX);
     } else if (e1 < e0 || e1 > n_entries || (s == 0 && e0 != 0)) {
       atomicOr(&ctrl->status, ERR_LP_LIST);
-    } else if (e1 - e0 > PF_MAX_LP) {
-      atomicOr(&ctrl->status, ERR_LP_LIMIT);
     } else {
       const uint64_t H = off[hp + 1] - off[hp];
       const uint64_t want = H > 0 ? H - 1 : 0;
@@ -42,25 +40,16 @@ __global__ void k_pf_scenarios(const uint64_t* __restrict__ off, uint32_t n_task
         launches += off[lp + 1] - off[lp];
         atomicOr(&role[lp], ROLE_LP);
       }
-      // (the age of a waiting request is counted in 32 bits)
-      if (launches >= (1ull << 32) - PF_MAX_LP) atomicOr(&ctrl->status, ERR_LP_LIMIT);
+      // (the age of a waiting request is counted in 32 bits: one tick per list entry, then one per kernel issued)
+      if (launches + (e1 - e0) >= (1ull << 32)) atomicOr(&ctrl->status, ERR_LP_LIMIT);
     }
   }
   const uint32_t k_wave = wave_max_u32(k_here);
   if (lane_id() == 0 && k_wave) atomicMax(&ctrl->n_class[3], k_wave);
 }
 
-#ifndef FIKIT_PW_THREADS
-#define FIKIT_PW_THREADS 128
-#endif
-#ifndef FIKIT_PW_OPENS
-#define FIKIT_PW_OPENS 3
-#endif
-#ifndef FIKIT_PW_TRIES
-#define FIKIT_PW_TRIES 6
-#endif
-constexpr int PW_THREADS = FIKIT_PW_THREADS;
-constexpr uint32_t PW_OPENS = FIKIT_PW_OPENS, PW_TRIES = FIKIT_PW_TRIES;   // per period: gaps opened, and decisions per gap opened
+constexpr int PW_THREADS = 128;
+constexpr uint32_t PW_OPENS = 3, PW_TRIES = 6;   // per period: gaps opened, and decisions per gap opened
 static_assert(2 * PW_OPENS + 7 < 16, "the staged results of a period fit the ring");
 constexpr uint32_t PW_OUT_CAP = 16;              // staged results: at most 7 left over + 2 per gap opened in a period
 
@@ -336,6 +325,71 @@ k_pf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
     }
   }
   for (; z < g_end; ++z) { fill_count[z] = 0; filled_ns[z] = 0; }
+}
+
+// Algorithm 1 with the whole of Algorithm 2 for the scenarios the group kernels do not take: predictions that do not
+// fit 32 bits (Ctrl::wide), or more low-priority tasks in a scenario than a wave has lanes.  One lane per scenario
+// steps through the gaps literally on the 64-bit arrays of k_gf_predict; every decision looks at all the scenario's
+// waiting requests.  The state of a list entry lives in its own output word while the walk runs: the low half of
+// lp_placed counts its kernels issued so far (= the position of its waiting request), the high half is the stamp of
+// that request; the high half is cleared at the end.  Rare and slow on purpose.
+__global__ void __launch_bounds__(64)
+k_pf_walk_wide(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task, const uint64_t* __restrict__ lp_off,
+               const uint32_t* __restrict__ lp_task, const uint32_t* __restrict__ lp_prio, uint64_t n_scen,
+               const uint64_t* __restrict__ gap_off, const int64_t* __restrict__ pe, const int64_t* __restrict__ pg,
+               int64_t margin, int64_t min_gap, uint32_t* __restrict__ fill_count, int64_t* __restrict__ filled_ns,
+               uint64_t* __restrict__ placed, int64_t* __restrict__ placed_ns, uint32_t only_if_wide, const Ctrl* ctrl) {
+  if (ctrl->status) return;
+  if (only_if_wide && !ctrl->wide) return;
+  const uint64_t s = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (s >= n_scen) return;
+  const uint32_t hp = hp_task[s];
+  const uint64_t h0 = off[hp], H = off[hp + 1] - h0;
+  const uint64_t e0 = lp_off[s], K = lp_off[s + 1] - e0;
+  const uint64_t g0 = gap_off[s];
+  for (uint64_t k = 0; k < K; ++k) { placed[e0 + k] = k << 32; placed_ns[e0 + k] = 0; }   // initial requests: enqueued in list order
+  uint64_t clock = K;
+  // predicted duration of the waiting request of entry k (whose state word is st), or -1 if the task has none left
+  auto waiting = [&](uint64_t k, uint64_t st) -> int64_t {
+    const uint32_t lp = lp_task[e0 + k];
+    const uint64_t l0 = off[lp], L = off[lp + 1] - l0, nxt = st & 0xffffffffull;
+    if (nxt >= L) return -1;
+    return pe[l0 + nxt] - (nxt ? pe[l0 + nxt - 1] : 0);
+  };
+  for (uint64_t i = 0; i + 1 < H; ++i) {
+    const int64_t G = pg[h0 + i];
+    uint32_t c = 0;
+    int64_t f = 0;
+    if (G >= min_gap && G >= margin) {
+      int64_t rem = G - margin;
+      for (;;) {
+        // BestPrioFit: the highest level with a request that fits; there the longest; among equally long ones the oldest
+        bool found = false;
+        uint64_t best = 0, best_stamp = 0;
+        uint32_t best_level = 0;
+        int64_t best_d = 0;
+        for (uint64_t k = 0; k < K; ++k) {
+          const uint64_t st = placed[e0 + k];
+          const int64_t d = waiting(k, st);
+          if (d < 0 || d > rem) continue;
+          const uint32_t level = lp_prio[e0 + k];
+          const uint64_t stamp = st >> 32;
+          if (!found || level < best_level || (level == best_level && (d > best_d || (d == best_d && stamp < best_stamp)))) {
+            found = true; best = k; best_level = level; best_d = d; best_stamp = stamp;
+          }
+        }
+        if (!found) break;
+        rem -= best_d; f += best_d; ++c;
+        const uint64_t st = placed[e0 + best];
+        placed[e0 + best] = (clock << 32) | ((st & 0xffffffffull) + 1);   // the task's following kernel is enqueued now
+        ++clock;
+        placed_ns[e0 + best] += best_d;
+      }
+    }
+    fill_count[g0 + i] = c;
+    filled_ns[g0 + i] = f;
+  }
+  for (uint64_t k = 0; k < K; ++k) placed[e0 + k] &= 0xffffffffull;
 }
 
 }  // namespace fikit

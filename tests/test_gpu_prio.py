@@ -145,36 +145,53 @@ def test_prio_argument_errors():
                                ([0, 1, 2], [0, 0], [1, 10], binding.FIKIT_INVALID_ARG),
                                ([0, 2, 1], [0, 0], [1, 1], binding.FIKIT_INVALID_ARG),       # offsets go down
                                ([1, 1, 2], [0, 0], [1, 1], binding.FIKIT_INVALID_ARG),       # first offset not 0
-                               ([0, 1, 2], [0, n_tasks], [1, 1], binding.FIKIT_INVALID_ARG),
-                               ([0, 65, 66], [0] * 66, [1] * 66, binding.FIKIT_UNSUPPORTED)):
+                               ([0, 1, 2], [0, n_tasks], [1, 1], binding.FIKIT_INVALID_ARG)):
         with pytest.raises(binding.FikitError) as e:
             call(lo, lt, lq)
         assert e.value.status == status, (lo, lq)
     with pytest.raises(binding.FikitError) as e:
         call([0, 1, 2], [0, 0], [1, 1], hp_=np.array([0, n_tasks], dtype=np.uint32))
     assert e.value.status == binding.FIKIT_INVALID_ARG
-    out = call([0, 64, 64], [0] * 64, [5] * 64)             # the most a scenario may hold
+    out = call([0, 64, 64], [0] * 64, [5] * 64)             # the most the group kernels take
     torch.cuda.synchronize()
     assert out.lp_placed.numel() == 64
 
 
-def test_prio_wide_predictions_are_refused():
+def test_prio_predictions_beyond_32_bits():
+    """A prediction of 2^32 - 1 ns or more: the 64-bit kernels take the call; results are the oracle's."""
     lens = [40 + k for k in range(8)]
     rec, off = ragged_trace(5, lens, 4)
     slow = rec["name_id"] == 1
     ex = (rec["end_ns"] - rec["start_ns"]).astype(np.int64)
     ex[slow] += 5_000_000_000                       # a prediction that does not fit 32 bits
-    start = np.cumsum(ex + 1000) - (ex + 1000)
+    gap = np.where(rec["name_id"] == 2, 11_000_000_000, 1000)              # and a kernel whose idle time such kernels fit into
+    start = np.cumsum(ex + gap) - (ex + gap)
     rec["start_ns"], rec["end_ns"] = start, start + ex
     prof, d_off, o_prof = check_profile(rec, off)
-    hp = np.arange(off.size - 1, dtype=np.uint32)
-    lo = np.arange(hp.size + 1, dtype=np.uint64)
-    with pytest.raises(binding.FikitError) as e:
-        binding.fikit_prio_fill(prof.ids, d_off, prof.rows, prof.task_row_offsets, binding.to_device_u32(hp, DEV),
-                                binding.to_device_u64(lo, DEV), binding.to_device_u32(hp[::-1].copy(), DEV),
-                                binding.to_device_u32(np.ones(hp.size, np.uint32), DEV),
-                                binding.to_device_u64(traces.gap_offsets(off, hp), DEV), margin_ns=0, min_gap_ns=0)
-    assert e.value.status == binding.FIKIT_UNSUPPORTED
+    rng = np.random.default_rng(3)
+    for k_max in (1, 3, 9):
+        hp, lo, lt, lq = prio_lists(rng, off.size - 1, 12, k_max)
+        for margin, min_gap in ((0, 0), (500, 2000)):
+            got, exp = check_prio(prof, d_off, off, o_prof, hp, lo, lt, lq, margin, min_gap)
+    assert int(exp[1].max()) > 2**32                 # (some gap did take more than 32 bits' worth)
+
+
+@pytest.mark.parametrize("k", [65, 66, 130, 700])
+def test_prio_more_tasks_in_a_scenario_than_a_wave_has_lanes(k):
+    cfg = traces.config(4, n_tasks=24, hp_launches=300, lp_launches=90)
+    rec, off = traces.build(cfg)
+    prof, d_off, o_prof = check_profile(rec, off)
+    rng = np.random.default_rng(k)
+    n_scen = 5
+    hp = rng.integers(0, cfg.n_tasks, n_scen).astype(np.uint32)
+    counts = np.array([k, 3, 0, k - 1, 64][:n_scen])
+    lo = np.zeros(n_scen + 1, dtype=np.uint64)
+    np.cumsum(counts, out=lo[1:])
+    lt = rng.integers(0, cfg.n_tasks, int(lo[-1])).astype(np.uint32)
+    lq = rng.integers(1, 10, int(lo[-1])).astype(np.uint32)
+    lq[rng.random(lq.shape[0]) < 0.6] = 2                      # many on one level: durations and ages decide
+    got, exp = check_prio(prof, d_off, off, o_prof, hp, lo, lt, lq, cfg.margin_ns, cfg.min_gap_ns)
+    assert int(exp[2].sum()) > 0
 
 
 @pytest.mark.parametrize("seed", range(10))

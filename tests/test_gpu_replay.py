@@ -149,15 +149,32 @@ def test_replay_error_statuses():
     with pytest.raises(oracle.OracleError) as oe:
         oracle.replay(*o_prof[:1], off, o_prof[1], o_prof[2], bad, hp, lp, 0, 0, True, go)
     assert oe.value.status == oracle.INVALID_ARG
-    # a prediction that does not fit 32 bits
+
+
+def test_replay_predictions_beyond_32_bits():
+    """A prediction of 2^32 - 1 ns or more: the 64-bit kernels take the call; results are the oracle's."""
+    lens = [40 + k for k in range(8)]
+    rec, off = ragged_trace(5, lens, 4)
     slow = rec["name_id"] == 1
     ex = (rec["end_ns"] - rec["start_ns"]).astype(np.int64)
     ex[slow] += 5_000_000_000
-    start = np.cumsum(ex + 1000) - (ex + 1000)
+    idle = np.where(rec["name_id"] == 2, 11_000_000_000, 1000)             # a kernel whose idle time such kernels fit into
+    start = np.cumsum(ex + idle) - (ex + idle)
     rec["start_ns"], rec["end_ns"] = start, start + ex
     prof, d_off, o_prof = check_profile(rec, off)
     d_gap, gap = check_measure(rec, off)
+    hp, lp = all_pairs(range(len(lens)))
+    for margin, min_gap in ((0, 0), (500, 2000), (10**10, 0)):
+        check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, margin, min_gap)
+    # actual idle times that differ from the predictions (shorter and longer), and a negative one
+    rng = np.random.default_rng(9)
+    other = np.where(gap >= 0, (gap * rng.uniform(0.2, 1.8, gap.size)).astype(np.int64), gap)
+    check_replay(prof, d_off, off, o_prof, torch.from_numpy(other).to(DEV), other, hp, lp, 0, 0)
+    bad = gap.copy()
+    bad[3] = -5
+    go = traces.gap_offsets(off, hp)
     with pytest.raises(binding.FikitError) as e:
-        binding.fikit_gapfill_replay(prof.ids, d_off, prof.rows, prof.task_row_offsets, d_gap, *tail, margin_ns=0,
-                                     min_gap_ns=0, feedback=False)
-    assert e.value.status == binding.FIKIT_UNSUPPORTED
+        binding.fikit_gapfill_replay(prof.ids, d_off, prof.rows, prof.task_row_offsets, torch.from_numpy(bad).to(DEV),
+                                     binding.to_device_u32(hp, DEV), binding.to_device_u32(lp, DEV), binding.to_device_u64(go, DEV),
+                                     margin_ns=0, min_gap_ns=0, feedback=False)
+    assert e.value.status == binding.FIKIT_INVALID_ARG

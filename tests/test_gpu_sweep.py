@@ -31,10 +31,9 @@ def test_sweep(seed):
     got = check_gapfill(prof, d_off, off, o_prof, hp, lp, margin, min_gap, predictor=predictor)
     go = traces.gap_offsets(off, hp)
     check_pairing(hp, lp, n_tasks, go, got.filled_ns.cpu().numpy(), got.lp_completion_ns.cpu().numpy())
-    if wide:
-        return          # the replay and the priority queues take 32-bit predictions only
+    # (with values beyond 32 bits the 64-bit kernels take the replay and the priority queues)
     d_gap, gap = check_measure(rec, off)
     check_replay(prof, d_off, off, o_prof, d_gap, gap, hp, lp, margin, min_gap, predictor=predictor)
-    k_max = int(rng.choice([1, 2, 3, 4, 6, 9, 20]))
+    k_max = int(rng.choice([1, 2, 3, 4, 6, 9, 20, 70]))
     hp2, lo, lt, lq = prio_lists(rng, n_tasks, int(rng.integers(1, 80)), k_max)
     check_prio(prof, d_off, off, o_prof, hp2, lo, lt, lq, margin, min_gap, predictor=predictor)
