@@ -43,51 +43,68 @@ GAPFILL_KERNELS = ("k_gf_predict", "k_gf_walk", "k_gf_predict32", "k_gf_walk_lan
 
 def source_hash():
     """Hash of the library sources, to tell whether stored counter readings still describe the library as it stands."""
-    import hashlib
-    h = hashlib.sha256()
-    d = os.path.join(ROOT, "paper_2311_10359_amd", "csrc")
-    for name in sorted(os.listdir(d)):
-        if name.endswith((".h", ".hip")):
-            h.update(name.encode())
-            h.update(open(os.path.join(d, name), "rb").read())
-    return h.hexdigest()[:16]
+    from paper_2311_10359_amd import profile_summary
+    return profile_summary.source_hash()
 
 
-def stored_traffic(kernel, workload):
-    """HBM bytes per launch from the committed rocprofv3 counter runs, or None if they are of another build."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic.json")
+
+
+def stored_counters(workload):
+    """The committed rocprofv3 counter readings (profiles/hbm_traffic.json, written by
+    `python -m paper_2311_10359_amd.profile_summary hbm`) if they are of this workload and of the library as it
+    stands, else None: counters read for another build say nothing about this one."""
     try:
-        data = json.load(open(path))
+        data = json.load(open(os.path.join(ROOT, TRAFFIC_FILE)))
     except (OSError, ValueError):
+        log(f"[bench] no stored HBM counters ({TRAFFIC_FILE}): roofline.traffic and hbm_by_call are left out")
         return None
-    if data.get("source_hash") != source_hash() or data.get("workload") != workload:
+    if data.get("workload") != workload:
+        log(f"[bench] stored HBM counters are of workload {data.get('workload')!r}, not {workload!r}: traffic left out")
+        return None
+    if data.get("source_hash") != source_hash():
+        log(f"[bench] stored HBM counters are of library sources {data.get('source_hash')}, these are {source_hash()}: "
+            "the kernels have changed since the counters were taken, traffic left out (null)")
+        return None
+    return data
+
+
+def stored_traffic(data, kernel):
+    """HBM bytes per launch of one kernel from the stored counter readings."""
+    if not data:
         return None
     return data.get("kernels", {}).get(kernel, {}).get("hbm_bytes_per_launch")
 
 
-def stored_call_traffic(workload):
-    """HBM bytes per call (all kernels of fikit_profile / of fikit_gapfill, one launch each per step) from
-    the committed counter runs, or None if they are of another build or workload."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    try:
-        data = json.load(open(path))
-    except (OSError, ValueError):
-        return None
-    if data.get("source_hash") != source_hash() or data.get("workload") != workload:
+def stored_call_traffic(data):
+    """HBM bytes per call (all kernels of fikit_profile / of fikit_gapfill, one launch each per step)."""
+    if not data:
         return None
     calls = {"fikit_profile": 0, "fikit_gapfill": 0}
     for kname, v in data.get("kernels", {}).items():
-        if not kname.startswith("k_"):
-            continue   # copies and fills of the benchmark itself
         nbytes = v["hbm_bytes_per_launch"]
-        if kname in ("k_validate_offsets", "k_clear_ctrl"):   # run once in either call (negligible bytes)
+        if kname in ("k_validate_offsets", "k_clear_ctrl", "k_fill_u32"):   # run in either call (negligible bytes)
             calls["fikit_profile"] += nbytes
             calls["fikit_gapfill"] += nbytes
-        elif kname.startswith("k_gf"):
+        elif kname.startswith(("k_gf", "k_pf")):
             calls["fikit_gapfill"] += nbytes
         else:
             calls["fikit_profile"] += nbytes
     return calls
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+A_REF_BYTES_PER_RECORD = 504   # what the sort-based formulation of the profile pass moves per record (hash + measure 88,
+                               # one histogram pass 8, eight scatter passes 48 each, reduce 24): the yardstick for "effective" GB/s
 
 
 def log(*a):
@@ -118,6 +135,9 @@ def main():
     ap.add_argument("--merge", action="store_true",
                     help="after the timed steps, also time fikit_profile_merge of the profile with itself (reported "
                          "beside the metric, not part of it)")
+    ap.add_argument("--rho", type=float, default=None,
+                    help="scale of the per-Kernel-ID share of the spread of times in the generated traces (default 1: an ID "
+                         "has a characteristic duration; 0: every launch is drawn independently)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware counter runs)")
     args = ap.parse_args()
@@ -129,19 +149,19 @@ def main():
     from paper_2311_10359_amd import traces
 
     if args.workload == "cfg4":
-        cfg = traces.config(4, n_tasks=2 * args.scenarios if args.scenarios else None)
+        cfg = traces.config(4, n_tasks=2 * args.scenarios if args.scenarios else None, rho=args.rho)
         sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 16384)   # about 12 s of oracle time
         name = "config 4: batched gap-fill"
     elif args.workload == "cfg2":
-        cfg = traces.config(2, n_tasks=args.tasks)
+        cfg = traces.config(2, n_tasks=args.tasks, rho=args.rho)
         sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 12)
         name = "config 2: skewed IDs (profile only)"
     elif args.workload == "cfg3":
-        cfg = traces.config(3, n_tasks=args.tasks)
+        cfg = traces.config(3, n_tasks=args.tasks, rho=args.rho)
         sample_tasks = args.cpu_sample_tasks or min(cfg.n_tasks, 48)
         name = "config 3: large profile (profile only)"
     else:
-        cfg = traces.config(1, n_tasks=args.tasks)
+        cfg = traces.config(1, n_tasks=args.tasks, rho=args.rho)
         sample_tasks = args.cpu_sample_tasks or cfg.n_tasks
         name = "config 1: medium"
     off = traces.task_offsets(cfg)
@@ -415,8 +435,12 @@ def main():
         algo_bytes = per_hp * n_hp * (n_scen // max(1, len(np.unique(hp)))) \
             + per_lp * n_lp * (n_scen // max(1, len(np.unique(lp)))) + 12 * n_gaps
     achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
+    counters = stored_counters(name) if args.rho is None and not args.scenarios and not args.tasks else None
+    traffic_source = (f"{TRAFFIC_FILE} (rocprofv3 FETCH_SIZE / WRITE_SIZE of an earlier run of this command on these library "
+                      f"sources, hash {counters['source_hash']}; summary: {counters.get('summary')})") if counters else None
     roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": stored_traffic(dom, name),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": stored_traffic(counters, dom),
+                "traffic_source": traffic_source,
                 "avg_launch_ms": round(avg_ms, 4), "algorithmic_bytes_per_launch": int(algo_bytes),
                 "share_of_step": round(dom_ms / args.steps / ms_per_step, 3)}
 
@@ -430,20 +454,31 @@ def main():
         t2 = time.perf_counter()
         pick = np.nonzero((hp < sample_tasks) & (lp < sample_tasks))[0] if n_scen else np.zeros(0, dtype=np.int64)
         s_hp, s_lp = hp[pick], lp[pick]
+        o_fill = None
         if pick.size:
-            oracle.gapfill(o_ids, s_off, o_rows, o_tro, s_hp, s_lp, cfg.margin_ns, cfg.min_gap_ns,
-                           traces.gap_offsets(s_off, s_hp))
+            o_fill = oracle.gapfill(o_ids, s_off, o_rows, o_tro, s_hp, s_lp, cfg.margin_ns, cfg.min_gap_ns,
+                                    traces.gap_offsets(s_off, s_hp))
         t3 = time.perf_counter()
         cpu = {"value": round(sample_n / (t3 - t1), 1), "unit": "records/s", "cores": 1, "kind": "oracle",
                "sample": f"first {sample_tasks} tasks ({sample_n} records, {pick.size} scenarios) of the same workload: "
                          f"profile {t2 - t1:.2f}s + gap fill {t3 - t2:.2f}s, single thread",
                "profile_records_per_s": round(sample_n / (t2 - t1), 1),
                "gapfill_scenarios_per_s": round(pick.size / (t3 - t2), 1) if pick.size else None,
-               "host_cpus": os.cpu_count()}
+               "cpu_model": cpu_model(), "host_cpus": os.cpu_count()}
         # the sample doubles as a spot check of the timed run's output
         got_rows = binding.rows_to_numpy(prof.rows[: len(o_rows)])
-        assert got_rows.tobytes() == o_rows.tobytes(), "benchmark output differs from the oracle on the sample"
-        log(f"[bench] oracle sample: {cpu['value'] / 1e6:.2f} M records/s on one core; sample rows match")
+        assert got_rows.tobytes() == o_rows.tobytes(), "benchmark output differs from the oracle on the sample (rows)"
+        assert np.array_equal(binding.u64_to_numpy(ids[:sample_n]), o_ids), "benchmark output differs from the oracle on the sample (IDs)"
+        checked = "rows and IDs"
+        if o_fill is not None and replay is None and prio is None:      # (those legs reuse the gap fill's output buffers)
+            assert np.array_equal(gf_out.lp_completion_ns.cpu().numpy()[pick], o_fill[2]), "completion times differ from the oracle"
+            assert np.array_equal(binding.u64_to_numpy(gf_out.lp_placed)[pick], o_fill[3]), "kernels placed differ from the oracle"
+            if np.array_equal(pick, np.arange(pick.size)):             # the sample's scenarios are the first ones: their gaps too
+                k = int(go[pick.size])
+                assert np.array_equal(binding.u32_to_numpy(gf_out.fill_count[:k]), o_fill[0]), "fill counts differ from the oracle"
+                assert np.array_equal(gf_out.filled_ns[:k].cpu().numpy(), o_fill[1]), "filled times differ from the oracle"
+            checked = "rows, IDs and gap-fill outputs"
+        log(f"[bench] oracle sample: {cpu['value'] / 1e6:.2f} M records/s on one core; the sample's {checked} match")
 
     out = {
         "metric": "launch records/s profiled + gap-fill scenarios/s; % of peak HBM GB/s",
@@ -452,10 +487,14 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
         "config": {"workload": name, "records": n, "tasks": cfg.n_tasks, "scenarios": n_scen, "gaps": n_gaps,
-                   "rows": prof.n_rows, "margin_ns": cfg.margin_ns, "min_gap_ns": cfg.min_gap_ns},
+                   "rows": prof.n_rows, "margin_ns": cfg.margin_ns, "min_gap_ns": cfg.min_gap_ns,
+                   "rho_exec": cfg.rho_exec, "rho_gap": cfg.rho_gap},
         "profile_records_per_s": round(n / (prof_ms * 1e-3), 1),
         "gapfill_scenarios_per_s": round(n_scen / (gf_ms * 1e-3), 1) if n_scen else None,
         "profile_ms": round(prof_ms, 3), "gapfill_ms": round(gf_ms, 3),
+        # the profile call against the sort-based formulation's bytes: what that formulation would have to sustain
+        # to be as fast (a design that moves fewer bytes shows up here as more than it could physically move)
+        "profile_effective_GB/s_at_504_B_per_record": round(n * A_REF_BYTES_PER_RECORD / (prof_ms * 1e-3) / 1e9, 1),
         "kernel_ms_per_step": {k: round(ms / args.steps, 3) for k, (ms, _) in trace.items()},
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -469,9 +508,10 @@ def main():
     if merge:
         out["profile_merge"] = merge
     # whole calls against the HBM peak: counter-measured bytes of every kernel of the call / the call's time
-    calls = stored_call_traffic(name)
+    calls = stored_call_traffic(counters)
     if calls:
         out["hbm_by_call"] = {
+            "traffic_source": traffic_source,
             "fikit_profile": {"bytes": calls["fikit_profile"], "GB/s": round(calls["fikit_profile"] / (prof_ms * 1e-3) / 1e9, 1),
                               "frac_of_peak": round(calls["fikit_profile"] / (prof_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
             "fikit_gapfill": {"bytes": calls["fikit_gapfill"], "GB/s": round(calls["fikit_gapfill"] / (gf_ms * 1e-3) / 1e9, 1),

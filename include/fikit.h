@@ -28,8 +28,10 @@
  *
  * Conventions
  *   - d_* arguments are device pointers, h_* are host pointers.  The caller owns every buffer,
- *     including the workspace; the library allocates no device memory and keeps no state
- *     between calls.  Inputs are left untouched.
+ *     including the workspace; the library allocates no device memory and its results depend
+ *     on nothing but a call's arguments (the only things it keeps between calls are the
+ *     measurement aid fikit_trace_* and the scratch address of fikit_gapfill_static).  Inputs
+ *     are left untouched.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default
  *     stream).  Every call synchronises that stream before it returns, so outputs and the
  *     returned status are final on return.

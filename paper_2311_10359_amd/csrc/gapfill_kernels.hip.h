@@ -138,7 +138,8 @@ k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off,
   // two neighbouring launches, so that a wave reads and writes 1 KiB of consecutive memory per access.
   constexpr int PRED_SUB = PRED_KPT / 2;
   __shared__ uint64_t sub_sum[2][PRED_SUB * 4];
-  const bool even = ((base & 1) == 0);   // 16-byte accesses need an even first index
+  const bool even = ((base & 1) == 0);   // 16-byte accesses to the workspace arrays need an even first index
+  const bool ids_vec = (reinterpret_cast<uintptr_t>(ids + base) & 15) == 0;   // and those to the caller's IDs an aligned address
   for (uint64_t c0 = 0; c0 < len; c0 += PRED_CHUNK) {
     int64_t e[PRED_KPT], g[PRED_KPT];
     uint64_t ie[PRED_SUB], io[PRED_SUB];
@@ -146,7 +147,7 @@ k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off,
     for (int k = 0; k < PRED_SUB; ++k) {
       const uint64_t i0 = c0 + static_cast<uint64_t>(k) * (2 * PRED_THREADS) + 2 * tid;
       uint64_t id0 = 0, id1 = 0;
-      if (even && i0 + 1 < len) {
+      if (ids_vec && i0 + 1 < len) {
         const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(ids + base + i0);
         id0 = v.x; id1 = v.y;
       } else {
@@ -384,11 +385,12 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
   __syncthreads();
   bool unknown = false, wide = false, bad_actual = false;
   uint64_t total = 0;
-  const bool even = ((base & 1) == 0);   // 16-byte accesses need an even first index
+  const bool even = ((base & 1) == 0);   // 16-byte accesses to the workspace arrays need an even first index
+  const bool ids_vec = (reinterpret_cast<uintptr_t>(ids + base) & 15) == 0;   // and those to the caller's IDs an aligned address
   for (uint64_t i0 = 2 * static_cast<uint64_t>(tid); i0 < len; i0 += 2 * PRED_THREADS) {
     uint64_t id0 = 0, id1 = 0;
     const bool two = i0 + 1 < len;
-    if (even && two) {
+    if (ids_vec && two) {
       const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(ids + base + i0);
       id0 = v.x; id1 = v.y;
     } else {

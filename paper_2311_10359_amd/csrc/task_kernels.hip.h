@@ -11,10 +11,12 @@
 //   2. The task's set of unique IDs (S_UID, Section 3.2) is built in an LDS hash table, then
 //      ranked so that rows come out in ascending ID order.
 //   3. count / sum / min / max per ID (sum / count = SK_j, SG_j of Section 3.2) by LDS atomics.
-//   4. Nearest-rank p50 / p95 per ID by most-significant-digit radix selection: per pass, every
-//      launch whose value still agrees with the digits fixed so far for its ID adds one to that
-//      ID's digit histogram in LDS; one thread per (ID, percentile) then walks the histogram to
-//      the digit that holds the wanted rank.  All IDs of the task advance together.
+//   4. Nearest-rank p50 / p95 per ID: a histogram over each ID's own range of values (on a scale that keeps
+//      the leading bits of large values) tells which bin holds each wanted rank; the few samples of those
+//      bins are listed and ranked by counting.  If some list would get long (many equal or clustered
+//      samples), most-significant-digit radix selection does the task instead: per pass, every launch whose
+//      value still agrees with the digits fixed so far for its ID adds one to that ID's digit histogram,
+//      and one thread per (ID, percentile) walks it to the digit that holds the wanted rank.
 //
 // Rows are staged in the task's own slice of two workspace arrays and moved to their final
 // place once every task's row count is known.  A task that does not fit (too many distinct IDs)
@@ -130,11 +132,21 @@ __device__ __forceinline__ uint32_t identity_tag(const uint32_t (&w)[8]) {
 // How the fast percentile path packs an (ID, array) pair's window into one word: the shift that turns a
 // value's offset from the window's low end into a bin number, then the bins that hold the two wanted ranks.
 constexpr int SEL_BINS_LOG2_MAX = 11;
-constexpr uint32_t SEL_SHIFT_MASK = 0x3fu, SEL_BIN_MASK = 0x1fffu, SEL_NO_BIN = SEL_BIN_MASK;   // "no samples"
-constexpr int SEL_B50_AT = 6, SEL_B95_AT = 19;
+constexpr uint32_t SEL_SHIFT_MASK = 0x3fu, SEL_LISTED = 0x40u, SEL_BIN_MASK = 0xfffu, SEL_NO_BIN = SEL_BIN_MASK;   // "no samples"
+constexpr int SEL_B50_AT = 7, SEL_B95_AT = 19;
 __device__ __forceinline__ uint32_t sel_shift(uint32_t y) { return y & SEL_SHIFT_MASK; }
 __device__ __forceinline__ uint32_t sel_b50(uint32_t y) { return (y >> SEL_B50_AT) & SEL_BIN_MASK; }
 __device__ __forceinline__ uint32_t sel_b95(uint32_t y) { return (y >> SEL_B95_AT) & SEL_BIN_MASK; }
+
+// The scale on which the fast percentile path lays out its bins: the bit pattern of the value as a float, without
+// its lowest 12 bits, i.e. the exponent and the leading 12 bits of the value.  Conversion rounds to nearest, which is
+// monotone, so ranks found on the scale are ranks of the values; values below 2^SCALE_EXACT_BITS map one to one and
+// come back exactly with value_of_scale.  Durations of one kernel spread over a range in proportion to their size
+// (the workloads draw them lognormal): bins of equal width on this scale then hold similar numbers of samples, where
+// bins of equal width in nanoseconds would crowd most samples into the lowest few.
+constexpr uint32_t SCALE_EXACT_BITS = 12, SCALE_DROP = 12;
+__device__ __forceinline__ uint32_t scale_of(uint32_t v) { return __float_as_uint(__uint2float_rn(v)) >> SCALE_DROP; }
+__device__ __forceinline__ uint32_t value_of_scale(uint32_t t) { return static_cast<uint32_t>(__uint_as_float(t << SCALE_DROP)); }
 
 // log2 of the number of bins the fast percentile path cuts an ID's value range into: about one bin
 // per WINDOW_SAMPLES_PER_BIN samples (the bin that holds a wanted rank is ranked directly afterwards), at least 2,
@@ -648,12 +660,16 @@ k_task_fused(const FusedArgs A) {
     {
       // window of the fast percentile path: the ID's own value range, cut into bins
       uint2* sel0 = reinterpret_cast<uint2*>(sm.ht_key);   // the ID table is dead by now
-      const uint32_t lo_e = emin, lo_g = gc ? gmin : 0;
-      const uint32_t re = mxe - lo_e, rg = mxg - lo_g;
+      const uint32_t lo_e = scale_of(emin), lo_g = scale_of(gc ? gmin : 0);
+      const uint32_t re = scale_of(mxe) - lo_e, rg = scale_of(mxg) - lo_g;
       const uint32_t we = re ? 32 - __builtin_clz(re) : 0, wg = rg ? 32 - __builtin_clz(rg) : 0;
       const uint32_t be = window_bins_log2(ec, B1), bg = window_bins_log2(gc, B1);
-      sel0[j] = make_uint2(lo_e, we > be ? we - be : 0);
-      sel0[D + j] = make_uint2(lo_g, wg > bg ? wg - bg : 0);
+      const uint32_t she = we > be ? we - be : 0, shg = wg > bg ? wg - bg : 0;
+      // a bin that is one step wide on the part of the scale that is one to one is the answer;
+      // otherwise the samples of the bin are listed and ranked
+      const uint32_t exact = 1u << SCALE_EXACT_BITS;
+      sel0[j] = make_uint2(lo_e, she | ((she || mxe >= exact) ? SEL_LISTED : 0u));
+      sel0[D + j] = make_uint2(lo_g, shg | ((shg || mxg >= exact) ? SEL_LISTED : 0u));
     }
     sm.npass[0][j] = static_cast<uint8_t>(((mxe ? 32 - __builtin_clz(mxe) : 1) + B - 1) / B);
     sm.npass[1][j] = static_cast<uint8_t>(((mxg ? 32 - __builtin_clz(mxg) : 1) + B - 1) / B);
@@ -666,7 +682,7 @@ k_task_fused(const FusedArgs A) {
   // a short list and ranked directly.  If some bin is too crowded for that (many equal or
   // clustered samples), the general multi-pass radix selection below does the whole job instead.
   // Tables of earlier phases are dead by now and are reused:
-  uint2* sel = reinterpret_cast<uint2*>(sm.ht_key);            // [2][DMAX]: x = window low end, y = shift | bin50 << 6 | bin95 << 19
+  uint2* sel = reinterpret_cast<uint2*>(sm.ht_key);            // [2][DMAX]: x = window low end (on the scale), y = shift | listed | bin50 << 7 | bin95 << 19
   uint16_t* lcnt = reinterpret_cast<uint16_t*>(sm.ht_cnt);     // [2][2][DMAX]: list lengths (array, list A / B, ID)
   uint16_t* loff = reinterpret_cast<uint16_t*>(sm.memo_claim); // [2][2][DMAX]: list starts
   constexpr uint32_t LIST_MAX = 64;
@@ -683,11 +699,11 @@ k_task_fused(const FusedArgs A) {
       uint32_t j = sl[r];
       asm volatile("" : "+v"(j));
       const uint2 se = sel[j];
-      const uint32_t de = (ev[r] - se.x) >> se.y;
+      const uint32_t de = (scale_of(ev[r]) - se.x) >> sel_shift(se.y);
       atomicAdd(&sm.u.hist[__umul24(de >> 1, PS) + j], (de & 1u) ? 0x10000u : 1u);
       if (gv[r] != NONE32) {
         const uint2 sg = sel[D + j];
-        const uint32_t dg = (gv[r] - sg.x) >> sg.y;
+        const uint32_t dg = (scale_of(gv[r]) - sg.x) >> sel_shift(sg.y);
         atomicAdd(&sm.u.hist[__umul24(dg >> 1, PS) + D + j], (dg & 1u) ? 0x10000u : 1u);
       }
     }
@@ -707,7 +723,8 @@ k_task_fused(const FusedArgs A) {
       const uint32_t arr = (live && q >= D) ? 1u : 0u, j = live ? q - arr * D : 0u;
       const uint32_t k50 = sm.kth[2 * arr][j], k95 = sm.kth[2 * arr + 1][j];
       const uint32_t cnt_all = arr ? sm.gcnt[j] : sm.rcnt[j];
-      const uint32_t sh = live ? sel_shift(sel[q].y) : 0u;
+      const uint32_t sy = live ? sel[q].y : 0u;
+      const bool listed = (sy & SEL_LISTED) != 0;
       const uint32_t words = live ? (1u << window_bins_log2(cnt_all, B1)) >> 1 : 0u, wpl = ((words + WG - 1) >> wg_log2) | 1u;   // (odd: the lanes' slices start on different banks)
       const uint32_t w_lo = gl * wpl < words ? gl * wpl : words, w_hi = w_lo + wpl < words ? w_lo + wpl : words;
       uint32_t mine = 0, incl = 0;
@@ -740,25 +757,25 @@ k_task_fused(const FusedArgs A) {
       if (live && cnt_all == 0) {
         if (gl == 0) {
           // no samples: both percentiles are 0, nothing to collect (SEL_NO_BIN never matches a bin number)
-          sel[q].y = sh | (SEL_NO_BIN << SEL_B50_AT) | (SEL_NO_BIN << SEL_B95_AT);
+          sel[q].y = sy | (SEL_NO_BIN << SEL_B50_AT) | (SEL_NO_BIN << SEL_B95_AT);
           lcnt[(2 * arr) * DMAX + j] = 0;
           lcnt[(2 * arr + 1) * DMAX + j] = 0;
         }
       } else if (live) {
-        // (bins one value wide, shift 0: the bin is the answer, nothing to collect)
+        // (bins that are the answer themselves: nothing to collect)
         if (has50) {
-          const uint32_t la = sh ? c50 : 0u;
+          const uint32_t la = listed ? c50 : 0u;
           atomicOr(&sel[q].y, bin50 << SEL_B50_AT);
           lcnt[(2 * arr) * DMAX + j] = static_cast<uint16_t>(la);
-          if (sh) sm.kth[2 * arr][j] = static_cast<uint16_t>(n50);
+          if (listed) sm.kth[2 * arr][j] = static_cast<uint16_t>(n50);
           if (la > LIST_MAX) atomicOr(&sm.fallback, 1u);
         }
         if (has95) {
           // (the lower rank may lie in this bin too: then one list serves both)
-          const uint32_t lb = (sh && !same_bin) ? c95 : 0u;
+          const uint32_t lb = (listed && !same_bin) ? c95 : 0u;
           atomicOr(&sel[q].y, bin95 << SEL_B95_AT);
           lcnt[(2 * arr + 1) * DMAX + j] = static_cast<uint16_t>(lb);
-          if (sh) sm.kth[2 * arr + 1][j] = static_cast<uint16_t>(n95);
+          if (listed) sm.kth[2 * arr + 1][j] = static_cast<uint16_t>(n95);
           if (lb > LIST_MAX) atomicOr(&sm.fallback, 1u);
         }
       }
@@ -795,17 +812,15 @@ k_task_fused(const FusedArgs A) {
           uint32_t j = sl[r];
           asm volatile("" : "+v"(j));
           const uint2 se = sel[j];
-          const uint32_t sh = sel_shift(se.y);
-          if (sh) {
-            const uint32_t de = (ev[r] - se.x) >> sh, b50 = sel_b50(se.y), b95 = sel_b95(se.y);
+          if (se.y & SEL_LISTED) {
+            const uint32_t de = (scale_of(ev[r]) - se.x) >> sel_shift(se.y), b50 = sel_b50(se.y), b95 = sel_b95(se.y);
             if (de == b50) lists[loff[j] + atomicAdd(&cursor[4 * j], 1u)] = ev[r];
             else if (de == b95) lists[loff[DMAX + j] + atomicAdd(&cursor[4 * j + 1], 1u)] = ev[r];
           }
           if (gv[r] != NONE32) {
             const uint2 sg = sel[D + j];
-            const uint32_t shg = sel_shift(sg.y);
-            if (shg) {
-              const uint32_t dg = (gv[r] - sg.x) >> shg, b50 = sel_b50(sg.y), b95 = sel_b95(sg.y);
+            if (sg.y & SEL_LISTED) {
+              const uint32_t dg = (scale_of(gv[r]) - sg.x) >> sel_shift(sg.y), b50 = sel_b50(sg.y), b95 = sel_b95(sg.y);
               if (dg == b50) lists[loff[2 * DMAX + j] + atomicAdd(&cursor[4 * j + 2], 1u)] = gv[r];
               else if (dg == b95) lists[loff[3 * DMAX + j] + atomicAdd(&cursor[4 * j + 3], 1u)] = gv[r];
             }
@@ -820,12 +835,12 @@ k_task_fused(const FusedArgs A) {
       for (uint32_t q = tid / GS; q < P2; q += NT / GS) {
         const uint32_t arr = q >= D ? 1u : 0u, j = q - arr * D;
         const uint2 se = sel[q];
-        const uint32_t sh = sel_shift(se.y), b50 = sel_b50(se.y), b95 = sel_b95(se.y);
+        const uint32_t b50 = sel_b50(se.y), b95 = sel_b95(se.y);
         uint64_t* row = staged_row(stage_a, stage_b, base, m, j);
-        if (b50 == SEL_NO_BIN || sh == 0) {
+        if (b50 == SEL_NO_BIN || !(se.y & SEL_LISTED)) {   // (not listed: bins one value wide where the scale is one to one)
           if (gl == 0) {
-            row[arr ? 12 : 6] = b50 == SEL_NO_BIN ? 0 : se.x + b50;
-            row[arr ? 13 : 7] = b50 == SEL_NO_BIN ? 0 : se.x + b95;
+            row[arr ? 12 : 6] = b50 == SEL_NO_BIN ? 0 : value_of_scale(se.x + b50);
+            row[arr ? 13 : 7] = b50 == SEL_NO_BIN ? 0 : value_of_scale(se.x + b95);
           }
           continue;
         }

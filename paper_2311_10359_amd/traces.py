@@ -72,6 +72,8 @@ class TraceConfig:
     margin_ns: int = 500
     min_gap_ns: int = 0
     runs: int = 1  # measured runs per task: the trace is cut into this many runs of (almost) equal length
+    rho_exec: float = RHO_EXEC  # share of the log-scale spread of execution times that belongs to the Kernel ID
+    rho_gap: float = RHO_GAP    # the same for idle times (0 for both: every launch drawn independently)
     overrides: tuple = ()  # the keyword overrides config() was called with (to rebuild it elsewhere)
 
     @property
@@ -84,7 +86,8 @@ def _const(v):
 
 
 def config(index: int, *, n_tasks: Optional[int] = None, launches: Optional[int] = None,
-           hp_launches: Optional[int] = None, lp_launches: Optional[int] = None, runs: Optional[int] = None) -> TraceConfig:
+           hp_launches: Optional[int] = None, lp_launches: Optional[int] = None, runs: Optional[int] = None,
+           rho: Optional[float] = None) -> TraceConfig:
     """The five workloads.  Keyword overrides shrink a workload while keeping its structure
     (same distributions, same ID pattern) so that it can be checked on a CPU in seconds."""
     ln = math.log
@@ -129,8 +132,12 @@ def config(index: int, *, n_tasks: Optional[int] = None, launches: Optional[int]
     else:
         raise ValueError(f"no workload {index}")
     ov = tuple((k, v) for k, v in (("n_tasks", n_tasks), ("launches", launches), ("hp_launches", hp_launches),
-                                   ("lp_launches", lp_launches), ("runs", runs)) if v is not None)
-    return replace(cfg, overrides=ov, runs=runs or 1)
+                                   ("lp_launches", lp_launches), ("runs", runs), ("rho", rho)) if v is not None)
+    cfg = replace(cfg, overrides=ov, runs=runs or 1)
+    if rho is not None:
+        # rho scales both shares: 1 keeps the defaults, 0 draws every launch independently of its Kernel ID
+        cfg = replace(cfg, rho_exec=RHO_EXEC * rho, rho_gap=RHO_GAP * rho)
+    return cfg
 
 
 def _rng(cfg: TraceConfig, task: int, stream: int) -> np.random.Generator:
@@ -222,9 +229,9 @@ def task_records(cfg: TraceConfig, task: int, out: Optional[np.ndarray] = None) 
     z_gap = rng.standard_normal(k)
     e_mu, e_sig = cfg.exec_mu(task), cfg.exec_sigma(task)
     g_mu, g_sig = cfg.gap_mu(task), cfg.gap_sigma(task)
-    le = e_mu + e_sig * (RHO_EXEC * z_exec[seq] + math.sqrt(1 - RHO_EXEC ** 2) * rng.standard_normal(n))
+    le = e_mu + e_sig * (cfg.rho_exec * z_exec[seq] + math.sqrt(1 - cfg.rho_exec ** 2) * rng.standard_normal(n))
     exec_ns = np.maximum(1, np.rint(np.exp(le))).astype(np.int64)
-    lg = g_mu + g_sig * (RHO_GAP * z_gap[seq] + math.sqrt(1 - RHO_GAP ** 2) * rng.standard_normal(n))
+    lg = g_mu + g_sig * (cfg.rho_gap * z_gap[seq] + math.sqrt(1 - cfg.rho_gap ** 2) * rng.standard_normal(n))
     gap_ns = np.maximum(0, np.rint(np.exp(lg))).astype(np.int64)
     if cfg.stall_frac > 0:
         u = rng.random(n)

@@ -24,6 +24,9 @@ def small_cases():
         "cfg3_large_3x30000": traces.config(3, n_tasks=3, launches=30000),
         "cfg4_batched_64": traces.config(4, n_tasks=64),                         # full-size scenarios
         "cfg4_batched_small": traces.config(4, n_tasks=40, hp_launches=500, lp_launches=1500),
+        # every launch drawn independently of its Kernel ID (wide value windows per ID), in the shapes the benchmark runs in
+        "cfg4_batched_64_rho0": traces.config(4, n_tasks=64, rho=0.0),
+        "cfg3_large_3x30000_rho0": traces.config(3, n_tasks=3, launches=30000, rho=0.0),
     }
 
 
@@ -241,6 +244,19 @@ def test_mixed_task_shapes_many_scenarios():
     hp, lp = all_pairs(range(len(lens)))
     check_gapfill(prof, d_off, off, o_prof, hp, lp, 100, 0)
     check_gapfill(prof, d_off, off, o_prof, hp, lp, 0, 2000, predictor=binding.FIKIT_PREDICT_MEAN)
+
+
+def test_gapfill_ids_at_an_address_that_is_not_16_byte_aligned():
+    """The IDs may sit at any 8-byte aligned address (a view that starts one element into a buffer)."""
+    cfg = traces.config(4, n_tasks=8200, hp_launches=30, lp_launches=50)      # 4100 scenarios: one lane each
+    rec, off = traces.build(cfg, threads=4)
+    prof, d_off, o_prof = check_profile(rec, off)
+    shifted = torch.empty(prof.ids.numel() + 1, dtype=torch.int64, device=DEV)
+    shifted[1:].copy_(prof.ids)
+    assert shifted[1:].data_ptr() % 16 == 8
+    hp, lp = traces.scenarios(cfg)
+    for pick in (slice(None), slice(0, 50)):                                  # ... and one wave each
+        check_gapfill(prof._replace(ids=shifted[1:]), d_off, off, o_prof, hp[pick], lp[pick], cfg.margin_ns, cfg.min_gap_ns)
 
 
 def test_all_distinct_ids_one_row_per_launch():
