@@ -25,6 +25,7 @@ enum : uint32_t {
   ERR_LP_LIST = 1u << 6,     // priority queues: list offsets not monotone, or a level outside 1..9
   ERR_LP_LIMIT = 1u << 7,    // priority queues: more low-priority tasks or launches in a scenario than supported
   ERR_ROWS = 1u << 8,        // merge: a row in the wrong task, or IDs of a task not strictly ascending
+  ERR_WAIT = 1u << 9,        // a tile of the sort gave up waiting for the tile before it (must not happen)
 };
 
 // Control block at the start of the workspace; cleared by k_clear_ctrl at the start of a call.

@@ -75,8 +75,8 @@ ProfileLayout profile_layout(uint64_t n, uint32_t n_tasks) {
   if (long_tasks > n_tasks) long_tasks = n_tasks;
   L.max_ptiles = n / PT_TILE + long_tasks;
   {
-    // tile histograms of the sort passes; before them the bucket boundaries of the long tasks' tiles live here
-    const uint64_t a = L.max_tiles * 256 * 4, b = L.max_ptiles * PT_ROWS * 2;
+    // digit counts and look-back words of the sort passes; before them the bucket boundaries of the long tasks' tiles live here
+    const uint64_t a = L.max_tiles * (DIGIT_WORDS_PER_TILE * 4 + 256 * 8), b = L.max_ptiles * PT_ROWS * 2;
     L.hist = c.take(a > b ? a : b);
   }
   uint64_t longest = L.max_tiles * 256;
@@ -162,6 +162,7 @@ int status_from_bits(uint32_t bits) {
   if (bits & ERR_BAD_RECORD) return FIKIT_BAD_RECORD;
   if (bits & ERR_UNKNOWN_ID) return FIKIT_UNKNOWN_ID;
   if (bits & ERR_LP_LIMIT) return FIKIT_UNSUPPORTED;
+  if (bits & ERR_WAIT) return FIKIT_HIP_ERROR;
   return FIKIT_OK;
 }
 
@@ -401,21 +402,28 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     // almost always differ in their upper four bytes already, so four passes over those are tried first; the
     // head search below also notices keys that are still out of order, and then all eight passes are run on
     // what the four left (any order of the (key, values) triples is a valid start).
-    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tile_scatter), hipFuncAttributeMaxDynamicSharedMemorySize,
+    FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_onesweep_pass), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   static_cast<int>(sizeof(TileSmem))));
+    uint32_t* digit_counts = hist;                                                    // [tile][DIGIT_WORDS_PER_TILE]
+    unsigned long long* look = reinterpret_cast<unsigned long long*>(ws + L.hist + L.max_tiles * DIGIT_WORDS_PER_TILE * 4);   // [tile][256]
+    uint32_t* tickets = wflag;                                                        // one per task (the long-task path is done with this array)
+    // Four passes over four key bytes, least significant first; each pass is one launch (see sort_kernels.hip.h).
     auto sort_passes = [&](int first_byte) -> int {
       uint64_t *kin = k1, *kout = k2;
       int64_t *ein = e0, *eout = e1, *gin = g0, *gout = g1;
-      for (int pass = first_byte; pass < 8; ++pass) {
-        const int shift = 8 * pass;
-        tr.mark("k_tile_hist");
-        hipLaunchKernelGGL(k_tile_hist, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(256), 0, st, d_task_offsets, n_tasks,
-                           tiles, kin, shift, hist);
-        tr.mark("scan_tile_hist");
-        if (int rc = scan_u32(hist, n_big_tiles * 256, sums, nullptr, st)) return rc;
-        tr.mark("k_tile_scatter");
-        hipLaunchKernelGGL(k_tile_scatter, dim3(static_cast<uint32_t>(n_big_tiles)), dim3(TILE_THREADS), sizeof(TileSmem), st, d_task_offsets,
-                           n_tasks, tiles, hist, shift, kin, kout, ein, eout, gin, gout);
+      const uint32_t nt = static_cast<uint32_t>(n_big_tiles);
+      tr.mark("k_digit_hist");
+      hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_big_tiles * DIGIT_WORDS_PER_TILE, 1024)), dim3(256), 0, st, digit_counts,
+                         n_big_tiles * DIGIT_WORDS_PER_TILE, 0u);
+      hipLaunchKernelGGL(k_digit_hist, dim3(nt), dim3(256), 0, st, d_task_offsets, n_tasks, tiles, kin, first_byte, digit_counts);
+      hipLaunchKernelGGL(k_digit_bases, dim3(n_tasks), dim3(256), 0, st, n_tasks, tiles, digit_counts);
+      for (int pass = 0; pass < SORT_PASSES_PER_ROUND; ++pass) {
+        tr.mark("k_onesweep_pass");
+        hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_big_tiles * 512, 1024)), dim3(256), 0, st, reinterpret_cast<uint32_t*>(look),
+                           n_big_tiles * 512, 0u);
+        hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 1024)), dim3(256), 0, st, tickets, static_cast<uint64_t>(n_tasks), 0u);
+        hipLaunchKernelGGL(k_onesweep_pass, dim3(onesweep_grid(nt)), dim3(TILE_THREADS), sizeof(TileSmem), st, d_task_offsets, n_tasks,
+                           tiles, digit_counts, pass, 8 * (first_byte + pass), nt, tickets, look, kin, kout, ein, eout, gin, gout, ctrl);
         FIKIT_HIP(hipGetLastError());
         uint64_t* tk = kin; kin = kout; kout = tk;
         int64_t* t = ein; ein = eout; eout = t;
@@ -436,7 +444,8 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     if (int rc = find_heads()) return rc;
     if (h.wide) {
       hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, &ctrl->wide, static_cast<uint64_t>(1), 0u);
-      if (int rc = sort_passes(0)) return rc;
+      if (int rc = sort_passes(0)) return rc;   // all eight bytes, least significant first
+      if (int rc = sort_passes(4)) return rc;
       if (int rc = find_heads()) return rc;
       if (h.wide) return FIKIT_HIP_ERROR;   // cannot happen: eight passes sort
     }

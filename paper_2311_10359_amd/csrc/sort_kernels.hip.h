@@ -4,7 +4,14 @@
 // and IDs ascend.
 //
 //   - tasks of at most LEAF records are sorted entirely in LDS by one workgroup (k_leaf_sort);
-//   - longer tasks go through eight passes of  tile histogram -> scan -> LDS-staged scatter.
+//   - longer tasks are sorted one 8-bit digit per pass, a pass being ONE launch over tiles:
+//       k_digit_hist     one read of the keys gives every task's digit counts for four passes at once
+//       k_digit_bases    their exclusive prefix sums = where every digit's bucket starts in the task
+//       k_onesweep_pass  per tile: rank the keys inside the tile (LDS), learn how many keys with each
+//                        digit the task's earlier tiles hold by looking back at what those tiles have
+//                        published (a chained scan: no histogram pass, no scan launches), and move
+//                        (key, execution time, idle time) to its place through LDS so that writes leave
+//                        in runs.
 //
 // Ranking inside a tile uses wavefront ballots: the lanes that hold the same digit find each
 // other with eight ballots, so ranks are stable without sorting.
@@ -238,26 +245,63 @@ k_leaf_sort(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* 
 }
 
 // ------------------------------------------------------------------ multi-pass path
-// Histogram of one tile's digits, stored so that a flat exclusive scan yields scatter offsets:
-// H[(tile_prefix[t] * 256) + d * tiles_t + j_local]  (within a task: digit-major, tile-minor).
+constexpr int SORT_PASSES_PER_ROUND = 4;       // digit counts are taken for this many passes at once
+constexpr uint32_t DIGIT_WORDS_PER_TILE = SORT_PASSES_PER_ROUND * 256 / 2;   // a task on this path has at least two tiles
+
+// Digit counts of four passes (key bytes first_byte .. first_byte + 3) of every task on the multi-pass path:
+// counts[(first tile of the task) * DIGIT_WORDS_PER_TILE + pass * 256 + digit].  The array must be zero.
 __global__ void __launch_bounds__(256)
-k_tile_hist(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix,
-            const uint64_t* __restrict__ keys, int shift, uint32_t* __restrict__ H) {
-  __shared__ uint32_t hist[256];
+k_digit_hist(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix,
+             const uint64_t* __restrict__ keys, int first_byte, uint32_t* __restrict__ counts) {
+  // (a few copies of every counter, one per group of lanes: a frequent key would otherwise serialise a wave on one address)
+  constexpr int COPIES = 8;
+  __shared__ uint32_t hist[SORT_PASSES_PER_ROUND][COPIES][256];
   const uint32_t j = blockIdx.x;
   const uint32_t t = task_of_tile(tile_prefix, n_tasks, j);
   const uint32_t tp = tile_prefix[t];
-  const uint32_t tiles_t = tile_prefix[t + 1] - tp;
-  const uint32_t jl = j - tp;
-  const uint64_t start = off[t] + static_cast<uint64_t>(jl) * TILE;
+  const uint64_t start = off[t] + static_cast<uint64_t>(j - tp) * TILE;
   const uint64_t end = off[t + 1];
   const uint32_t m = static_cast<uint32_t>(end - start < TILE ? end - start : TILE);
-  hist[threadIdx.x] = 0;
+  for (uint32_t x = threadIdx.x; x < SORT_PASSES_PER_ROUND * COPIES * 256; x += 256) (&hist[0][0][0])[x] = 0;
   __syncthreads();
-  for (uint32_t i = threadIdx.x; i < m; i += 256) atomicAdd(&hist[static_cast<uint32_t>(keys[start + i] >> shift) & 0xffu], 1u);
+  const uint32_t copy = threadIdx.x % COPIES;
+  for (uint32_t i = threadIdx.x; i < m; i += 256) {
+    const uint32_t k = static_cast<uint32_t>(keys[start + i] >> (8 * first_byte));
+#pragma unroll
+    for (int p = 0; p < SORT_PASSES_PER_ROUND; ++p) atomicAdd(&hist[p][copy][(k >> (8 * p)) & 0xffu], 1u);
+  }
   __syncthreads();
-  H[static_cast<uint64_t>(tp) * 256 + static_cast<uint64_t>(threadIdx.x) * tiles_t + jl] = hist[threadIdx.x];
+  uint32_t* out = counts + static_cast<uint64_t>(tp) * DIGIT_WORDS_PER_TILE;
+#pragma unroll
+  for (int p = 0; p < SORT_PASSES_PER_ROUND; ++p) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int q = 0; q < COPIES; ++q) c += hist[p][q][threadIdx.x];
+    if (c) atomicAdd(&out[p * 256 + threadIdx.x], c);
+  }
 }
+
+// Turns every task's digit counts into exclusive prefix sums, pass by pass (one workgroup per task).
+__global__ void __launch_bounds__(256)
+k_digit_bases(uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix, uint32_t* __restrict__ counts) {
+  __shared__ uint32_t aux[8];
+  const uint32_t t = blockIdx.x;
+  if (t >= n_tasks || tile_prefix[t + 1] == tile_prefix[t]) return;
+  uint32_t* c = counts + static_cast<uint64_t>(tile_prefix[t]) * DIGIT_WORDS_PER_TILE;
+  for (int p = 0; p < SORT_PASSES_PER_ROUND; ++p) {
+    uint32_t total;
+    const uint32_t before = block_excl_scan_256(c[p * 256 + threadIdx.x], aux, total);
+    c[p * 256 + threadIdx.x] = before;
+  }
+}
+
+// What a tile publishes per digit for the tiles after it: first how many keys with the digit it holds itself, later how
+// many the task holds up to and including it.  The state sits in the top two bits, the count below.
+constexpr unsigned long long LOOK_EMPTY = 0ull, LOOK_OWN = 1ull << 62, LOOK_UPTO = 2ull << 62, LOOK_COUNT = (1ull << 62) - 1;
+constexpr uint32_t LOOK_SPIN_LIMIT = 1u << 24;   // fruitless polls before a tile gives up (seconds; never reached)
+constexpr uint32_t LOOK_BATCH = 8;               // earlier tiles looked at per round trip (registers: two per tile)
+constexpr uint32_t ONESWEEP_SPREAD = 64;         // neighbouring workgroups of a pass work this many tile ranges apart
+__host__ __device__ inline uint32_t onesweep_grid(uint32_t n_tiles) { return ((n_tiles + ONESWEEP_SPREAD - 1) / ONESWEEP_SPREAD) * ONESWEEP_SPREAD; }
 
 struct TileSmem {
   uint64_t stage[TILE];
@@ -266,24 +310,39 @@ struct TileSmem {
   uint32_t aux[8];
 };
 
-// Stable scatter of one tile by the current digit.  Hs is H after the exclusive scan.
-__global__ void __launch_bounds__(TILE_THREADS)
-k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix,
-               const uint32_t* __restrict__ Hs, int shift, const uint64_t* __restrict__ key_in, uint64_t* __restrict__ key_out,
-               const int64_t* __restrict__ exec_in, int64_t* __restrict__ exec_out,
-               const int64_t* __restrict__ gap_in, int64_t* __restrict__ gap_out) {
+// One pass of the sort over one tile: stable scatter by the digit at `shift`.
+//   ticket    [n_tasks] zero when the pass starts.  A workgroup is sent to a task by its number (spread so that
+//             workgroups that start together work on different tasks: a task's tiles depend on one another, the tasks
+//             do not), and takes the task's next tile from the task's counter.  So every tile a tile waits for was
+//             taken earlier, by a workgroup that is already running: the waits always end.  Launch
+//             onesweep_grid(n_tiles) workgroups.
+//   bases     k_digit_bases' output; `pass` names the digit's row in it.
+//   look      [n_tiles][256] words, zero (LOOK_EMPTY) when the pass starts.
+// A tile that has polled a word LOOK_SPIN_LIMIT times sets ERR_WAIT, publishes zeros and leaves without writing; tiles
+// that see ERR_WAIT leave too, and no key is ever written outside its task: the call then fails, nothing hangs.
+__global__ void __launch_bounds__(TILE_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8)))   // (two workgroups per compute unit)
+k_onesweep_pass(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix,
+                const uint32_t* __restrict__ bases, int pass, int shift, uint32_t n_tiles, uint32_t* __restrict__ ticket,
+                unsigned long long* __restrict__ look, const uint64_t* __restrict__ key_in, uint64_t* __restrict__ key_out,
+                const int64_t* __restrict__ exec_in, int64_t* __restrict__ exec_out,
+                const int64_t* __restrict__ gap_in, int64_t* __restrict__ gap_out, Ctrl* ctrl) {
   extern __shared__ __align__(16) unsigned char tile_raw[];
   TileSmem& sm = *reinterpret_cast<TileSmem*>(tile_raw);
-  const uint32_t j = blockIdx.x;
-  const uint32_t t = task_of_tile(tile_prefix, n_tasks, j);
+  const uint32_t tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const uint32_t per = (n_tiles + ONESWEEP_SPREAD - 1) / ONESWEEP_SPREAD;
+  const uint32_t home = (blockIdx.x % ONESWEEP_SPREAD) * per + blockIdx.x / ONESWEEP_SPREAD;   // a tile of the task to work on
+  if (home >= n_tiles) return;
+  const uint32_t t = task_of_tile(tile_prefix, n_tasks, home);
   const uint32_t tp = tile_prefix[t];
-  const uint32_t tiles_t = tile_prefix[t + 1] - tp;
-  const uint32_t jl = j - tp;
+  if (tid == 0) sm.aux[7] = atomicAdd(&ticket[t], 1u);
+  __syncthreads();
+  const uint32_t jl = sm.aux[7];   // (below the task's number of tiles: as many workgroups are sent to a task as it has tiles)
+  const uint32_t j = tp + jl;
   const uint64_t task_start = off[t];
   const uint64_t start = task_start + static_cast<uint64_t>(jl) * TILE;
   const uint64_t end = off[t + 1];
   const uint32_t m = static_cast<uint32_t>(end - start < TILE ? end - start : TILE);
-  const uint32_t tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+
   for (uint32_t d = lane; d < 256; d += WAVE) sm.cnt[w][d] = 0;
   __builtin_amdgcn_wave_barrier();
 
@@ -300,11 +359,52 @@ k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_
     const uint32_t pos = wave_base + r * WAVE + lane;
     rk[r] = wave_rank_digit(static_cast<uint32_t>(k[r] >> shift) & 0xffu, pos < m, sm.cnt[w]);
   }
-  tile_digit_offsets<TILE_WAVES>(sm.cnt, sm.aux, nullptr);
+  tile_digit_offsets<TILE_WAVES>(sm.cnt, sm.aux, sm.gdst);   // gdst[d] = this tile's count of digit d, for now
   if (tid < 256) {
+    const uint32_t own = sm.gdst[tid];
     const uint32_t ls = sm.cnt[0][tid];  // wave 0's start of digit tid == the digit's local start
-    const uint64_t hbase = static_cast<uint64_t>(tp) * 256;
-    const uint32_t rel = Hs[hbase + static_cast<uint64_t>(tid) * tiles_t + jl] - Hs[hbase];
+    unsigned long long* mine = look + static_cast<uint64_t>(j) * 256 + tid;
+    unsigned long long before = 0;   // keys with this digit in the task's earlier tiles
+    bool gave_up = false;
+    if (jl > 0) {
+      // (the words carry their whole message themselves, count and state in one: no ordering with other memory is needed)
+      __hip_atomic_store(mine, LOOK_OWN | own, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // The task's earlier tiles are looked at LOOK_BATCH at a time (independent loads, one round trip), nearest first:
+      // own counts add up until a tile is met that already knows the count up to itself.
+      uint32_t back = 1, polls = 0;
+      bool done = false;
+      while (!done && back <= jl) {
+        const uint32_t n = jl - back + 1 < LOOK_BATCH ? jl - back + 1 : LOOK_BATCH;
+        unsigned long long v[LOOK_BATCH];
+#pragma unroll
+        for (uint32_t i = 0; i < LOOK_BATCH; ++i)
+          v[i] = i < n ? __hip_atomic_load(look + static_cast<uint64_t>(j - back - i) * 256 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                       : LOOK_EMPTY;
+        uint32_t used = 0;
+#pragma unroll
+        for (uint32_t i = 0; i < LOOK_BATCH; ++i) {
+          if (!done && used == i && i < n) {
+            const unsigned long long state = v[i] & ~LOOK_COUNT;
+            if (state != LOOK_EMPTY) {
+              before += v[i] & LOOK_COUNT;
+              ++used;
+              done = state == LOOK_UPTO;
+            }
+          }
+        }
+        back += used;
+        if (used == 0) {   // the nearest tile not yet looked at has published nothing so far
+          if (++polls >= LOOK_SPIN_LIMIT) { gave_up = true; break; }
+          __builtin_amdgcn_s_sleep(1);
+        }
+      }
+    }
+    if (gave_up) {
+      atomicOr(&ctrl->status, ERR_WAIT);
+      before = 0;
+    }
+    __hip_atomic_store(mine, LOOK_UPTO | ((before + own) & LOOK_COUNT), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t rel = bases[static_cast<uint64_t>(tp) * DIGIT_WORDS_PER_TILE + pass * 256 + tid] + static_cast<uint32_t>(before);
     sm.gdst[tid] = static_cast<uint32_t>(task_start) + rel - ls;  // modulo 2^32; positions fit 32 bits
   }
   uint32_t lpos[TILE_KPT];
@@ -315,16 +415,23 @@ k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_
     if (pos < m) sm.stage[lpos[r]] = k[r];
   }
   __syncthreads();
+  // (a thread of this workgroup that gave up set the bit before the barrier; a tile that does not see another tile's
+  // bit yet writes inside its own task only)
+  if (tid == 0) sm.aux[6] = __hip_atomic_load(&ctrl->status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ERR_WAIT;
+  __syncthreads();
+  if (sm.aux[6]) return;   // (the same decision for the whole workgroup)
+  const uint32_t lo32 = static_cast<uint32_t>(task_start), hi32 = static_cast<uint32_t>(end);
   // keys leave in sorted order: consecutive threads write consecutive addresses inside a digit run
   uint32_t dst[TILE_KPT];
 #pragma unroll
   for (int r = 0; r < TILE_KPT; ++r) {
     const uint32_t i = tid + r * TILE_THREADS;
-    dst[r] = 0;
+    dst[r] = hi32;
     if (i < m) {
       const uint64_t kk = sm.stage[i];
       dst[r] = sm.gdst[static_cast<uint32_t>(kk >> shift) & 0xffu] + i;
-      key_out[dst[r]] = kk;
+      if (dst[r] < lo32 || dst[r] >= hi32) dst[r] = hi32;   // (cannot happen; a place outside the task is never written)
+      if (dst[r] != hi32) key_out[dst[r]] = kk;
     }
   }
   __syncthreads();
@@ -338,7 +445,7 @@ k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_
 #pragma unroll
   for (int r = 0; r < TILE_KPT; ++r) {
     const uint32_t i = tid + r * TILE_THREADS;
-    if (i < m) exec_out[dst[r]] = static_cast<int64_t>(sm.stage[i]);
+    if (i < m && dst[r] != hi32) exec_out[dst[r]] = static_cast<int64_t>(sm.stage[i]);
   }
   __syncthreads();
   // payload 2: idle time
@@ -351,7 +458,7 @@ k_tile_scatter(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_
 #pragma unroll
   for (int r = 0; r < TILE_KPT; ++r) {
     const uint32_t i = tid + r * TILE_THREADS;
-    if (i < m) gap_out[dst[r]] = static_cast<int64_t>(sm.stage[i]);
+    if (i < m && dst[r] != hi32) gap_out[dst[r]] = static_cast<int64_t>(sm.stage[i]);
   }
 }
 

@@ -388,8 +388,7 @@ def test_general_path_ids_that_share_their_upper_half():
     binding.fikit_trace_enable(True)
     try:
         check_profile(rec, np.array([0, n, n + 50], dtype=np.uint64))
-        passes = binding.fikit_trace_read()["k_tile_scatter"][1]
+        passes = binding.fikit_trace_read()["k_onesweep_pass"][1]
     finally:
         binding.fikit_trace_enable(False)
-    # (one more pass belongs to the partition by the top ID bits that was tried first)
-    assert passes in (12, 13), f"{passes} scatter passes: the four-pass sort was not followed by the full one"
+    assert passes == 12, f"{passes} sort passes: the four-pass sort was not followed by the full one"
