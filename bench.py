@@ -59,9 +59,10 @@ def stored_counters(workload):
     except (OSError, ValueError):
         log(f"[bench] no stored HBM counters ({TRAFFIC_FILE}): roofline.traffic and hbm_by_call are left out")
         return None
-    if data.get("workload") != workload:
-        log(f"[bench] stored HBM counters are of workload {data.get('workload')!r}, not {workload!r}: traffic left out")
+    if workload not in data.get("workloads", {}):
+        log(f"[bench] stored HBM counters cover {sorted(data.get('workloads', {}))}, not {workload!r}: traffic left out")
         return None
+    data = data["workloads"][workload]
     if data.get("source_hash") != source_hash():
         log(f"[bench] stored HBM counters are of library sources {data.get('source_hash')}, these are {source_hash()}: "
             "the kernels have changed since the counters were taken, traffic left out (null)")

@@ -3,14 +3,17 @@
 A measurement aid beside bench.py: nothing in the library or its binding uses it.  Three sub-commands:
 
   python -m paper_2311_10359_amd.profile_summary ktrace <k_kernel_stats.csv> <out.txt> --cmd "..." [--note "..."]
-      per kernel: calls, total and average duration, share of device time (rocprofv3 --kernel-trace --stats)
+                                                     [--trace <k_kernel_trace.csv>]
+      per kernel: calls, total and average duration, share of device time (rocprofv3 --kernel-trace --stats);
+      with --trace also the duration of the 1 GiB calibration copy (bench.py --calibration-copy), the longest
+      copy kernel of the run, and the bandwidth it stands for
 
   python -m paper_2311_10359_amd.profile_summary hbm <fetch.csv> <write.csv> <out.txt> --cmd "..." --workload NAME
                                                      [--json profiles/hbm_traffic.json]
       HBM bytes per kernel and dispatch from two counter runs (FETCH_SIZE in one, WRITE_SIZE in the other; KiB
       per dispatch), each scaled by what the same counter reads for a plain 1 GiB device-to-device copy in the
-      same run (bench.py --calibration-copy).  With --json also writes the per-kernel bytes, tagged with a hash
-      of the library sources, for bench.py to quote.
+      same run (bench.py --calibration-copy).  With --json also stores the per-kernel bytes under the
+      workload's name, tagged with a hash of the library sources, for bench.py to quote.
 
   python -m paper_2311_10359_amd.profile_summary pmc <counter_collection.csv> [<more.csv> ...] <out.txt> --cmd "..."
                                                      [--kernels substring,substring]
@@ -56,6 +59,13 @@ def ktrace(args) -> None:
         for r in rows:
             f.write(f"{short_name(r['Name'])[:66]:66s} {int(r['Calls']):6d} {float(r['TotalDurationNs']) / 1e3:14.1f} "
                     f"{float(r['AverageNs']) / 1e3:12.1f} {float(r['Percentage']):7.2f}\n")
+        if args.trace:
+            copies = [int(r["End_Timestamp"]) - int(r["Start_Timestamp"]) for r in csv.DictReader(open(args.trace))
+                      if "copyBuffer" in r["Kernel_Name"]]
+            if copies:
+                ns = max(copies)
+                f.write(f"\nplain device-to-device copy of 1 GiB (the longest copy kernel of the run): {ns / 1e3:.1f} us = "
+                        f"{2 * (1 << 30) / ns / 1e3:.2f} TB/s read + written\n")
     print(open(out).read())
 
 
@@ -118,8 +128,14 @@ def hbm(args) -> None:
                     f"{total_r / 1e9:.2f} GB read + {total_w / 1e9:.2f} GB written = {(total_r + total_w) / 1e9:.2f} GB\n")
     print(open(out).read())
     if args.json:
-        json.dump({"workload": args.workload, "source_hash": source_hash(), "fetch_scale": ff, "write_scale": fw,
-                   "summary": os.path.relpath(out, ROOT), "kernels": kernels}, open(args.json, "w"), indent=1)
+        try:
+            stored = json.load(open(args.json))
+        except (OSError, ValueError):
+            stored = {}
+        stored.setdefault("workloads", {})[args.workload] = {
+            "source_hash": source_hash(), "fetch_scale": ff, "write_scale": fw,
+            "summary": os.path.relpath(os.path.abspath(out), ROOT), "kernels": kernels}
+        json.dump({"workloads": stored["workloads"]}, open(args.json, "w"), indent=1)
         print("wrote", args.json)
 
 
@@ -170,6 +186,7 @@ def main() -> None:
     ap.add_argument("--workload", default="")
     ap.add_argument("--json", default="")
     ap.add_argument("--kernels", default="")
+    ap.add_argument("--trace", default="", help="ktrace: the run's k_kernel_trace.csv")
     ap.add_argument("--calls", type=int, default=0, help="hbm: calls of the library in the run (warm-up + steps), for the per-call total")
     args = ap.parse_args()
     {"ktrace": ktrace, "hbm": hbm, "pmc": pmc}[args.what](args)
