@@ -697,7 +697,7 @@ k_task_fused(const FusedArgs A) {
     const uint32_t i = r * NT + tid;
     if (i < m) {
       uint32_t j = sl[r];
-      asm volatile("" : "+v"(j));
+      asm volatile("" : "+v"(j));  // (an opaque copy: keeps the address arithmetic inside the loop, out of registers that live across it)
       const uint2 se = sel[j];
       const uint32_t de = (scale_of(ev[r]) - se.x) >> sel_shift(se.y);
       atomicAdd(&sm.u.hist[__umul24(de >> 1, PS) + j], (de & 1u) ? 0x10000u : 1u);
@@ -810,7 +810,7 @@ k_task_fused(const FusedArgs A) {
         const uint32_t i = r * NT + tid;
         if (i < m) {
           uint32_t j = sl[r];
-          asm volatile("" : "+v"(j));
+          asm volatile("" : "+v"(j));  // (as above)
           const uint2 se = sel[j];
           if (se.y & SEL_LISTED) {
             const uint32_t de = (scale_of(ev[r]) - se.x) >> sel_shift(se.y), b50 = sel_b50(se.y), b95 = sel_b95(se.y);

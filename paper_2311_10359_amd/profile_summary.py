@@ -28,19 +28,24 @@ import csv
 import hashlib
 import json
 import os
+import re
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 GIB_IN_KIB = 1 << 20
 
 
 def source_hash() -> str:
-    """Hash of the library sources: tells whether stored counter readings still describe the library as it stands."""
+    """Hash of the library sources without their comments and white space: tells whether stored counter readings
+    still describe the code of the library as it stands."""
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2311_10359_amd", "csrc")
     for name in sorted(os.listdir(d)):
         if name.endswith((".h", ".hip")):
+            text = open(os.path.join(d, name), encoding="utf-8").read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            text = re.sub(r"//[^\n]*", "", text)
             h.update(name.encode())
-            h.update(open(os.path.join(d, name), "rb").read())
+            h.update("".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 
