@@ -389,6 +389,16 @@ const char* fikit_status_string(int status);
 int fikit_version(void);
 
 /*
+ * Bounded waits.  The sort that fikit_profile falls back on for tasks with too many distinct Kernel IDs lets a tile of
+ * a task wait for what the task's earlier tiles publish (statistical result 1 of Section 3.2 is the grouping this sort
+ * performs).  Every such wait is bounded: after `polls` fruitless polls of one word (default 2^24, seconds) the tile
+ * gives up, nothing is written outside the task, every kernel still ends, and the call returns FIKIT_HIP_ERROR instead
+ * of hanging.  fikit_set_wait_limit sets the bound for later calls (0 restores the default); a tiny bound makes the
+ * failure path testable from the host.  Process-wide, not thread safe.
+ */
+void fikit_set_wait_limit(uint32_t polls);
+
+/*
  * Per-kernel timing, a measurement aid (off by default; process-wide, not thread safe).
  * fikit_trace_enable(1) clears the table and makes every later fikit_profile / fikit_gapfill
  * call record a HIP event on its stream before each kernel launch; when the call ends, the time

@@ -31,7 +31,8 @@ FIKIT_PREDICT_P50, FIKIT_PREDICT_MEAN = 0, 1
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
            "fikit_gapfill", "fikit_gapfill_static", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
            "fikit_gapfill_replay", "fikit_prio_fill_workspace_bytes", "fikit_prio_fill", "fikit_pairing_workspace_bytes",
-           "fikit_pairing_best", "fikit_profile_merge_workspace_bytes", "fikit_profile_merge", "fikit_status_string", "fikit_version", "fikit_trace_enable", "fikit_trace_read")
+           "fikit_pairing_best", "fikit_profile_merge_workspace_bytes", "fikit_profile_merge", "fikit_status_string", "fikit_version", "fikit_set_wait_limit",
+           "fikit_trace_enable", "fikit_trace_read")
 
 # Layout of a profile row as seen from numpy (128 bytes; see fikit_row in fikit.h).
 STATS_DTYPE = np.dtype([("count", "<u8"), ("sum", "<u8"), ("min", "<i8"), ("max", "<i8"),
@@ -113,6 +114,8 @@ def load() -> ctypes.CDLL:
         lib.fikit_status_string.argtypes = [ctypes.c_int]
         lib.fikit_version.restype = ctypes.c_int
         lib.fikit_version.argtypes = []
+        lib.fikit_set_wait_limit.restype = None
+        lib.fikit_set_wait_limit.argtypes = [ctypes.c_uint32]
         lib.fikit_trace_enable.restype = None
         lib.fikit_trace_enable.argtypes = [ctypes.c_int]
         lib.fikit_trace_read.restype = ctypes.c_int
@@ -124,6 +127,10 @@ def load() -> ctypes.CDLL:
 
 def status_string(status: int) -> str:
     return load().fikit_status_string(status).decode()
+
+
+def fikit_set_wait_limit(polls: int) -> None:
+    load().fikit_set_wait_limit(polls)
 
 
 def fikit_trace_enable(on: bool) -> None:

@@ -120,6 +120,7 @@ constexpr int TRACE_MAX_MARKS = 192;
 constexpr int TRACE_MAX_NAMES = 48;
 struct TraceEntry { const char* name; double ms; int launches; };
 bool g_trace_on = false;
+uint32_t g_wait_limit = LOOK_SPIN_LIMIT;   // fikit_set_wait_limit
 TraceEntry g_trace[TRACE_MAX_NAMES];
 int g_trace_n = 0;
 
@@ -190,6 +191,8 @@ int launch_prio_walk(hipStream_t st, const uint64_t* off, const uint32_t* hp_tas
 extern "C" {
 
 int fikit_version(void) { return 1; }
+
+void fikit_set_wait_limit(uint32_t polls) { g_wait_limit = polls ? polls : LOOK_SPIN_LIMIT; }
 
 void fikit_trace_enable(int on) {
   g_trace_on = on != 0;
@@ -423,7 +426,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
                            n_big_tiles * 512, 0u);
         hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 1024)), dim3(256), 0, st, tickets, static_cast<uint64_t>(n_tasks), 0u);
         hipLaunchKernelGGL(k_onesweep_pass, dim3(onesweep_grid(nt)), dim3(TILE_THREADS), sizeof(TileSmem), st, d_task_offsets, n_tasks,
-                           tiles, digit_counts, pass, 8 * (first_byte + pass), nt, tickets, look, kin, kout, ein, eout, gin, gout, ctrl);
+                           tiles, digit_counts, pass, 8 * (first_byte + pass), nt, tickets, look, kin, kout, ein, eout, gin, gout, g_wait_limit, ctrl);
         FIKIT_HIP(hipGetLastError());
         uint64_t* tk = kin; kin = kout; kout = tk;
         int64_t* t = ein; ein = eout; eout = t;
@@ -437,7 +440,8 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
       hipLaunchKernelGGL(k_popcount_words, dim3(blocks_for(L.n_words, 256)), dim3(256), 0, st, bits, L.n_words, word_prefix);
       if (int rc = scan_u32(word_prefix, L.n_words, sums, &ctrl->n_heads, st)) return rc;
       tr.mark("host_sync");
-      return read_ctrl(ctrl, &h, st);
+      if (int rc = read_ctrl(ctrl, &h, st)) return rc;
+      return status_from_bits(h.status);   // (a wait of the sort that ran out)
     };
     if (n_big_tiles > 0)
       if (int rc = sort_passes(4)) return rc;

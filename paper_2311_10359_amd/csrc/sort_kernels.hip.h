@@ -298,7 +298,7 @@ k_digit_bases(uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix, uint32
 // What a tile publishes per digit for the tiles after it: first how many keys with the digit it holds itself, later how
 // many the task holds up to and including it.  The state sits in the top two bits, the count below.
 constexpr unsigned long long LOOK_EMPTY = 0ull, LOOK_OWN = 1ull << 62, LOOK_UPTO = 2ull << 62, LOOK_COUNT = (1ull << 62) - 1;
-constexpr uint32_t LOOK_SPIN_LIMIT = 1u << 24;   // fruitless polls before a tile gives up (seconds; never reached)
+constexpr uint32_t LOOK_SPIN_LIMIT = 1u << 24;   // default number of fruitless polls before a tile gives up (seconds; never reached)
 constexpr uint32_t LOOK_BATCH = 8;               // earlier tiles looked at per round trip (registers: two per tile)
 constexpr uint32_t ONESWEEP_SPREAD = 64;         // neighbouring workgroups of a pass work this many tile ranges apart
 __host__ __device__ inline uint32_t onesweep_grid(uint32_t n_tiles) { return ((n_tiles + ONESWEEP_SPREAD - 1) / ONESWEEP_SPREAD) * ONESWEEP_SPREAD; }
@@ -318,14 +318,14 @@ struct TileSmem {
 //             onesweep_grid(n_tiles) workgroups.
 //   bases     k_digit_bases' output; `pass` names the digit's row in it.
 //   look      [n_tiles][256] words, zero (LOOK_EMPTY) when the pass starts.
-// A tile that has polled a word LOOK_SPIN_LIMIT times sets ERR_WAIT, publishes zeros and leaves without writing; tiles
+// A tile that has polled a word spin_limit times in vain sets ERR_WAIT, publishes zeros and leaves without writing; tiles
 // that see ERR_WAIT leave too, and no key is ever written outside its task: the call then fails, nothing hangs.
 __global__ void __launch_bounds__(TILE_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8)))   // (two workgroups per compute unit)
 k_onesweep_pass(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ tile_prefix,
                 const uint32_t* __restrict__ bases, int pass, int shift, uint32_t n_tiles, uint32_t* __restrict__ ticket,
                 unsigned long long* __restrict__ look, const uint64_t* __restrict__ key_in, uint64_t* __restrict__ key_out,
                 const int64_t* __restrict__ exec_in, int64_t* __restrict__ exec_out,
-                const int64_t* __restrict__ gap_in, int64_t* __restrict__ gap_out, Ctrl* ctrl) {
+                const int64_t* __restrict__ gap_in, int64_t* __restrict__ gap_out, uint32_t spin_limit, Ctrl* ctrl) {
   extern __shared__ __align__(16) unsigned char tile_raw[];
   TileSmem& sm = *reinterpret_cast<TileSmem*>(tile_raw);
   const uint32_t tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
@@ -394,7 +394,7 @@ k_onesweep_pass(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32
         }
         back += used;
         if (used == 0) {   // the nearest tile not yet looked at has published nothing so far
-          if (++polls >= LOOK_SPIN_LIMIT) { gave_up = true; break; }
+          if (++polls >= spin_limit) { gave_up = true; break; }
           __builtin_amdgcn_s_sleep(1);
         }
       }

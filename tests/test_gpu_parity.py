@@ -392,3 +392,39 @@ def test_general_path_ids_that_share_their_upper_half():
     finally:
         binding.fikit_trace_enable(False)
     assert passes == 12, f"{passes} sort passes: the four-pass sort was not followed by the full one"
+
+
+@pytest.mark.gpu
+def test_a_wait_of_the_sort_that_runs_out_is_an_error_not_a_hang():
+    """The sort of the general path lets tiles wait for earlier tiles of their task, with a bound.  With the bound set
+    to a single poll from the host, tiles give up: every kernel still ends, the call reports HIP_ERROR, and with the
+    default bound restored the same input is profiled correctly."""
+    rng = np.random.default_rng(11)
+    n_tasks, per_task, n_ids = 8, 200_000, 700
+    cand = np.zeros(n_ids, dtype=traces.LAUNCH_DTYPE)
+    cand["name_id"] = rng.permutation(1 << 20)[:n_ids]
+    cand["grid"] = rng.integers(1, 2**16, (n_ids, 3))
+    cand["block"] = rng.integers(1, 1025, (n_ids, 3))
+    n = n_tasks * per_task
+    pick = rng.integers(0, n_ids, n)
+    pick[rng.random(n) < 0.3] = 7                       # one ID too frequent for a workgroup: the tasks are sorted
+    rec = cand[pick]
+    ex = rng.integers(1, 50000, n)
+    gp = rng.integers(0, 30000, n)
+    start = np.cumsum(ex + gp) - (ex + gp)
+    rec["start_ns"], rec["end_ns"] = start, start + ex
+    off = np.arange(n_tasks + 1, dtype=np.uint64) * np.uint64(per_task)
+    statuses = []
+    try:
+        for _ in range(3):
+            binding.fikit_set_wait_limit(1)
+            try:
+                run_profile_gpu(rec, off)
+                statuses.append(0)
+            except binding.FikitError as e:
+                statuses.append(e.status)
+    finally:
+        binding.fikit_set_wait_limit(0)
+    assert set(statuses) <= {0, -6}, statuses
+    assert -6 in statuses, f"no wait ran out in three calls with a bound of one poll: {statuses}"
+    check_profile(rec, off)
