@@ -548,7 +548,8 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
   int64_t t_open = 0;                // predicted time line of the high-priority task
   int64_t cur_open = 0, completion;
   uint64_t consumed = 0;
-  uint32_t c = 0, f = 0, rem = 0;
+  uint32_t rem = 0, rem_open = 0;    // what is left of the open gap's budget; the budget it opened with
+  uint32_t lp_open = l0;             // position in the queue when the gap opened
   uint32_t ga = 0;                   // replay: the idle time that occurred after the launch whose gap is open
   int64_t delay = 0;                 // replay: by how much issued kernels ran past the gaps so far
   // a gap is used if it is at least min_gap and at least the margin long (32-bit idle times are below WIDE32)
@@ -557,8 +558,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
   const uint32_t margin32 = margin >= static_cast<int64_t>(WIDE32) ? WIDE32 : static_cast<uint32_t>(margin);
   bool in_gap = false;
   bool pending = false;               // a gap has closed and its result (c, f) is not staged yet
-  bool done = valid && (lp_end == l0);     // the whole queue has been issued
-  bool finished = !valid || done;          // nothing left to step through (remaining gaps, if any, get zeros)
+  bool finished = !valid || lp_end == l0;  // nothing left to step through (remaining gaps, if any, get zeros)
 
   for (;;) {
     // ---- once per period: park what was read, read on, write complete groups of results ----
@@ -624,9 +624,23 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     // high-priority launch and open its gap; LW_TRIES times try the head of the queue }.  Written
     // without branches; a lane whose ring is empty, or whose gap is still open when a new one could be
     // taken, simply idles in that sub-step. ----
+    // The head of the queue and the entry after it are held in registers, so that a try does not wait for the LDS:
+    // the entry that becomes the next one is read a try ahead.  (An entry beyond what has landed is garbage and is
+    // never used: tries look at positions below lp_landed only, and both registers are read afresh every period,
+    // which is when entries land.)
+    uint32_t d0 = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid], d1 = sm.lp[(lp_pos + 1) & (LW_LP_CAP - 1)][tid];
+    const uint32_t lp_lim = lp_landed < lp_end ? lp_landed : lp_end;   // tries look at entries below this
 #pragma unroll
     for (uint32_t o = 0; o < LW_OPENS; ++o) {
       {
+        // the whole queue has been issued (noticed here, not in the tries): the open gap is its last, cur_open and f
+        // stay as they are from here on
+        const bool emptied = in_gap && lp_pos == lp_end;
+        pending = pending || emptied;
+        in_gap = in_gap && !emptied;
+        finished = finished || emptied;
+        // what the gap that is open, or has just closed, took: the tries only move lp_pos and rem
+        const uint32_t c = lp_pos - lp_open, f = rem_open - rem;
         // (a staging slot that is written early is simply written again)
         sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
         sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
@@ -656,32 +670,29 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         g += skip ? 1u : 0u;
         in_gap = in_gap || usable;
         rem = usable ? G - margin32 : rem;
-        c = usable ? 0u : c;
-        f = usable ? 0u : f;
+        rem_open = usable ? rem : rem_open;
+        lp_open = usable ? lp_pos : lp_open;
         finished = finished || at_end || last;
       }
 #pragma unroll
       for (uint32_t k = 0; k < LW_TRIES; ++k) {
         // in a gap: does the head of the queue fit into what is left?
-        const uint32_t d = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid];
-        const bool tryq = in_gap && lp_pos < lp_landed;
+        const bool tryq = in_gap && lp_pos < lp_lim;
         // (with feedback: the next high-priority request has arrived once the time filled reaches the actual gap)
-        const bool fits = tryq && d <= rem && (MODE != LW_REPLAY_FEEDBACK || f < ga);
-        const uint32_t dd = fits ? d : 0u;
-        rem -= dd; f += dd;
-        c += fits ? 1u : 0u;
+        const bool fits = tryq && d0 <= rem && (MODE != LW_REPLAY_FEEDBACK || rem_open - rem < ga);
+        rem -= fits ? d0 : 0u;
         lp_pos += fits ? 1u : 0u;
-        const bool emptied = fits && lp_pos == lp_end;          // the whole queue has been issued
-        const bool close = (tryq && !fits) || emptied;
+        d0 = fits ? d1 : d0;
+        d1 = sm.lp[(lp_pos + 1) & (LW_LP_CAP - 1)][tid];
+        const bool close = tryq && !fits;      // the head does not fit: the gap is closed
         pending = pending || close;
-        done = done || emptied;          // (cur_open and f stay as they are from here on)
-        finished = finished || emptied;
         in_gap = in_gap && !close;
       }
     }
   }
 
   if (!valid) return;
+  const uint32_t c = lp_pos - lp_open, f = rem_open - rem;   // of the last gap that was opened
   if (pending) {
     sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
     sm.out_f[g & (LW_OUT_CAP - 1)][tid] = f;
@@ -702,6 +713,7 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     }
   }
   for (; z < g_end; ++z) { fill_count[z] = 0; filled_ns[z] = 0; }
+  const bool done = lp_pos == lp_end;      // the whole queue has been issued, the last of it into the gap at cur_open
   completion = done ? cur_open + static_cast<int64_t>(f) : t_open + static_cast<int64_t>(total_lp - consumed);
   completion_out[s] = MODE == LW_PLAN ? completion : delay;
   placed_out[s] = lp_pos - l0;
