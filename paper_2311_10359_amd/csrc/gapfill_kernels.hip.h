@@ -482,9 +482,13 @@ constexpr uint32_t LW_OPENS = 4, LW_TRIES = 4;     // per period (between two ro
 constexpr uint32_t LW_LP_CHUNK = 16, LW_LP_CAP = 32;   // low-priority ring: entries read at a time, capacity
 constexpr uint32_t LW_HP_CHUNK = 8, LW_HP_CAP = 16;    // high-priority ring
 constexpr uint32_t LW_OUT_CHUNK = 8, LW_OUT_CAP = 32;  // staged results
+// The first rows of the low-priority ring are kept a second time behind its last row, so that the LW_TRIES entries
+// from any position on are consecutive rows (one address, constant offsets).
+constexpr uint32_t LW_LP_MIRROR = LW_TRIES - 1;
+static_assert(LW_LP_MIRROR < LW_LP_CHUNK, "the rows that are mirrored land together");
 
 struct LaneWalkSmem {   // [entry][lane]: a lane's entries fall on one bank whatever position it is at
-  uint32_t lp[LW_LP_CAP][LW_THREADS];
+  uint32_t lp[LW_LP_CAP + LW_LP_MIRROR][LW_THREADS];
   uint32_t hp_e[LW_HP_CAP][LW_THREADS];
   uint32_t hp_g[LW_HP_CAP][LW_THREADS];
   uint32_t out_c[LW_OUT_CAP][LW_THREADS];
@@ -576,7 +580,12 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const uint32_t at = (lp_req + 4 * k) & (LW_LP_CAP - 1);
-        sm.lp[at][tid] = lr[k].x; sm.lp[at + 1][tid] = lr[k].y; sm.lp[at + 2][tid] = lr[k].z; sm.lp[at + 3][tid] = lr[k].w;
+        const uint32_t v[4] = {lr[k].x, lr[k].y, lr[k].z, lr[k].w};
+#pragma unroll
+        for (uint32_t i = 0; i < 4; ++i) {
+          sm.lp[at + i][tid] = v[i];
+          if (at + i < LW_LP_MIRROR) sm.lp[LW_LP_CAP + at + i][tid] = v[i];
+        }
       }
       lp_landed = lp_req + LW_LP_CHUNK;
       lp_fly = false;
@@ -624,14 +633,13 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     // high-priority launch and open its gap; LW_TRIES times try the head of the queue }.  Written
     // without branches; a lane whose ring is empty, or whose gap is still open when a new one could be
     // taken, simply idles in that sub-step. ----
-    // The head of the queue and the entry after it are held in registers, so that a try does not wait for the LDS:
-    // the entry that becomes the next one is read a try ahead.  (An entry beyond what has landed is garbage and is
-    // never used: tries look at positions below lp_landed only, and both registers are read afresh every period,
-    // which is when entries land.)
-    uint32_t d0 = sm.lp[lp_pos & (LW_LP_CAP - 1)][tid], d1 = sm.lp[(lp_pos + 1) & (LW_LP_CAP - 1)][tid];
     const uint32_t lp_lim = lp_landed < lp_end ? lp_landed : lp_end;   // tries look at entries below this
 #pragma unroll
     for (uint32_t o = 0; o < LW_OPENS; ++o) {
+      // the queue entries that the tries after this opening may look at, read ahead of the opening's own work
+      uint32_t w[LW_TRIES];
+#pragma unroll
+      for (uint32_t k = 0; k < LW_TRIES; ++k) w[k] = sm.lp[(lp_pos & (LW_LP_CAP - 1)) + k][tid];
       {
         // the whole queue has been issued (noticed here, not in the tries): the open gap is its last, cur_open and f
         // stay as they are from here on
@@ -674,20 +682,24 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         lp_open = usable ? lp_pos : lp_open;
         finished = finished || at_end || last;
       }
+      // In a gap: does the head of the queue fit into what is left?  Then the entry behind it, and so on: an entry is
+      // tried only behind one that fit, so the k-th try of an opening looks at the k-th entry from where the queue stood.
+      const int32_t room = static_cast<int32_t>(lp_lim - lp_pos);   // entries that have landed (<= 0: none)
+      bool active = in_gap;
+      uint32_t nfit = 0;
 #pragma unroll
       for (uint32_t k = 0; k < LW_TRIES; ++k) {
-        // in a gap: does the head of the queue fit into what is left?
-        const bool tryq = in_gap && lp_pos < lp_lim;
+        const bool tryq = active && static_cast<int32_t>(k) < room;
         // (with feedback: the next high-priority request has arrived once the time filled reaches the actual gap)
-        const bool fits = tryq && d0 <= rem && (MODE != LW_REPLAY_FEEDBACK || rem_open - rem < ga);
-        rem -= fits ? d0 : 0u;
-        lp_pos += fits ? 1u : 0u;
-        d0 = fits ? d1 : d0;
-        d1 = sm.lp[(lp_pos + 1) & (LW_LP_CAP - 1)][tid];
+        const bool fits = tryq && w[k] <= rem && (MODE != LW_REPLAY_FEEDBACK || rem_open - rem < ga);
+        rem -= fits ? w[k] : 0u;
+        nfit = fits ? k + 1 : nfit;
         const bool close = tryq && !fits;      // the head does not fit: the gap is closed
         pending = pending || close;
         in_gap = in_gap && !close;
+        active = fits;
       }
+      lp_pos += nfit;
     }
   }
 
