@@ -550,7 +550,8 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
   uint32_t flushed = g_first;        // results below this are in memory
   const uint32_t g_end = g_first + n_gaps;
   int64_t t_open = 0;                // predicted time line of the high-priority task
-  int64_t cur_open = 0, completion;
+  uint32_t g_cur = 0;                // idle time of the gap opened last (its opening time is t_open - g_cur)
+  int64_t completion;
   uint64_t consumed = 0;
   uint32_t rem = 0, rem_open = 0;    // what is left of the open gap's budget; the budget it opened with
   uint32_t lp_open = l0;             // position in the queue when the gap opened
@@ -641,13 +642,14 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
 #pragma unroll
       for (uint32_t k = 0; k < LW_TRIES; ++k) w[k] = sm.lp[(lp_pos & (LW_LP_CAP - 1)) + k][tid];
       {
-        // the whole queue has been issued (noticed here, not in the tries): the open gap is its last, cur_open and f
+        // the whole queue has been issued (noticed here, not in the tries): the open gap is its last, the time line and f
         // stay as they are from here on
         const bool emptied = in_gap && lp_pos == lp_end;
         pending = pending || emptied;
         in_gap = in_gap && !emptied;
         finished = finished || emptied;
-        // what the gap that is open, or has just closed, took: the tries only move lp_pos and rem
+        // what the gap that is open, or has just closed, took (the tries only move lp_pos and rem; a gap that was
+        // skipped took nothing)
         const uint32_t c = lp_pos - lp_open, f = rem_open - rem;
         // (a staging slot that is written early is simply written again)
         sm.out_c[g & (LW_OUT_CAP - 1)][tid] = c;
@@ -655,7 +657,6 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         g += pending ? 1u : 0u;
         consumed += pending ? f : 0u;
         if (MODE != LW_PLAN) delay += (pending && f > ga) ? static_cast<int64_t>(f - ga) : 0;
-        pending = false;
         const uint32_t E = sm.hp_e[hp_pos & (LW_HP_CAP - 1)][tid], G = sm.hp_g[hp_pos & (LW_HP_CAP - 1)][tid];
         // between gaps: the next high-priority launch runs, then its gap opens (the last launch has none)
         const bool idle = !finished && !in_gap;
@@ -666,20 +667,17 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         const bool gap = take && !last;
         if (MODE == LW_PLAN) {
           t_open += take ? static_cast<int64_t>(E) : 0;
-          cur_open = gap ? t_open : cur_open;
-          t_open += gap ? static_cast<int64_t>(G) : 0;
+          t_open += gap ? static_cast<int64_t>(G) : 0;     // (the time line after the gap: the gap opened g_cur earlier)
+          g_cur = gap ? G : g_cur;
         }
         const bool usable = gap && G >= gap_floor;
         if (MODE != LW_PLAN) ga = usable ? E : ga;
-        const bool skip = gap && !usable;
-        // a skipped gap reports zeros
-        sm.out_c[g & (LW_OUT_CAP - 1)][tid] = 0u;
-        sm.out_f[g & (LW_OUT_CAP - 1)][tid] = 0u;
-        g += skip ? 1u : 0u;
         in_gap = in_gap || usable;
-        rem = usable ? G - margin32 : rem;
-        rem_open = usable ? rem : rem_open;
-        lp_open = usable ? lp_pos : lp_open;
+        // a gap that is skipped is closed at once and reports zeros when the next one is opened
+        pending = gap && !usable;
+        rem = gap ? G - margin32 : rem;
+        rem_open = gap ? rem : rem_open;
+        lp_open = gap ? lp_pos : lp_open;
         finished = finished || at_end || last;
       }
       // In a gap: does the head of the queue fit into what is left?  Then the entry behind it, and so on: an entry is
@@ -725,8 +723,9 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
     }
   }
   for (; z < g_end; ++z) { fill_count[z] = 0; filled_ns[z] = 0; }
-  const bool done = lp_pos == lp_end;      // the whole queue has been issued, the last of it into the gap at cur_open
-  completion = done ? cur_open + static_cast<int64_t>(f) : t_open + static_cast<int64_t>(total_lp - consumed);
+  // the whole queue has been issued: the last of it into the gap opened last, after which the time line stood still
+  const bool done = lp_pos == lp_end;
+  completion = done ? t_open - static_cast<int64_t>(g_cur) + static_cast<int64_t>(f) : t_open + static_cast<int64_t>(total_lp - consumed);
   completion_out[s] = MODE == LW_PLAN ? completion : delay;
   placed_out[s] = lp_pos - l0;
 }
