@@ -62,6 +62,14 @@ __device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src) {
   return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
+// The value that lane `src` holds, where `src` is the same in every lane of the wave: no trip through the LDS
+// crossbar as for a shuffle, the lane is selected by a scalar.
+__device__ __forceinline__ uint64_t read_lane_u64(uint64_t v, uint32_t src) {
+  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(v)), static_cast<int>(src)));
+  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(v >> 32)), static_cast<int>(src)));
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int m) {
   uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), m, WAVE);
   uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), m, WAVE);

@@ -206,6 +206,13 @@ k_gf_predict(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off,
 
 // The walk.  GW lanes cooperate on one scenario (GW divides 64): they read GW predicted gaps
 // at a time, and search the low-priority prefix sums GW candidates at a time with a ballot.
+// A value of the group's lane `idx`, where idx is the same in all lanes of the group (a whole wave: scalar lane select).
+template <int GW>
+__device__ __forceinline__ int64_t group_value(int64_t v, uint32_t gbase, uint32_t idx) {
+  if constexpr (GW == WAVE) return static_cast<int64_t>(read_lane_u64(static_cast<uint64_t>(v), idx));
+  else return static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(v), gbase + idx));
+}
+
 template <int GW, bool WINDOW>
 __global__ void __launch_bounds__(256)
 k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task, const uint32_t* __restrict__ lp_task,
@@ -259,14 +266,14 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
       // Gaps that the head of the queue does not fit into take nothing and change nothing: every lane tests
       // its own gap against the head, and the group goes straight to the first gap that takes something.
       // (with the window the prefix sum at the head comes from the lane that holds entry p: wb <= p < wb + GW)
-      const int64_t head_abs = WINDOW ? static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(win0), gbase + static_cast<uint32_t>(p - wb)))
+      const int64_t head_abs = WINDOW ? group_value<GW>(win0, gbase, static_cast<uint32_t>(p - wb))
                                       : head_pe;
       const int64_t head = p < L ? head_abs - consumed : INT64_MAX;
       const bool takes = gl >= k && gl < steps && my_g >= min_gap && my_g >= margin && head <= my_g - margin;
       const uint64_t tb = (ballot(takes) >> gbase) & gmask;
       if (tb == 0) break;
       k = static_cast<uint32_t>(__builtin_ctzll(tb));
-      const int64_t G = static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(my_g), gbase + k));
+      const int64_t G = group_value<GW>(my_g, gbase, k);
       uint32_t c = 0;
       int64_t f = 0;
       if (G >= min_gap && G >= margin && p < L) {
@@ -287,7 +294,7 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
           const bool fits = val <= limit;
           const uint64_t b = (ballot(fits) >> gbase) & gmask;
           const uint32_t cnt = (b == gmask) ? GW : static_cast<uint32_t>(__builtin_ctzll(~b));
-          if (cnt > 0) last_fit = static_cast<int64_t>(shfl_u64(static_cast<uint64_t>(val), gbase + cnt - 1));
+          if (cnt > 0) last_fit = group_value<GW>(val, gbase, cnt - 1);
           c += cnt;
           // keep the window under the search position
           if (WINDOW && p + c >= wb + GW) {
