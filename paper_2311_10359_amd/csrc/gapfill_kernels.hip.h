@@ -347,7 +347,11 @@ k_gf_walk(const uint64_t* __restrict__ off, const uint32_t* __restrict__ hp_task
 // queue entry, so lanes of a wave do not wait for the slowest gap.  Streams are read 64 bytes per lane
 // at a time into registers and parked in per-lane LDS rings one period later, which hides the memory
 // latency; a lane whose ring is empty simply idles for a sub-step.  Results are staged
-// in LDS and written 8 gaps at a time.
+// in LDS and written 8 gaps at a time.  With one wave per SIMD (65,536 scenarios fill the chip exactly
+// once) a SIMD issues one instruction of its wave every four cycles at best, so the kernel's time is its
+// number of instructions: the tries after an opening read all their queue entries at once and ahead of
+// use, and whatever can be derived when a gap's result is staged (its count, its filled time, its opening
+// time) is not carried through the tries.
 
 constexpr uint32_t WIDE32 = 0xffffffffu;   // 32-bit predictions must be below this
 
