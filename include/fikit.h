@@ -33,8 +33,8 @@
  *     measurement aid fikit_trace_* and the scratch address of fikit_gapfill_static).  Inputs
  *     are left untouched.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default
- *     stream).  Every call synchronises that stream before it returns, so outputs and the
- *     returned status are final on return.
+ *     stream).  Every call but fikit_gapfill_static synchronises that stream before it returns, so
+ *     outputs and the returned status are final on return.
  *   - Return value: FIKIT_OK or a negative fikit_status.  Nothing aborts or throws.  After an
  *     error the contents of the output buffers are unspecified.
  *   - Everything is integer arithmetic (nanoseconds, counts); results are exact.
@@ -97,7 +97,8 @@ typedef enum fikit_status {
   FIKIT_ROW_CAPACITY = -3,        /* more rows than row_capacity; *h_n_rows holds the need       */
   FIKIT_BAD_RECORD = -4,          /* some record has end_ns < start_ns                          */
   FIKIT_UNKNOWN_ID = -5,          /* a scenario launch whose ID is absent from its task's rows  */
-  FIKIT_HIP_ERROR = -6,           /* the HIP runtime reported an error                          */
+  FIKIT_HIP_ERROR = -6,           /* the HIP runtime reported an error, or a bounded wait ran out
+                                     (fikit_set_wait_limit)                                      */
   FIKIT_UNSUPPORTED = -7,         /* fikit_prio_fill: a scenario whose list entries and launches
                                      together number 2^32 or more                                 */
   FIKIT_TOO_LARGE = -8            /* fikit_gapfill_static: more launches or tasks than its built-in
