@@ -277,8 +277,11 @@ k_task_fused(const FusedArgs A) {
     // The unit's launches lie in one run per tile of its task: between the boundaries of its first bucket and of
     // the bucket after its last.  Run table in LDS (the space of the identity memo, which units do not use):
     // where each run starts in the tile-ordered arrays, and how many of the unit's launches precede it.
-    uint32_t* run_at = reinterpret_cast<uint32_t*>(&sm.u.memo);
+    uint32_t* run_at = reinterpret_cast<uint32_t*>(&sm.u);
     uint32_t* run_before = run_at + UNIT_RUNS_MAX;          // [tiles + 1]
+    uint16_t* run_of = reinterpret_cast<uint16_t*>(run_before + UNIT_RUNS_MAX + 4);   // [m]: the run that holds each launch
+    static_assert(sizeof(sm.u) >= (2 * UNIT_RUNS_MAX + 4) * 4 + 2 * NT * KPT, "run tables of a unit");
+    static_assert(UNIT_RUNS_MAX <= 0x10000, "runs are numbered in 16 bits");
     const uint32_t ub = A.ubuckets[unit], d0 = ub & 0xffffu, d1 = ub >> 16;
     const uint32_t tp = A.tile_prefix[t], tiles_t = A.tile_prefix[t + 1] - tp;
     const uint64_t task_start = A.off[t];
@@ -303,19 +306,20 @@ k_task_fused(const FusedArgs A) {
       if (tid == 0) atomicOr(&ctrl->status, ERR_OFFSETS);
       return;
     }
+    // every run writes its number over the launches it holds, so that a launch finds its run with one look
+    for (uint32_t j = tid; j < tiles_t; j += NT) {
+      const uint32_t hi = run_before[j + 1];
+      for (uint32_t i = run_before[j]; i < hi; ++i) run_of[i] = static_cast<uint16_t>(j);
+    }
+    __syncthreads();
     // all of a thread's launches are located first and then read together, so that their loads are in flight at once
-    const uint64_t tiles_per_launch = (static_cast<uint64_t>(tiles_t) << 32) / m;   // tiles / m in 32.32 fixed point
     uint32_t at[KPT];
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
       const uint32_t i = r * NT + tid;
       at[r] = 0;
       if (i < m) {
-        // runs are of similar length: start at the proportional guess, then step to the run that holds launch i
-        uint32_t j = static_cast<uint32_t>((static_cast<uint64_t>(i) * tiles_per_launch) >> 32);
-        j = j < tiles_t ? j : tiles_t - 1;
-        while (run_before[j] > i) --j;
-        while (run_before[j + 1] <= i) ++j;
+        const uint32_t j = run_of[i];
         at[r] = run_at[j] + (i - run_before[j]);
       }
     }
