@@ -139,6 +139,9 @@ def main():
     ap.add_argument("--rho", type=float, default=None,
                     help="scale of the per-Kernel-ID share of the spread of times in the generated traces (default 1: an ID "
                          "has a characteristic duration; 0: every launch is drawn independently)")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="a step is fikit_profile followed by fikit_gapfill; default: the two as one call, "
+                         "fikit_profile_gapfill, in which the profile's kernels hand the predictions to the gap fill")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware counter runs)")
     args = ap.parse_args()
@@ -225,8 +228,10 @@ def main():
     ids = torch.empty(n, dtype=torch.int64, device=dev)
     rows = torch.empty((row_cap, 128), dtype=torch.uint8, device=dev)
     tro = torch.empty(cfg.n_tasks + 1, dtype=torch.int64, device=dev)
+    one_call = bool(n_scen) and not args.two_calls
     ws_bytes = max(binding.fikit_profile_workspace_bytes(n, cfg.n_tasks),
-                   binding.fikit_gapfill_workspace_bytes(n, cfg.n_tasks, n_scen))
+                   binding.fikit_gapfill_workspace_bytes(n, cfg.n_tasks, n_scen),
+                   binding.fikit_profile_gapfill_workspace_bytes(n, cfg.n_tasks, n_scen) if one_call else 0)
     ws = binding.workspace(ws_bytes, dev)
     gf_out = binding.GapFill(torch.empty(n_gaps, dtype=torch.int32, device=dev),
                              torch.empty(n_gaps, dtype=torch.int64, device=dev),
@@ -239,6 +244,16 @@ def main():
         e = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if timers is not None else None
         if e:
             e[0].record()
+        if one_call:
+            prof, _ = binding.fikit_profile_gapfill(d_rec, d_off, d_hp, d_lp, d_go, margin_ns=cfg.margin_ns,
+                                                    min_gap_ns=cfg.min_gap_ns, n_gaps=n_gaps, ids_out=ids, rows_out=rows,
+                                                    task_row_offsets_out=tro, out=gf_out, workspace_buf=ws,
+                                                    row_capacity=row_cap)
+            if e:
+                e[1].record()
+                e[2].record()
+                timers.append(e)
+            return prof
         prof = binding.fikit_profile(d_rec, d_off, ids_out=ids, rows_out=rows, task_row_offsets_out=tro,
                                      workspace_buf=ws, row_capacity=row_cap)
         if e:
@@ -273,6 +288,11 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     prof_ms = float(np.median([a[0].elapsed_time(a[1]) for a in timers]))
     gf_ms = float(np.median([a[1].elapsed_time(a[2]) for a in timers]))
+    if one_call:
+        # one call: the gap fill's share is the time of its own kernels (the trace's gf_* and k_gf_* entries), the
+        # profile's the rest; the predictions are written by the profile's kernels and count there
+        gf_ms = sum(ms for k, (ms, _) in trace.items() if k.startswith(("gf_", "k_gf_"))) / args.steps
+        prof_ms = prof_ms - gf_ms
     log(f"[bench] {ms_per_step:.2f} ms/step (profile {prof_ms:.2f} ms, gap fill {gf_ms:.2f} ms), {prof.n_rows} rows")
     for k, (ms, cnt) in sorted(trace.items(), key=lambda kv: -kv[1][0]):
         log(f"[bench]   {k:18s} {ms / args.steps:9.3f} ms/step  {cnt // args.steps:3d} launches/step")
@@ -430,6 +450,15 @@ def main():
     avg_ms = dom_ms / dom_cnt
     if dom in ALGO_BYTES_PER_RECORD:
         algo_bytes = ALGO_BYTES_PER_RECORD[dom] * units[dom]
+        if one_call and n_scen >= 4096 and dom.startswith("k_task_fused_"):
+            # one call: the task kernels also write the predictions that the gap fill reads (4 bytes per launch of a
+            # task used as queue, 8 per launch of a task used as trace), which k_gf_predict32 writes otherwise
+            lo, hi = {"k_task_fused_small": (0, 4096), "k_task_fused_mid": (4096, 8192), "k_task_fused_medium": (8192, 16384)}[dom]
+            in_class = (lens > lo) & (lens <= hi)
+            is_hp, is_lp = np.zeros(cfg.n_tasks, dtype=bool), np.zeros(cfg.n_tasks, dtype=bool)
+            is_hp[hp] = True
+            is_lp[lp] = True
+            algo_bytes += 8 * int(lens[in_class & is_hp].sum()) + 4 * int(lens[in_class & is_lp].sum())
     elif dom == "k_gf_predict":      # IDs read; prefix sums, idle times and gap-open times written (8 bytes each)
         algo_bytes = 8 * (n_hp + n_lp) + 8 * n_lp + 16 * n_hp
     elif dom == "k_gf_predict32":    # IDs read; 32-bit execution times (queue) and (execution, idle) pairs (trace) written
@@ -492,7 +521,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
         "config": {"workload": name, "records": n, "tasks": cfg.n_tasks, "scenarios": n_scen, "gaps": n_gaps,
                    "rows": prof.n_rows, "margin_ns": cfg.margin_ns, "min_gap_ns": cfg.min_gap_ns,
-                   "rho_exec": cfg.rho_exec, "rho_gap": cfg.rho_gap},
+                   "rho_exec": cfg.rho_exec, "rho_gap": cfg.rho_gap,
+                   "entry_points": "fikit_profile_gapfill" if one_call else "fikit_profile, fikit_gapfill"},
         "profile_records_per_s": round(n / (prof_ms * 1e-3), 1),
         "gapfill_scenarios_per_s": round(n_scen / (gf_ms * 1e-3), 1) if n_scen else None,
         "profile_ms": round(prof_ms, 3), "gapfill_ms": round(gf_ms, 3),

@@ -20,7 +20,7 @@
  *                    long as its predicted duration does not exceed what is left of the gap
  *                    (Algorithm 2 with a single waiting request is first-in-first-out).
  *
- * Beside these two: fikit_measure (the per-launch measurements themselves), fikit_gapfill_replay (the
+ * Both at once: fikit_profile_gapfill.  Beside these: fikit_measure (the per-launch measurements themselves), fikit_gapfill_replay (the
  * fill replayed against the idle times that occurred, without and with real-time feedback),
  * fikit_prio_fill (several low-priority tasks per scenario in the priority queues of Algorithm 2),
  * fikit_pairing_best (the best partner of every high-priority task among evaluated combinations) and
@@ -183,6 +183,31 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
                   uint32_t* d_fill_count, int64_t* d_filled_ns, int64_t* d_lp_completion_ns,
                   uint64_t* d_lp_placed, void* d_workspace, size_t workspace_bytes,
                   void* hip_stream);
+
+/* Bytes of device workspace fikit_profile_gapfill needs for these sizes (0 on size overflow). */
+size_t fikit_profile_gapfill_workspace_bytes(uint64_t n_records, uint32_t n_tasks, uint64_t n_scenarios);
+
+/*
+ * fikit_profile followed by fikit_gapfill on the same traces, as one call: the measurement-phase statistics
+ * (Section 3.2) and Algorithm 1 driven by them.  Arguments and outputs are those of the two calls (d_ids_out is
+ * required here; the profile's outputs are the gap fill's inputs), and every output equals what the two calls give
+ * one after the other.  The difference is inside: a task that one workgroup profiles whole has its launches'
+ * predicted durations and idle times written by that workgroup while the launches are still in its registers, so
+ * the gap fill need not read the Kernel IDs again and look every one up (with at least 4096 scenarios and
+ * predictions below 2^32 - 1 ns; otherwise, and for the tasks that take other paths, exactly the kernels of the two
+ * calls run).
+ *
+ *   d_workspace   256-byte aligned, at least fikit_profile_gapfill_workspace_bytes(...) bytes.
+ *
+ * Errors: those of fikit_profile (after which the gap fill is not attempted) and of fikit_gapfill.
+ */
+int fikit_profile_gapfill(const fikit_launch* d_records, uint64_t n_records, const uint64_t* d_task_offsets,
+                          uint32_t n_tasks, uint64_t* d_ids_out, fikit_row* d_rows_out, uint64_t row_capacity,
+                          uint64_t* d_task_row_offsets, uint64_t* h_n_rows, const uint32_t* d_hp_task,
+                          const uint32_t* d_lp_task, uint64_t n_scenarios, const fikit_gapfill_params* h_params,
+                          const uint64_t* d_gap_offsets, uint32_t* d_fill_count, int64_t* d_filled_ns,
+                          int64_t* d_lp_completion_ns, uint64_t* d_lp_placed, void* d_workspace,
+                          size_t workspace_bytes, void* hip_stream);
 
 /* Largest inputs of fikit_gapfill_static. */
 #define FIKIT_STATIC_MAX_IDS (1u << 20)   /* launches of all tasks together */

@@ -29,7 +29,7 @@ FIKIT_STATIC_MAX_TASKS = 16384
 FIKIT_PREDICT_P50, FIKIT_PREDICT_MEAN = 0, 1
 
 EXPORTS = ("fikit_profile_workspace_bytes", "fikit_profile", "fikit_gapfill_workspace_bytes",
-           "fikit_gapfill", "fikit_gapfill_static", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
+           "fikit_gapfill", "fikit_profile_gapfill_workspace_bytes", "fikit_profile_gapfill", "fikit_gapfill_static", "fikit_measure_workspace_bytes", "fikit_measure", "fikit_replay_workspace_bytes",
            "fikit_gapfill_replay", "fikit_prio_fill_workspace_bytes", "fikit_prio_fill", "fikit_pairing_workspace_bytes",
            "fikit_pairing_best", "fikit_profile_merge_workspace_bytes", "fikit_profile_merge", "fikit_status_string", "fikit_version", "fikit_set_wait_limit",
            "fikit_trace_enable", "fikit_trace_read")
@@ -85,6 +85,11 @@ def load() -> ctypes.CDLL:
         lib.fikit_gapfill.restype = ctypes.c_int
         lib.fikit_gapfill.argtypes = [vp, vp, u32, vp, vp, vp, vp, u64, ctypes.POINTER(_GapfillParams), vp,
                                       vp, vp, vp, vp, vp, sz, vp]
+        lib.fikit_profile_gapfill_workspace_bytes.restype = sz
+        lib.fikit_profile_gapfill_workspace_bytes.argtypes = [u64, u32, u64]
+        lib.fikit_profile_gapfill.restype = ctypes.c_int
+        lib.fikit_profile_gapfill.argtypes = [vp, u64, vp, u32, vp, vp, u64, vp, ctypes.POINTER(u64), vp, vp, u64,
+                                              ctypes.POINTER(_GapfillParams), vp, vp, vp, vp, vp, vp, sz, vp]
         lib.fikit_gapfill_static.restype = ctypes.c_int
         lib.fikit_gapfill_static.argtypes = [vp, u64, vp, u32, vp, vp, vp, vp, u64, ctypes.POINTER(_GapfillParams), vp, u64,
                                              vp, vp, vp, vp, vp, vp]
@@ -255,6 +260,58 @@ def fikit_gapfill(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Ten
     if st != FIKIT_OK:
         raise FikitError(st, "fikit_gapfill")
     return out
+
+
+def fikit_profile_gapfill_workspace_bytes(n_records: int, n_tasks: int, n_scenarios: int) -> int:
+    return int(load().fikit_profile_gapfill_workspace_bytes(n_records, n_tasks, n_scenarios))
+
+
+def fikit_profile_gapfill(records: torch.Tensor, task_offsets: torch.Tensor, hp_task: torch.Tensor, lp_task: torch.Tensor,
+                          gap_offsets: torch.Tensor, *, margin_ns: int, min_gap_ns: int, predictor: int = FIKIT_PREDICT_P50,
+                          n_gaps: Optional[int] = None, row_capacity: Optional[int] = None,
+                          ids_out: Optional[torch.Tensor] = None, rows_out: Optional[torch.Tensor] = None,
+                          task_row_offsets_out: Optional[torch.Tensor] = None, out: Optional[GapFill] = None,
+                          workspace_buf: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """fikit_profile and fikit_gapfill as one call -> (Profile, GapFill).  Arguments as in the two."""
+    lib = load()
+    dev = records.device
+    assert records.dtype == torch.uint8 and records.is_contiguous()
+    n = records.numel() // LAUNCH_BYTES
+    assert records.numel() == n * LAUNCH_BYTES
+    n_tasks = task_offsets.numel() - 1
+    s = hp_task.numel()
+    assert hp_task.dtype == torch.int32 and lp_task.dtype == torch.int32 and lp_task.numel() == s
+    assert gap_offsets.dtype == torch.int64 and gap_offsets.numel() == s + 1
+    for t in (task_offsets, hp_task, lp_task, gap_offsets):
+        assert t.is_contiguous() and t.device == dev
+    if n_gaps is None:
+        n_gaps = int(gap_offsets[-1].item()) if s else 0
+    if row_capacity is None:
+        row_capacity = rows_out.shape[0] if rows_out is not None else n
+    if ids_out is None:
+        ids_out = torch.empty(n, dtype=torch.int64, device=dev)
+    if rows_out is None:
+        rows_out = torch.empty((row_capacity, ROW_BYTES), dtype=torch.uint8, device=dev)
+    if task_row_offsets_out is None:
+        task_row_offsets_out = torch.empty(n_tasks + 1, dtype=torch.int64, device=dev)
+    if out is None:
+        out = GapFill(torch.empty(n_gaps, dtype=torch.int32, device=dev),
+                      torch.empty(n_gaps, dtype=torch.int64, device=dev),
+                      torch.empty(s, dtype=torch.int64, device=dev),
+                      torch.empty(s, dtype=torch.int64, device=dev))
+    if workspace_buf is None:
+        workspace_buf = workspace(fikit_profile_gapfill_workspace_bytes(n, n_tasks, s), dev)
+    params = _GapfillParams(margin_ns, min_gap_ns, predictor, 0)
+    n_rows = ctypes.c_uint64(0)
+    with torch.cuda.device(dev):
+        st = lib.fikit_profile_gapfill(_ptr(records), n, _ptr(task_offsets), n_tasks, _ptr(ids_out), _ptr(rows_out), row_capacity,
+                                       _ptr(task_row_offsets_out), ctypes.byref(n_rows), _ptr(hp_task), _ptr(lp_task), s,
+                                       ctypes.byref(params), _ptr(gap_offsets), _ptr(out.fill_count), _ptr(out.filled_ns),
+                                       _ptr(out.lp_completion_ns), _ptr(out.lp_placed), _ptr(workspace_buf),
+                                       workspace_buf.numel(), _stream_handle(stream))
+    if st != FIKIT_OK:
+        raise FikitError(st, "fikit_profile_gapfill", int(n_rows.value))
+    return Profile(ids_out, rows_out[: int(n_rows.value)], task_row_offsets_out, int(n_rows.value)), out
 
 
 def fikit_gapfill_static(ids: torch.Tensor, task_offsets: torch.Tensor, rows: torch.Tensor, task_row_offsets: torch.Tensor,

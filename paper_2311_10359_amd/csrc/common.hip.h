@@ -28,6 +28,9 @@ enum : uint32_t {
   ERR_WAIT = 1u << 9,        // a tile of the sort gave up waiting for the tile before it (must not happen)
 };
 
+// What a task is used as by the scenarios of a gap-fill call.
+constexpr uint32_t ROLE_HP = 1u, ROLE_LP = 2u;
+
 // Control block at the start of the workspace; cleared by k_clear_ctrl at the start of a call.
 struct Ctrl {
   uint32_t status;        // ERR_* bits

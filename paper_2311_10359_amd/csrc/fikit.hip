@@ -228,10 +228,25 @@ size_t fikit_profile_workspace_bytes(uint64_t n_records, uint32_t n_tasks) {
   return static_cast<size_t>(profile_layout(n_records, n_tasks).total);
 }
 
-int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint64_t* d_task_offsets,
-                  uint32_t n_tasks, uint64_t* d_ids_out, fikit_row* d_rows_out, uint64_t row_capacity,
-                  uint64_t* d_task_row_offsets, uint64_t* h_n_rows, void* d_workspace, size_t workspace_bytes,
-                  void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Where the one-workgroup kernels of the profile put the predictions for a gap fill that follows (see FusedArgs).
+struct PredEmit {
+  const uint32_t* role;
+  uint32_t* lp_e;
+  uint2* hp_eg;
+  uint64_t* lp_total;
+  uint32_t* done;
+  uint32_t predictor;
+};
+
+// fikit_profile; with `emit` the kernels that hold a whole task in one workgroup also write the task's predictions.
+int profile_run(const fikit_launch* d_records, uint64_t n_records, const uint64_t* d_task_offsets,
+                uint32_t n_tasks, uint64_t* d_ids_out, fikit_row* d_rows_out, uint64_t row_capacity,
+                uint64_t* d_task_row_offsets, uint64_t* h_n_rows, void* d_workspace, size_t workspace_bytes,
+                void* hip_stream, const PredEmit* emit) {
   if (!h_n_rows) return FIKIT_INVALID_ARG;
   *h_n_rows = 0;
   if (!d_task_offsets || !d_task_row_offsets || !d_workspace) return FIKIT_INVALID_ARG;
@@ -313,6 +328,10 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   FusedArgs fa{};
   fa.rec = d_records; fa.off = d_task_offsets; fa.ids = ids; fa.e0 = e0; fa.g0 = g0; fa.key0 = k1;
   fa.stage_a = e1; fa.stage_b = g1; fa.dcount = dcount; fa.gflag = gflag; fa.ctrl = ctrl;
+  if (emit) {
+    fa.pred_role = emit->role; fa.pred_lp_e = emit->lp_e; fa.pred_hp_eg = emit->hp_eg; fa.pred_lp_total = emit->lp_total;
+    fa.pred_done = emit->done; fa.predictor = emit->predictor;
+  }
   {
     tr.mark("k_task_fused_small");
     fa.list = lists; fa.count = &ctrl->n_class[0]; fa.max_len = FUSE_SMALL_MAX;
@@ -355,6 +374,7 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
     hipLaunchKernelGGL(k_msd_units, dim3(n_tasks), dim3(MSD_SLOTS), 0, st, d_task_offsets, n_tasks, is_long, mtiles, bucket_size, wflag,
                        ustart, ulen, utask, udcount, ubuckets, mflag, gflag, lists, static_cast<uint32_t>(n_units), ctrl);
     FusedArgs ua = fa;
+    ua.pred_role = nullptr;   // (units are parts of tasks: their task's predictions are left to the gap fill)
     ua.ustart = ustart; ua.ulen = ulen; ua.utask = utask; ua.ubuckets = ubuckets; ua.tile_prefix = mtiles; ua.bound = bound;
     ua.tile_len = PT_TILE; ua.part_id = k1; ua.part_kg = part_kg; ua.mflag = mflag; ua.dcount = udcount;
     tr.mark("k_unit_fused_small");
@@ -504,6 +524,18 @@ int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint6
   return FIKIT_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int fikit_profile(const fikit_launch* d_records, uint64_t n_records, const uint64_t* d_task_offsets,
+                  uint32_t n_tasks, uint64_t* d_ids_out, fikit_row* d_rows_out, uint64_t row_capacity,
+                  uint64_t* d_task_row_offsets, uint64_t* h_n_rows, void* d_workspace, size_t workspace_bytes,
+                  void* hip_stream) {
+  return profile_run(d_records, n_records, d_task_offsets, n_tasks, d_ids_out, d_rows_out, row_capacity, d_task_row_offsets,
+                     h_n_rows, d_workspace, workspace_bytes, hip_stream, nullptr);
+}
+
 // The per-launch arrays of the gap fill are read in 64-byte pieces that may reach past the last launch.
 constexpr uint64_t GF_PAD = 256;
 // One lane per scenario pays off once there are about as many scenarios as the GPU has lanes to run at a time.
@@ -526,13 +558,17 @@ bool gapfill_params_ok(const fikit_gapfill_params* p) {
          p->predictor <= FIKIT_PREDICT_MEAN;
 }
 
+// The gap fill in two parts: what has to come before the predictions (checks, task roles, work lists) and the rest.
+enum GfPart { GF_ALL, GF_SETUP, GF_REST };
+
 // Enqueues every kernel of the gap fill on `st`; `ws` holds gapfill_ws_bytes(n_ids, n_tasks) bytes whose first 64
 // are the control block.  Nothing is read back and nothing is allocated here.
 int gapfill_enqueue(hipStream_t st, Tracer& tr, const uint64_t* d_ids, uint64_t n_ids, const uint64_t* d_task_offsets,
                     uint32_t n_tasks, const fikit_row* d_rows, const uint64_t* d_task_row_offsets, const uint32_t* d_hp_task,
                     const uint32_t* d_lp_task, uint64_t n_scenarios, const fikit_gapfill_params* h_params,
                     const uint64_t* d_gap_offsets, uint64_t n_gaps, uint32_t* d_fill_count, int64_t* d_filled_ns,
-                    int64_t* d_lp_completion_ns, uint64_t* d_lp_placed, unsigned char* ws, bool set_attributes) {
+                    int64_t* d_lp_completion_ns, uint64_t* d_lp_placed, unsigned char* ws, bool set_attributes,
+                    GfPart part = GF_ALL, PredEmit* emit = nullptr) {
   Carver c;
   Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + c.take(256));
   uint32_t* role = reinterpret_cast<uint32_t*>(ws + c.take(static_cast<uint64_t>(n_tasks) * 4));
@@ -545,6 +581,12 @@ int gapfill_enqueue(hipStream_t st, Tracer& tr, const uint64_t* d_ids, uint64_t 
   uint32_t* lp_e = reinterpret_cast<uint32_t*>(pe);
   uint2* hp_eg = reinterpret_cast<uint2*>(pg);
 
+  const bool lanes = n_scenarios >= GF_LANES_MIN_SCENARIOS && n_gaps < MAX_ELEMS;
+  if (emit) {   // (what a profile that runs between the two parts may fill in; only the lane kernels read this form)
+    emit->role = lanes ? role : nullptr;
+    emit->lp_e = lp_e; emit->hp_eg = hp_eg; emit->lp_total = lp_total; emit->predictor = static_cast<uint32_t>(h_params->predictor);
+  }
+  if (part != GF_REST) {
   tr.mark("gf_setup");
   hipLaunchKernelGGL(k_clear_ctrl, dim3(1), dim3(64), 0, st, ctrl);
   hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, role, static_cast<uint64_t>(n_tasks), 0u);
@@ -554,13 +596,16 @@ int gapfill_enqueue(hipStream_t st, Tracer& tr, const uint64_t* d_ids, uint64_t 
   tr.mark("gf_lists");
   hipLaunchKernelGGL(k_gf_lists, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, d_task_offsets, n_tasks, role, 8192u, glists,
                      ctrl);
+  FIKIT_HIP(hipGetLastError());
+  }
+  if (part == GF_SETUP) return FIKIT_OK;
   // Many scenarios: one lane per scenario on 32-bit predictions; the 64-bit kernels then only run if a
   // prediction did not fit (they check Ctrl::wide).  Few scenarios: the 64-bit kernels, a group of lanes each.
-  const bool lanes = n_scenarios >= GF_LANES_MIN_SCENARIOS && n_gaps < MAX_ELEMS;
   if (lanes) {
     tr.mark("k_gf_predict32");
     hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
-                       d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total, static_cast<uint32_t>(h_params->predictor), ctrl);
+                       d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total,
+                       static_cast<uint32_t>(h_params->predictor), emit ? emit->done : static_cast<const uint32_t*>(nullptr), ctrl);
     tr.mark("k_gf_walk_lanes");
     if (set_attributes)
       FIKIT_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_gf_walk_lanes<LW_PLAN>),
@@ -629,6 +674,71 @@ int fikit_gapfill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint32_
   tr.mark("host_sync");
   Ctrl h{};
   if (int rc = read_ctrl(reinterpret_cast<const Ctrl*>(ws), &h, st)) return rc;
+  return status_from_bits(h.status);
+}
+
+size_t fikit_profile_gapfill_workspace_bytes(uint64_t n_records, uint32_t n_tasks, uint64_t n_scenarios) {
+  const size_t a = fikit_profile_workspace_bytes(n_records, n_tasks), b = fikit_gapfill_workspace_bytes(n_records, n_tasks, n_scenarios);
+  if (a == 0 || b == 0) return 0;
+  return static_cast<size_t>(ws_align(a) + ws_align(b) + ws_align(static_cast<uint64_t>(n_tasks) * 4));
+}
+
+int fikit_profile_gapfill(const fikit_launch* d_records, uint64_t n_records, const uint64_t* d_task_offsets, uint32_t n_tasks,
+                          uint64_t* d_ids_out, fikit_row* d_rows_out, uint64_t row_capacity, uint64_t* d_task_row_offsets,
+                          uint64_t* h_n_rows, const uint32_t* d_hp_task, const uint32_t* d_lp_task, uint64_t n_scenarios,
+                          const fikit_gapfill_params* h_params, const uint64_t* d_gap_offsets, uint32_t* d_fill_count,
+                          int64_t* d_filled_ns, int64_t* d_lp_completion_ns, uint64_t* d_lp_placed, void* d_workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  if (!h_n_rows) return FIKIT_INVALID_ARG;
+  *h_n_rows = 0;
+  if (!gapfill_params_ok(h_params)) return FIKIT_INVALID_ARG;
+  if (!d_ids_out || !d_workspace || !d_task_offsets || n_records >= MAX_ELEMS || n_scenarios >= MAX_ELEMS) return FIKIT_INVALID_ARG;
+  if (n_scenarios > 0 && (!d_hp_task || !d_lp_task || !d_gap_offsets || !d_lp_completion_ns || !d_lp_placed || n_tasks == 0))
+    return FIKIT_INVALID_ARG;
+  if (!aligned(d_hp_task, 4) || !aligned(d_lp_task, 4) || !aligned(d_gap_offsets, 8) || !aligned(d_fill_count, 4) ||
+      !aligned(d_filled_ns, 8) || !aligned(d_lp_completion_ns, 8) || !aligned(d_lp_placed, 8) || !aligned(d_workspace, 256))
+    return FIKIT_INVALID_ARG;
+  const size_t need = fikit_profile_gapfill_workspace_bytes(n_records, n_tasks, n_scenarios);
+  if (need == 0) return FIKIT_INVALID_ARG;
+  if (workspace_bytes < need) return FIKIT_WORKSPACE_TOO_SMALL;
+  unsigned char* ws = static_cast<unsigned char*>(d_workspace);
+  const uint64_t prof_bytes = ws_align(fikit_profile_workspace_bytes(n_records, n_tasks));
+  const uint64_t gf_bytes = ws_align(fikit_gapfill_workspace_bytes(n_records, n_tasks, n_scenarios));
+  unsigned char* gf_ws = ws + prof_bytes;
+  uint32_t* done = reinterpret_cast<uint32_t*>(gf_ws + gf_bytes);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (n_scenarios == 0)
+    return fikit_profile(d_records, n_records, d_task_offsets, n_tasks, d_ids_out, d_rows_out, row_capacity, d_task_row_offsets,
+                         h_n_rows, ws, prof_bytes, hip_stream);
+
+  uint64_t n_gaps = 0;
+  FIKIT_HIP(hipMemcpyAsync(&n_gaps, d_gap_offsets + n_scenarios, 8, hipMemcpyDeviceToHost, st));
+  FIKIT_HIP(hipStreamSynchronize(st));
+  if (n_gaps > 0 && (!d_fill_count || !d_filled_ns)) return FIKIT_INVALID_ARG;
+
+  // 1. the gap fill's checks and task roles; 2. the profile, whose one-workgroup kernels also write the predictions
+  // of the tasks that the scenarios use; 3. the predictions of the remaining tasks, and the fill.
+  PredEmit emit{};
+  emit.done = done;
+  {
+    Tracer tr(st);
+    hipLaunchKernelGGL(k_fill_u32, dim3(blocks_for(n_tasks, 256)), dim3(256), 0, st, done, static_cast<uint64_t>(n_tasks), 0u);
+    if (int rc = gapfill_enqueue(st, tr, d_ids_out, n_records, d_task_offsets, n_tasks, d_rows_out, d_task_row_offsets, d_hp_task,
+                                 d_lp_task, n_scenarios, h_params, d_gap_offsets, n_gaps, d_fill_count, d_filled_ns,
+                                 d_lp_completion_ns, d_lp_placed, gf_ws, true, GF_SETUP, &emit))
+      return rc;
+  }
+  if (int rc = profile_run(d_records, n_records, d_task_offsets, n_tasks, d_ids_out, d_rows_out, row_capacity, d_task_row_offsets,
+                           h_n_rows, ws, prof_bytes, hip_stream, emit.role ? &emit : nullptr))
+    return rc;
+  Tracer tr(st);
+  if (int rc = gapfill_enqueue(st, tr, d_ids_out, n_records, d_task_offsets, n_tasks, d_rows_out, d_task_row_offsets, d_hp_task,
+                               d_lp_task, n_scenarios, h_params, d_gap_offsets, n_gaps, d_fill_count, d_filled_ns,
+                               d_lp_completion_ns, d_lp_placed, gf_ws, true, GF_REST, &emit))
+    return rc;
+  tr.mark("host_sync");
+  Ctrl h{};
+  if (int rc = read_ctrl(reinterpret_cast<const Ctrl*>(gf_ws), &h, st)) return rc;
   return status_from_bits(h.status);
 }
 
@@ -801,7 +911,7 @@ int fikit_gapfill_replay(const uint64_t* d_ids, const uint64_t* d_task_offsets, 
   tr.mark("k_gf_predict32");
   hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
                      d_task_row_offsets, role, glists, d_actual_gap_ns, lp_e, hp_eg, lp_total,
-                     static_cast<uint32_t>(h_params->predictor), ctrl);
+                     static_cast<uint32_t>(h_params->predictor), static_cast<const uint32_t*>(nullptr), ctrl);
   const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
   const dim3 grid(blocks_for(n_scenarios, LW_THREADS)), block(LW_THREADS);
   if (h_params->feedback) {
@@ -911,7 +1021,7 @@ int fikit_prio_fill(const uint64_t* d_ids, const uint64_t* d_task_offsets, uint3
     tr.mark("k_gf_predict32");
     hipLaunchKernelGGL(k_gf_predict32, dim3(n_tasks), dim3(PRED_THREADS), 0, st, d_ids, d_task_offsets, n_tasks, d_rows,
                        d_task_row_offsets, role, glists, static_cast<const int64_t*>(nullptr), lp_e, hp_eg, lp_total,
-                       static_cast<uint32_t>(h_params->predictor), ctrl);
+                       static_cast<uint32_t>(h_params->predictor), static_cast<const uint32_t*>(nullptr), ctrl);
     const uint32_t vec_ok = (aligned(d_fill_count, 16) && aligned(d_filled_ns, 16)) ? 1u : 0u;
     tr.mark("k_pf_walk");
     int rc = FIKIT_OK;

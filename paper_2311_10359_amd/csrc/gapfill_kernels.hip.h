@@ -12,8 +12,6 @@
 
 namespace fikit {
 
-constexpr uint32_t ROLE_HP = 1u, ROLE_LP = 2u;
-
 // Checks scenario arguments (n_gaps: the number of per-gap output slots the host sized its buffers for) and
 // records in role[t] how each task is used.
 __global__ void k_gf_scenarios(const uint64_t* __restrict__ off, uint32_t n_tasks, const uint32_t* __restrict__ hp_task,
@@ -360,11 +358,13 @@ constexpr uint32_t WIDE32 = 0xffffffffu;   // 32-bit predictions must be below t
 //   hp_eg[i] (execution time, idle time), for tasks used as high-priority trace
 // For the replay against actual idle times (actual != nullptr) the first word of hp_eg[i] holds the idle
 // time that really followed launch i instead (clamped to WIDE32, which no filled time can reach).
+// pred_done (may be null): tasks whose predictions exist already and are left alone.
 __global__ void __launch_bounds__(PRED_THREADS)
 k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ off, uint32_t n_tasks,
                const fikit_row* __restrict__ rows, const uint64_t* __restrict__ row_off, const uint32_t* __restrict__ role,
                const uint32_t* __restrict__ lists, const int64_t* __restrict__ actual, uint32_t* __restrict__ lp_e,
-               uint2* __restrict__ hp_eg, uint64_t* __restrict__ lp_total, uint32_t predictor, Ctrl* ctrl) {
+               uint2* __restrict__ hp_eg, uint64_t* __restrict__ lp_total, uint32_t predictor,
+               const uint32_t* __restrict__ pred_done, Ctrl* ctrl) {
   __shared__ PredTable tb;
   __shared__ uint64_t wave_tot[PRED_THREADS / WAVE];
   if (ctrl->status & (ERR_OFFSETS | ERR_TASK_INDEX | ERR_GAP_OFFSETS)) return;
@@ -373,6 +373,7 @@ k_gf_predict32(const uint64_t* __restrict__ ids, const uint64_t* __restrict__ of
   const uint32_t t = blockIdx.x < n_short ? lists[blockIdx.x] : lists[static_cast<uint64_t>(n_tasks) + (blockIdx.x - n_short)];
   const uint32_t rl = role[t];
   if (rl == 0) return;
+  if (pred_done && pred_done[t]) return;   // (the profile kernels wrote this task's predictions already)
   const uint64_t base = off[t], len = off[t + 1] - base;
   const uint64_t r0 = row_off[t], nr = row_off[t + 1] - r0;
   const uint32_t tid = threadIdx.x;

@@ -203,6 +203,15 @@ struct FusedArgs {
   uint32_t* dcount;            // rows per task / per unit
   uint32_t* gflag;             // task takes the general path
   Ctrl* ctrl;
+  // Predictions for a gap fill that follows (whole tasks only; pred_role null: none).  A task that is the
+  // high-priority trace or the low-priority queue of some scenario gets the predicted value of every launch written
+  // in the form the one-lane-per-scenario walk reads, and is marked in pred_done.
+  const uint32_t* pred_role;   // per task: ROLE_HP | ROLE_LP
+  uint32_t* pred_lp_e;         // per launch: predicted execution time (tasks used as queue)
+  uint2* pred_hp_eg;           // per launch: predicted (execution time, idle time) (tasks used as trace)
+  uint64_t* pred_lp_total;     // per task: sum of its launches' predicted execution times (queue)
+  uint32_t* pred_done;         // per task: 1 once its predictions are written
+  uint32_t predictor;          // a fikit_predictor
 };
 
 // Adds one launch's execution time and (if it has one) idle time to the sums, minima and maxima of ID-table slot s.
@@ -633,6 +642,9 @@ k_task_fused(const FusedArgs A) {
     }
   }
   __syncthreads();
+  // (predictions: a thread stages at most one row, DMAX <= NT, and keeps that ID's means for after the barrier)
+  const bool emit = !UNITS && A.pred_role != nullptr;
+  uint32_t mean_e = 0, mean_g = 0;
   for (uint32_t j = tid; j < D; j += NT) {
     uint64_t* row = staged_row(stage_a, stage_b, base, m, j);
     const uint32_t ec = sm.rcnt[j];
@@ -655,6 +667,10 @@ k_task_fused(const FusedArgs A) {
     row[8] = gc; row[9] = gsum;
     row[10] = gc ? gmin : 0; row[11] = gc ? gmax : 0;
     row[14] = 0; row[15] = 0;
+    if (emit && A.predictor != FIKIT_PREDICT_P50) {
+      mean_e = ec ? static_cast<uint32_t>(esum / ec) : 0u;
+      mean_g = gc ? static_cast<uint32_t>(gsum / gc) : 0u;
+    }
     sm.kth[0][j] = static_cast<uint16_t>(rank_index_u32(50, ec));
     sm.kth[1][j] = static_cast<uint16_t>(rank_index_u32(95, ec));
     sm.kth[2][j] = static_cast<uint16_t>(gc ? rank_index_u32(50, gc) : 0);
@@ -679,6 +695,39 @@ k_task_fused(const FusedArgs A) {
     sm.npass[1][j] = static_cast<uint8_t>(((mxg ? 32 - __builtin_clz(mxg) : 1) + B - 1) / B);
   }
   __syncthreads();  // acc is dead from here on; hist reuses the space
+  static_assert(DMAX <= NT, "one staged row per thread at most");
+  // predicted value per ID (by rank), in the space of the ranked IDs, which are in the rows by now
+  uint32_t* pred_e = reinterpret_cast<uint32_t*>(sm.rkey);
+  uint32_t* pred_g = pred_e + DMAX;
+  const bool emit_p50 = emit && A.predictor == FIKIT_PREDICT_P50;
+  if (emit && tid < D) { pred_e[tid] = mean_e; pred_g[tid] = mean_g; }
+  // Writes the predictions of the task's launches (sl: rank of every launch's ID).  Called by all threads once the
+  // percentiles are final.
+  auto emit_predictions = [&]() {
+    __syncthreads();
+    const uint32_t rl = A.pred_role[t];
+    if (rl & ROLE_LP) {
+#pragma unroll
+      for (int r = 0; r < KPT; ++r) {
+        const uint32_t i = r * NT + tid;
+        if (i < m) A.pred_lp_e[base + i] = pred_e[sl[r]];
+      }
+      if (tid < WAVE) {
+        uint64_t total = 0;
+        for (uint32_t j = tid; j < D; j += WAVE) total += static_cast<uint64_t>(sm.rcnt[j]) * pred_e[j];
+        total = wave_sum_u64(total);
+        if (tid == 0) A.pred_lp_total[t] = total;
+      }
+    }
+    if (rl & ROLE_HP) {
+#pragma unroll
+      for (int r = 0; r < KPT; ++r) {
+        const uint32_t i = r * NT + tid;
+        if (i < m) { const uint32_t j = sl[r]; A.pred_hp_eg[base + i] = make_uint2(pred_e[j], pred_g[j]); }
+      }
+    }
+    if (tid == 0 && rl != 0) A.pred_done[t] = 1u;
+  };
 
   // ---- 4. nearest-rank percentiles ---------------------------------------------------------------
   // Fast way: one histogram pass over each ID's own value range [min, max] (2^B bins), which
@@ -843,7 +892,9 @@ k_task_fused(const FusedArgs A) {
         uint64_t* row = staged_row(stage_a, stage_b, base, m, j);
         if (b50 == SEL_NO_BIN || !(se.y & SEL_LISTED)) {   // (not listed: bins one value wide where the scale is one to one)
           if (gl == 0) {
-            row[arr ? 12 : 6] = b50 == SEL_NO_BIN ? 0 : value_of_scale(se.x + b50);
+            const uint32_t v50 = b50 == SEL_NO_BIN ? 0 : value_of_scale(se.x + b50);
+            row[arr ? 12 : 6] = v50;
+            if (emit_p50) (arr ? pred_g : pred_e)[j] = v50;
             row[arr ? 13 : 7] = b50 == SEL_NO_BIN ? 0 : value_of_scale(se.x + b95);
           }
           continue;
@@ -854,7 +905,7 @@ k_task_fused(const FusedArgs A) {
         for (uint32_t x = gl; x < ca; x += GS) {
           const uint32_t v = la[x];
           const uint32_t rank = list_rank(la, ca, v, x);
-          if (rank == k50) row[arr ? 12 : 6] = v;
+          if (rank == k50) { row[arr ? 12 : 6] = v; if (emit_p50) (arr ? pred_g : pred_e)[j] = v; }
           if (cb == 0 && rank == k95) row[arr ? 13 : 7] = v;
         }
         if (cb) {
@@ -866,6 +917,7 @@ k_task_fused(const FusedArgs A) {
           }
         }
       }
+      if (emit) emit_predictions();
       if (tid == 0) dcount[unit] = D;
       return;
     }
@@ -967,7 +1019,9 @@ k_task_fused(const FusedArgs A) {
     const uint4 pf = sm.pref[j];
     row[6] = pf.x; row[7] = pf.y;
     row[12] = pf.z; row[13] = pf.w;
+    if (emit_p50) { pred_e[j] = pf.x; pred_g[j] = pf.z; }
   }
+  if (emit) emit_predictions();
   if (tid == 0) dcount[unit] = D;
 }
 

@@ -109,6 +109,29 @@ def test_profile_only_workloads_full_size(index):
     compare_whole_workload(cfg, off, {"ids": prof.ids, "rows": prof.rows, "task_row_offsets": prof.task_row_offsets}, say=say)
 
 
+def test_config4_one_call_full_size():
+    """The benchmark's default step: fikit_profile_gapfill over the whole workload, every output against the oracle."""
+    cfg = traces.config(4)
+    say(f"config 4 ({cfg.name}), {cfg.n_records} records, profile and gap fill as one call")
+    d_rec, off = upload(cfg)
+    d_off = binding.to_device_u64(off, DEV)
+    hp, lp = traces.scenarios(cfg)
+    go = traces.gap_offsets(off, hp)
+    d_go = binding.to_device_u64(go, DEV)
+    row_cap = sum(cfg.ids(t) for t in range(cfg.n_tasks))
+    t0 = time.time()
+    prof, got = binding.fikit_profile_gapfill(d_rec, d_off, binding.to_device_u32(hp, DEV), binding.to_device_u32(lp, DEV), d_go,
+                                              margin_ns=cfg.margin_ns, min_gap_ns=cfg.min_gap_ns, row_capacity=row_cap)
+    torch.cuda.synchronize()
+    say(f"  fikit_profile_gapfill: {prof.n_rows} rows, {hp.size} scenarios in {time.time() - t0:.2f}s")
+    del d_rec
+    check_global_properties(prof, off, cfg.n_tasks)
+    whole = compare_whole_workload(cfg, off, {"ids": prof.ids, "rows": prof.rows, "task_row_offsets": prof.task_row_offsets,
+                                              "gap_offsets": d_go, "fill_count": got.fill_count, "filled_ns": got.filled_ns,
+                                              "lp_completion_ns": got.lp_completion_ns, "lp_placed": got.lp_placed}, say=say)
+    assert whole["equal_scenarios"] == hp.size and whole["equal_tasks"] == cfg.n_tasks
+
+
 def test_config4_batched_gapfill_full_size():
     cfg = traces.config(4)
     say(f"config 4 ({cfg.name}), {cfg.n_records} records")
