@@ -468,7 +468,9 @@ def main():
         algo_bytes = per_hp * n_hp * (n_scen // max(1, len(np.unique(hp)))) \
             + per_lp * n_lp * (n_scen // max(1, len(np.unique(lp)))) + 12 * n_gaps
     achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
-    counters = stored_counters(name) if args.rho is None and not args.scenarios and not args.tasks else None
+    # (stored counters of a workload with scenarios are of the one-call step)
+    counters = stored_counters(name if one_call or not n_scen else name + " (two calls)") \
+        if args.rho is None and not args.scenarios and not args.tasks else None
     traffic_source = (f"{TRAFFIC_FILE} (rocprofv3 FETCH_SIZE / WRITE_SIZE of an earlier run of this command on these library "
                       f"sources, hash {counters['source_hash']}; summary: {counters.get('summary')})") if counters else None
     roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
