@@ -17,6 +17,10 @@
 //      samples), most-significant-digit radix selection does the task instead: per pass, every launch whose
 //      value still agrees with the digits fixed so far for its ID adds one to that ID's digit histogram,
 //      and one thread per (ID, percentile) walks it to the digit that holds the wanted rank.
+//   5. (Only when a gap fill follows in the same call.)  Algorithm 1 predicts a launch's duration and the idle time
+//      after it from its ID's row.  With every launch's row number still in a register and the rows' medians or
+//      means in LDS, the workgroup writes those predictions per launch itself, so that the gap fill does not have
+//      to read the Kernel IDs again and look each one up.
 //
 // Rows are staged in the task's own slice of two workspace arrays and moved to their final
 // place once every task's row count is known.  A task that does not fit (too many distinct IDs)
