@@ -524,7 +524,8 @@ def main():
         "config": {"workload": name, "records": n, "tasks": cfg.n_tasks, "scenarios": n_scen, "gaps": n_gaps,
                    "rows": prof.n_rows, "margin_ns": cfg.margin_ns, "min_gap_ns": cfg.min_gap_ns,
                    "rho_exec": cfg.rho_exec, "rho_gap": cfg.rho_gap,
-                   "entry_points": "fikit_profile_gapfill" if one_call else "fikit_profile, fikit_gapfill"},
+                   "entry_points": "fikit_profile_gapfill" if one_call else "fikit_profile, fikit_gapfill",
+                   "generator": f"numpy {np.__version__} PCG64, base seed {traces.BASE_SEED}"},
         "profile_records_per_s": round(n / (prof_ms * 1e-3), 1),
         "gapfill_scenarios_per_s": round(n_scen / (gf_ms * 1e-3), 1) if n_scen else None,
         "profile_ms": round(prof_ms, 3), "gapfill_ms": round(gf_ms, 3),
