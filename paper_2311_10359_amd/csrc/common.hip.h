@@ -73,6 +73,13 @@ __device__ __forceinline__ uint64_t read_lane_u64(uint64_t v, uint32_t src) {
   return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
+// A 16-byte load that tells the caches that its data will not be used again.
+typedef uint32_t u32x4_native __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_once(const uint4* p) {
+  const u32x4_native v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_native*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int m) {
   uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), m, WAVE);
   uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), m, WAVE);

@@ -390,7 +390,10 @@ k_task_fused(const FusedArgs A) {
         qrun[u] = 0; qnrun[u] = 1;
         if (i < m) {
           const uint4* p = reinterpret_cast<const uint4*>(rec + base + i);
-          qa[u] = p[0]; qb[u] = p[1]; qc[u] = p[2];
+          // A record is read once.  Its first 48 bytes are loaded with the hint that they will not be used again;
+          // the load that touches its line last (the run) is an ordinary one: with every touch hinted the line is
+          // fetched anew per touch and the kernel takes half as long again, with none it is a few percent slower.
+          qa[u] = load_once(p); qb[u] = load_once(p + 1); qc[u] = load_once(p + 2);
           qrun[u] = rec[base + i].run;
           // the next launch is the next lane's; only the wave's last lane has to read it
           if (lane == WAVE - 1 && i + 1 < m) { qn[u] = rec[base + i + 1].start_ns; qnrun[u] = rec[base + i + 1].run; }
