@@ -693,22 +693,37 @@ k_gf_walk_lanes(const uint64_t* __restrict__ off, const uint32_t* __restrict__ h
         finished = finished || at_end || last;
       }
       // In a gap: does the head of the queue fit into what is left?  Then the entry behind it, and so on: an entry is
-      // tried only behind one that fit, so the k-th try of an opening looks at the k-th entry from where the queue stood.
+      // tried only behind one that fit, so the k-th try of an opening looks at the k-th entry from where the queue stood,
+      // and the tries end at the first entry that does not fit.  The running sums of those entries only grow (a sum
+      // beyond 32 bits stays at the largest value, which no gap reaches), so the number of entries that fit is the
+      // number of running sums within what is left, at most the entries that have landed.
       const int32_t room = static_cast<int32_t>(lp_lim - lp_pos);   // entries that have landed (<= 0: none)
-      bool active = in_gap;
-      uint32_t nfit = 0;
+      uint32_t run[LW_TRIES];
+      run[0] = w[0];
 #pragma unroll
-      for (uint32_t k = 0; k < LW_TRIES; ++k) {
-        const bool tryq = active && static_cast<int32_t>(k) < room;
-        // (with feedback: the next high-priority request has arrived once the time filled reaches the actual gap)
-        const bool fits = tryq && w[k] <= rem && (MODE != LW_REPLAY_FEEDBACK || rem_open - rem < ga);
-        rem -= fits ? w[k] : 0u;
-        nfit = fits ? k + 1 : nfit;
-        const bool close = tryq && !fits;      // the head does not fit: the gap is closed
-        pending = pending || close;
-        in_gap = in_gap && !close;
-        active = fits;
+      for (uint32_t k = 1; k < LW_TRIES; ++k) run[k] = __builtin_elementwise_add_sat(run[k - 1], w[k]);
+      uint32_t n = 0;
+#pragma unroll
+      for (uint32_t k = 0; k < LW_TRIES; ++k) n += run[k] <= rem ? 1u : 0u;
+      if (MODE == LW_REPLAY_FEEDBACK) {
+        // (with feedback: the next high-priority request has arrived once the time filled reaches the actual gap;
+        // an entry is issued only while the time filled before it is below that)
+        const uint32_t f0 = rem_open - rem;
+        uint32_t n2 = f0 < ga ? 1u : 0u;
+#pragma unroll
+        for (uint32_t k = 1; k < LW_TRIES; ++k) n2 += __builtin_elementwise_add_sat(f0, run[k - 1]) < ga ? 1u : 0u;
+        n = n < n2 ? n : n2;
       }
+      const int32_t capped = room < static_cast<int32_t>(LW_TRIES) ? room : static_cast<int32_t>(LW_TRIES);
+      const uint32_t avail = capped > 0 ? static_cast<uint32_t>(capped) : 0u;
+      const uint32_t nfit = in_gap ? (n < avail ? n : avail) : 0u;
+      const bool close = in_gap && n < avail;   // an entry that was there did not fit: the gap is closed
+      uint32_t taken = 0;
+#pragma unroll
+      for (uint32_t k = 0; k < LW_TRIES; ++k) taken = nfit > k ? run[k] : taken;
+      rem -= taken;
+      pending = pending || close;
+      in_gap = in_gap && !close;
       lp_pos += nfit;
     }
   }
