@@ -218,16 +218,28 @@ struct FusedArgs {
   uint32_t predictor;          // a fikit_predictor
 };
 
+// Where the sums of step 1 keep the number of launches: a task of this kernel has at most 2^14 launches of less than
+// 2^32 ns, so a sum stays below 2^46.
+constexpr int EARLY_COUNT_AT = 46;
+static_assert(FUSE_MAX <= (1u << (EARLY_COUNT_AT - 32)), "sums of execution times stay below the count's bits");
+
 // Adds one launch's execution time and (if it has one) idle time to the sums, minima and maxima of ID-table slot s.
 template <typename Smem>
 __device__ __forceinline__ void early_stats(Smem& sm, uint32_t s, uint32_t e, uint32_t g) {
-  atomicAdd(reinterpret_cast<unsigned long long*>(&sm.early.esum[s]), static_cast<unsigned long long>(e));
-  atomicMin(&sm.early.emin[s], e);
-  atomicMax(&sm.early.emax[s], e);
+  // A minimum only falls and a maximum only rises: a value that does not pass what is read now cannot pass what is
+  // there later, so most launches leave the four extremes alone.
+  const uint32_t emin = __hip_atomic_load(&sm.early.emin[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  const uint32_t emax = __hip_atomic_load(&sm.early.emax[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  const uint32_t gmin = __hip_atomic_load(&sm.early.gmin[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  const uint32_t gmax = __hip_atomic_load(&sm.early.gmax[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  // the launch is counted in the same word as its execution time is summed in (EARLY_COUNT_AT)
+  atomicAdd(reinterpret_cast<unsigned long long*>(&sm.early.esum[s]), static_cast<unsigned long long>(e) + (1ull << EARLY_COUNT_AT));
+  if (e < emin) atomicMin(&sm.early.emin[s], e);
+  if (e > emax) atomicMax(&sm.early.emax[s], e);
   if (g != NONE32) {
     atomicAdd(reinterpret_cast<unsigned long long*>(&sm.early.gsum[s]), static_cast<unsigned long long>(g));
-    atomicMin(&sm.early.gmin[s], g);
-    atomicMax(&sm.early.gmax[s], g);
+    if (g < gmin) atomicMin(&sm.early.gmin[s], g);
+    if (g > gmax) atomicMax(&sm.early.gmax[s], g);
   } else {
     atomicAdd(&sm.early.nogap[s], 1u);   // (the last launch of a run)
   }
@@ -369,8 +381,8 @@ k_task_fused(const FusedArgs A) {
           }
         }
         if (!placed) atomicOr(&sm.fallback, 1u);
-        atomicAdd(&sm.ht_cnt[h], 1u);
         if (ESTATS) early_stats(sm, h, ev[r], gv[r]);
+        else atomicAdd(&sm.ht_cnt[h], 1u);
         sl[r] = h;
       }
     }
@@ -497,8 +509,8 @@ k_task_fused(const FusedArgs A) {
             }
           }
           ids[base + i] = id;
-          atomicAdd(&sm.ht_cnt[slot], 1u);
           if (ESTATS) early_stats(sm, slot, ev[r], gv[r]);
+          else atomicAdd(&sm.ht_cnt[slot], 1u);
           sl[r] = slot;
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -563,7 +575,7 @@ k_task_fused(const FusedArgs A) {
       sm.slot_rank[s] = static_cast<uint16_t>(rank);
       if (ESTATS) sm.rslot[rank] = static_cast<uint16_t>(s);
       sm.rkey[rank] = k;
-      sm.rcnt[rank] = sm.ht_cnt[s];
+      sm.rcnt[rank] = ESTATS ? static_cast<uint32_t>(sm.early.esum[s] >> EARLY_COUNT_AT) : sm.ht_cnt[s];
     }
     __syncthreads();
   }
@@ -661,7 +673,7 @@ k_task_fused(const FusedArgs A) {
       const uint32_t s = sm.rslot[j];
       gc = ec - sm.early.nogap[s];
       sm.gcnt[j] = gc;
-      esum = sm.early.esum[s]; emin = sm.early.emin[s]; emax = sm.early.emax[s];
+      esum = sm.early.esum[s] & ((1ull << EARLY_COUNT_AT) - 1); emin = sm.early.emin[s]; emax = sm.early.emax[s];
       gsum = sm.early.gsum[s]; gmin = sm.early.gmin[s]; gmax = sm.early.gmax[s];
     } else {
       gc = sm.gcnt[j];
