@@ -286,6 +286,7 @@ def main():
     trace = binding.fikit_trace_read()
     binding.fikit_trace_enable(False)
     ms_per_step = elapsed / args.steps * 1e3
+    step_ms = [a[0].elapsed_time(a[2]) for a in timers]   # every step by its own events (device time of its calls)
     prof_ms = float(np.median([a[0].elapsed_time(a[1]) for a in timers]))
     gf_ms = float(np.median([a[1].elapsed_time(a[2]) for a in timers]))
     if one_call:
@@ -529,6 +530,8 @@ def main():
         "profile_records_per_s": round(n / (prof_ms * 1e-3), 1),
         "gapfill_scenarios_per_s": round(n_scen / (gf_ms * 1e-3), 1) if n_scen else None,
         "profile_ms": round(prof_ms, 3), "gapfill_ms": round(gf_ms, 3),
+        "step_ms_by_events": {"median": round(float(np.median(step_ms)), 3), "min": round(min(step_ms), 3),
+                              "max": round(max(step_ms), 3)},
         # the profile call against the sort-based formulation's bytes: what that formulation would have to sustain
         # to be as fast (a design that moves fewer bytes shows up here as more than it could physically move)
         "profile_effective_GB/s_at_504_B_per_record": round(n * A_REF_BYTES_PER_RECORD / (prof_ms * 1e-3) / 1e9, 1),
